@@ -1,0 +1,177 @@
+/*
+ * thk.h -- C ABI of libthk: query-driven key-cache channel pruning (ThinK) and
+ * decode attention over the pruned cache, hand-written HIP for gfx950.
+ *
+ * Conventions that hold for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library
+ *     allocates nothing, frees nothing and never synchronises.  Work is enqueued
+ *     on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Base pointers must be 16-byte aligned (THK_ERR_ALIGN otherwise).
+ *   - Argument errors are reported synchronously and enqueue nothing.  A launch
+ *     failure is reported as THK_ERR_HIP.
+ *   - Dense row-major layouts, last index contiguous:
+ *       K, V      [L][B][N_kv][S][D]
+ *       Q_obs     [L][B][N_q ][S_obs][D]
+ *       score     [L][B][N_kv][D]            float
+ *       idx       [L][B][N_kv][T]            int16, 0-based, ascending
+ *       K_pruned  [L][B][N_kv][S][ld_keep]   element type of K
+ *       q, out    [L][B][N_q ][D]
+ *       K_tail, V_tail [L][B][N_kv][S_tail_cap][D]
+ *     Query head n reads KV head n / (N_q / N_kv).
+ *   - Scratch memory comes from the caller: `ws` of at least
+ *     thk_workspace_bytes(shape, op) bytes, 16-byte aligned (THK_ERR_WORKSPACE).
+ *   - Inputs must be finite; results for NaN/Inf inputs are unspecified.
+ *   - Element types: fp32 and bf16.  D must be 128.
+ */
+#ifndef THK_H
+#define THK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  THK_OK = 0,
+  THK_ERR_NULL = 1,        /* a required pointer is NULL                       */
+  THK_ERR_SHAPE = 2,       /* a size is out of range or inconsistent           */
+  THK_ERR_UNSUPPORTED = 3, /* valid in principle, not built (D != 128, dtype)  */
+  THK_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                 */
+  THK_ERR_WORKSPACE = 5,   /* ws is NULL or smaller than thk_workspace_bytes   */
+  THK_ERR_HIP = 6          /* the HIP runtime refused a launch                 */
+} thk_status;
+
+typedef enum { THK_F32 = 0, THK_BF16 = 1 } thk_dtype;
+
+typedef enum {
+  THK_OP_SCORE = 0,  /* thk_score                       */
+  THK_OP_DECODE = 1, /* thk_decode_attn                 */
+  THK_OP_PRUNE = 2   /* thk_prune                       */
+} thk_op;
+
+/* Problem statement in the paper's B x S x L x N x D terms (Sec. 1). */
+typedef struct {
+  int32_t L;       /* layers handled by this call, >= 1                          */
+  int32_t B;       /* batch, >= 1                                                */
+  int32_t N_q;     /* query heads; N_q % N_kv == 0                               */
+  int32_t N_kv;    /* key/value heads                                            */
+  int32_t D;       /* channels per head; must be 128                             */
+  int64_t S;       /* keys in the prunable segment, >= 1                         */
+  int32_t S_obs;   /* observation-window queries, 1..S (score / prune only)      */
+  int32_t T;       /* channels kept, 1..D                                        */
+  int32_t ld_keep; /* row stride of K_pruned in elements, >= T; 0 means T        */
+  int32_t dtype;   /* thk_dtype of Q, K, V, K_pruned, out                        */
+  int32_t n_split; /* pieces the S axis is cut into per unit; 0 = library choice */
+} thk_shape;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t thk_version(void);
+
+/* Static string for a status code. */
+const char *thk_status_string(thk_status st);
+
+/*
+ * T = floor((1 - lambda) * D): the number of channels kept at pruning ratio
+ * lambda (Sec. 3.1, below Eq. 1; constraint of Eq. 2).  Evaluated in fp64; a
+ * product within 1e-9 below an integer counts as that integer.  Returns -1 for
+ * D < 1 or lambda outside [0, 1).  Host-only arithmetic.
+ */
+int32_t thk_keep_count(int32_t D, double lambda);
+
+/*
+ * Bytes of caller-provided scratch that `op` needs for `shape` (including the
+ * shape's n_split; 0 there means the library's own choice, which this function
+ * reproduces).  Returns 0 for an invalid shape.  Host-only arithmetic.
+ */
+size_t thk_workspace_bytes(const thk_shape *shape, int32_t op);
+
+/* The n_split the library would use for `op` when shape->n_split == 0. */
+int32_t thk_default_split(const thk_shape *shape, int32_t op);
+
+/*
+ * Query-driven channel score (Sec. 3.2, Score_i[j] = ||Q_i[-S_obs:, j] K_i[:, j]^T||_F).
+ * The matrix is an outer product of two columns, so the score is
+ * ||Q_obs[:, c]||_2 * ||K[:, c]||_2; with grouped queries the scores of the
+ * N_q / N_kv query heads that read one KV head are added.  No 1/sqrt(D), mask
+ * or softmax enters.  Squares are summed in fp32 chains of at most 16 terms,
+ * merged and square-rooted in fp64, and the product is rounded once to float.
+ *   in : q_obs, k (device)           out: score (device, float)
+ *   ws : THK_OP_SCORE bytes.
+ */
+thk_status thk_score(const thk_shape *shape, const void *q_obs, const void *k,
+                     float *score, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Magnitude-only criterion M[n, d] = ||K[n, :, d]||_p, p = 1 or 2 (Eq. 1), in
+ * the same layout and precision as thk_score; q_obs is not read.
+ */
+thk_status thk_score_magnitude(const thk_shape *shape, const void *k, int32_t p,
+                               float *score, void *ws, size_t ws_bytes,
+                               void *stream);
+
+/*
+ * Top_T selection (Sec. 3.1 I = Top_T(M, T); Sec. 3.2 I_i): per unit the T
+ * channels of largest score, equal scores resolved towards the lower channel
+ * index, written in ascending channel order (the order a binary keep-mask
+ * yields, Fig. 1).  Scores are compared as floats exactly as given.
+ *   in : score (device, float)       out: idx (device, int16)
+ */
+thk_status thk_select_topk(const thk_shape *shape, const float *score,
+                           int16_t *idx, void *stream);
+
+/*
+ * K_pruned[s][t] = K[s][idx[t]] -- a bit copy of the kept channels (Fig. 1;
+ * Sec. 3.3 "pruned keys with a reduced channel size").  Columns [T, ld_keep)
+ * of K_pruned are not written.  idx entries must lie in [0, D).
+ */
+thk_status thk_compact_keys(const thk_shape *shape, const void *k,
+                            const int16_t *idx, void *k_pruned, void *stream);
+
+/*
+ * End-of-prefill prune = thk_score + thk_select_topk + thk_compact_keys, run
+ * over groups of units small enough that the second read of K is served from
+ * the memory-side cache.  `score` may be NULL (then it lives in ws).
+ *   ws : THK_OP_PRUNE bytes.
+ */
+thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,
+                     float *score, int16_t *idx, void *k_pruned, void *ws,
+                     size_t ws_bytes, void *stream);
+
+/*
+ * Decode attention over the two key segments (Sec. 3.3, Fig. 2, with the
+ * attention formula of Sec. 3.2).  Per query head n with KV head h:
+ *   z_s     = (sum_t q[n][idx[h][t]] * K_pruned[h][s][t]) / sqrt(D),   s < S
+ *   z_{S+j} = (sum_c q[n][c] * K_tail[h][j][c]) / sqrt(D),             j < s_tail
+ *   out[n]  = softmax(z) . [V ; V_tail]
+ * one softmax over all S + s_tail logits; sqrt(D) uses the original D.  fp32
+ * arithmetic; out has the input element type (bf16: round to nearest even).
+ * k_tail / v_tail may be NULL iff s_tail == 0; 0 <= s_tail <= s_tail_cap.
+ * S_obs in the shape is ignored.  With n_split > 1 partial (max, sum, acc[D])
+ * states go through ws and a second kernel merges them in split order without
+ * atomics, so repeated calls give identical bits.
+ *   ws : THK_OP_DECODE bytes.
+ */
+thk_status thk_decode_attn(const thk_shape *shape, const void *q,
+                           const void *k_pruned, const int16_t *idx,
+                           const void *v, const void *k_tail,
+                           const void *v_tail, int32_t s_tail,
+                           int32_t s_tail_cap, void *out, void *ws,
+                           size_t ws_bytes, void *stream);
+
+/*
+ * Append one newly decoded token per (layer, batch, KV head) to the unpruned
+ * tail segment (Sec. 3.3: new keys stay at full D):
+ *   K_tail[..][s_tail][:] = k_new[..][:],  V_tail[..][s_tail][:] = v_new[..][:]
+ * k_new, v_new [L][B][N_kv][D].  Requires 0 <= s_tail < s_tail_cap.  The caller
+ * then attends with s_tail + 1.
+ */
+thk_status thk_tail_append(const thk_shape *shape, const void *k_new,
+                           const void *v_new, void *k_tail, void *v_tail,
+                           int32_t s_tail, int32_t s_tail_cap, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* THK_H */

@@ -1,0 +1,168 @@
+"""ctypes binding of libthk.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors on the GPU (or raw integer device addresses); PyTorch
+supplies device memory and the HIP stream, nothing else.  There is no fallback:
+if the library is missing, loading raises.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libthk.so")
+
+THK_F32, THK_BF16 = 0, 1
+THK_OP_SCORE, THK_OP_DECODE, THK_OP_PRUNE = 0, 1, 2
+
+
+class ThkError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__(f"{where}: {thk_status_string(status)} (status {int(status)})")
+
+
+class thk_shape(ctypes.Structure):
+    _fields_ = [("L", ctypes.c_int32), ("B", ctypes.c_int32), ("N_q", ctypes.c_int32),
+                ("N_kv", ctypes.c_int32), ("D", ctypes.c_int32), ("S", ctypes.c_int64),
+                ("S_obs", ctypes.c_int32), ("T", ctypes.c_int32), ("ld_keep", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("n_split", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def load():
+    """Load libthk.so; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with __graft_entry__.build()")
+    L = ctypes.CDLL(_LIB_PATH)
+    sp, vp, i32 = ctypes.POINTER(thk_shape), ctypes.c_void_p, ctypes.c_int32
+    L.thk_version.restype = i32
+    L.thk_version.argtypes = []
+    L.thk_status_string.restype = ctypes.c_char_p
+    L.thk_status_string.argtypes = [ctypes.c_int]
+    L.thk_keep_count.restype = i32
+    L.thk_keep_count.argtypes = [i32, ctypes.c_double]
+    L.thk_workspace_bytes.restype = ctypes.c_size_t
+    L.thk_workspace_bytes.argtypes = [sp, i32]
+    L.thk_default_split.restype = i32
+    L.thk_default_split.argtypes = [sp, i32]
+    L.thk_score.restype = ctypes.c_int
+    L.thk_score.argtypes = [sp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.thk_score_magnitude.restype = ctypes.c_int
+    L.thk_score_magnitude.argtypes = [sp, vp, i32, vp, vp, ctypes.c_size_t, vp]
+    L.thk_select_topk.restype = ctypes.c_int
+    L.thk_select_topk.argtypes = [sp, vp, vp, vp]
+    L.thk_compact_keys.restype = ctypes.c_int
+    L.thk_compact_keys.argtypes = [sp, vp, vp, vp, vp]
+    L.thk_prune.restype = ctypes.c_int
+    L.thk_prune.argtypes = [sp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.thk_decode_attn.restype = ctypes.c_int
+    L.thk_decode_attn.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    L.thk_tail_append.restype = ctypes.c_int
+    L.thk_tail_append.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp]
+    _lib = L
+    return L
+
+
+def make_shape(L, B, N_q, N_kv, D, S, S_obs, T, ld_keep=0, dtype=THK_BF16, n_split=0):
+    return thk_shape(L, B, N_q, N_kv, D, S, S_obs, T, ld_keep, dtype, n_split)
+
+
+def _ptr(x):
+    """Device address of a torch tensor (or pass an int / None through)."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return ctypes.c_void_p(x)
+    return ctypes.c_void_p(x.data_ptr())
+
+
+def _nbytes(ws):
+    if ws is None:
+        return 0
+    if isinstance(ws, tuple):
+        return ws[1]
+    return ws.numel() * ws.element_size()
+
+
+def _ws(ws):
+    return _ptr(ws[0] if isinstance(ws, tuple) else ws)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(st, where):
+    if st != 0:
+        raise ThkError(st, where)
+
+
+def thk_version():
+    return int(load().thk_version())
+
+
+def thk_status_string(st):
+    return load().thk_status_string(int(st)).decode()
+
+
+def thk_keep_count(D, lam):
+    return int(load().thk_keep_count(D, lam))
+
+
+def thk_workspace_bytes(shape, op):
+    return int(load().thk_workspace_bytes(ctypes.byref(shape), op))
+
+
+def thk_default_split(shape, op):
+    return int(load().thk_default_split(ctypes.byref(shape), op))
+
+
+def thk_score(shape, q_obs, k, score, ws, stream=None):
+    _check(load().thk_score(ctypes.byref(shape), _ptr(q_obs), _ptr(k), _ptr(score), _ws(ws),
+                            _nbytes(ws), _stream(stream)), "thk_score")
+
+
+def thk_score_magnitude(shape, k, p, score, ws, stream=None):
+    _check(load().thk_score_magnitude(ctypes.byref(shape), _ptr(k), p, _ptr(score), _ws(ws),
+                                      _nbytes(ws), _stream(stream)), "thk_score_magnitude")
+
+
+def thk_select_topk(shape, score, idx, stream=None):
+    _check(load().thk_select_topk(ctypes.byref(shape), _ptr(score), _ptr(idx), _stream(stream)),
+           "thk_select_topk")
+
+
+def thk_compact_keys(shape, k, idx, k_pruned, stream=None):
+    _check(load().thk_compact_keys(ctypes.byref(shape), _ptr(k), _ptr(idx), _ptr(k_pruned),
+                                   _stream(stream)), "thk_compact_keys")
+
+
+def thk_prune(shape, q_obs, k, score, idx, k_pruned, ws, stream=None):
+    _check(load().thk_prune(ctypes.byref(shape), _ptr(q_obs), _ptr(k), _ptr(score), _ptr(idx),
+                            _ptr(k_pruned), _ws(ws), _nbytes(ws), _stream(stream)), "thk_prune")
+
+
+def thk_decode_attn(shape, q, k_pruned, idx, v, k_tail, v_tail, s_tail, s_tail_cap, out, ws,
+                    stream=None):
+    _check(load().thk_decode_attn(ctypes.byref(shape), _ptr(q), _ptr(k_pruned), _ptr(idx), _ptr(v),
+                                  _ptr(k_tail), _ptr(v_tail), s_tail, s_tail_cap, _ptr(out),
+                                  _ws(ws), _nbytes(ws), _stream(stream)), "thk_decode_attn")
+
+
+def thk_tail_append(shape, k_new, v_new, k_tail, v_tail, s_tail, s_tail_cap, stream=None):
+    _check(load().thk_tail_append(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(k_tail),
+                                  _ptr(v_tail), s_tail, s_tail_cap, _stream(stream)),
+           "thk_tail_append")

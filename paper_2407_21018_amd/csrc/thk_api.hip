@@ -1,0 +1,273 @@
+// C ABI of libthk: argument checks, workspace carving, launch sizing.
+// Everything here is host code; no entry point allocates or synchronises.
+#include <math.h>
+#include <stdlib.h>
+
+#include "thk_internal.h"
+
+using namespace thk;
+
+namespace {
+
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+inline int elem_bytes(int dtype) { return dtype == THK_BF16 ? 2 : 4; }
+inline int64_t units_of(const thk_shape *s) { return (int64_t)s->L * s->B * s->N_kv; }
+inline int ld_of(const thk_shape *s) { return s->ld_keep ? s->ld_keep : s->T; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+constexpr int kMaxSplit = 4096;
+constexpr int64_t kMaxGrid = 2147483647LL;
+
+// Shape checks common to all entry points.
+thk_status check_shape(const thk_shape *s, bool need_obs) {
+  if (s == nullptr) return THK_ERR_NULL;
+  if (s->L < 1 || s->B < 1 || s->N_q < 1 || s->N_kv < 1 || s->D < 1 || s->S < 1) return THK_ERR_SHAPE;
+  if (s->N_q % s->N_kv != 0) return THK_ERR_SHAPE;
+  if (s->T < 1 || s->T > s->D) return THK_ERR_SHAPE;
+  if (s->ld_keep != 0 && s->ld_keep < s->T) return THK_ERR_SHAPE;
+  if (need_obs && (s->S_obs < 1 || (int64_t)s->S_obs > s->S)) return THK_ERR_SHAPE;
+  if (s->n_split < 0 || s->n_split > kMaxSplit) return THK_ERR_SHAPE;
+  if (s->dtype != THK_F32 && s->dtype != THK_BF16) return THK_ERR_UNSUPPORTED;
+  if (s->D != kD) return THK_ERR_UNSUPPORTED;
+  if (s->S > (int64_t)1 << 40 || units_of(s) > kMaxGrid) return THK_ERR_SHAPE;
+  return THK_OK;
+}
+
+// Split of the S axis for the column reduction: `rows` rows per piece.
+struct Split { int n; int64_t rows; };
+
+Split score_split(const thk_shape *s, int64_t units) {
+  int n = s->n_split;
+  if (n == 0) {
+    // aim at ~16 blocks per compute unit over the call, pieces of >= 256 rows
+    n = (int)ceil_div((int64_t)kCUs * 16, units);
+    const int64_t cap = ceil_div(s->S, 256);
+    if (n > cap) n = (int)cap;
+    if (n > kMaxSplit) n = kMaxSplit;
+    if (n < 1) n = 1;
+  }
+  int64_t rows = ceil_div(s->S, n);
+  rows = ceil_div(rows, 16) * 16;
+  return {n, rows};
+}
+
+int group_width(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
+
+Split decode_split(const thk_shape *s) {
+  int n = s->n_split;
+  const int G = s->N_q / s->N_kv;
+  const int64_t wgs = units_of(s) * (G / group_width(G));
+  if (n == 0) {
+    // ~8 blocks per compute unit, pieces of whole 256-row block passes
+    n = (int)ceil_div((int64_t)kCUs * 8, wgs);
+    const int64_t cap = ceil_div(s->S, 256);
+    if (n > cap) n = (int)cap;
+    if (n > kMaxSplit) n = kMaxSplit;
+    if (n < 1) n = 1;
+  }
+  int64_t rows = ceil_div(s->S, n);
+  rows = ceil_div(rows, 64) * 64;
+  if (s->n_split == 0) n = (int)ceil_div(s->S, rows);   // drop empty pieces
+  return {n, rows};
+}
+
+// Units per group in thk_prune: the group's K slab should stay resident in the
+// memory-side cache between the scoring read and the compaction read.
+int64_t prune_group_units(const thk_shape *s) {
+  size_t budget = (size_t)64 << 20;
+  if (const char *e = getenv("THK_PRUNE_GROUP_MIB")) {
+    const long v = atol(e);
+    if (v > 0) budget = (size_t)v << 20;
+  }
+  const size_t per_unit = (size_t)s->S * kD * elem_bytes(s->dtype);
+  int64_t g = (int64_t)(budget / per_unit);
+  if (g < 1) g = 1;
+  const int64_t U = units_of(s);
+  return g > U ? U : g;
+}
+
+size_t score_ws_bytes(const thk_shape *s, int64_t units) {
+  return (size_t)units * score_split(s, units).n * kD * sizeof(double);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t thk_version(void) { return 100; }
+
+const char *thk_status_string(thk_status st) {
+  switch (st) {
+    case THK_OK: return "ok";
+    case THK_ERR_NULL: return "null pointer";
+    case THK_ERR_SHAPE: return "invalid shape";
+    case THK_ERR_UNSUPPORTED: return "unsupported configuration";
+    case THK_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case THK_ERR_WORKSPACE: return "workspace missing or too small";
+    case THK_ERR_HIP: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+int32_t thk_keep_count(int32_t D, double lambda) {
+  if (D < 1 || !(lambda >= 0.0) || !(lambda < 1.0)) return -1;
+  return (int32_t)floor((1.0 - lambda) * (double)D + 1e-9);
+}
+
+int32_t thk_default_split(const thk_shape *s, int32_t op) {
+  if (check_shape(s, false) != THK_OK) return 0;
+  thk_shape t = *s;
+  t.n_split = 0;
+  if (op == THK_OP_DECODE) return decode_split(&t).n;
+  if (op == THK_OP_SCORE) return score_split(&t, units_of(&t)).n;
+  if (op == THK_OP_PRUNE) return score_split(&t, prune_group_units(&t)).n;
+  return 0;
+}
+
+size_t thk_workspace_bytes(const thk_shape *s, int32_t op) {
+  if (check_shape(s, false) != THK_OK) return 0;
+  switch (op) {
+    case THK_OP_SCORE:
+      return score_ws_bytes(s, units_of(s));
+    case THK_OP_DECODE: {
+      const Split sp = decode_split(s);
+      if (sp.n == 1) return 16;
+      return (size_t)s->L * s->B * s->N_q * sp.n * (kD + 2) * sizeof(float);
+    }
+    case THK_OP_PRUNE:
+      // partial sums of one group + a score array for the whole call
+      return score_ws_bytes(s, prune_group_units(s)) + (size_t)units_of(s) * kD * sizeof(float);
+  }
+  return 0;
+}
+
+static thk_status score_common(const thk_shape *s, int mode, const void *q_obs, const void *k,
+                               float *score, void *ws, size_t ws_bytes, void *stream) {
+  thk_status st = check_shape(s, mode == 0);
+  if (st != THK_OK) return st;
+  if (k == nullptr || score == nullptr || (mode == 0 && q_obs == nullptr)) return THK_ERR_NULL;
+  if (!aligned16(k) || !aligned16(score) || (mode == 0 && !aligned16(q_obs))) return THK_ERR_ALIGN;
+  const int64_t U = units_of(s);
+  const Split sp = score_split(s, U);
+  if (U * sp.n > kMaxGrid) return THK_ERR_SHAPE;
+  if (ws == nullptr || !aligned16(ws) || ws_bytes < score_ws_bytes(s, U)) return THK_ERR_WORKSPACE;
+  hipStream_t hs = (hipStream_t)stream;
+  if (launch_colsum(s->dtype, k, (double *)ws, U, s->S, sp.n, sp.rows, mode == 1 ? 1 : 2, hs) != hipSuccess)
+    return THK_ERR_HIP;
+  if (launch_finalize(s->dtype, mode, (const double *)ws, q_obs, score, nullptr, U, s->N_q / s->N_kv,
+                      s->S_obs, sp.n, s->T, hs) != hipSuccess)
+    return THK_ERR_HIP;
+  return THK_OK;
+}
+
+thk_status thk_score(const thk_shape *s, const void *q_obs, const void *k, float *score, void *ws,
+                     size_t ws_bytes, void *stream) {
+  return score_common(s, 0, q_obs, k, score, ws, ws_bytes, stream);
+}
+
+thk_status thk_score_magnitude(const thk_shape *s, const void *k, int32_t p, float *score,
+                               void *ws, size_t ws_bytes, void *stream) {
+  if (p != 1 && p != 2) return s == nullptr ? THK_ERR_NULL : THK_ERR_SHAPE;
+  return score_common(s, p == 1 ? 1 : 2, nullptr, k, score, ws, ws_bytes, stream);
+}
+
+thk_status thk_select_topk(const thk_shape *s, const float *score, int16_t *idx, void *stream) {
+  thk_status st = check_shape(s, false);
+  if (st != THK_OK) return st;
+  if (score == nullptr || idx == nullptr) return THK_ERR_NULL;
+  if (!aligned16(score) || !aligned16(idx)) return THK_ERR_ALIGN;
+  if (launch_select(score, idx, units_of(s), s->T, (hipStream_t)stream) != hipSuccess) return THK_ERR_HIP;
+  return THK_OK;
+}
+
+thk_status thk_compact_keys(const thk_shape *s, const void *k, const int16_t *idx, void *k_pruned,
+                            void *stream) {
+  thk_status st = check_shape(s, false);
+  if (st != THK_OK) return st;
+  if (k == nullptr || idx == nullptr || k_pruned == nullptr) return THK_ERR_NULL;
+  if (!aligned16(k) || !aligned16(idx) || !aligned16(k_pruned)) return THK_ERR_ALIGN;
+  if (units_of(s) * ceil_div(s->S, 512) > kMaxGrid) return THK_ERR_SHAPE;
+  if (launch_compact(s->dtype, k, idx, k_pruned, units_of(s), s->S, s->T, ld_of(s), (hipStream_t)stream) != hipSuccess)
+    return THK_ERR_HIP;
+  return THK_OK;
+}
+
+thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float *score,
+                     int16_t *idx, void *k_pruned, void *ws, size_t ws_bytes, void *stream) {
+  thk_status st = check_shape(s, true);
+  if (st != THK_OK) return st;
+  if (q_obs == nullptr || k == nullptr || idx == nullptr || k_pruned == nullptr) return THK_ERR_NULL;
+  if (!aligned16(q_obs) || !aligned16(k) || !aligned16(idx) || !aligned16(k_pruned) ||
+      (score != nullptr && !aligned16(score)))
+    return THK_ERR_ALIGN;
+  if (ws == nullptr || !aligned16(ws) || ws_bytes < thk_workspace_bytes(s, THK_OP_PRUNE)) return THK_ERR_WORKSPACE;
+  const int64_t U = units_of(s);
+  const int64_t gu = prune_group_units(s);
+  const Split sp = score_split(s, gu);
+  if (gu * sp.n > kMaxGrid || gu * ceil_div(s->S, 512) > kMaxGrid) return THK_ERR_SHAPE;
+  double *partial = (double *)ws;
+  float *sc = score != nullptr ? score : (float *)((char *)ws + score_ws_bytes(s, gu));
+  const int eb = elem_bytes(s->dtype);
+  const int ld = ld_of(s);
+  const int G = s->N_q / s->N_kv;
+  hipStream_t hs = (hipStream_t)stream;
+  for (int64_t u0 = 0; u0 < U; u0 += gu) {
+    const int64_t nu = (U - u0 < gu) ? U - u0 : gu;
+    const char *kg = (const char *)k + (size_t)u0 * s->S * kD * eb;
+    if (launch_colsum(s->dtype, kg, partial, nu, s->S, sp.n, sp.rows, 2, hs) != hipSuccess) return THK_ERR_HIP;
+    // unit u reads query heads u * G .. u * G + G - 1, so a group starting at u0 starts u0 * G heads in
+    const char *qg = (const char *)q_obs + (size_t)u0 * G * s->S_obs * kD * eb;
+    if (launch_finalize(s->dtype, 0, partial, qg, sc + (size_t)u0 * kD, idx + (size_t)u0 * s->T, nu, G,
+                        s->S_obs, sp.n, s->T, hs) != hipSuccess)
+      return THK_ERR_HIP;
+    if (launch_compact(s->dtype, kg, idx + (size_t)u0 * s->T, (char *)k_pruned + (size_t)u0 * s->S * ld * eb,
+                       nu, s->S, s->T, ld, hs) != hipSuccess)
+      return THK_ERR_HIP;
+  }
+  return THK_OK;
+}
+
+thk_status thk_decode_attn(const thk_shape *s, const void *q, const void *k_pruned,
+                           const int16_t *idx, const void *v, const void *k_tail,
+                           const void *v_tail, int32_t s_tail, int32_t s_tail_cap, void *out,
+                           void *ws, size_t ws_bytes, void *stream) {
+  thk_status st = check_shape(s, false);
+  if (st != THK_OK) return st;
+  if (q == nullptr || k_pruned == nullptr || idx == nullptr || v == nullptr || out == nullptr) return THK_ERR_NULL;
+  if (s_tail < 0 || s_tail_cap < 0 || s_tail > s_tail_cap) return THK_ERR_SHAPE;
+  if (s_tail > 0 && (k_tail == nullptr || v_tail == nullptr)) return THK_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_pruned) || !aligned16(idx) || !aligned16(v) || !aligned16(out) ||
+      (s_tail > 0 && (!aligned16(k_tail) || !aligned16(v_tail))))
+    return THK_ERR_ALIGN;
+  const Split sp = decode_split(s);
+  const int G = s->N_q / s->N_kv;
+  if (units_of(s) * (G / group_width(G)) * sp.n > kMaxGrid) return THK_ERR_SHAPE;
+  if (sp.n > 1 && (ws == nullptr || !aligned16(ws) || ws_bytes < thk_workspace_bytes(s, THK_OP_DECODE)))
+    return THK_ERR_WORKSPACE;
+  DecodeArgs a;
+  a.q = q; a.kp = k_pruned; a.v = v; a.kt = k_tail; a.vt = v_tail; a.idx = idx; a.out = out;
+  a.ws = (float *)ws;
+  a.S = s->S; a.rows_per_split = sp.rows;
+  a.T = s->T; a.ldk = ld_of(s); a.N_q = s->N_q; a.N_kv = s->N_kv;
+  a.s_tail = s_tail; a.s_tail_cap = s_tail_cap; a.n_split = sp.n; a.dtype = s->dtype;
+  a.units = units_of(s);
+  a.kp_bytes = (size_t)a.units * s->S * a.ldk * elem_bytes(s->dtype);
+  a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)s->D));
+  if (launch_decode(a, (hipStream_t)stream) != hipSuccess) return THK_ERR_HIP;
+  return THK_OK;
+}
+
+thk_status thk_tail_append(const thk_shape *s, const void *k_new, const void *v_new, void *k_tail,
+                           void *v_tail, int32_t s_tail, int32_t s_tail_cap, void *stream) {
+  thk_status st = check_shape(s, false);
+  if (st != THK_OK) return st;
+  if (k_new == nullptr || v_new == nullptr || k_tail == nullptr || v_tail == nullptr) return THK_ERR_NULL;
+  if (s_tail < 0 || s_tail >= s_tail_cap) return THK_ERR_SHAPE;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_tail) || !aligned16(v_tail)) return THK_ERR_ALIGN;
+  if (launch_tail_append(s->dtype, k_new, v_new, k_tail, v_tail, units_of(s), s_tail, s_tail_cap,
+                         (hipStream_t)stream) != hipSuccess)
+    return THK_ERR_HIP;
+  return THK_OK;
+}
+
+}  // extern "C"

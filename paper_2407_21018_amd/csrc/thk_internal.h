@@ -1,0 +1,79 @@
+// Internal declarations shared by the libthk translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "thk.h"
+
+namespace thk {
+
+constexpr int kD = 128;     // channels per head (the only size built)
+constexpr int kWave = 64;   // wavefront width on CDNA4
+constexpr int kCUs = 256;   // compute units of an MI355X
+
+// ---- element access ------------------------------------------------------
+// A 16-byte chunk holds VEC elements; unpack() widens them to float exactly.
+template <int DT> struct Elem;
+template <> struct Elem<THK_F32> {
+  static constexpr int EB = 4, VEC = 4;
+  __device__ static inline void unpack(const uint4 &r, float (&f)[4]) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+  __device__ static inline float load1(const void *p, size_t i) { return ((const float *)p)[i]; }
+  __device__ static inline void store1(void *p, size_t i, float x) { ((float *)p)[i] = x; }
+};
+template <> struct Elem<THK_BF16> {
+  static constexpr int EB = 2, VEC = 8;
+  __device__ static inline void unpack(const uint4 &r, float (&f)[8]) {
+    f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+    f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+    f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+  __device__ static inline float load1(const void *p, size_t i) {
+    return __uint_as_float((uint32_t)((const uint16_t *)p)[i] << 16);
+  }
+  // fp32 -> bf16, round to nearest even (finite inputs)
+  __device__ static inline uint16_t round_bf16(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+  }
+  __device__ static inline void store1(void *p, size_t i, float x) { ((uint16_t *)p)[i] = round_bf16(x); }
+};
+
+// ---- launchers (one per kernel family; each returns hipGetLastError()) ----
+// Column sums of squares (p == 2) or of absolute values (p == 1) of K per
+// unit, cut into n_split pieces of rows_per_split rows: partial[U][n_split][D].
+hipError_t launch_colsum(int dtype, const void *k, double *partial, int64_t U, int64_t S,
+                         int n_split, int64_t rows_per_split, int p, hipStream_t st);
+
+// score (and optionally idx) from the partial sums and Q_obs.
+//   mode 0: query-driven (Sec. 3.2); mode 1: magnitude l1; mode 2: magnitude l2.
+hipError_t launch_finalize(int dtype, int mode, const double *partial, const void *q_obs,
+                           float *score, int16_t *idx /*may be null*/, int64_t U, int G,
+                           int S_obs, int n_split, int T, hipStream_t st);
+
+hipError_t launch_select(const float *score, int16_t *idx, int64_t U, int T, hipStream_t st);
+
+hipError_t launch_compact(int dtype, const void *k, const int16_t *idx, void *kp, int64_t U,
+                          int64_t S, int T, int ld_keep, hipStream_t st);
+
+struct DecodeArgs {
+  const void *q, *kp, *v, *kt, *vt;
+  const int16_t *idx;
+  void *out;
+  float *ws;
+  int64_t S, rows_per_split;
+  size_t kp_bytes;            // total bytes of K_pruned (bounds the flat tile loads)
+  int32_t T, ldk, N_q, N_kv, s_tail, s_tail_cap, n_split, dtype;
+  int64_t units;              // L * B * N_kv
+  float scale_log2;           // log2(e) / sqrt(D)
+};
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t st);
+
+hipError_t launch_tail_append(int dtype, const void *k_new, const void *v_new, void *k_tail,
+                              void *v_tail, int64_t U, int s_tail, int cap, hipStream_t st);
+
+}  // namespace thk

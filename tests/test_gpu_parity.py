@@ -1,0 +1,200 @@
+"""GPU parity: every C-ABI entry point against the CPU fp64 oracle, element by
+element, on seeded inputs that span several tiles and a ragged tail."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_21018_amd as thk
+from oracle import oracle as O
+from paper_2407_21018_amd.synth import as_numpy
+from helpers import (ATTN_TOL, DT, SCORE_TOL, TDT, attn_rel_err, check_idx_with_tie_rule, gpu_compact,
+                     gpu_decode, gpu_prune, gpu_score, gpu_select, oracle_prune, ws_tensor)
+
+pytestmark = pytest.mark.gpu
+D = 128
+
+
+def _randn(shape, dtype, seed, scale_sigma=1.0, dev="cuda"):
+    g = torch.Generator(device=dev); g.manual_seed(seed)
+    x = torch.randn(*shape, generator=g, device=dev)
+    if scale_sigma:
+        sc = torch.exp(scale_sigma * torch.randn(shape[-1], generator=g, device=dev))
+        x = x * sc
+    return x.to(TDT[dtype])
+
+
+# ----------------------------------------------------------------- score ----
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("G,n_split,S", [(1, 0, 1037), (4, 3, 1037), (2, 7, 600), (1, 1, 64), (1, 0, 5), (4, 64, 4100)])
+def test_score_matches_oracle(dtype, G, n_split, S):
+    L, B, N_kv, S_obs = 2, 2, 2, min(32, S)
+    q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, 11)
+    k = _randn((L, B, N_kv, S, D), dtype, 12)
+    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, 64, 0, DT[dtype], n_split)
+    got = gpu_score(shape, q_obs, k).cpu().numpy().astype(np.float64).reshape(L, B, N_kv, D)
+    want = O.score(as_numpy(q_obs), as_numpy(k), dtype)
+    rel = np.abs(got - want) / want
+    print(f"score {dtype} G={G} split={n_split} S={S}: max rel err {rel.max():.3e}")
+    assert rel.max() <= SCORE_TOL
+
+
+@pytest.mark.parametrize("p", [1, 2])
+def test_magnitude_score_matches_oracle(p):
+    L, B, N_kv, S = 1, 2, 3, 777
+    k = _randn((L, B, N_kv, S, D), "bf16", 13)
+    shape = thk.make_shape(L, B, N_kv, N_kv, D, S, 1, 64, 0, thk.THK_BF16, 0)
+    U = L * B * N_kv
+    score = torch.empty(U, D, dtype=torch.float32, device="cuda")
+    ws = ws_tensor(thk.thk_workspace_bytes(shape, thk.THK_OP_SCORE))
+    thk.thk_score_magnitude(shape, k, p, score, ws)
+    torch.cuda.synchronize()
+    want = O.score_magnitude(as_numpy(k), "bf16", p).reshape(U, D)
+    rel = np.abs(score.cpu().numpy().astype(np.float64) - want) / want
+    assert rel.max() <= SCORE_TOL
+
+
+# ---------------------------------------------------------------- select ----
+@pytest.mark.parametrize("T", [1, 2, 51, 63, 64, 65, 76, 127, 128])
+def test_select_bit_exact_on_same_scores(T):
+    """Both sides decide on the same fp32 scores: no tolerance."""
+    U = 70
+    g = torch.Generator(device="cuda"); g.manual_seed(100 + T)
+    score = torch.randn(U, D, generator=g, device="cuda").abs()
+    score[3] = score[3].round(decimals=1)      # many exact ties
+    score[4] = 0.0                             # all equal
+    score[5, ::2] = score[5, 1::2]             # duplicated pairs
+    score[6] = torch.arange(D, device="cuda").float()        # ascending
+    score[7] = torch.arange(D, 0, -1, device="cuda").float()  # descending
+    shape = thk.make_shape(1, 1, U, U, D, 1, 1, T, 0, thk.THK_F32, 0)
+    got = gpu_select(shape, score).cpu().numpy()
+    want = O.select_topk(score.cpu().numpy().astype(np.float64), T)
+    np.testing.assert_array_equal(got, want)
+
+
+# --------------------------------------------------------------- compact ----
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("S,T,ld", [(1024, 64, 0), (1056, 76, 0), (2048 + 32, 51, 0), (1037, 51, 0), (1037, 76, 80),
+                                     (520, 128, 0), (16, 1, 0), (3, 7, 0), (4096, 89, 0), (8, 51, 0)])
+def test_compact_bit_exact(dtype, S, T, ld):
+    L, B, N_kv = 1, 2, 3
+    k = _randn((L, B, N_kv, S, D), dtype, 21)
+    g = torch.Generator(device="cpu"); g.manual_seed(S + T)
+    score = torch.rand(L * B * N_kv, D, generator=g).numpy().astype(np.float64)
+    idx_np = O.select_topk(score, T)
+    idx = torch.from_numpy(idx_np).cuda()
+    shape = thk.make_shape(L, B, N_kv, N_kv, D, S, 1, T, ld, DT[dtype], 0)
+    kp = gpu_compact(shape, k, idx)
+    want = O.compact_keys(as_numpy(k).reshape(L * B * N_kv, S, D), idx_np, dtype, ld)
+    np.testing.assert_array_equal(as_numpy(kp), want)   # padding columns stay zero on both sides
+
+
+# ---------------------------------------------------------------- decode ----
+def _decode_case(dtype, B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma, seed):
+    N_q = N_kv * G
+    q = _randn((1, B, N_q, D), dtype, seed, sigma)
+    k = _randn((1, B, N_kv, S, D), dtype, seed + 1, sigma)
+    v = _randn((1, B, N_kv, S, D), dtype, seed + 2, 0)
+    kt = _randn((1, B, N_kv, max(cap, 1), D), dtype, seed + 3, sigma)
+    vt = _randn((1, B, N_kv, max(cap, 1), D), dtype, seed + 4, 0)
+    g = torch.Generator(device="cpu"); g.manual_seed(seed + 5)
+    idx_np = O.select_topk(torch.rand(B * N_kv, D, generator=g).numpy().astype(np.float64), T)
+    idx = torch.from_numpy(idx_np).cuda()
+    shape = thk.make_shape(1, B, N_q, N_kv, D, S, 1, T, ld, DT[dtype], n_split)
+    kp = gpu_compact(shape, k, idx)
+    out = gpu_decode(shape, q, kp, idx, v, kt if s_tail else None, vt if s_tail else None, s_tail, cap)
+    U = B * N_kv
+    ref = O.decode_attn(as_numpy(q)[0], as_numpy(kp).reshape(B, N_kv, S, -1), idx_np.reshape(B, N_kv, T),
+                        as_numpy(v)[0], dtype, as_numpy(kt)[0] if s_tail else None,
+                        as_numpy(vt)[0] if s_tail else None, s_tail)
+    err = attn_rel_err(out, ref.reshape(B * N_q, D))
+    return err, out
+
+
+DECODE_CASES = [
+    # B N_kv G   S    T   ld split tail cap sigma
+    (2, 2, 1, 1037, 64, 0, 0, 0, 0, 1.0),
+    (2, 2, 1, 1037, 76, 0, 0, 0, 0, 1.0),
+    (2, 2, 1, 1037, 51, 0, 0, 0, 0, 1.0),
+    (1, 2, 4, 1037, 64, 0, 3, 0, 0, 1.0),
+    (1, 2, 4, 2048, 76, 0, 0, 17, 64, 1.0),
+    (1, 1, 8, 1500, 51, 0, 2, 64, 64, 1.0),
+    (1, 1, 3, 700, 64, 0, 0, 1, 4, 1.0),
+    (1, 2, 2, 900, 89, 0, 7, 5, 16, 1.0),
+    (1, 2, 1, 1, 64, 0, 0, 0, 0, 1.0),
+    (1, 2, 1, 1, 64, 0, 0, 1, 1, 1.0),
+    (1, 2, 1, 63, 128, 0, 0, 0, 0, 1.0),
+    (1, 2, 1, 65, 1, 0, 0, 0, 0, 1.0),
+    (1, 2, 1, 300, 7, 0, 2, 3, 8, 1.0),
+    (1, 2, 1, 1037, 76, 80, 0, 0, 0, 1.0),
+    (1, 2, 1, 1037, 51, 56, 4, 9, 16, 1.0),
+    (2, 3, 1, 4096, 76, 0, 0, 0, 0, 0.0),      # diffuse softmax: V accumulation dominates
+    (1, 2, 4, 8192, 64, 0, 64, 0, 0, 0.0),
+    (1, 2, 1, 5000, 64, 0, 0, 33, 64, 2.0),    # heavy-tailed scales: near one-hot softmax
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("case", DECODE_CASES, ids=lambda c: "-".join(map(str, c)))
+def test_decode_matches_oracle(dtype, case):
+    B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma = case
+    err, _ = _decode_case(dtype, B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma, 1000 + S + T)
+    print(f"decode {dtype} {case}: max rel err {err.max():.3e}")
+    assert err.max() <= ATTN_TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_decode_split_invariance_and_determinism(dtype):
+    outs = {}
+    for n_split in (1, 2, 7, 64):
+        err, out = _decode_case(dtype, 1, 2, 4, 8192 + 100, 64, 0, n_split, 11, 16, 1.0, 77)
+        assert err.max() <= ATTN_TOL[dtype]
+        _, out2 = _decode_case(dtype, 1, 2, 4, 8192 + 100, 64, 0, n_split, 11, 16, 1.0, 77)
+        assert torch.equal(out, out2), "two runs must be bit-identical (no atomics)"
+        outs[n_split] = out.float()
+    ref = outs[1]
+    for n_split, o in outs.items():
+        rel = ((o - ref).abs().amax(-1) / ref.abs().amax(-1)).max().item()
+        assert rel <= ATTN_TOL[dtype], f"n_split={n_split} deviates by {rel}"
+
+
+# ----------------------------------------------------------------- prune ----
+@pytest.mark.parametrize("dtype,G,S,T,sigma", [("bf16", 1, 2048, 76, 1.5), ("bf16", 4, 4096 + 64, 64, 1.0),
+                                                ("f32", 1, 1037, 64, 1.0), ("bf16", 1, 1024, 51, 2.0)])
+def test_prune_pipeline_matches_oracle(dtype, G, S, T, sigma, monkeypatch):
+    monkeypatch.setenv("THK_PRUNE_GROUP_MIB", "1")     # several groups, some starting mid-batch
+    L, B, N_kv, S_obs = 2, 2, 3, 32
+    q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, 31, sigma)
+    k = _randn((L, B, N_kv, S, D), dtype, 32, sigma)
+    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T, 0, DT[dtype], 0)
+    score, idx, kp = gpu_prune(shape, q_obs, k)
+    o_sc, o_idx, o_kp = oracle_prune(q_obs, k, dtype, T)
+    U = L * B * N_kv
+    rel = np.abs(score.cpu().numpy().astype(np.float64) - o_sc.reshape(U, D)) / o_sc.reshape(U, D)
+    assert rel.max() <= SCORE_TOL
+    differing = check_idx_with_tie_rule(idx.cpu().numpy(), o_idx, o_sc, T)
+    kp_np, o_kp = as_numpy(kp), o_kp.reshape(U, S, T)
+    same = [u for u in range(U) if u not in differing]
+    np.testing.assert_array_equal(kp_np[same], o_kp[same])
+    # the separate entry points give the same bits as the fused call
+    sc2 = gpu_score(shape, q_obs, k)
+    idx2 = gpu_select(shape, sc2)
+    kp2 = gpu_compact(shape, k, idx2)
+    assert torch.equal(sc2, score) and torch.equal(idx2, idx) and torch.equal(kp2, kp)
+
+
+def test_tail_append():
+    L, B, N_kv, cap = 1, 3, 5, 8
+    shape = thk.make_shape(L, B, N_kv, N_kv, D, 16, 1, 64, 0, thk.THK_BF16, 0)
+    kt = torch.zeros(L * B * N_kv, cap, D, dtype=torch.bfloat16, device="cuda"); vt = torch.zeros_like(kt)
+    news = []
+    for j in range(cap):
+        kn = _randn((L * B * N_kv, D), "bf16", 50 + j); vn = _randn((L * B * N_kv, D), "bf16", 90 + j)
+        thk.thk_tail_append(shape, kn, vn, kt, vt, j, cap)
+        news.append((kn, vn))
+    torch.cuda.synchronize()
+    for j, (kn, vn) in enumerate(news):
+        assert torch.equal(kt[:, j], kn) and torch.equal(vt[:, j], vn)
+    with pytest.raises(thk.ThkError):
+        thk.thk_tail_append(shape, news[0][0], news[0][1], kt, vt, cap, cap)
