@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the ThinK hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input of the
+LLaMA-2-7B-shaped workload: prune the key caches of all 32 layers (score ->
+Top_T -> compaction), then one decode-attention step per layer over the pruned
+cache.  Inputs are resident in HBM before the timed region.  Prints ONE JSON
+line; `value` is the algorithmic bytes of a step divided by its time.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload id (synth.CONFIGS); 2 = the metric's")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg_id, cfg, T, device):
+    """Time the oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import oracle as O
+    from paper_2407_21018_amd import synth
+    sample_B = 1
+    sub = dict(cfg, B=sample_B)
+    q_obs, k, v = synth.gen_prefill(cfg_id, 0, device, **sub)
+    q, _, _ = synth.gen_decode(cfg_id, 0, 0, device, **sub)
+    qn, kn, vn, q1 = synth.as_numpy(q_obs), synth.as_numpy(k), synth.as_numpy(v), synth.as_numpy(q)
+    dt = cfg["dtype"]
+    eb = 2 if dt == "bf16" else 4
+    O.lib()
+    t0 = time.perf_counter()
+    sc = O.score(qn, kn, dt)
+    idx = O.select_topk(sc, T)
+    kp = O.compact_keys(kn, idx, dt)
+    t1 = time.perf_counter()
+    O.decode_attn(q1[0], kp[0], idx[0], vn[0], dt)
+    t2 = time.perf_counter()
+    U = sample_B * cfg["N_kv"]
+    by = U * cfg["S"] * eb * (cfg["D"] + 2 * T) + qn.nbytes + U * cfg["S"] * eb * (T + cfg["D"])
+    return {"value": by / (t2 - t0) / 1e9, "unit": "GB/s", "cores": O.max_threads(), "kind": "oracle",
+            "sample": f"1 of {cfg['L']} layers, batch row 0 of {cfg['B']} ({U} units): prune + 1 decode step",
+            "prune_ms_per_layer_equiv": (t1 - t0) * 1e3 * cfg["B"] / sample_B,
+            "decode_us_per_step_equiv": (t2 - t1) * 1e6 * cfg["B"] / sample_B}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (units are independent; no collective "
+              "exists in the path) -- run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2407_21018_amd as thk
+    from paper_2407_21018_amd import synth
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg_id = args.config
+    cfg = synth.CONFIGS[cfg_id]
+    L, B, N_q, N_kv, D, S, S_obs = (cfg[k] for k in ("L", "B", "N_q", "N_kv", "D", "S", "S_obs"))
+    T = thk.thk_keep_count(D, cfg["lam"])
+    dt = synth.torch_dtype(cfg["dtype"])
+    tdt = thk.THK_BF16 if cfg["dtype"] == "bf16" else thk.THK_F32
+    eb = 2 if cfg["dtype"] == "bf16" else 4
+    U = B * N_kv                      # units per layer
+    steps_per_layer = cfg["steps"]
+    cap = cfg["tail_cap"]
+
+    # ---- inputs, resident in HBM ------------------------------------------
+    q_obs = torch.empty(L, B, N_q, S_obs, D, dtype=dt, device=dev)
+    k = torch.empty(L, B, N_kv, S, D, dtype=dt, device=dev)
+    v = torch.empty(L, B, N_kv, S, D, dtype=dt, device=dev)
+    for l in range(L):
+        q_obs[l], k[l], v[l] = (t[0] for t in synth.gen_prefill(cfg_id, l, dev, **cfg))
+    dec = [[synth.gen_decode(cfg_id, l, s, dev, **cfg) for s in range(steps_per_layer)] for l in range(L)]
+    score = torch.empty(L * U, D, dtype=torch.float32, device=dev)
+    idx = torch.empty(L * U, T, dtype=torch.int16, device=dev)
+    kp = torch.empty(L, U, S, T, dtype=dt, device=dev)
+    out = torch.empty(L, B * N_q, D, dtype=dt, device=dev)
+    kt = torch.zeros(L, U, max(cap, 1), D, dtype=dt, device=dev)
+    vt = torch.zeros_like(kt)
+    shape_all = thk.make_shape(L, B, N_q, N_kv, D, S, S_obs, T, 0, tdt, 0)
+    shape_1 = thk.make_shape(1, B, N_q, N_kv, D, S, S_obs, T, 0, tdt, 0)
+    ws = torch.empty(max(thk.thk_workspace_bytes(shape_all, thk.THK_OP_PRUNE),
+                         thk.thk_workspace_bytes(shape_1, thk.THK_OP_DECODE), 16), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def step(rec=None):
+        """Whole hot path once.  rec: list receiving (name, start_event, end_event)."""
+        a = ev(); a.record()
+        thk.thk_prune(shape_all, q_obs, k, score, idx, kp, ws)
+        b = ev(); b.record()
+        if rec is not None:
+            rec.append(("prune", a, b))
+        for s in range(steps_per_layer):
+            for l in range(L):
+                q, k_new, v_new = dec[l][s]
+                if cap:
+                    thk.thk_tail_append(shape_1, k_new, v_new, kt[l], vt[l], s, cap)
+                c = ev(); c.record()
+                thk.thk_decode_attn(shape_1, q, kp[l], idx[l * U:(l + 1) * U], v[l],
+                                    kt[l] if cap else None, vt[l] if cap else None,
+                                    s + 1 if cap else 0, cap, out[l], ws)
+                d = ev(); d.record()
+                if rec is not None:
+                    rec.append(("decode", c, d))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    recs = []
+    t0 = time.perf_counter()
+    e0 = ev(); e0.record()
+    for _ in range(args.steps):
+        step(recs)
+    e1 = ev(); e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    prune_ms = [a.elapsed_time(b) for n, a, b in recs if n == "prune"]
+    dec_us = [a.elapsed_time(b) * 1e3 for n, a, b in recs if n == "decode"]
+    prune_ms_layer = sum(prune_ms) / len(prune_ms) / L
+    dec_us_step = sum(dec_us) / len(dec_us)
+
+    # ---- algorithmic bytes (per layer), K and V counted once per KV head -----
+    qobs_bytes = B * N_q * S_obs * D * eb
+    prune_bytes = U * S * eb * (D + 2 * T) + qobs_bytes
+    mean_tail = (steps_per_layer + 1) / 2 if cap else 0
+    decode_bytes = U * eb * (S * (T + D) + mean_tail * 2 * D)
+    step_bytes = L * (prune_bytes + steps_per_layer * decode_bytes)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    prune_gbs = prune_bytes / (prune_ms_layer * 1e-3) / 1e9
+    dec_gbs = decode_bytes / (dec_us_step * 1e-6) / 1e9
+    # dominant kernel by time inside a step
+    if prune_ms_layer * L >= dec_us_step * 1e-3 * L * steps_per_layer:
+        roof = {"kernel": "thk_prune (k_colsum + k_finalize + k_compact_flat per group)",
+                "achieved": prune_gbs, "launch_us": prune_ms_layer * L * 1e3, "bytes_per_launch": prune_bytes * L}
+    else:
+        roof = {"kernel": "thk_decode_attn (k_decode + k_decode_merge)", "achieved": dec_gbs,
+                "launch_us": dec_us_step, "bytes_per_launch": decode_bytes}
+    roof.update({"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": roof["achieved"] / HBM_PEAK_GBS,
+                 "traffic": None})
+
+    res = {
+        "metric": "pruned-K decode attention us/step + achieved HBM GB/s; prune ms per layer",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": f"configs[{cfg_id - 1}]: L={L} B={B} N_q={N_q} N_kv={N_kv} D={D} S={S} "
+                               f"S_obs={S_obs} lambda={cfg['lam']} T={T} {cfg['dtype']}; prune all layers, "
+                               f"then {steps_per_layer} decode step(s) per layer",
+                   "step_bytes": step_bytes},
+        "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+        "prune_ms_per_layer": prune_ms_layer, "prune_GBps": prune_gbs, "prune_frac": prune_gbs / HBM_PEAK_GBS,
+        "decode_us_per_step": dec_us_step, "decode_GBps": dec_gbs, "decode_frac": dec_gbs / HBM_PEAK_GBS,
+        "host_wall_s": wall,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg_id, cfg, T, dev)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -105,6 +105,23 @@ def _stream(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
+def _need(x, n, name, where):
+    """Host-side guard: a tensor handed to a kernel must hold at least the n elements
+    the shape implies (a short tensor would make the kernel read or write out of bounds)."""
+    if x is None or isinstance(x, int):
+        return
+    if x.numel() < n:
+        raise ValueError(f"{where}: {name} holds {x.numel()} elements, the shape needs {n}")
+    if not x.is_contiguous():
+        raise ValueError(f"{where}: {name} must be contiguous")
+
+
+def _dims(s):
+    U = s.L * s.B * s.N_kv
+    H = s.L * s.B * s.N_q
+    return U, H, (s.ld_keep or s.T)
+
+
 def _check(st, where):
     if st != 0:
         raise ThkError(st, where)
@@ -131,38 +148,73 @@ def thk_default_split(shape, op):
 
 
 def thk_score(shape, q_obs, k, score, ws, stream=None):
+    U, H, _ = _dims(shape)
+    _need(q_obs, H * shape.S_obs * shape.D, "q_obs", "thk_score")
+    _need(k, U * shape.S * shape.D, "k", "thk_score")
+    _need(score, U * shape.D, "score", "thk_score")
     _check(load().thk_score(ctypes.byref(shape), _ptr(q_obs), _ptr(k), _ptr(score), _ws(ws),
                             _nbytes(ws), _stream(stream)), "thk_score")
 
 
 def thk_score_magnitude(shape, k, p, score, ws, stream=None):
+    U, _, _ = _dims(shape)
+    _need(k, U * shape.S * shape.D, "k", "thk_score_magnitude")
+    _need(score, U * shape.D, "score", "thk_score_magnitude")
     _check(load().thk_score_magnitude(ctypes.byref(shape), _ptr(k), p, _ptr(score), _ws(ws),
                                       _nbytes(ws), _stream(stream)), "thk_score_magnitude")
 
 
 def thk_select_topk(shape, score, idx, stream=None):
+    U, _, _ = _dims(shape)
+    _need(score, U * shape.D, "score", "thk_select_topk")
+    _need(idx, U * shape.T, "idx", "thk_select_topk")
     _check(load().thk_select_topk(ctypes.byref(shape), _ptr(score), _ptr(idx), _stream(stream)),
            "thk_select_topk")
 
 
 def thk_compact_keys(shape, k, idx, k_pruned, stream=None):
+    U, _, ld = _dims(shape)
+    _need(k, U * shape.S * shape.D, "k", "thk_compact_keys")
+    _need(idx, U * shape.T, "idx", "thk_compact_keys")
+    _need(k_pruned, U * shape.S * ld, "k_pruned", "thk_compact_keys")
     _check(load().thk_compact_keys(ctypes.byref(shape), _ptr(k), _ptr(idx), _ptr(k_pruned),
                                    _stream(stream)), "thk_compact_keys")
 
 
 def thk_prune(shape, q_obs, k, score, idx, k_pruned, ws, stream=None):
+    U, H, ld = _dims(shape)
+    _need(q_obs, H * shape.S_obs * shape.D, "q_obs", "thk_prune")
+    _need(k, U * shape.S * shape.D, "k", "thk_prune")
+    _need(score, U * shape.D, "score", "thk_prune")
+    _need(idx, U * shape.T, "idx", "thk_prune")
+    _need(k_pruned, U * shape.S * ld, "k_pruned", "thk_prune")
     _check(load().thk_prune(ctypes.byref(shape), _ptr(q_obs), _ptr(k), _ptr(score), _ptr(idx),
                             _ptr(k_pruned), _ws(ws), _nbytes(ws), _stream(stream)), "thk_prune")
 
 
 def thk_decode_attn(shape, q, k_pruned, idx, v, k_tail, v_tail, s_tail, s_tail_cap, out, ws,
                     stream=None):
+    U, H, ld = _dims(shape)
+    w = "thk_decode_attn"
+    _need(q, H * shape.D, "q", w)
+    _need(out, H * shape.D, "out", w)
+    _need(k_pruned, U * shape.S * ld, "k_pruned", w)
+    _need(idx, U * shape.T, "idx", w)
+    _need(v, U * shape.S * shape.D, "v", w)
+    if s_tail > 0:
+        _need(k_tail, U * s_tail_cap * shape.D, "k_tail", w)
+        _need(v_tail, U * s_tail_cap * shape.D, "v_tail", w)
     _check(load().thk_decode_attn(ctypes.byref(shape), _ptr(q), _ptr(k_pruned), _ptr(idx), _ptr(v),
                                   _ptr(k_tail), _ptr(v_tail), s_tail, s_tail_cap, _ptr(out),
                                   _ws(ws), _nbytes(ws), _stream(stream)), "thk_decode_attn")
 
 
 def thk_tail_append(shape, k_new, v_new, k_tail, v_tail, s_tail, s_tail_cap, stream=None):
+    U, _, _ = _dims(shape)
+    _need(k_new, U * shape.D, "k_new", "thk_tail_append")
+    _need(v_new, U * shape.D, "v_new", "thk_tail_append")
+    _need(k_tail, U * s_tail_cap * shape.D, "k_tail", "thk_tail_append")
+    _need(v_tail, U * s_tail_cap * shape.D, "v_tail", "thk_tail_append")
     _check(load().thk_tail_append(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(k_tail),
                                   _ptr(v_tail), s_tail, s_tail_cap, _stream(stream)),
            "thk_tail_append")

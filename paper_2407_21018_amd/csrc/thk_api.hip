@@ -39,8 +39,8 @@ struct Split { int n; int64_t rows; };
 Split score_split(const thk_shape *s, int64_t units) {
   int n = s->n_split;
   if (n == 0) {
-    // aim at ~16 blocks per compute unit over the call, pieces of >= 256 rows
-    n = (int)ceil_div((int64_t)kCUs * 16, units);
+    // aim at ~8 blocks per compute unit over the call, pieces of >= 256 rows
+    n = (int)ceil_div((int64_t)kCUs * 8, units);
     const int64_t cap = ceil_div(s->S, 256);
     if (n > cap) n = (int)cap;
     if (n > kMaxSplit) n = kMaxSplit;

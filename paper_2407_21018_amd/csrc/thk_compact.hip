@@ -46,17 +46,14 @@ __global__ __launch_bounds__(256) void k_compact_flat(const void *__restrict__ k
 
   for (int64_t r0 = s0 + (int64_t)wave * TR; r0 < s1; r0 += 4 * TR) {
     const int nr = (int)min((int64_t)TR, s1 - r0);
+    // rows past the end of a ragged last tile re-read its last row (kept in bounds, never gathered)
     uint4 r[NLD];
+    const uint4 *tsrc = src + (size_t)r0 * CPR;
+    const int cmax = nr * CPR - 1;
 #pragma unroll
-    for (int j = 0; j < NLD; ++j) {
-      const int c = j * kWave + lane;
-      if (c / CPR < nr) r[j] = src[(size_t)r0 * CPR + c];
-    }
+    for (int j = 0; j < NLD; ++j) r[j] = tsrc[min(j * kWave + lane, cmax)];
 #pragma unroll
-    for (int j = 0; j < NLD; ++j) {
-      const int c = j * kWave + lane;
-      if (c / CPR < nr) tile[c] = r[j];
-    }
+    for (int j = 0; j < NLD; ++j) tile[j * kWave + lane] = r[j];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");

@@ -129,43 +129,111 @@ __global__ __launch_bounds__(256) void k_select(const float *__restrict__ score,
 }
 
 // ---------------------------------------------------------------------------
-// One 128-thread block per unit, thread c owns channel c.
+// One 512-thread block per unit.
+//   1. split merge: thread (sg, c) adds the partial sums of splits sg, sg+4, ..
+//      for channel c; the four strands are added in fixed order.
+//   2. query norms: the unit's G heads hold G * S_obs contiguous rows of Q_obs;
+//      heads are taken four at a time, each thread squares (in fp64) the VEC
+//      channels it owns over the rows of its row group, row groups are folded
+//      by shuffles inside a wave and through LDS across the 8 waves.
+//   3. threads 0..127 form the score of their channel; wave 0 may select.
+// All sums run in a fixed order, so repeated calls give identical bits.
 // ---------------------------------------------------------------------------
+constexpr int kFinThreads = 512;
+
 template <int DT>
-__global__ __launch_bounds__(128) void k_finalize(int mode, const double *__restrict__ partial,
-                                                  const void *__restrict__ q_obs,
-                                                  float *__restrict__ score,
-                                                  int16_t *__restrict__ idx, int G,
-                                                  int S_obs, int n_split, int T) {
+__global__ __launch_bounds__(kFinThreads) void k_finalize(int mode, const double *__restrict__ partial,
+                                                          const void *__restrict__ q_obs,
+                                                          float *__restrict__ score,
+                                                          int16_t *__restrict__ idx, int G,
+                                                          int S_obs, int n_split, int T) {
   using E = Elem<DT>;
-  const int c = threadIdx.x;
+  constexpr int VEC = E::VEC, LPR = kD / VEC, RG = kFinThreads / LPR, NW = kFinThreads / kWave;
+  constexpr int GC = 4;   // heads per pass
+  __shared__ double red[GC][NW][kD];
+  __shared__ float s_sc[kD];
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int64_t u = blockIdx.x;
-  double kacc = 0.0;
-  for (int sp = 0; sp < n_split; ++sp) kacc += partial[((size_t)u * n_split + sp) * kD + c];
-  double sc;
-  if (mode == 0) {
-    // unit u = (layer*batch, KV head h) reads query heads u * G .. u * G + G - 1
-    double tot = 0.0;
-    for (int g = 0; g < G; ++g) {
-      const size_t qb = ((size_t)(u * G + g) * S_obs) * kD;
-      double qss = 0.0;
-      for (int i = 0; i < S_obs; ++i) {
-        const double x = (double)E::load1(q_obs, qb + (size_t)i * kD + c);
-        qss += x * x;
-      }
-      tot += sqrt(qss);
+
+  // ---- 1. split merge ----------------------------------------------------
+  {
+    const int c = tid % kD, sg = tid / kD;
+    const double *p = partial + (size_t)u * n_split * kD + c;
+    double a = 0.0;
+    int sp = sg;
+    for (; sp + 12 < n_split; sp += 16) {
+      const double x0 = p[(size_t)sp * kD], x1 = p[(size_t)(sp + 4) * kD];
+      const double x2 = p[(size_t)(sp + 8) * kD], x3 = p[(size_t)(sp + 12) * kD];
+      a += x0; a += x1; a += x2; a += x3;
     }
-    sc = tot * sqrt(kacc);
-  } else {
-    sc = (mode == 1) ? kacc : sqrt(kacc);
+    for (; sp < n_split; sp += 4) a += p[(size_t)sp * kD];
+    red[0][sg][c] = a;
   }
-  const float scf = (float)sc;
-  score[(size_t)u * kD + c] = scf;
+  __syncthreads();
+  double kacc = 0.0;
+  if (tid < kD) kacc = ((red[0][0][tid] + red[0][1][tid]) + red[0][2][tid]) + red[0][3][tid];
+  __syncthreads();
+
+  // ---- 2. query norms ------------------------------------------------------
+  double tot = 0.0;
+  if (mode == 0) {
+    const int cl = tid % LPR, rg = tid / LPR;
+    // unit u = (layer*batch, KV head) reads query heads u * G .. u * G + G - 1
+    const uint4 *qbase = (const uint4 *)((const char *)q_obs + (size_t)u * G * S_obs * kD * E::EB);
+    for (int g0 = 0; g0 < G; g0 += GC) {
+      const int ng = min(GC, G - g0);
+      double qa[GC][VEC];
+#pragma unroll
+      for (int g = 0; g < GC; ++g)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) qa[g][v] = 0.0;
+      for (int i0 = 0; i0 < S_obs; i0 += RG) {
+        uint4 r[GC];
+        const int i = i0 + rg;
+#pragma unroll
+        for (int g = 0; g < GC; ++g)
+          r[g] = (g < ng && i < S_obs) ? qbase[((size_t)(g0 + g) * S_obs + i) * LPR + cl]
+                                       : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int g = 0; g < GC; ++g) {
+          float f[VEC];
+          E::unpack(r[g], f);
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) qa[g][v] += (double)f[v] * (double)f[v];
+        }
+      }
+#pragma unroll
+      for (int g = 0; g < GC; ++g) {
+#pragma unroll
+        for (int off = LPR; off < kWave; off <<= 1)
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) qa[g][v] += __shfl_xor(qa[g][v], off);
+        if (lane < LPR)
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) red[g][wave][lane * VEC + v] = qa[g][v];
+      }
+      __syncthreads();
+      if (tid < kD)
+        for (int g = 0; g < ng; ++g) {
+          double qss = 0.0;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) qss += red[g][w][tid];
+          tot += sqrt(qss);
+        }
+      __syncthreads();
+    }
+  }
+
+  // ---- 3. score, optional selection ----------------------------------------
+  if (tid < kD) {
+    const double sc = mode == 0 ? tot * sqrt(kacc) : (mode == 1 ? kacc : sqrt(kacc));
+    const float scf = (float)sc;
+    score[(size_t)u * kD + tid] = scf;
+    s_sc[tid] = scf;
+  }
   if (idx != nullptr) {
-    __shared__ float s_sc[kD];
-    s_sc[c] = scf;
     __syncthreads();
-    if (c < kWave) select_wave(s_sc[c], s_sc[c + 64], T, idx + (size_t)u * T, c);
+    if (tid < kWave) select_wave(s_sc[tid], s_sc[tid + 64], T, idx + (size_t)u * T, tid);
   }
 }
 
@@ -186,7 +254,7 @@ hipError_t launch_colsum(int dtype, const void *k, double *partial, int64_t U, i
 hipError_t launch_finalize(int dtype, int mode, const double *partial, const void *q_obs,
                            float *score, int16_t *idx, int64_t U, int G, int S_obs,
                            int n_split, int T, hipStream_t st) {
-  const dim3 grid((unsigned)U), block(128);
+  const dim3 grid((unsigned)U), block(kFinThreads);
   if (dtype == THK_BF16)
     hipLaunchKernelGGL((k_finalize<THK_BF16>), grid, block, 0, st, mode, partial, q_obs, score, idx, G, S_obs, n_split, T);
   else
