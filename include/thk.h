@@ -6,7 +6,10 @@
  *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library
  *     allocates nothing, frees nothing and never synchronises.  Work is enqueued
  *     on `stream` (a hipStream_t passed as void*; NULL = the default stream).
- *   - Base pointers must be 16-byte aligned (THK_ERR_ALIGN otherwise).
+ *   - Base pointers must be 16-byte aligned (THK_ERR_ALIGN otherwise), and the
+ *     16-byte granule that holds a tensor's last element must be readable to its
+ *     end (kernels load whole aligned granules; true of any hipMalloc'ed buffer
+ *     and of any sub-range of one).
  *   - Argument errors are reported synchronously and enqueue nothing.  A launch
  *     failure is reported as THK_ERR_HIP.
  *   - Dense row-major layouts, last index contiguous:

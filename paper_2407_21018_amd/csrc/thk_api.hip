@@ -58,8 +58,12 @@ Split decode_split(const thk_shape *s) {
   const int G = s->N_q / s->N_kv;
   const int64_t wgs = units_of(s) * (G / group_width(G));
   if (n == 0) {
-    // ~8 blocks per compute unit, pieces of whole 256-row block passes
-    n = (int)ceil_div((int64_t)kCUs * 8, wgs);
+    // about one resident set of blocks (4 per compute unit) over the call, a power of two
+    // pieces per unit, each at least 256 rows; big calls still get two pieces per unit so
+    // that the last blocks to finish are short
+    n = 1;
+    while ((int64_t)n * 2 * wgs <= (int64_t)kCUs * 4) n *= 2;
+    if (n == 1 && s->S >= 2048) n = 2;
     const int64_t cap = ceil_div(s->S, 256);
     if (n > cap) n = (int)cap;
     if (n > kMaxSplit) n = kMaxSplit;

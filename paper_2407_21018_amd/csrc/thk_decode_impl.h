@@ -1,0 +1,447 @@
+// Decode attention over the pruned key cache plus the unpruned tail
+// (Sec. 3.3, Fig. 2; attention formula of Sec. 3.2) -- gfx950, wave64.
+// Template body shared by the per-(dtype, group width) translation units.
+//
+// Work split.  A 256-thread block serves one (unit, query-head group, S-split):
+// GT query heads that read the same KV head share every K and V byte the block
+// streams.  Its four wavefronts work independently on tiles of TR rows, each
+// with its own running softmax state (max, sum, acc[128]); the states are merged
+// once at the end through LDS.  With n_split > 1 the block writes its state to
+// the workspace and k_decode_merge combines the splits in index order.
+//
+// One tile, one wavefront.
+//   K_pruned rows are T elements long and in general not 16-byte multiples, but
+//   a run of whole rows is a flat byte range.  The range, widened to 16-byte
+//   boundaries, is fetched with coalesced 16-byte loads into registers (the
+//   next tile's range is in flight while the current tile is computed) and
+//   mirrored into the wave's LDS slab.  LPK = 64 / TR lanes then walk one row
+//   out of LDS, each taking a contiguous share of its channels, so the q.K dot
+//   product needs at most one neighbour exchange.  V rows are 128 elements:
+//   they go straight into registers, 16 bytes per lane, each lane accumulating
+//   its VEC output channels over the rows it sees.  The tile's probabilities
+//   travel from the row layout to the V layout through a TR-float LDS line per
+//   query head.
+#pragma once
+#include <math.h>
+
+#include "thk_internal.h"
+
+namespace thk {
+
+constexpr int kTailRows = 16;   // rows per tile in the full-width tail segment
+constexpr int kQS = kD + 8;     // floats per query vector in LDS: 128 channels + 8 zeros
+
+__device__ inline void wave_sync_lds() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Cross-lane reductions over the 64 lanes with DPP row shifts and row
+// broadcasts: after the four row_shr steps lane 15 of every 16-lane row holds
+// the row's result, row_bcast:15 folds rows 0->1 and 2->3, row_bcast:31 folds
+// the lower half into rows 2 and 3, and lane 63 holds the total.
+template <int CTRL, int ROW_MASK>
+__device__ inline float dpp_move(float identity, float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(x), CTRL,
+                                                    ROW_MASK, 0xf, false));
+}
+__device__ inline float wave_max(float x) {
+  const float id = -INFINITY;
+  x = fmaxf(x, dpp_move<0x111, 0xf>(id, x));   // row_shr:1
+  x = fmaxf(x, dpp_move<0x112, 0xf>(id, x));   // row_shr:2
+  x = fmaxf(x, dpp_move<0x114, 0xf>(id, x));   // row_shr:4
+  x = fmaxf(x, dpp_move<0x118, 0xf>(id, x));   // row_shr:8
+  x = fmaxf(x, dpp_move<0x142, 0xa>(id, x));   // row_bcast:15 into rows 1, 3
+  x = fmaxf(x, dpp_move<0x143, 0xc>(id, x));   // row_bcast:31 into rows 2, 3
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+__device__ inline float wave_sum(float x) {
+  x += dpp_move<0x111, 0xf>(0.f, x);
+  x += dpp_move<0x112, 0xf>(0.f, x);
+  x += dpp_move<0x114, 0xf>(0.f, x);
+  x += dpp_move<0x118, 0xf>(0.f, x);
+  x += dpp_move<0x142, 0xa>(0.f, x);
+  x += dpp_move<0x143, 0xc>(0.f, x);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+// value of the neighbouring lane (lane ^ 1): quad_perm [1,0,3,2]
+__device__ inline float lane_swap1(float x) { return dpp_move<0xB1, 0xf>(0.f, x); }
+
+// RA bytes of an LDS row at element offset t, widened to floats.
+template <int DT, int RA>
+__device__ inline void lds_row_read(const char *rowp, int t, float *f) {
+  using E = Elem<DT>;
+  const char *p = rowp + (size_t)t * E::EB;
+  if constexpr (DT == THK_BF16) {
+    if constexpr (RA == 16) {
+      float g[8]; E::unpack(*(const uint4 *)p, g);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) f[i] = g[i];
+    } else if constexpr (RA == 8) {
+      const uint2 r = *(const uint2 *)p;
+      f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+      f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+    } else if constexpr (RA == 4) {
+      const uint32_t r = *(const uint32_t *)p;
+      f[0] = __uint_as_float(r << 16); f[1] = __uint_as_float(r & 0xffff0000u);
+    } else {
+      f[0] = __uint_as_float((uint32_t) * (const uint16_t *)p << 16);
+    }
+  } else {
+    if constexpr (RA == 16) {
+      const float4 r = *(const float4 *)p; f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w;
+    } else if constexpr (RA == 8) {
+      const float2 r = *(const float2 *)p; f[0] = r.x; f[1] = r.y;
+    } else {
+      f[0] = *(const float *)p;
+    }
+  }
+}
+
+template <int DT, int GT>
+struct TileState {
+  float m[GT];                       // running max (log2 domain)
+  float l[GT];                       // per-lane partial sum of probabilities
+  float acc[GT][Elem<DT>::VEC];      // per-lane partial output channels
+};
+
+// Issue the global loads of a tile of `nrows` rows, W elements wide with row
+// stride ld (elements), starting at byte kbeg of tensor kg.  The range is
+// widened to 16-byte boundaries, so up to 15 bytes before the first row and
+// after the last row are read as well: before is always inside the tensor (its
+// base is 16-byte aligned); after can pass the tensor's last element by less
+// than 16 bytes, inside the 16-byte granule that holds it (the API requires
+// that granule to be readable).  Chunk indices past the range are clamped to
+// its last chunk: no lane is predicated off, and the duplicates land in LDS
+// slots that no row read touches.
+// kr receives KB chunks per lane (the tile's K bytes staged in registers);
+// returns the byte distance between the widened start and the first row.
+template <int DT, int KB>
+__device__ __forceinline__ int k_issue(u32x4 (&kr)[KB], const char *__restrict__ kg, size_t kbeg,
+                                       int nrows, int W, int ld, int lane) {
+  constexpr int EB = Elem<DT>::EB;
+  const size_t kend = kbeg + ((size_t)(nrows - 1) * ld + W) * EB;
+  const size_t a0 = kbeg & ~(size_t)15;
+  const int last = (int)((kend - a0 + 15) >> 4) - 1;
+  const char *p = kg + a0;
+#pragma unroll
+  for (int j = 0; j < KB; ++j) kr[j] = *(const u32x4 *)(p + (size_t)min(j * kWave + lane, last) * 16);
+  return (int)(kbeg - a0);
+}
+
+template <int KB>
+__device__ __forceinline__ void k_commit(const u32x4 (&kr)[KB], char *kbuf, int lane) {
+#pragma unroll
+  for (int j = 0; j < KB; ++j) ((u32x4 *)kbuf)[j * kWave + lane] = kr[j];   // kbuf holds KB * 64 chunks
+}
+
+// Shape of the value loads of one TR-row tile: NV wave-wide loads per batch.
+template <int DT, int TR>
+struct VShape {
+  static constexpr int LPR = kD / Elem<DT>::VEC;     // lanes (16-byte chunks) per V row
+  static constexpr int RPL = kWave / LPR;            // V rows per wave-wide load
+  static constexpr int NL = TR / RPL;                // loads per lane per tile
+  static constexpr int NV = NL < 16 ? NL : 16;       // loads per lane per batch
+  static constexpr int NB = NL / NV;                 // batches per tile
+};
+
+// Batch b of a tile's value rows into registers.  Rows past a ragged tile's end
+// re-read its last row: their probability is 0.
+template <int DT, int TR, int NV>
+__device__ __forceinline__ void v_issue(u32x4 (&vr)[NV], const u32x4 *__restrict__ vg,
+                                        int nrows, int b, int lane) {
+  using VS = VShape<DT, TR>;
+  if (nrows == TR) {
+#pragma unroll
+    for (int i = 0; i < VS::NV; ++i) vr[i] = vg[(size_t)(b * VS::NV + i) * kWave + lane];
+  } else {
+    const int vrow = lane / VS::LPR, vcol = lane % VS::LPR;
+#pragma unroll
+    for (int i = 0; i < VS::NV; ++i)
+      vr[i] = vg[(size_t)min((b * VS::NV + i) * VS::RPL + vrow, nrows - 1) * VS::LPR + vcol];
+  }
+}
+
+// One tile whose K bytes are already in LDS (kbuf): logits, running softmax,
+// acc += p.V.  vg: the tile's value rows (16-byte chunks, 128 elements per row).
+// qs: [GT][kQS] floats, entries 128..135 of every vector are zero.
+template <int DT, int GT, int RA, int TR, int NV>
+__device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld,
+                                             const float *__restrict__ qs,
+                                             const u32x4 *__restrict__ vg,
+                                             u32x4 (&vr)[NV], const char *kbuf,
+                                             float *ps, TileState<DT, GT> &st, float scale, int lane) {
+  using E = Elem<DT>;
+  using VS = VShape<DT, TR>;
+  constexpr int VEC = E::VEC, EB = E::EB;
+  constexpr int LPK = kWave / TR;            // lanes that share one K row (1 or 2)
+  constexpr int EPR = RA / EB;               // elements per LDS row read (one granule)
+  const int vrow = lane / VS::LPR;
+  const int r = lane / LPK, h = lane % LPK;
+
+  // ---- logits: LPK lanes per row, contiguous granule ranges ----------------
+  const int rr = min(r, nrows - 1);
+  const char *rowp = kbuf + shift + (size_t)rr * ld * EB;
+  const int n_gran = W / EPR;
+  const int gran0 = (n_gran + LPK - 1) / LPK;              // granules of lane share 0 = trip count
+  const int my_first = h * gran0;
+  const int my_cnt = (LPK == 1 || h == 0) ? gran0 : n_gran - gran0;
+  float z[GT];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) z[g] = 0.f;
+#pragma unroll 2
+  for (int i = 0; i < gran0; ++i) {
+    // a lane whose share is exhausted re-reads granule 0 against the zero slot of q
+    const bool valid = (LPK == 1) || i < my_cnt;
+    const int tk = valid ? (my_first + i) * EPR : 0;
+    const int tq = valid ? tk : kD;
+    float f[EPR];
+    lds_row_read<DT, RA>(rowp, tk, f);
+#pragma unroll
+    for (int g = 0; g < GT; ++g)
+#pragma unroll
+      for (int e = 0; e < EPR; ++e) z[g] = fmaf(f[e], qs[g * kQS + tq + e], z[g]);
+  }
+  for (int t = n_gran * EPR; t < W; ++t) {   // elements past the last whole granule: share 0
+    const float f = E::load1(rowp, t);
+    const int tq = (LPK == 1 || h == 0) ? t : kD;
+#pragma unroll
+    for (int g = 0; g < GT; ++g) z[g] = fmaf(f, qs[g * kQS + tq], z[g]);
+  }
+  if constexpr (LPK == 2) {
+#pragma unroll
+    for (int g = 0; g < GT; ++g) z[g] += lane_swap1(z[g]);
+  }
+
+  // ---- running softmax (base-2 exponent, scale folded in) ----------------
+  // every row is held by LPK lanes, so l counts each probability LPK times
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    const float zz = r < nrows ? z[g] * scale : -INFINITY;
+    const float m_new = fmaxf(st.m[g], wave_max(zz));   // finite: the tile has >= 1 row
+    const float corr = exp2f(st.m[g] - m_new);
+    const float p = exp2f(zz - m_new);
+    st.l[g] = st.l[g] * corr + p;
+    st.m[g] = m_new;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) st.acc[g][v] *= corr;
+    ps[g * TR + r] = p;
+  }
+  wave_sync_lds();
+
+  // ---- acc += p . V --------------------------------------------------------
+#pragma unroll
+  for (int b = 0; b < VS::NB; ++b) {
+#pragma unroll
+    for (int i = 0; i < VS::NV; ++i) {
+      const int row = (b * VS::NV + i) * VS::RPL + vrow;
+      float f[VEC];
+      E::unpack(vr[i], f);
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        const float p = ps[g * TR + row];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) st.acc[g][v] = fmaf(p, f[v], st.acc[g][v]);
+      }
+    }
+    if (b + 1 < VS::NB) v_issue<DT, TR, NV>(vr, vg, nrows, b + 1, lane);
+  }
+  wave_sync_lds();   // ps and kbuf are rewritten by the next tile
+}
+
+// KB: 16-byte K chunks a lane may have to stage for one TR-row pruned tile.
+// WPE: resident waves per SIMD the register budget is set for.
+template <int DT, int GT, int RA, int KB, int TR, int WPE>
+__global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, int kbuf_bytes) {
+  using E = Elem<DT>;
+  using VS = VShape<DT, TR>;
+  constexpr int VEC = E::VEC, EB = E::EB, LPR = VS::LPR, LPK = kWave / TR;
+  constexpr int KBT = kTailRows * kD * EB / 16 / kWave;   // chunks per lane of a tail tile
+  extern __shared__ uint4 smem[];
+  float *qk = (float *)smem;                 // [GT][kQS] gathered query channels, 0 beyond T
+  float *qf = qk + GT * kQS;                 // [GT][kQS] full query
+  float *mrg = qf + GT * kQS;                // [4][GT][130] per-wave states for the final merge
+  char *wbase = (char *)(mrg + 4 * GT * (kD + 2));
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int wstride = kbuf_bytes + GT * TR * 4;
+  char *kbuf = wbase + (size_t)wave * wstride;
+  float *ps = (float *)(kbuf + kbuf_bytes);
+
+  const int sp = (int)(blockIdx.x % a.n_split);
+  const int64_t ug = blockIdx.x / a.n_split;
+  const int gi = (int)(ug % groups);
+  const int64_t u = ug / groups;             // (layer, batch, KV head)
+  const int G = a.N_q / a.N_kv;
+  const int64_t bn0 = u * G + (int64_t)gi * GT;   // first query head served (heads of unit u: u*G ..)
+
+  const int64_t s0 = min(a.S, (int64_t)sp * a.rows_per_split);
+  const int64_t s1 = min(a.S, s0 + a.rows_per_split);
+  const int nt_p = (int)((s1 - s0 + TR - 1) / TR);
+  const int nt_t = (sp == a.n_split - 1) ? (a.s_tail + kTailRows - 1) / kTailRows : 0;
+  const char *kpg = (const char *)a.kp;
+
+  constexpr int NV = VS::NV;
+  const size_t krow0 = (size_t)u * a.S + s0;             // first K_pruned / V row of this block
+  const u32x4 *vbase = (const u32x4 *)a.v + krow0 * LPR;
+
+  // the first tile's key and value bytes start moving before anything else happens
+  u32x4 kr[KB];
+  u32x4 vr[NV];
+  int shift_next = 0;
+  if (wave < nt_p) {
+    const int nr = (int)min((int64_t)TR, s1 - s0 - (int64_t)wave * TR);
+    shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)wave * TR) * a.ldk * EB, nr, a.T, a.ldk, lane);
+    v_issue<DT, TR, NV>(vr, vbase + (size_t)wave * TR * LPR, nr, 0, lane);
+  }
+
+  // query: gather the kept channels (Sec. 3.3: the query is pruned with the stored mask)
+  const int16_t *uidx = a.idx + (size_t)u * a.T;
+  for (int o = tid; o < GT * kQS; o += 256) {
+    const int g = o / kQS, c = o % kQS;
+    const size_t qb = (size_t)(bn0 + g) * kD;
+    qf[o] = c < kD ? E::load1(a.q, qb + c) : 0.f;
+    qk[o] = c < a.T ? E::load1(a.q, qb + uidx[c]) : 0.f;
+  }
+  __syncthreads();
+
+  TileState<DT, GT> st;
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    st.m[g] = -INFINITY; st.l[g] = 0.f;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) st.acc[g][v] = 0.f;
+  }
+
+  // ---- pruned segment: the K bytes of this wave's next tile are in flight while
+  // the current one is computed
+  for (int ti = wave; ti < nt_p; ti += 4) {
+    const int nrows = (int)min((int64_t)TR, s1 - s0 - (int64_t)ti * TR);
+    const u32x4 *vg = vbase + (size_t)ti * TR * LPR;
+    const int shift = shift_next;
+    k_commit<KB>(kr, kbuf, lane);
+    if (ti != wave) v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
+    if (ti + 4 < nt_p) {
+      const int nr = (int)min((int64_t)TR, s1 - s0 - (int64_t)(ti + 4) * TR);
+      shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)(ti + 4) * TR) * a.ldk * EB, nr, a.T, a.ldk, lane);
+    }
+    wave_sync_lds();
+    tile_compute<DT, GT, RA, TR, NV>(shift, nrows, a.T, a.ldk, qk, vg, vr, kbuf, ps, st, a.scale_log2, lane);
+  }
+
+  // ---- unpruned tail segment (full-width keys, full query) ------------------
+  for (int ti = wave; ti < nt_t; ti += 4) {
+    const int j0 = ti * kTailRows;
+    const int nrows = min(kTailRows, a.s_tail - j0);
+    const size_t row0 = (size_t)u * a.s_tail_cap + j0;
+    u32x4 kt[KBT];
+    k_issue<DT, KBT>(kt, (const char *)a.kt, row0 * kD * EB, nrows, kD, kD, lane);
+    const u32x4 *vg = (const u32x4 *)a.vt + row0 * LPR;
+    v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
+    k_commit<KBT>(kt, kbuf, lane);
+    wave_sync_lds();
+    tile_compute<DT, GT, 16, TR, NV>(0, nrows, kD, kD, qf, vg, vr, kbuf, ps, st, a.scale_log2, lane);
+  }
+
+  // ---- wave state -> LDS ---------------------------------------------------
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    const float lt = wave_sum(st.l[g]) * (1.0f / LPK);
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) st.acc[g][v] += __shfl_xor(st.acc[g][v], off);
+    float *rec = mrg + (size_t)(wave * GT + g) * (kD + 2);
+    if (lane == 0) { rec[0] = st.m[g]; rec[1] = lt; }
+    if (lane < LPR)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) rec[2 + lane * VEC + v] = st.acc[g][v];
+  }
+  __syncthreads();
+
+  // ---- merge the four waves; write the output or this split's state --------
+  for (int o = tid; o < GT * kD; o += 256) {
+    const int g = o / kD, c = o % kD;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, mrg[(size_t)(w * GT + g) * (kD + 2)]);
+    float Lsum = 0.f, A = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float *rec = mrg + (size_t)(w * GT + g) * (kD + 2);
+      const float wgt = rec[0] == -INFINITY ? 0.f : exp2f(rec[0] - M);
+      Lsum = fmaf(rec[1], wgt, Lsum);
+      A = fmaf(rec[2 + c], wgt, A);
+    }
+    const size_t bn = (size_t)(bn0 + g);
+    if (a.n_split == 1) {
+      E::store1(a.out, bn * kD + c, A / Lsum);
+    } else {
+      float *rec = a.ws + (bn * a.n_split + sp) * (kD + 2);
+      rec[2 + c] = A;
+      if (c == 0) { rec[0] = M; rec[1] = Lsum; }
+    }
+  }
+}
+
+// ---- host side: pick the instantiation for a shape --------------------------
+struct DecodeLaunch {
+  int ra;      // byte alignment of K_pruned rows (16, 8, 4, 2)
+  int kb;      // staged chunks per lane needed for one tile
+};
+
+template <int DT>
+inline DecodeLaunch decode_launch_params(const DecodeArgs &a, int tr) {
+  constexpr int eb = Elem<DT>::EB;
+  DecodeLaunch p;
+  // every row starts at a multiple of ld * eb bytes from the 16-byte aligned base
+  const size_t rowb = (size_t)a.ldk * eb;
+  p.ra = 16;
+  while (rowb % p.ra) p.ra >>= 1;
+  const int max_nch = (int)((tr * rowb + (p.ra == 16 ? 0 : 14) + 15) / 16);
+  p.kb = (max_nch + kWave - 1) / kWave;
+  return p;
+}
+
+template <int DT, int GT, int RA, int KB, int TR, int WPE>
+inline hipError_t decode_launch_one(const DecodeArgs &a, int groups, hipStream_t st) {
+  constexpr int eb = Elem<DT>::EB;
+  int kbuf = KB * kWave * 16;                      // every staged chunk has an LDS slot
+  const int tailbuf = kTailRows * kD * eb;
+  if (kbuf < tailbuf) kbuf = tailbuf;
+  const size_t lds = (size_t)(2 * GT * kQS + 4 * GT * (kD + 2)) * 4 + 4 * ((size_t)kbuf + GT * TR * 4);
+  const dim3 grid((unsigned)(a.units * groups * a.n_split)), block(256);
+  if (lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void *)k_decode<DT, GT, RA, KB, TR, WPE>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k_decode<DT, GT, RA, KB, TR, WPE>), grid, block, lds, st, a, groups, kbuf);
+  return hipGetLastError();
+}
+
+template <int DT, int GT, int KB, int TR, int WPE>
+inline hipError_t decode_launch_ra(const DecodeArgs &a, int ra, int groups, hipStream_t st) {
+  if (ra == 16) return decode_launch_one<DT, GT, 16, KB, TR, WPE>(a, groups, st);
+  if (ra == 8) return decode_launch_one<DT, GT, 8, KB, TR, WPE>(a, groups, st);
+  if (ra == 4) return decode_launch_one<DT, GT, 4, KB, TR, WPE>(a, groups, st);
+  if constexpr (DT == THK_BF16) {
+    if (ra == 2) return decode_launch_one<DT, GT, 2, KB, TR, WPE>(a, groups, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+// Tiles of 32 rows: two lanes share a key row, waves stay light (4 per SIMD when
+// K staging is narrow and at most two query heads share the block, else 3).
+template <int DT, int GT>
+hipError_t decode_launch_gt(const DecodeArgs &a, int groups, hipStream_t st) {
+  constexpr int TR = 32;
+  const DecodeLaunch p = decode_launch_params<DT>(a, TR);
+  constexpr int KBN = (DT == THK_BF16) ? 5 : 10;   // T <= 79
+  constexpr int KBW = (DT == THK_BF16) ? 9 : 17;   // up to ld_keep = 128
+  if (p.kb <= KBN) return decode_launch_ra<DT, GT, KBN, TR, (GT <= 2 ? 4 : 3)>(a, p.ra, groups, st);
+  if (p.kb <= KBW) return decode_launch_ra<DT, GT, KBW, TR, 3>(a, p.ra, groups, st);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace thk

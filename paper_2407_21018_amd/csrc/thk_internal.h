@@ -11,12 +11,16 @@ constexpr int kD = 128;     // channels per head (the only size built)
 constexpr int kWave = 64;   // wavefront width on CDNA4
 constexpr int kCUs = 256;   // compute units of an MI355X
 
+// 16 bytes as a native vector: register arrays of this type are promoted to VGPRs reliably
+// (arrays of the uint4 class type are copied member-wise through memcpy and can end up in scratch).
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 // ---- element access ------------------------------------------------------
 // A 16-byte chunk holds VEC elements; unpack() widens them to float exactly.
 template <int DT> struct Elem;
 template <> struct Elem<THK_F32> {
   static constexpr int EB = 4, VEC = 4;
-  __device__ static inline void unpack(const uint4 &r, float (&f)[4]) {
+  template <class V4> __device__ static inline void unpack(const V4 &r, float (&f)[4]) {
     f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
     f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
   }
@@ -25,7 +29,7 @@ template <> struct Elem<THK_F32> {
 };
 template <> struct Elem<THK_BF16> {
   static constexpr int EB = 2, VEC = 8;
-  __device__ static inline void unpack(const uint4 &r, float (&f)[8]) {
+  template <class V4> __device__ static inline void unpack(const V4 &r, float (&f)[8]) {
     f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
     f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
     f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
