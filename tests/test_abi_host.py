@@ -1,0 +1,115 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2407_21018_amd as thk
+from oracle import oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+A = 4096      # a 16-byte aligned fake device address (never dereferenced on these paths)
+BIG = 1 << 40
+
+
+def _declared():
+    hdr = open(os.path.join(ROOT, "include", "thk.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    return sorted(set(re.findall(r"\b(thk_[a-z_]+)\s*\(", hdr)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(thk.lib_path())
+    names = _declared()
+    assert {"thk_score", "thk_select_topk", "thk_compact_keys", "thk_decode_attn", "thk_prune",
+            "thk_tail_append", "thk_workspace_bytes", "thk_keep_count"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in thk.h but not exported"
+
+
+def test_binding_has_the_same_names():
+    for n in _declared():
+        assert hasattr(thk, n), f"binding lacks {n}"
+
+
+def test_keep_count_matches_oracle():
+    for D in (8, 64, 128):
+        for lam in (0.0, 0.1, 0.25, 0.3, 0.4, 0.5, 0.6, 0.75, 0.9, 0.99):
+            assert thk.thk_keep_count(D, lam) == O.keep_count(D, lam)
+    assert thk.thk_keep_count(128, 1.0) == -1 and thk.thk_keep_count(0, 0.5) == -1
+
+
+def _shape(**kw):
+    d = dict(L=1, B=2, N_q=8, N_kv=2, D=128, S=1000, S_obs=32, T=64, ld_keep=0, dtype=thk.THK_BF16, n_split=0)
+    d.update(kw)
+    return thk.make_shape(**d)
+
+
+def _status(fn, *a, **k):
+    try:
+        fn(*a, **k)
+    except thk.ThkError as e:
+        return e.status
+    return 0
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(N_q=7), 2), (dict(T=0), 2), (dict(T=129), 2), (dict(S=0), 2), (dict(S_obs=0), 2),
+    (dict(S_obs=1001), 2), (dict(ld_keep=63), 2), (dict(n_split=-1), 2), (dict(n_split=5000), 2),
+    (dict(B=0), 2), (dict(D=64, T=32), 3), (dict(dtype=7), 3),
+])
+def test_bad_shapes_are_rejected_before_launch(kw, want):
+    s = _shape(**kw)
+    assert _status(thk.thk_score, s, A, A, A, (A, BIG), stream=0) == want
+    assert _status(thk.thk_prune, s, A, A, A, A, A, (A, BIG), stream=0) == want
+    if "S_obs" not in kw:      # S_obs is ignored outside score / prune
+        assert thk.thk_workspace_bytes(s, thk.THK_OP_SCORE) == 0
+        assert _status(thk.thk_select_topk, s, A, A, stream=0) == want
+        assert _status(thk.thk_compact_keys, s, A, A, A, stream=0) == want
+        assert _status(thk.thk_decode_attn, s, A, A, A, A, None, None, 0, 0, A, (A, BIG), stream=0) == want
+        assert _status(thk.thk_tail_append, s, A, A, A, A, 0, 4, stream=0) == want
+
+
+def test_null_alignment_workspace_and_tail_errors():
+    s = _shape()
+    assert _status(thk.thk_score, s, None, A, A, (A, BIG), stream=0) == 1
+    assert _status(thk.thk_score, s, A, A + 8, A, (A, BIG), stream=0) == 4
+    assert _status(thk.thk_score, s, A, A, A, (A, 8), stream=0) == 5
+    assert _status(thk.thk_score, s, A, A, A, (None, 0), stream=0) == 5
+    assert _status(thk.thk_score, s, A, A, A, (A + 4, BIG), stream=0) == 5
+    assert _status(thk.thk_select_topk, s, A, None, stream=0) == 1
+    assert _status(thk.thk_compact_keys, s, A, A, A + 2, stream=0) == 4
+    assert _status(thk.thk_prune, s, A, A, None, A, A, (A, 16), stream=0) == 5
+    assert _status(thk.thk_score_magnitude, s, A, 3, A, (A, BIG), stream=0) == 2
+    # decode: tail arguments
+    dec = lambda *a: _status(thk.thk_decode_attn, s, *a, stream=0)
+    assert dec(A, A, A, A, None, None, 1, 4, A, (A, BIG)) == 1      # tail rows but no tail buffers
+    assert dec(A, A, A, A, A, A, 5, 4, A, (A, BIG)) == 2            # s_tail > cap
+    assert dec(A, A, A, A, A, A, -1, 4, A, (A, BIG)) == 2
+    assert dec(A, A, A, A, None, None, 0, 0, A, (A, 16)) == 5       # split > 1 needs a workspace
+    assert dec(A, A, A, A, None, None, 0, 0, A + 1, (A, BIG)) == 4
+    assert _status(thk.thk_tail_append, s, A, A, A, A, 4, 4, stream=0) == 2   # tail full
+    assert "workspace" in thk.thk_status_string(5) and thk.thk_status_string(0) == "ok"
+
+
+def test_workspace_sizes_follow_the_split():
+    s = _shape(S=4096, B=4, N_q=32, N_kv=32, T=76)
+    n_dec = thk.thk_default_split(s, thk.THK_OP_DECODE)
+    assert n_dec >= 1
+    want = 16 if n_dec == 1 else 4 * 32 * n_dec * 130 * 4
+    assert thk.thk_workspace_bytes(s, thk.THK_OP_DECODE) == want
+    n_sc = thk.thk_default_split(s, thk.THK_OP_SCORE)
+    assert thk.thk_workspace_bytes(s, thk.THK_OP_SCORE) == 4 * 32 * n_sc * 128 * 8
+    s2 = _shape(S=4096, B=4, N_q=32, N_kv=32, T=76, n_split=7)
+    assert thk.thk_workspace_bytes(s2, thk.THK_OP_DECODE) == 4 * 32 * 7 * 130 * 4
+    assert thk.thk_workspace_bytes(s2, thk.THK_OP_SCORE) == 4 * 32 * 7 * 128 * 8
+
+
+def test_binding_refuses_short_tensors():
+    torch = pytest.importorskip("torch")
+    s = _shape()
+    k = torch.zeros(10, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        thk.thk_compact_keys(s, k, A, A, stream=0)
