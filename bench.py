@@ -30,32 +30,40 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(cfg_id, cfg, T, device):
-    """Time the oracle, as it stands, on a bounded sample of the same workload."""
-    import numpy as np
+def cpu_baseline(cfg_id, cfg, T, device, budget_s=20.0):
+    """Time the oracle, as it stands, on the same workload, layer after layer, until the
+    workload is done or about budget_s seconds of oracle time have been spent."""
     from oracle import oracle as O
     from paper_2407_21018_amd import synth
-    sample_B = 1
-    sub = dict(cfg, B=sample_B)
-    q_obs, k, v = synth.gen_prefill(cfg_id, 0, device, **sub)
-    q, _, _ = synth.gen_decode(cfg_id, 0, 0, device, **sub)
-    qn, kn, vn, q1 = synth.as_numpy(q_obs), synth.as_numpy(k), synth.as_numpy(v), synth.as_numpy(q)
     dt = cfg["dtype"]
     eb = 2 if dt == "bf16" else 4
+    U = cfg["B"] * cfg["N_kv"]
     O.lib()
-    t0 = time.perf_counter()
-    sc = O.score(qn, kn, dt)
-    idx = O.select_topk(sc, T)
-    kp = O.compact_keys(kn, idx, dt)
-    t1 = time.perf_counter()
-    O.decode_attn(q1[0], kp[0], idx[0], vn[0], dt)
-    t2 = time.perf_counter()
-    U = sample_B * cfg["N_kv"]
-    by = U * cfg["S"] * eb * (cfg["D"] + 2 * T) + qn.nbytes + U * cfg["S"] * eb * (T + cfg["D"])
-    return {"value": by / (t2 - t0) / 1e9, "unit": "GB/s", "cores": O.max_threads(), "kind": "oracle",
-            "sample": f"1 of {cfg['L']} layers, batch row 0 of {cfg['B']} ({U} units): prune + 1 decode step",
-            "prune_ms_per_layer_equiv": (t1 - t0) * 1e3 * cfg["B"] / sample_B,
-            "decode_us_per_step_equiv": (t2 - t1) * 1e6 * cfg["B"] / sample_B}
+    t_prune = t_dec = 0.0
+    nbytes = 0
+    layers = 0
+    for l in range(cfg["L"]):
+        q_obs, k, v = synth.gen_prefill(cfg_id, l, device, **cfg)
+        q, _, _ = synth.gen_decode(cfg_id, l, 0, device, **cfg)
+        qn, kn, vn, q1 = synth.as_numpy(q_obs), synth.as_numpy(k), synth.as_numpy(v), synth.as_numpy(q)
+        del q_obs, k, v
+        t0 = time.perf_counter()
+        sc = O.score(qn, kn, dt)
+        idx = O.select_topk(sc, T)
+        kp = O.compact_keys(kn, idx, dt)
+        t1 = time.perf_counter()
+        O.decode_attn(q1[0], kp[0], idx[0], vn[0], dt)
+        t2 = time.perf_counter()
+        t_prune += t1 - t0
+        t_dec += t2 - t1
+        nbytes += U * cfg["S"] * eb * (cfg["D"] + 2 * T) + qn.nbytes + U * cfg["S"] * eb * (T + cfg["D"])
+        layers += 1
+        if t_prune + t_dec > budget_s:
+            break
+    return {"value": nbytes / (t_prune + t_dec) / 1e9, "unit": "GB/s", "cores": O.max_threads(), "kind": "oracle",
+            "sample": f"{layers} of {cfg['L']} layers, all {U} units each: prune + 1 decode step per layer "
+                      f"({t_prune + t_dec:.1f} s of oracle time)",
+            "prune_ms_per_layer": t_prune / layers * 1e3, "decode_us_per_step": t_dec / layers * 1e6}
 
 
 def main():
@@ -101,45 +109,61 @@ def main():
     torch.cuda.synchronize()
 
     def ev():
-        return torch.cuda.Event(enable_timing=True)
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()          # torch creates the HIP event on first record; done outside the timed region
+        return e
 
-    def step(rec=None):
-        """Whole hot path once.  rec: list receiving (name, start_event, end_event)."""
-        a = ev(); a.record()
+    n_dec = steps_per_layer * L
+    # event pairs the library records around the main kernel of each call (thk_profile_next)
+    pairs = [[(ev(), ev()) for _ in range(1 + n_dec)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+
+    def step(evs=None, ph=None):
+        """Whole hot path once.  evs: this step's event pairs (prune first, then one per decode call);
+        ph: three events recorded before the prune, after it, and after the last decode call."""
+        if evs is not None:
+            thk.thk_profile_next(*evs[0])
+            ph[0].record()
         thk.thk_prune(shape_all, q_obs, k, score, idx, kp, ws)
-        b = ev(); b.record()
-        if rec is not None:
-            rec.append(("prune", a, b))
+        if ph is not None:
+            ph[1].record()
+        i = 1
         for s in range(steps_per_layer):
             for l in range(L):
                 q, k_new, v_new = dec[l][s]
                 if cap:
                     thk.thk_tail_append(shape_1, k_new, v_new, kt[l], vt[l], s, cap)
-                c = ev(); c.record()
+                if evs is not None:
+                    thk.thk_profile_next(*evs[i])
+                    i += 1
                 thk.thk_decode_attn(shape_1, q, kp[l], idx[l * U:(l + 1) * U], v[l],
                                     kt[l] if cap else None, vt[l] if cap else None,
                                     s + 1 if cap else 0, cap, out[l], ws)
-                d = ev(); d.record()
-                if rec is not None:
-                    rec.append(("decode", c, d))
+        if ph is not None:
+            ph[2].record()
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    recs = []
     t0 = time.perf_counter()
-    e0 = ev(); e0.record()
-    for _ in range(args.steps):
-        step(recs)
-    e1 = ev(); e1.record()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    phases = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    e0.record()
+    for i in range(args.steps):
+        step(pairs[i], phases[i])
+    e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = e0.elapsed_time(e1) / args.steps
 
-    prune_ms = [a.elapsed_time(b) for n, a, b in recs if n == "prune"]
-    dec_us = [a.elapsed_time(b) * 1e3 for n, a, b in recs if n == "decode"]
-    prune_ms_layer = sum(prune_ms) / len(prune_ms) / L
-    dec_us_step = sum(dec_us) / len(dec_us)
+    # main-kernel durations measured inside the timed region
+    prune_kernel_us = [p[0][0].elapsed_time(p[0][1]) * 1e3 for p in pairs]
+    dec_kernel_us = [a.elapsed_time(b) * 1e3 for p in pairs for (a, b) in p[1:]]
+    prune_k_us = sum(prune_kernel_us) / len(prune_kernel_us)
+    dec_k_us = sum(dec_kernel_us) / len(dec_kernel_us)
+    # whole calls (all kernels of a call and the gaps between them)
+    prune_ms_layer = sum(p[0].elapsed_time(p[1]) for p in phases) / args.steps / L
+    dec_us_step = sum(p[1].elapsed_time(p[2]) for p in phases) / args.steps / n_dec * 1e3
 
     # ---- algorithmic bytes (per layer), K and V counted once per KV head -----
     qobs_bytes = B * N_q * S_obs * D * eb
@@ -149,17 +173,20 @@ def main():
     step_bytes = L * (prune_bytes + steps_per_layer * decode_bytes)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    prune_gbs = prune_bytes / (prune_ms_layer * 1e-3) / 1e9
-    dec_gbs = decode_bytes / (dec_us_step * 1e-6) / 1e9
-    # dominant kernel by time inside a step
-    if prune_ms_layer * L >= dec_us_step * 1e-3 * L * steps_per_layer:
-        roof = {"kernel": "thk_prune (k_colsum + k_finalize + k_compact_flat per group)",
-                "achieved": prune_gbs, "launch_us": prune_ms_layer * L * 1e3, "bytes_per_launch": prune_bytes * L}
-    else:
-        roof = {"kernel": "thk_decode_attn (k_decode + k_decode_merge)", "achieved": dec_gbs,
-                "launch_us": dec_us_step, "bytes_per_launch": decode_bytes}
-    roof.update({"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": roof["achieved"] / HBM_PEAK_GBS,
-                 "traffic": None})
+    fused = thk.thk_default_split(shape_all, thk.THK_OP_PRUNE) >= 0 and os.environ.get("THK_PRUNE_PATH", "f")[0] != "s"
+    prune_kernel = "k_prune_fused" if fused else "k_compact_flat"
+    prune_kernel_bytes = L * prune_bytes if fused else L * U * S * eb * (D + T)
+    kernels = {
+        prune_kernel: {"launches_per_step": 1, "avg_us": prune_k_us, "bytes_per_launch": prune_kernel_bytes,
+                       "GBps": prune_kernel_bytes / prune_k_us / 1e3},
+        "k_decode": {"launches_per_step": n_dec, "avg_us": dec_k_us, "bytes_per_launch": decode_bytes,
+                     "GBps": decode_bytes / dec_k_us / 1e3},
+    }
+    # the dominant kernel = most time inside a step
+    dom = max(kernels, key=lambda n: kernels[n]["avg_us"] * kernels[n]["launches_per_step"])
+    roof = {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": kernels[dom]["GBps"] / HBM_PEAK_GBS, "traffic": None,
+            "launch_us": kernels[dom]["avg_us"], "bytes_per_launch": kernels[dom]["bytes_per_launch"]}
 
     res = {
         "metric": "pruned-K decode attention us/step + achieved HBM GB/s; prune ms per layer",
@@ -171,9 +198,12 @@ def main():
                                f"then {steps_per_layer} decode step(s) per layer",
                    "step_bytes": step_bytes},
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,
-        "prune_ms_per_layer": prune_ms_layer, "prune_GBps": prune_gbs, "prune_frac": prune_gbs / HBM_PEAK_GBS,
-        "decode_us_per_step": dec_us_step, "decode_GBps": dec_gbs, "decode_frac": dec_gbs / HBM_PEAK_GBS,
+        "prune_ms_per_layer": prune_ms_layer, "prune_GBps": prune_bytes / prune_ms_layer / 1e6,
+        "prune_frac": prune_bytes / prune_ms_layer / 1e6 / HBM_PEAK_GBS,
+        "decode_us_per_step": dec_us_step, "decode_GBps": decode_bytes / dec_us_step / 1e3,
+        "decode_frac": decode_bytes / dec_us_step / 1e3 / HBM_PEAK_GBS,
         "host_wall_s": wall,
+        "kernels": kernels,
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -133,9 +133,13 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
                             const int16_t *idx, void *k_pruned, void *stream);
 
 /*
- * End-of-prefill prune = thk_score + thk_select_topk + thk_compact_keys, run
- * over groups of units small enough that the second read of K is served from
- * the memory-side cache.  `score` may be NULL (then it lives in ws).
+ * End-of-prefill prune = thk_score + thk_select_topk + thk_compact_keys in one
+ * call.  When K_pruned is dense (ld_keep == T) and S * T * sizeof(element) is a
+ * multiple of 16, a single kernel does all three steps per row block, so that
+ * the compaction re-reads K from cache rather than HBM; otherwise the three
+ * kernels run one after the other.  Scores agree with thk_score to fp64
+ * summation order (the last float bit can differ).  `score` may be NULL (then
+ * it lives in ws).
  *   ws : THK_OP_PRUNE bytes.
  */
 thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,
@@ -173,6 +177,17 @@ thk_status thk_decode_attn(const thk_shape *shape, const void *q,
 thk_status thk_tail_append(const thk_shape *shape, const void *k_new,
                            const void *v_new, void *k_tail, void *v_tail,
                            int32_t s_tail, int32_t s_tail_cap, void *stream);
+
+/*
+ * Timing hook for benchmarks: the NEXT thk_prune or thk_decode_attn call made by
+ * this host thread records `ev_start` immediately before and `ev_stop`
+ * immediately after its main kernel (the one-launch prune kernel, or the
+ * compaction kernel of the staged form; the attention kernel, not the split
+ * merge) on that call's stream.  Both are hipEvent_t handles passed as void*,
+ * created by the caller with timing enabled; the pair is used once.  Passing
+ * NULL for either cancels a pending pair.
+ */
+void thk_profile_next(void *ev_start, void *ev_stop);
 
 #ifdef __cplusplus
 }

@@ -65,6 +65,8 @@ def load():
     L.thk_prune.argtypes = [sp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.thk_decode_attn.restype = ctypes.c_int
     L.thk_decode_attn.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    L.thk_profile_next.restype = None
+    L.thk_profile_next.argtypes = [vp, vp]
     L.thk_tail_append.restype = ctypes.c_int
     L.thk_tail_append.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp]
     _lib = L
@@ -218,3 +220,14 @@ def thk_tail_append(shape, k_new, v_new, k_tail, v_tail, s_tail, s_tail_cap, str
     _check(load().thk_tail_append(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(k_tail),
                                   _ptr(v_tail), s_tail, s_tail_cap, _stream(stream)),
            "thk_tail_append")
+
+
+def thk_profile_next(ev_start, ev_stop):
+    """ev_start / ev_stop: torch.cuda.Event(enable_timing=True) that have been recorded once
+    (torch creates the HIP event lazily), raw hipEvent_t integers, or None to cancel."""
+    def h(e):
+        if e is None or isinstance(e, int):
+            return e
+        return e.cuda_event
+    load().thk_profile_next(ctypes.c_void_p(h(ev_start)) if ev_start is not None else None,
+                            ctypes.c_void_p(h(ev_stop)) if ev_stop is not None else None)

@@ -7,6 +7,21 @@
 
 using namespace thk;
 
+namespace thk {
+namespace {
+thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+}
+void profile_mark(bool start, hipStream_t st) {
+  if (g_prof_start == nullptr || g_prof_stop == nullptr) return;
+  if (start) {
+    (void)hipEventRecord(g_prof_start, st);
+  } else {
+    (void)hipEventRecord(g_prof_stop, st);
+    g_prof_start = g_prof_stop = nullptr;
+  }
+}
+}  // namespace thk
+
 namespace {
 
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
@@ -75,10 +90,11 @@ Split decode_split(const thk_shape *s) {
   return {n, rows};
 }
 
-// Units per group in thk_prune: the group's K slab should stay resident in the
-// memory-side cache between the scoring read and the compaction read.
+// Units per group in the staged form of thk_prune (three launches per group).
+// Small groups would let the compaction re-read K from the memory-side cache,
+// but measured launch overheads outweigh that; the default keeps groups large.
 int64_t prune_group_units(const thk_shape *s) {
-  size_t budget = (size_t)64 << 20;
+  size_t budget = (size_t)1024 << 20;
   if (const char *e = getenv("THK_PRUNE_GROUP_MIB")) {
     const long v = atol(e);
     if (v > 0) budget = (size_t)v << 20;
@@ -90,6 +106,37 @@ int64_t prune_group_units(const thk_shape *s) {
   return g > U ? U : g;
 }
 
+// ---- one-launch prune: eligibility and blocking -------------------------------
+long env_long(const char *name, long dflt) {
+  const char *e = getenv(name);
+  if (e == nullptr || *e == 0) return dflt;
+  return atol(e);
+}
+
+struct FusedPlan { bool ok; int NB; int64_t RB; };
+
+// The fused kernel needs the flat K_pruned layout (dense rows, 16-byte aligned
+// units).  Its blocks take 512 rows each (measured best on MI355X) and the
+// blocks of a unit wait for each other, so units of more than 64 blocks (long
+// sequences spread over few units) go through the staged path instead.
+FusedPlan fused_plan(const thk_shape *s) {
+  FusedPlan p{false, 0, 0};
+  const char *path = getenv("THK_PRUNE_PATH");
+  if (path != nullptr && path[0] == 's') return p;   // "staged": the three-kernel path
+  const int eb = elem_bytes(s->dtype);
+  if (ld_of(s) != s->T || ((size_t)s->S * s->T * eb) % 16 != 0) return p;
+  int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 512);
+  if (rb < 32) rb = 32;
+  rb = ceil_div(rb, 32) * 32;
+  const int64_t nb = ceil_div(s->S, rb);
+  const bool forced = path != nullptr && path[0] == 'f';   // "fused": regardless of block count
+  if (nb > (forced ? 256 : 64)) return p;
+  p.RB = rb;
+  p.NB = (int)nb;
+  p.ok = units_of(s) * p.NB <= kMaxGrid;
+  return p;
+}
+
 size_t score_ws_bytes(const thk_shape *s, int64_t units) {
   return (size_t)units * score_split(s, units).n * kD * sizeof(double);
 }
@@ -99,6 +146,11 @@ size_t score_ws_bytes(const thk_shape *s, int64_t units) {
 extern "C" {
 
 int32_t thk_version(void) { return 100; }
+
+void thk_profile_next(void *ev_start, void *ev_stop) {
+  g_prof_start = (ev_start != nullptr && ev_stop != nullptr) ? (hipEvent_t)ev_start : nullptr;
+  g_prof_stop = (ev_start != nullptr && ev_stop != nullptr) ? (hipEvent_t)ev_stop : nullptr;
+}
 
 const char *thk_status_string(thk_status st) {
   switch (st) {
@@ -138,9 +190,16 @@ size_t thk_workspace_bytes(const thk_shape *s, int32_t op) {
       if (sp.n == 1) return 16;
       return (size_t)s->L * s->B * s->N_q * sp.n * (kD + 2) * sizeof(float);
     }
-    case THK_OP_PRUNE:
-      // partial sums of one group + a score array for the whole call
-      return score_ws_bytes(s, prune_group_units(s)) + (size_t)units_of(s) * kD * sizeof(float);
+    case THK_OP_PRUNE: {
+      // a score array for the whole call + the larger of the two paths' scratch
+      const FusedPlan fp = fused_plan(s);
+      size_t a = score_ws_bytes(s, prune_group_units(s));
+      if (fp.ok) {
+        const size_t b = prune_fused_ws_bytes(units_of(s), fp.NB);
+        if (b > a) a = b;
+      }
+      return ((a + 15) & ~(size_t)15) + (size_t)units_of(s) * kD * sizeof(float);
+    }
   }
   return 0;
 }
@@ -206,15 +265,25 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
     return THK_ERR_ALIGN;
   if (ws == nullptr || !aligned16(ws) || ws_bytes < thk_workspace_bytes(s, THK_OP_PRUNE)) return THK_ERR_WORKSPACE;
   const int64_t U = units_of(s);
+  const int G = s->N_q / s->N_kv;
+  hipStream_t hs = (hipStream_t)stream;
+  const size_t score_off = thk_workspace_bytes(s, THK_OP_PRUNE) - (size_t)U * kD * sizeof(float);
+  float *sc = score != nullptr ? score : (float *)((char *)ws + score_off);
+  const FusedPlan fp = fused_plan(s);
+  if (fp.ok) {
+    const int spin = (int)env_long("THK_PRUNE_SPIN_LIMIT", 4096);
+    if (launch_prune_fused(s->dtype, q_obs, k, sc, idx, k_pruned, ws, U, s->S, G, s->S_obs, s->T, fp.NB,
+                           fp.RB, spin < 0 ? 0 : spin, hs) != hipSuccess)
+      return THK_ERR_HIP;
+    return THK_OK;
+  }
+  // staged path: score -> select -> compact per group of units
   const int64_t gu = prune_group_units(s);
   const Split sp = score_split(s, gu);
   if (gu * sp.n > kMaxGrid || gu * ceil_div(s->S, 512) > kMaxGrid) return THK_ERR_SHAPE;
   double *partial = (double *)ws;
-  float *sc = score != nullptr ? score : (float *)((char *)ws + score_ws_bytes(s, gu));
   const int eb = elem_bytes(s->dtype);
   const int ld = ld_of(s);
-  const int G = s->N_q / s->N_kv;
-  hipStream_t hs = (hipStream_t)stream;
   for (int64_t u0 = 0; u0 < U; u0 += gu) {
     const int64_t nu = (U - u0 < gu) ? U - u0 : gu;
     const char *kg = (const char *)k + (size_t)u0 * s->S * kD * eb;
@@ -224,9 +293,11 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
     if (launch_finalize(s->dtype, 0, partial, qg, sc + (size_t)u0 * kD, idx + (size_t)u0 * s->T, nu, G,
                         s->S_obs, sp.n, s->T, hs) != hipSuccess)
       return THK_ERR_HIP;
-    if (launch_compact(s->dtype, kg, idx + (size_t)u0 * s->T, (char *)k_pruned + (size_t)u0 * s->S * ld * eb,
-                       nu, s->S, s->T, ld, hs) != hipSuccess)
-      return THK_ERR_HIP;
+    profile_mark(true, hs);
+    const hipError_t ce = launch_compact(s->dtype, kg, idx + (size_t)u0 * s->T,
+                                         (char *)k_pruned + (size_t)u0 * s->S * ld * eb, nu, s->S, s->T, ld, hs);
+    profile_mark(false, hs);
+    if (ce != hipSuccess) return THK_ERR_HIP;
   }
   return THK_OK;
 }

@@ -68,12 +68,14 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st) {
   const int gt = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
   const int groups = G / gt;
   hipError_t e;
+  profile_mark(true, st);
   if (a.dtype == THK_BF16)
     e = gt == 4 ? decode_launch_bf16_g4(a, groups, st)
                 : gt == 2 ? decode_launch_bf16_g2(a, groups, st) : decode_launch_bf16_g1(a, groups, st);
   else
     e = gt == 4 ? decode_launch_f32_g4(a, groups, st)
                 : gt == 2 ? decode_launch_f32_g2(a, groups, st) : decode_launch_f32_g1(a, groups, st);
+  profile_mark(false, st);
   if (e != hipSuccess) return e;
   if (a.n_split > 1) {
     const int64_t heads = a.units / a.N_kv * a.N_q;

@@ -47,6 +47,9 @@ template <> struct Elem<THK_BF16> {
   __device__ static inline void store1(void *p, size_t i, float x) { ((uint16_t *)p)[i] = round_bf16(x); }
 };
 
+// ---- one-shot timing hook (thk_profile_next): record around a call's main kernel ----
+void profile_mark(bool start, hipStream_t st);   // no-op unless a pair is pending; stop consumes it
+
 // ---- launchers (one per kernel family; each returns hipGetLastError()) ----
 // Column sums of squares (p == 2) or of absolute values (p == 1) of K per
 // unit, cut into n_split pieces of rows_per_split rows: partial[U][n_split][D].
@@ -63,6 +66,12 @@ hipError_t launch_select(const float *score, int16_t *idx, int64_t U, int T, hip
 
 hipError_t launch_compact(int dtype, const void *k, const int16_t *idx, void *kp, int64_t U,
                           int64_t S, int T, int ld_keep, hipStream_t st);
+
+// One-launch prune (flat K_pruned layout only).  ws: prune_fused_ws_bytes(U, NB) bytes.
+size_t prune_fused_ws_bytes(int64_t U, int NB);
+hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float *score, int16_t *idx,
+                              void *kp, void *ws, int64_t U, int64_t S, int G, int S_obs, int T,
+                              int NB, int64_t RB, int spin_limit, hipStream_t st);
 
 struct DecodeArgs {
   const void *q, *kp, *v, *kt, *vt;

@@ -1,0 +1,254 @@
+// Device-side building blocks of the prune path, shared by the stand-alone
+// kernels (k_colsum, k_finalize, k_select, k_compact_flat) and the fused one.
+#pragma once
+#include "thk_internal.h"
+
+namespace thk {
+
+// ---------------------------------------------------------------------------
+// Column reduction of rows [s0, s1) of one [S, 128] unit by a 256-thread block:
+// sums of squares (P == 2) or of absolute values (P == 1) per channel, written
+// as 128 doubles to `out`.  A 16-byte load covers VEC channels, so LPR = 128 /
+// VEC lanes cover a row and the block covers RPB rows per step; each thread
+// keeps the same VEC channels for all its rows.  Squares of bf16 values are
+// exact in fp32; fp32 chains are UNR terms long and are then folded into fp64
+// accumulators, which carry every later merge.  red: LDS, 4 x 128 doubles.
+// ---------------------------------------------------------------------------
+template <int DT, int P>
+__device__ __forceinline__ void colsum_block(const u32x4 *__restrict__ base, int64_t s0, int64_t s1,
+                                             double *__restrict__ out, double (*red)[kD]) {
+  using E = Elem<DT>;
+  constexpr int VEC = E::VEC, LPR = kD / VEC, RPB = 256 / LPR, UNR = 8;
+  const int tid = threadIdx.x;
+  const int cl = tid % LPR, rg = tid / LPR;
+  double dacc[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) dacc[v] = 0.0;
+
+  for (int64_t s = s0 + rg; s < s1; s += (int64_t)RPB * UNR) {
+    u32x4 r[UNR];
+#pragma unroll
+    for (int j = 0; j < UNR; ++j) {
+      const int64_t row = s + (int64_t)j * RPB;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      r[j] = row < s1 ? base[row * LPR + cl] : zero;
+    }
+    float facc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) facc[v] = 0.f;
+#pragma unroll
+    for (int j = 0; j < UNR; ++j) {
+      float f[VEC];
+      E::unpack(r[j], f);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v)
+        facc[v] = (P == 2) ? fmaf(f[v], f[v], facc[v]) : facc[v] + fabsf(f[v]);
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) dacc[v] += (double)facc[v];
+  }
+
+  // rows held by the other lane groups of this wave
+#pragma unroll
+  for (int off = LPR; off < kWave; off <<= 1)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) dacc[v] += __shfl_xor(dacc[v], off);
+
+  const int wave = tid / kWave, lane = tid % kWave;
+  if (lane < LPR)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) red[wave][lane * VEC + v] = dacc[v];
+  __syncthreads();
+  if (tid < kD) out[tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
+}
+
+// ---------------------------------------------------------------------------
+// sum over the G query heads of unit u of ||Q_obs,g[:, c]||_2 (Sec. 3.2, with the
+// observation window), for c = threadIdx.x < 128 (other threads return 0).
+// The unit's heads hold G * S_obs contiguous rows of Q_obs; heads are taken
+// kQnHeads at a time, each thread squares (in fp64) the VEC channels it owns
+// over the rows of its row group, row groups are folded by shuffles inside a
+// wave and through LDS across the waves.  NT threads per block, all of which
+// must call; red: LDS [kQnHeads][NT / 64][128] doubles.
+// ---------------------------------------------------------------------------
+constexpr int kQnHeads = 4;
+
+template <int DT, int NT>
+__device__ __forceinline__ double unit_query_norm(const void *__restrict__ q_obs, int64_t u, int G,
+                                                  int S_obs, double (*red)[NT / kWave][kD]) {
+  using E = Elem<DT>;
+  constexpr int VEC = E::VEC, LPR = kD / VEC, RG = NT / LPR, NW = NT / kWave, GC = kQnHeads;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int cl = tid % LPR, rg = tid / LPR;
+  // unit u = (layer*batch, KV head) reads query heads u * G .. u * G + G - 1
+  const u32x4 *qbase = (const u32x4 *)((const char *)q_obs + (size_t)u * G * S_obs * kD * E::EB);
+  double tot = 0.0;
+  for (int g0 = 0; g0 < G; g0 += GC) {
+    const int ng = min(GC, G - g0);
+    double qa[GC][VEC];
+#pragma unroll
+    for (int g = 0; g < GC; ++g)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) qa[g][v] = 0.0;
+    for (int i0 = 0; i0 < S_obs; i0 += RG) {
+      u32x4 r[GC];
+      const int i = i0 + rg;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int g = 0; g < GC; ++g)
+        r[g] = (g < ng && i < S_obs) ? qbase[((size_t)(g0 + g) * S_obs + i) * LPR + cl] : zero;
+#pragma unroll
+      for (int g = 0; g < GC; ++g) {
+        float f[VEC];
+        E::unpack(r[g], f);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) qa[g][v] += (double)f[v] * (double)f[v];
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < GC; ++g) {
+#pragma unroll
+      for (int off = LPR; off < kWave; off <<= 1)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) qa[g][v] += __shfl_xor(qa[g][v], off);
+      if (lane < LPR)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) red[g][wave][lane * VEC + v] = qa[g][v];
+    }
+    __syncthreads();
+    if (tid < kD)
+      for (int g = 0; g < ng; ++g) {
+        double qss = 0.0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) qss += red[g][w][tid];
+        tot += sqrt(qss);
+      }
+    __syncthreads();
+  }
+  return tot;
+}
+
+// ---------------------------------------------------------------------------
+// Top_T of 128 scores with one wavefront: two keys per lane, bitonic sort of
+// 64-bit keys (order-preserving score bits << 32 | 127 - channel, so that equal
+// scores rank the lower channel first and all keys are distinct), then every
+// lane compares its own keys with the T-th largest and the kept channels are
+// emitted in ascending order through ballot + prefix popcount.
+// ---------------------------------------------------------------------------
+__device__ inline unsigned long long score_key(float s, int c) {
+  uint32_t b = __float_as_uint(s);
+  b = (b & 0x80000000u) ? ~b : (b | 0x80000000u);   // unsigned order == float order
+  return ((unsigned long long)b << 32) | (uint32_t)(kD - 1 - c);
+}
+
+__device__ inline void select_wave(float s_lo, float s_hi, int T, int16_t *out, int lane) {
+  using u64 = unsigned long long;
+  const u64 k0 = score_key(s_lo, lane), k1 = score_key(s_hi, lane + 64);
+  u64 a0 = k0, a1 = k1;   // sorted position i = r * 64 + lane holds a_r
+#pragma unroll
+  for (int k = 2; k <= 128; k <<= 1) {
+#pragma unroll
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      if (j == 64) {   // partner sits in the other register of the same lane
+        const u64 hi = a0 > a1 ? a0 : a1, lo = a0 > a1 ? a1 : a0;
+        a0 = hi; a1 = lo;
+      } else {
+        const u64 o0 = __shfl_xor(a0, j), o1 = __shfl_xor(a1, j);
+        const bool lower = (lane & j) == 0;
+        const bool desc0 = (lane & k) == 0;          // i = lane
+        const bool desc1 = ((lane + 64) & k) == 0;   // i = lane + 64
+        const u64 mx0 = a0 > o0 ? a0 : o0, mn0 = a0 > o0 ? o0 : a0;
+        const u64 mx1 = a1 > o1 ? a1 : o1, mn1 = a1 > o1 ? o1 : a1;
+        a0 = (desc0 == lower) ? mx0 : mn0;
+        a1 = (desc1 == lower) ? mx1 : mn1;
+      }
+    }
+  }
+  const int pos = T - 1;
+  const u64 t0 = __shfl(a0, pos & 63), t1 = __shfl(a1, pos & 63);
+  const u64 thr = (pos >> 6) ? t1 : t0;
+  const bool keep0 = k0 >= thr, keep1 = k1 >= thr;
+  const u64 m0 = __ballot(keep0), m1 = __ballot(keep1);
+  const u64 below = (1ull << lane) - 1ull;
+  if (keep0) out[__popcll(m0 & below)] = (int16_t)lane;
+  if (keep1) out[__popcll(m0) + __popcll(m1 & below)] = (int16_t)(lane + 64);
+}
+
+// ---------------------------------------------------------------------------
+// Compaction of rows [s0, s1) of one unit (K_pruned rows dense, unit start
+// 16-byte aligned) by a 256-thread block.  Each wavefront works alone on tiles
+// of 32 rows:
+//   1. 16-byte coalesced loads of the full-width rows into its LDS tile;
+//   2. for every 16-byte chunk of the OUTPUT slab, a table lookup gives the LDS
+//      element offsets of its VEC source elements (the pattern of
+//      row * 128 + idx[t] repeats every 8 output rows because 8 * T elements is
+//      a whole number of chunks), the elements are gathered from LDS, packed
+//      and stored with one 16-byte store.
+// s0 must be a multiple of 32 and (s1 - s0) * T a multiple of VEC.
+// tab: LDS, 8 * T uint16 (<= 2 KiB); tiles: LDS, 4 x [32][128] elements.
+// ---------------------------------------------------------------------------
+constexpr int kCompactTileRows = 32;
+
+__device__ __forceinline__ void compact_build_tab(uint16_t *tab, const int16_t *uidx, int T) {
+  const int period = 8 * T;
+  for (int e = threadIdx.x; e < period; e += 256) {
+    const int row = e / T, t = e - row * T;
+    tab[e] = (uint16_t)(row * kD + (int)uidx[t]);
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
+                                             int64_t s0, int64_t s1, int T, const uint16_t *tab,
+                                             u32x4 *tiles) {
+  using E = Elem<DT>;
+  constexpr int VEC = E::VEC, CPR = kD / VEC, TR = kCompactTileRows;
+  constexpr int NLD = TR * CPR / kWave;   // 16-byte loads per lane per tile
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  u32x4 *tile = tiles + wave * (TR * CPR);
+  const int period = 8 * T;
+  for (int64_t r0 = s0 + (int64_t)wave * TR; r0 < s1; r0 += 4 * TR) {
+    const int nr = (int)min((int64_t)TR, s1 - r0);
+    // rows past the end of a ragged last tile re-read its last row (kept in bounds, never gathered)
+    u32x4 r[NLD];
+    const u32x4 *tsrc = src + (size_t)r0 * CPR;
+    const int cmax = nr * CPR - 1;
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) r[j] = tsrc[min(j * kWave + lane, cmax)];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) tile[j * kWave + lane] = r[j];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    const int nchunks = nr * T / VEC;
+    u32x4 *o = dst + (size_t)r0 * T / VEC;
+    for (int c = lane; c < nchunks; c += kWave) {
+      const int e0 = c * VEC;
+      const int pb = e0 / period;
+      const int pe = e0 - pb * period;
+      const int rowbase = pb * 8 * kD;
+      u32x4 w;
+      if constexpr (DT == THK_BF16) {
+        const uint16_t *tl = (const uint16_t *)tile + rowbase;
+        const u32x4 offs = *(const u32x4 *)(tab + pe);   // 8 offsets
+        const uint32_t o0 = offs.x & 0xffffu, o1 = offs.x >> 16, o2 = offs.y & 0xffffu, o3 = offs.y >> 16;
+        const uint32_t o4 = offs.z & 0xffffu, o5 = offs.z >> 16, o6 = offs.w & 0xffffu, o7 = offs.w >> 16;
+        w.x = (uint32_t)tl[o0] | ((uint32_t)tl[o1] << 16);
+        w.y = (uint32_t)tl[o2] | ((uint32_t)tl[o3] << 16);
+        w.z = (uint32_t)tl[o4] | ((uint32_t)tl[o5] << 16);
+        w.w = (uint32_t)tl[o6] | ((uint32_t)tl[o7] << 16);
+      } else {
+        const uint32_t *tl = (const uint32_t *)tile + rowbase;
+        const uint2 offs = *(const uint2 *)(tab + pe);   // 4 offsets
+        w.x = tl[offs.x & 0xffffu]; w.y = tl[offs.x >> 16];
+        w.z = tl[offs.y & 0xffffu]; w.w = tl[offs.y >> 16];
+      }
+      o[c] = w;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+}  // namespace thk
