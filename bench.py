@@ -27,6 +27,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload id (synth.CONFIGS); 2 = the metric's")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference dispatches of known size "
+                         "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -64,6 +67,18 @@ def cpu_baseline(cfg_id, cfg, T, device, budget_s=20.0):
             "sample": f"{layers} of {cfg['L']} layers, all {U} units each: prune + 1 decode step per layer "
                       f"({t_prune + t_dec:.1f} s of oracle time)",
             "prune_ms_per_layer": t_prune / layers * 1e3, "decode_us_per_step": t_dec / layers * 1e6}
+
+
+def measured_traffic(kernel):
+    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 counter summaries
+    (profiles/*.txt, lines 'traffic_bytes_per_launch <kernel> <bytes>'); None when absent."""
+    import glob
+    for f in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(f):
+            w = line.split()
+            if len(w) == 3 and w[0] == "traffic_bytes_per_launch" and w[1] == kernel:
+                return float(w[2])
+    return None
 
 
 def main():
@@ -142,6 +157,14 @@ def main():
         if ph is not None:
             ph[2].record()
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB per dispatch
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -185,7 +208,8 @@ def main():
     # the dominant kernel = most time inside a step
     dom = max(kernels, key=lambda n: kernels[n]["avg_us"] * kernels[n]["launches_per_step"])
     roof = {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": kernels[dom]["GBps"] / HBM_PEAK_GBS, "traffic": None,
+            "frac": kernels[dom]["GBps"] / HBM_PEAK_GBS,
+            "traffic": measured_traffic(dom) if cfg_id == 2 else None,
             "launch_us": kernels[dom]["avg_us"], "bytes_per_launch": kernels[dom]["bytes_per_launch"]}
 
     res = {
