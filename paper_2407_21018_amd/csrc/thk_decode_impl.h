@@ -99,6 +99,24 @@ __device__ inline void lds_row_read(const char *rowp, int t, float *f) {
   }
 }
 
+// DW consecutive 32-bit words from LDS (address aligned to DW * 4 bytes).
+template <int DW>
+__device__ inline void lds_words(const char *p, uint32_t (&w)[DW]) {
+  if constexpr (DW == 4) {
+    const u32x4 r = *(const u32x4 *)p; w[0] = r.x; w[1] = r.y; w[2] = r.z; w[3] = r.w;
+  } else if constexpr (DW == 2) {
+    const uint2 r = *(const uint2 *)p; w[0] = r.x; w[1] = r.y;
+  } else {
+    w[0] = *(const uint32_t *)p;
+  }
+}
+
+// a.lo * b.lo + a.hi * b.hi + c with a, b pairs of bf16 (v_dot2c_f32_bf16)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ inline float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
 template <int DT, int GT>
 struct TileState {
   float m[GT];                       // running max (log2 domain)
@@ -165,10 +183,12 @@ __device__ __forceinline__ void v_issue(u32x4 (&vr)[NV], const u32x4 *__restrict
 
 // One tile whose K bytes are already in LDS (kbuf): logits, running softmax,
 // acc += p.V.  vg: the tile's value rows (16-byte chunks, 128 elements per row).
-// qs: [GT][kQS] floats, entries 128..135 of every vector are zero.
+// qs: [GT][kQS] floats, entries 128..135 of every vector are zero; qp: the same
+// vectors as packed bf16 pairs, [GT][kQS / 2] words (bf16 inputs only).
 template <int DT, int GT, int RA, int TR, int NV>
 __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld,
                                              const float *__restrict__ qs,
+                                             const uint32_t *__restrict__ qp,
                                              const u32x4 *__restrict__ vg,
                                              u32x4 (&vr)[NV], const char *kbuf,
                                              float *ps, TileState<DT, GT> &st, float scale, int lane) {
@@ -190,18 +210,39 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
   float z[GT];
 #pragma unroll
   for (int g = 0; g < GT; ++g) z[g] = 0.f;
+  if constexpr (DT == THK_BF16 && RA >= 4) {
+    // bf16 pairs straight from LDS into v_dot2c_f32_bf16: products are exact, sums in fp32
+    constexpr int DW = RA / 4;   // words per granule
 #pragma unroll 2
-  for (int i = 0; i < gran0; ++i) {
-    // a lane whose share is exhausted re-reads granule 0 against the zero slot of q
-    const bool valid = (LPK == 1) || i < my_cnt;
-    const int tk = valid ? (my_first + i) * EPR : 0;
-    const int tq = valid ? tk : kD;
-    float f[EPR];
-    lds_row_read<DT, RA>(rowp, tk, f);
+    for (int i = 0; i < gran0; ++i) {
+      // a lane whose share is exhausted re-reads granule 0 against the zero slot of q
+      const bool valid = (LPK == 1) || i < my_cnt;
+      const int tk = valid ? (my_first + i) * EPR : 0;
+      const int tq = valid ? tk : kD;
+      uint32_t kw[DW];
+      lds_words<DW>(rowp + (size_t)tk * EB, kw);
 #pragma unroll
-    for (int g = 0; g < GT; ++g)
+      for (int g = 0; g < GT; ++g) {
+        uint32_t qw[DW];
+        lds_words<DW>((const char *)(qp + g * (kQS / 2) + tq / 2), qw);
 #pragma unroll
-      for (int e = 0; e < EPR; ++e) z[g] = fmaf(f[e], qs[g * kQS + tq + e], z[g]);
+        for (int d = 0; d < DW; ++d) z[g] = dot2_bf16(kw[d], qw[d], z[g]);
+      }
+    }
+  } else {
+#pragma unroll 2
+    for (int i = 0; i < gran0; ++i) {
+      // a lane whose share is exhausted re-reads granule 0 against the zero slot of q
+      const bool valid = (LPK == 1) || i < my_cnt;
+      const int tk = valid ? (my_first + i) * EPR : 0;
+      const int tq = valid ? tk : kD;
+      float f[EPR];
+      lds_row_read<DT, RA>(rowp, tk, f);
+#pragma unroll
+      for (int g = 0; g < GT; ++g)
+#pragma unroll
+        for (int e = 0; e < EPR; ++e) z[g] = fmaf(f[e], qs[g * kQS + tq + e], z[g]);
+    }
   }
   for (int t = n_gran * EPR; t < W; ++t) {   // elements past the last whole granule: share 0
     const float f = E::load1(rowp, t);
@@ -216,17 +257,29 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
 
   // ---- running softmax (base-2 exponent, scale folded in) ----------------
   // every row is held by LPK lanes, so l counts each probability LPK times
+  float pr[GT];
 #pragma unroll
   for (int g = 0; g < GT; ++g) {
     const float zz = r < nrows ? z[g] * scale : -INFINITY;
     const float m_new = fmaxf(st.m[g], wave_max(zz));   // finite: the tile has >= 1 row
-    const float corr = exp2f(st.m[g] - m_new);
-    const float p = exp2f(zz - m_new);
-    st.l[g] = st.l[g] * corr + p;
-    st.m[g] = m_new;
+    if (m_new != st.m[g]) {                             // wave-uniform; rare after the first tiles
+      const float corr = __builtin_amdgcn_exp2f(st.m[g] - m_new);
+      st.l[g] *= corr;
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) st.acc[g][v] *= corr;
-    ps[g * TR + r] = p;
+      for (int v = 0; v < VEC; ++v) st.acc[g][v] *= corr;
+      st.m[g] = m_new;
+    }
+    pr[g] = __builtin_amdgcn_exp2f(zz - m_new);
+    st.l[g] += pr[g];
+  }
+  // probabilities to LDS as [row][GT]
+  if constexpr (GT == 4) {
+    *(float4 *)(ps + r * 4) = make_float4(pr[0], pr[1], pr[2], pr[3]);
+  } else if constexpr (GT == 2) {
+    *(float2 *)(ps + r * 2) = make_float2(pr[0], pr[1]);
+  } else {
+#pragma unroll
+    for (int g = 0; g < GT; ++g) ps[r * GT + g] = pr[g];
   }
   wave_sync_lds();
 
@@ -238,12 +291,21 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
       const int row = (b * VS::NV + i) * VS::RPL + vrow;
       float f[VEC];
       E::unpack(vr[i], f);
+      float pv[GT];
+      if constexpr (GT == 4) {
+        const float4 t4 = *(const float4 *)(ps + row * 4);
+        pv[0] = t4.x; pv[1] = t4.y; pv[2] = t4.z; pv[3] = t4.w;
+      } else if constexpr (GT == 2) {
+        const float2 t2 = *(const float2 *)(ps + row * 2);
+        pv[0] = t2.x; pv[1] = t2.y;
+      } else {
 #pragma unroll
-      for (int g = 0; g < GT; ++g) {
-        const float p = ps[g * TR + row];
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) st.acc[g][v] = fmaf(p, f[v], st.acc[g][v]);
+        for (int g = 0; g < GT; ++g) pv[g] = ps[row * GT + g];
       }
+#pragma unroll
+      for (int g = 0; g < GT; ++g)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) st.acc[g][v] = fmaf(pv[g], f[v], st.acc[g][v]);
     }
     if (b + 1 < VS::NB) v_issue<DT, TR, NV>(vr, vg, nrows, b + 1, lane);
   }
@@ -261,7 +323,9 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   extern __shared__ uint4 smem[];
   float *qk = (float *)smem;                 // [GT][kQS] gathered query channels, 0 beyond T
   float *qf = qk + GT * kQS;                 // [GT][kQS] full query
-  float *mrg = qf + GT * kQS;                // [4][GT][130] per-wave states for the final merge
+  uint32_t *qkp = (uint32_t *)(qf + GT * kQS);   // [GT][kQS/2] qk as packed bf16 pairs (bf16 inputs)
+  uint32_t *qfp = qkp + GT * (kQS / 2);          // [GT][kQS/2] qf as packed bf16 pairs
+  float *mrg = (float *)(qfp + GT * (kQS / 2));  // [4][GT][130] per-wave states for the final merge
   char *wbase = (char *)(mrg + 4 * GT * (kD + 2));
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int wstride = kbuf_bytes + GT * TR * 4;
@@ -303,6 +367,17 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     qf[o] = c < kD ? E::load1(a.q, qb + c) : 0.f;
     qk[o] = c < a.T ? E::load1(a.q, qb + uidx[c]) : 0.f;
   }
+  if constexpr (DT == THK_BF16) {
+    const uint16_t *q16 = (const uint16_t *)a.q;
+    for (int o = tid; o < GT * (kQS / 2); o += 256) {
+      const int g = o / (kQS / 2), c = 2 * (o % (kQS / 2));
+      const size_t qb = (size_t)(bn0 + g) * kD;
+      const uint32_t f0 = c < kD ? q16[qb + c] : 0u, f1 = c + 1 < kD ? q16[qb + c + 1] : 0u;
+      const uint32_t k0 = c < a.T ? q16[qb + uidx[c]] : 0u, k1 = c + 1 < a.T ? q16[qb + uidx[c + 1]] : 0u;
+      qfp[o] = f0 | (f1 << 16);
+      qkp[o] = k0 | (k1 << 16);
+    }
+  }
   __syncthreads();
 
   TileState<DT, GT> st;
@@ -326,7 +401,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
       shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)(ti + 4) * TR) * a.ldk * EB, nr, a.T, a.ldk, lane);
     }
     wave_sync_lds();
-    tile_compute<DT, GT, RA, TR, NV>(shift, nrows, a.T, a.ldk, qk, vg, vr, kbuf, ps, st, a.scale_log2, lane);
+    tile_compute<DT, GT, RA, TR, NV>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st, a.scale_log2, lane);
   }
 
   // ---- unpruned tail segment (full-width keys, full query) ------------------
@@ -340,7 +415,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
     k_commit<KBT>(kt, kbuf, lane);
     wave_sync_lds();
-    tile_compute<DT, GT, 16, TR, NV>(0, nrows, kD, kD, qf, vg, vr, kbuf, ps, st, a.scale_log2, lane);
+    tile_compute<DT, GT, 16, TR, NV>(0, nrows, kD, kD, qf, qfp, vg, vr, kbuf, ps, st, a.scale_log2, lane);
   }
 
   // ---- wave state -> LDS ---------------------------------------------------
@@ -409,7 +484,7 @@ inline hipError_t decode_launch_one(const DecodeArgs &a, int groups, hipStream_t
   int kbuf = KB * kWave * 16;                      // every staged chunk has an LDS slot
   const int tailbuf = kTailRows * kD * eb;
   if (kbuf < tailbuf) kbuf = tailbuf;
-  const size_t lds = (size_t)(2 * GT * kQS + 4 * GT * (kD + 2)) * 4 + 4 * ((size_t)kbuf + GT * TR * 4);
+  const size_t lds = (size_t)(3 * GT * kQS + 4 * GT * (kD + 2)) * 4 + 4 * ((size_t)kbuf + GT * TR * 4);
   const dim3 grid((unsigned)(a.units * groups * a.n_split)), block(256);
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void *)k_decode<DT, GT, RA, KB, TR, WPE>,
