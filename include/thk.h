@@ -93,6 +93,10 @@ size_t thk_workspace_bytes(const thk_shape *shape, int32_t op);
 /* The n_split the library would use for `op` when shape->n_split == 0. */
 int32_t thk_default_split(const thk_shape *shape, int32_t op);
 
+/* 1 if thk_prune would run `shape` as one fused launch, 0 for the staged three-kernel form
+ * (or an invalid shape).  Host-only. */
+int32_t thk_prune_is_fused(const thk_shape *shape);
+
 /*
  * Query-driven channel score (Sec. 3.2, Score_i[j] = ||Q_i[-S_obs:, j] K_i[:, j]^T||_F).
  * The matrix is an outer product of two columns, so the score is

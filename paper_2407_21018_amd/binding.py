@@ -53,6 +53,8 @@ def load():
     L.thk_workspace_bytes.argtypes = [sp, i32]
     L.thk_default_split.restype = i32
     L.thk_default_split.argtypes = [sp, i32]
+    L.thk_prune_is_fused.restype = i32
+    L.thk_prune_is_fused.argtypes = [sp]
     L.thk_score.restype = ctypes.c_int
     L.thk_score.argtypes = [sp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.thk_score_magnitude.restype = ctypes.c_int
@@ -147,6 +149,10 @@ def thk_workspace_bytes(shape, op):
 
 def thk_default_split(shape, op):
     return int(load().thk_default_split(ctypes.byref(shape), op))
+
+
+def thk_prune_is_fused(shape):
+    return int(load().thk_prune_is_fused(ctypes.byref(shape)))
 
 
 def thk_score(shape, q_obs, k, score, ws, stream=None):

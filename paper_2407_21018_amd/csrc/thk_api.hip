@@ -125,7 +125,12 @@ FusedPlan fused_plan(const thk_shape *s) {
   if (path != nullptr && path[0] == 's') return p;   // "staged": the three-kernel path
   const int eb = elem_bytes(s->dtype);
   if (ld_of(s) != s->T || ((size_t)s->S * s->T * eb) % 16 != 0) return p;
-  int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 512);
+  int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 0);
+  if (rb <= 0) {
+    // 512 rows per block; small calls get shorter blocks until the launch has ~4 blocks per CU
+    rb = 512;
+    while (rb > 64 && units_of(s) * ceil_div(s->S, rb) < (int64_t)kCUs * 4) rb /= 2;
+  }
   if (rb < 32) rb = 32;
   rb = ceil_div(rb, 32) * 32;
   const int64_t nb = ceil_div(s->S, rb);
@@ -178,6 +183,11 @@ int32_t thk_default_split(const thk_shape *s, int32_t op) {
   if (op == THK_OP_SCORE) return score_split(&t, units_of(&t)).n;
   if (op == THK_OP_PRUNE) return score_split(&t, prune_group_units(&t)).n;
   return 0;
+}
+
+int32_t thk_prune_is_fused(const thk_shape *s) {
+  if (check_shape(s, true) != THK_OK) return 0;
+  return fused_plan(s).ok ? 1 : 0;
 }
 
 size_t thk_workspace_bytes(const thk_shape *s, int32_t op) {
