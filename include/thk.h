@@ -13,11 +13,12 @@
  *   - Argument errors are reported synchronously and enqueue nothing.  A launch
  *     failure is reported as THK_ERR_HIP.
  *   - Dense row-major layouts, last index contiguous:
- *       K, V      [L][B][N_kv][S][D]
+ *       K         [L][B][N_kv][S][D]         (prefill keys, input of score / compaction)
+ *       V         [L][B][N_kv][S_cap][D]     (decode; S_cap = S unless set)
  *       Q_obs     [L][B][N_q ][S_obs][D]
  *       score     [L][B][N_kv][D]            float
  *       idx       [L][B][N_kv][T]            int16, 0-based, ascending
- *       K_pruned  [L][B][N_kv][S][ld_keep]   element type of K
+ *       K_pruned  [L][B][N_kv][S_cap][ld_keep]  element type of K; S_cap = S unless set
  *       q, out    [L][B][N_q ][D]
  *       K_tail, V_tail [L][B][N_kv][S_tail_cap][D]
  *     Query head n reads KV head n / (N_q / N_kv).
@@ -67,6 +68,10 @@ typedef struct {
   int32_t ld_keep; /* row stride of K_pruned in elements, >= T; 0 means T        */
   int32_t dtype;   /* thk_dtype of Q, K, V, K_pruned, out                        */
   int32_t n_split; /* pieces the S axis is cut into per unit; 0 = library choice */
+  int32_t S_recent;/* prune: the last S_recent of the S scored keys are NOT compacted    */
+                   /* (they stay at full width with the caller); 0 <= S_recent < S       */
+  int64_t S_cap;   /* rows allocated per unit in K_pruned and V (cache capacity), >= the */
+                   /* rows in use; 0 means dense: S (S - S_recent for thk_prune's output)*/
 } thk_shape;
 
 /* Library version, major*10000 + minor*100 + patch. */
@@ -130,8 +135,8 @@ thk_status thk_select_topk(const thk_shape *shape, const float *score,
 
 /*
  * K_pruned[s][t] = K[s][idx[t]] -- a bit copy of the kept channels (Fig. 1;
- * Sec. 3.3 "pruned keys with a reduced channel size").  Columns [T, ld_keep)
- * of K_pruned are not written.  idx entries must lie in [0, D).
+ * Sec. 3.3 "pruned keys with a reduced channel size") for rows s < S - S_recent.
+ * Columns [T, ld_keep) of K_pruned are not written.  idx entries must lie in [0, D).
  */
 thk_status thk_compact_keys(const thk_shape *shape, const void *k,
                             const int16_t *idx, void *k_pruned, void *stream);
@@ -158,7 +163,9 @@ thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,
  *   out[n]  = softmax(z) . [V ; V_tail]
  * one softmax over all S + s_tail logits; sqrt(D) uses the original D.  fp32
  * arithmetic; out has the input element type (bf16: round to nearest even).
- * k_tail / v_tail may be NULL iff s_tail == 0; 0 <= s_tail <= s_tail_cap.
+ * k_tail may be NULL iff s_tail == 0; 0 <= s_tail <= s_tail_cap.  v_tail == NULL
+ * with s_tail > 0 selects the unified value cache: the tail's value rows are rows
+ * [S, S + s_tail) of v (needs S_cap >= S + s_tail).
  * S_obs in the shape is ignored.  With n_split > 1 partial (max, sum, acc[D])
  * states go through ws and a second kernel merges them in split order without
  * atomics, so repeated calls give identical bits.
@@ -181,6 +188,40 @@ thk_status thk_decode_attn(const thk_shape *shape, const void *q,
 thk_status thk_tail_append(const thk_shape *shape, const void *k_new,
                            const void *v_new, void *k_tail, void *v_tail,
                            int32_t s_tail, int32_t s_tail_cap, void *stream);
+
+/*
+ * Cache growth (Sec. 3.3: recent and newly generated keys stay un-pruned; Appendix
+ * "Implementation with quantization": a residual buffer of new tokens is pruned
+ * with the stored mask and appended once it is full).
+ *
+ * thk_compact_rows: K_pruned[u][dst_row0 + r][t] = src[u][src_row0 + r][idx[u][t]],
+ *   r < n_rows, for every unit u.  src has src_unit_rows rows of D per unit (the
+ *   prefill K with src_unit_rows = S, or a tail buffer with src_unit_rows = cap);
+ *   K_pruned has S_cap rows per unit (shape->S_cap, 0 = shape->S).  shape->S is
+ *   not otherwise used.  Requires dst_row0 + n_rows <= rows per unit of K_pruned.
+ * thk_copy_rows: dst[u][dst_row0 + r][:] = src[u][src_row0 + r][:], r < n_rows, rows of
+ *   D elements.  src and dst may be the same buffer when dst_row0 <= src_row0.
+ * thk_cache_append: K_tail[u][s_tail] = k_new[u]; V[u][S + s_tail] = v_new[u]
+ *   (unified value cache, S_cap rows per unit; needs S + s_tail < S_cap).
+ * thk_tail_flush: the n_flush oldest tail keys are compacted with the stored index
+ *   list into K_pruned rows [S, S + n_flush) and the remaining s_tail - n_flush tail
+ *   rows move to the front of the tail.  With a separate value tail (v, v_tail not
+ *   NULL) the flushed value rows are copied into V rows [S, S + n_flush) and v_tail
+ *   is shifted likewise; with the unified value cache pass v = v_tail = NULL.  The
+ *   caller then uses S + n_flush and s_tail - n_flush.
+ */
+thk_status thk_compact_rows(const thk_shape *shape, const void *src, int64_t src_unit_rows,
+                            int64_t src_row0, const int16_t *idx, void *k_pruned,
+                            int64_t dst_row0, int64_t n_rows, void *stream);
+thk_status thk_copy_rows(const thk_shape *shape, const void *src, int64_t src_unit_rows,
+                         int64_t src_row0, void *dst, int64_t dst_unit_rows, int64_t dst_row0,
+                         int64_t n_rows, void *stream);
+thk_status thk_cache_append(const thk_shape *shape, const void *k_new, const void *v_new,
+                            void *k_tail, void *v, int32_t s_tail, int32_t s_tail_cap,
+                            void *stream);
+thk_status thk_tail_flush(const thk_shape *shape, const int16_t *idx, void *k_pruned,
+                          void *k_tail, void *v, void *v_tail, int32_t s_tail,
+                          int32_t s_tail_cap, int32_t n_flush, void *stream);
 
 /*
  * Timing hook for benchmarks: the NEXT thk_prune or thk_decode_attn call made by

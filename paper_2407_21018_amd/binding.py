@@ -24,7 +24,8 @@ class thk_shape(ctypes.Structure):
     _fields_ = [("L", ctypes.c_int32), ("B", ctypes.c_int32), ("N_q", ctypes.c_int32),
                 ("N_kv", ctypes.c_int32), ("D", ctypes.c_int32), ("S", ctypes.c_int64),
                 ("S_obs", ctypes.c_int32), ("T", ctypes.c_int32), ("ld_keep", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("n_split", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("n_split", ctypes.c_int32), ("S_recent", ctypes.c_int32),
+                ("S_cap", ctypes.c_int64)]
 
 
 _lib = None
@@ -67,6 +68,15 @@ def load():
     L.thk_prune.argtypes = [sp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.thk_decode_attn.restype = ctypes.c_int
     L.thk_decode_attn.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    i64 = ctypes.c_int64
+    L.thk_compact_rows.restype = ctypes.c_int
+    L.thk_compact_rows.argtypes = [sp, vp, i64, i64, vp, vp, i64, i64, vp]
+    L.thk_copy_rows.restype = ctypes.c_int
+    L.thk_copy_rows.argtypes = [sp, vp, i64, i64, vp, i64, i64, i64, vp]
+    L.thk_cache_append.restype = ctypes.c_int
+    L.thk_cache_append.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp]
+    L.thk_tail_flush.restype = ctypes.c_int
+    L.thk_tail_flush.argtypes = [sp, vp, vp, vp, vp, vp, i32, i32, i32, vp]
     L.thk_profile_next.restype = None
     L.thk_profile_next.argtypes = [vp, vp]
     L.thk_tail_append.restype = ctypes.c_int
@@ -75,8 +85,8 @@ def load():
     return L
 
 
-def make_shape(L, B, N_q, N_kv, D, S, S_obs, T, ld_keep=0, dtype=THK_BF16, n_split=0):
-    return thk_shape(L, B, N_q, N_kv, D, S, S_obs, T, ld_keep, dtype, n_split)
+def make_shape(L, B, N_q, N_kv, D, S, S_obs, T, ld_keep=0, dtype=THK_BF16, n_split=0, S_recent=0, S_cap=0):
+    return thk_shape(L, B, N_q, N_kv, D, S, S_obs, T, ld_keep, dtype, n_split, S_recent, S_cap)
 
 
 def _ptr(x):
@@ -124,6 +134,10 @@ def _dims(s):
     U = s.L * s.B * s.N_kv
     H = s.L * s.B * s.N_q
     return U, H, (s.ld_keep or s.T)
+
+
+def _cache_rows(s, used):
+    return s.S_cap or used
 
 
 def _check(st, where):
@@ -184,7 +198,7 @@ def thk_compact_keys(shape, k, idx, k_pruned, stream=None):
     U, _, ld = _dims(shape)
     _need(k, U * shape.S * shape.D, "k", "thk_compact_keys")
     _need(idx, U * shape.T, "idx", "thk_compact_keys")
-    _need(k_pruned, U * shape.S * ld, "k_pruned", "thk_compact_keys")
+    _need(k_pruned, U * _cache_rows(shape, shape.S - shape.S_recent) * ld, "k_pruned", "thk_compact_keys")
     _check(load().thk_compact_keys(ctypes.byref(shape), _ptr(k), _ptr(idx), _ptr(k_pruned),
                                    _stream(stream)), "thk_compact_keys")
 
@@ -195,7 +209,7 @@ def thk_prune(shape, q_obs, k, score, idx, k_pruned, ws, stream=None):
     _need(k, U * shape.S * shape.D, "k", "thk_prune")
     _need(score, U * shape.D, "score", "thk_prune")
     _need(idx, U * shape.T, "idx", "thk_prune")
-    _need(k_pruned, U * shape.S * ld, "k_pruned", "thk_prune")
+    _need(k_pruned, U * _cache_rows(shape, shape.S - shape.S_recent) * ld, "k_pruned", "thk_prune")
     _check(load().thk_prune(ctypes.byref(shape), _ptr(q_obs), _ptr(k), _ptr(score), _ptr(idx),
                             _ptr(k_pruned), _ws(ws), _nbytes(ws), _stream(stream)), "thk_prune")
 
@@ -206,9 +220,10 @@ def thk_decode_attn(shape, q, k_pruned, idx, v, k_tail, v_tail, s_tail, s_tail_c
     w = "thk_decode_attn"
     _need(q, H * shape.D, "q", w)
     _need(out, H * shape.D, "out", w)
-    _need(k_pruned, U * shape.S * ld, "k_pruned", w)
+    rows = _cache_rows(shape, shape.S)
+    _need(k_pruned, U * rows * ld, "k_pruned", w)
     _need(idx, U * shape.T, "idx", w)
-    _need(v, U * shape.S * shape.D, "v", w)
+    _need(v, U * rows * shape.D, "v", w)
     if s_tail > 0:
         _need(k_tail, U * s_tail_cap * shape.D, "k_tail", w)
         _need(v_tail, U * s_tail_cap * shape.D, "v_tail", w)
@@ -226,6 +241,45 @@ def thk_tail_append(shape, k_new, v_new, k_tail, v_tail, s_tail, s_tail_cap, str
     _check(load().thk_tail_append(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(k_tail),
                                   _ptr(v_tail), s_tail, s_tail_cap, _stream(stream)),
            "thk_tail_append")
+
+
+def thk_compact_rows(shape, src, src_unit_rows, src_row0, idx, k_pruned, dst_row0, n_rows, stream=None):
+    U, _, ld = _dims(shape)
+    _need(src, U * src_unit_rows * shape.D, "src", "thk_compact_rows")
+    _need(idx, U * shape.T, "idx", "thk_compact_rows")
+    _need(k_pruned, U * _cache_rows(shape, shape.S) * ld, "k_pruned", "thk_compact_rows")
+    _check(load().thk_compact_rows(ctypes.byref(shape), _ptr(src), src_unit_rows, src_row0, _ptr(idx),
+                                   _ptr(k_pruned), dst_row0, n_rows, _stream(stream)), "thk_compact_rows")
+
+
+def thk_copy_rows(shape, src, src_unit_rows, src_row0, dst, dst_unit_rows, dst_row0, n_rows, stream=None):
+    U, _, _ = _dims(shape)
+    _need(src, U * src_unit_rows * shape.D, "src", "thk_copy_rows")
+    _need(dst, U * dst_unit_rows * shape.D, "dst", "thk_copy_rows")
+    _check(load().thk_copy_rows(ctypes.byref(shape), _ptr(src), src_unit_rows, src_row0, _ptr(dst),
+                                dst_unit_rows, dst_row0, n_rows, _stream(stream)), "thk_copy_rows")
+
+
+def thk_cache_append(shape, k_new, v_new, k_tail, v, s_tail, s_tail_cap, stream=None):
+    U, _, _ = _dims(shape)
+    _need(k_new, U * shape.D, "k_new", "thk_cache_append")
+    _need(v_new, U * shape.D, "v_new", "thk_cache_append")
+    _need(k_tail, U * s_tail_cap * shape.D, "k_tail", "thk_cache_append")
+    _need(v, U * _cache_rows(shape, shape.S) * shape.D, "v", "thk_cache_append")
+    _check(load().thk_cache_append(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(k_tail), _ptr(v),
+                                   s_tail, s_tail_cap, _stream(stream)), "thk_cache_append")
+
+
+def thk_tail_flush(shape, idx, k_pruned, k_tail, v, v_tail, s_tail, s_tail_cap, n_flush, stream=None):
+    U, _, ld = _dims(shape)
+    rows = _cache_rows(shape, shape.S)
+    _need(idx, U * shape.T, "idx", "thk_tail_flush")
+    _need(k_pruned, U * rows * ld, "k_pruned", "thk_tail_flush")
+    _need(k_tail, U * s_tail_cap * shape.D, "k_tail", "thk_tail_flush")
+    _need(v, U * rows * shape.D, "v", "thk_tail_flush")
+    _need(v_tail, U * s_tail_cap * shape.D, "v_tail", "thk_tail_flush")
+    _check(load().thk_tail_flush(ctypes.byref(shape), _ptr(idx), _ptr(k_pruned), _ptr(k_tail), _ptr(v),
+                                 _ptr(v_tail), s_tail, s_tail_cap, n_flush, _stream(stream)), "thk_tail_flush")
 
 
 def thk_profile_next(ev_start, ev_stop):

@@ -29,6 +29,9 @@ inline int elem_bytes(int dtype) { return dtype == THK_BF16 ? 2 : 4; }
 inline int64_t units_of(const thk_shape *s) { return (int64_t)s->L * s->B * s->N_kv; }
 inline int ld_of(const thk_shape *s) { return s->ld_keep ? s->ld_keep : s->T; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+// rows of the prunable segment that get compacted, and rows between units of K_pruned / V
+inline int64_t keep_rows(const thk_shape *s) { return s->S - s->S_recent; }
+inline int64_t cache_rows(const thk_shape *s, int64_t used) { return s->S_cap ? s->S_cap : used; }
 
 constexpr int kMaxSplit = 4096;
 constexpr int64_t kMaxGrid = 2147483647LL;
@@ -42,6 +45,8 @@ thk_status check_shape(const thk_shape *s, bool need_obs) {
   if (s->ld_keep != 0 && s->ld_keep < s->T) return THK_ERR_SHAPE;
   if (need_obs && (s->S_obs < 1 || (int64_t)s->S_obs > s->S)) return THK_ERR_SHAPE;
   if (s->n_split < 0 || s->n_split > kMaxSplit) return THK_ERR_SHAPE;
+  if (s->S_recent < 0 || (int64_t)s->S_recent >= s->S) return THK_ERR_SHAPE;
+  if (s->S_cap < 0) return THK_ERR_SHAPE;
   if (s->dtype != THK_F32 && s->dtype != THK_BF16) return THK_ERR_UNSUPPORTED;
   if (s->D != kD) return THK_ERR_UNSUPPORTED;
   if (s->S > (int64_t)1 << 40 || units_of(s) > kMaxGrid) return THK_ERR_SHAPE;
@@ -124,7 +129,9 @@ FusedPlan fused_plan(const thk_shape *s) {
   const char *path = getenv("THK_PRUNE_PATH");
   if (path != nullptr && path[0] == 's') return p;   // "staged": the three-kernel path
   const int eb = elem_bytes(s->dtype);
-  if (ld_of(s) != s->T || ((size_t)s->S * s->T * eb) % 16 != 0) return p;
+  if (s->S_cap != 0 && s->S_cap < keep_rows(s)) return p;
+  if (!compact_is_flat(s->dtype, s->T, ld_of(s), cache_rows(s, keep_rows(s)), 0, keep_rows(s))) return p;
+  (void)eb;
   int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 0);
   if (rb <= 0) {
     // 512 rows per block; small calls get shorter blocks until the launch has ~4 blocks per CU
@@ -260,8 +267,90 @@ thk_status thk_compact_keys(const thk_shape *s, const void *k, const int16_t *id
   if (k == nullptr || idx == nullptr || k_pruned == nullptr) return THK_ERR_NULL;
   if (!aligned16(k) || !aligned16(idx) || !aligned16(k_pruned)) return THK_ERR_ALIGN;
   if (units_of(s) * ceil_div(s->S, 512) > kMaxGrid) return THK_ERR_SHAPE;
-  if (launch_compact(s->dtype, k, idx, k_pruned, units_of(s), s->S, s->T, ld_of(s), (hipStream_t)stream) != hipSuccess)
+  if (s->S_cap != 0 && s->S_cap < keep_rows(s)) return THK_ERR_SHAPE;
+  if (launch_compact(s->dtype, k, s->S, 0, idx, k_pruned, cache_rows(s, keep_rows(s)), 0, units_of(s),
+                     keep_rows(s), s->T, ld_of(s), (hipStream_t)stream) != hipSuccess)
     return THK_ERR_HIP;
+  return THK_OK;
+}
+
+thk_status thk_compact_rows(const thk_shape *s, const void *src, int64_t src_unit_rows, int64_t src_row0,
+                            const int16_t *idx, void *k_pruned, int64_t dst_row0, int64_t n_rows,
+                            void *stream) {
+  thk_status st = check_shape(s, false);
+  if (st != THK_OK) return st;
+  if (src == nullptr || idx == nullptr || k_pruned == nullptr) return THK_ERR_NULL;
+  const int64_t dst_unit_rows = cache_rows(s, s->S);
+  if (n_rows < 0 || src_row0 < 0 || dst_row0 < 0 || src_row0 + n_rows > src_unit_rows ||
+      dst_row0 + n_rows > dst_unit_rows)
+    return THK_ERR_SHAPE;
+  if (!aligned16(src) || !aligned16(idx) || !aligned16(k_pruned)) return THK_ERR_ALIGN;
+  if (units_of(s) * ceil_div(n_rows > 0 ? n_rows : 1, 512) > kMaxGrid) return THK_ERR_SHAPE;
+  if (launch_compact(s->dtype, src, src_unit_rows, src_row0, idx, k_pruned, dst_unit_rows, dst_row0,
+                     units_of(s), n_rows, s->T, ld_of(s), (hipStream_t)stream) != hipSuccess)
+    return THK_ERR_HIP;
+  return THK_OK;
+}
+
+thk_status thk_copy_rows(const thk_shape *s, const void *src, int64_t src_unit_rows, int64_t src_row0,
+                         void *dst, int64_t dst_unit_rows, int64_t dst_row0, int64_t n_rows,
+                         void *stream) {
+  thk_status st = check_shape(s, false);
+  if (st != THK_OK) return st;
+  if (src == nullptr || dst == nullptr) return THK_ERR_NULL;
+  if (n_rows < 0 || src_row0 < 0 || dst_row0 < 0 || src_row0 + n_rows > src_unit_rows ||
+      dst_row0 + n_rows > dst_unit_rows)
+    return THK_ERR_SHAPE;
+  if (src == dst && (dst_unit_rows != src_unit_rows || dst_row0 > src_row0)) return THK_ERR_SHAPE;
+  if (!aligned16(src) || !aligned16(dst)) return THK_ERR_ALIGN;
+  if (launch_copy_rows(s->dtype, src, src_unit_rows, src_row0, dst, dst_unit_rows, dst_row0, units_of(s),
+                       n_rows, (hipStream_t)stream) != hipSuccess)
+    return THK_ERR_HIP;
+  return THK_OK;
+}
+
+thk_status thk_cache_append(const thk_shape *s, const void *k_new, const void *v_new, void *k_tail,
+                            void *v, int32_t s_tail, int32_t s_tail_cap, void *stream) {
+  thk_status st = check_shape(s, false);
+  if (st != THK_OK) return st;
+  if (k_new == nullptr || v_new == nullptr || k_tail == nullptr || v == nullptr) return THK_ERR_NULL;
+  if (s_tail < 0 || s_tail >= s_tail_cap) return THK_ERR_SHAPE;
+  if (s->S + s_tail >= cache_rows(s, s->S)) return THK_ERR_SHAPE;   // the value cache is full
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_tail) || !aligned16(v)) return THK_ERR_ALIGN;
+  if (launch_tail_append(s->dtype, k_new, v_new, k_tail, v, units_of(s), s_tail_cap, s_tail,
+                         cache_rows(s, s->S), s->S + s_tail, (hipStream_t)stream) != hipSuccess)
+    return THK_ERR_HIP;
+  return THK_OK;
+}
+
+thk_status thk_tail_flush(const thk_shape *s, const int16_t *idx, void *k_pruned, void *k_tail, void *v,
+                          void *v_tail, int32_t s_tail, int32_t s_tail_cap, int32_t n_flush,
+                          void *stream) {
+  thk_status st = check_shape(s, false);
+  if (st != THK_OK) return st;
+  if (idx == nullptr || k_pruned == nullptr || k_tail == nullptr) return THK_ERR_NULL;
+  if ((v == nullptr) != (v_tail == nullptr)) return THK_ERR_NULL;
+  if (s_tail < 0 || s_tail > s_tail_cap || n_flush < 0 || n_flush > s_tail) return THK_ERR_SHAPE;
+  const int64_t unit_rows = cache_rows(s, s->S);
+  if (s->S + n_flush > unit_rows) return THK_ERR_SHAPE;   // no room left in the pruned cache
+  if (!aligned16(idx) || !aligned16(k_pruned) || !aligned16(k_tail) ||
+      (v != nullptr && (!aligned16(v) || !aligned16(v_tail))))
+    return THK_ERR_ALIGN;
+  hipStream_t hs = (hipStream_t)stream;
+  const int64_t U = units_of(s);
+  if (launch_compact(s->dtype, k_tail, s_tail_cap, 0, idx, k_pruned, unit_rows, s->S, U, n_flush, s->T,
+                     ld_of(s), hs) != hipSuccess)
+    return THK_ERR_HIP;
+  if (launch_copy_rows(s->dtype, k_tail, s_tail_cap, n_flush, k_tail, s_tail_cap, 0, U, s_tail - n_flush,
+                       hs) != hipSuccess)
+    return THK_ERR_HIP;
+  if (v != nullptr) {
+    if (launch_copy_rows(s->dtype, v_tail, s_tail_cap, 0, v, unit_rows, s->S, U, n_flush, hs) != hipSuccess)
+      return THK_ERR_HIP;
+    if (launch_copy_rows(s->dtype, v_tail, s_tail_cap, n_flush, v_tail, s_tail_cap, 0, U, s_tail - n_flush,
+                         hs) != hipSuccess)
+      return THK_ERR_HIP;
+  }
   return THK_OK;
 }
 
@@ -282,12 +371,15 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
   const FusedPlan fp = fused_plan(s);
   if (fp.ok) {
     const int spin = (int)env_long("THK_PRUNE_SPIN_LIMIT", 4096);
-    if (launch_prune_fused(s->dtype, q_obs, k, sc, idx, k_pruned, ws, U, s->S, G, s->S_obs, s->T, fp.NB,
-                           fp.RB, spin < 0 ? 0 : spin, hs) != hipSuccess)
+    if (launch_prune_fused(s->dtype, q_obs, k, sc, idx, k_pruned, ws, U, s->S, keep_rows(s),
+                           cache_rows(s, keep_rows(s)), G, s->S_obs, s->T, fp.NB, fp.RB, spin < 0 ? 0 : spin,
+                           hs) != hipSuccess)
       return THK_ERR_HIP;
     return THK_OK;
   }
   // staged path: score -> select -> compact per group of units
+  if (s->S_cap != 0 && s->S_cap < keep_rows(s)) return THK_ERR_SHAPE;
+  const int64_t kp_rows = cache_rows(s, keep_rows(s));
   const int64_t gu = prune_group_units(s);
   const Split sp = score_split(s, gu);
   if (gu * sp.n > kMaxGrid || gu * ceil_div(s->S, 512) > kMaxGrid) return THK_ERR_SHAPE;
@@ -304,8 +396,9 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
                         s->S_obs, sp.n, s->T, hs) != hipSuccess)
       return THK_ERR_HIP;
     profile_mark(true, hs);
-    const hipError_t ce = launch_compact(s->dtype, kg, idx + (size_t)u0 * s->T,
-                                         (char *)k_pruned + (size_t)u0 * s->S * ld * eb, nu, s->S, s->T, ld, hs);
+    const hipError_t ce = launch_compact(s->dtype, kg, s->S, 0, idx + (size_t)u0 * s->T,
+                                         (char *)k_pruned + (size_t)u0 * kp_rows * ld * eb, kp_rows, 0, nu,
+                                         keep_rows(s), s->T, ld, hs);
     profile_mark(false, hs);
     if (ce != hipSuccess) return THK_ERR_HIP;
   }
@@ -320,9 +413,12 @@ thk_status thk_decode_attn(const thk_shape *s, const void *q, const void *k_prun
   if (st != THK_OK) return st;
   if (q == nullptr || k_pruned == nullptr || idx == nullptr || v == nullptr || out == nullptr) return THK_ERR_NULL;
   if (s_tail < 0 || s_tail_cap < 0 || s_tail > s_tail_cap) return THK_ERR_SHAPE;
-  if (s_tail > 0 && (k_tail == nullptr || v_tail == nullptr)) return THK_ERR_NULL;
+  if (s_tail > 0 && k_tail == nullptr) return THK_ERR_NULL;
+  const bool unified_v = s_tail > 0 && v_tail == nullptr;   // tail values follow row S in v
+  const int64_t unit_rows = cache_rows(s, s->S);
+  if (unit_rows < s->S + (unified_v ? s_tail : 0)) return THK_ERR_SHAPE;
   if (!aligned16(q) || !aligned16(k_pruned) || !aligned16(idx) || !aligned16(v) || !aligned16(out) ||
-      (s_tail > 0 && (!aligned16(k_tail) || !aligned16(v_tail))))
+      (s_tail > 0 && (!aligned16(k_tail) || (v_tail != nullptr && !aligned16(v_tail)))))
     return THK_ERR_ALIGN;
   const Split sp = decode_split(s);
   const int G = s->N_q / s->N_kv;
@@ -336,7 +432,8 @@ thk_status thk_decode_attn(const thk_shape *s, const void *q, const void *k_prun
   a.T = s->T; a.ldk = ld_of(s); a.N_q = s->N_q; a.N_kv = s->N_kv;
   a.s_tail = s_tail; a.s_tail_cap = s_tail_cap; a.n_split = sp.n; a.dtype = s->dtype;
   a.units = units_of(s);
-  a.kp_bytes = (size_t)a.units * s->S * a.ldk * elem_bytes(s->dtype);
+  a.unit_rows = unit_rows;
+  a.unified_v = unified_v ? 1 : 0;
   a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)s->D));
   if (launch_decode(a, (hipStream_t)stream) != hipSuccess) return THK_ERR_HIP;
   return THK_OK;
@@ -349,8 +446,8 @@ thk_status thk_tail_append(const thk_shape *s, const void *k_new, const void *v_
   if (k_new == nullptr || v_new == nullptr || k_tail == nullptr || v_tail == nullptr) return THK_ERR_NULL;
   if (s_tail < 0 || s_tail >= s_tail_cap) return THK_ERR_SHAPE;
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_tail) || !aligned16(v_tail)) return THK_ERR_ALIGN;
-  if (launch_tail_append(s->dtype, k_new, v_new, k_tail, v_tail, units_of(s), s_tail, s_tail_cap,
-                         (hipStream_t)stream) != hipSuccess)
+  if (launch_tail_append(s->dtype, k_new, v_new, k_tail, v_tail, units_of(s), s_tail_cap, s_tail, s_tail_cap,
+                         s_tail, (hipStream_t)stream) != hipSuccess)
     return THK_ERR_HIP;
   return THK_OK;
 }

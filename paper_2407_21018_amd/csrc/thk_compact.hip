@@ -1,103 +1,151 @@
-// Key compaction K_pruned[s][t] = K[s][idx[t]] (Fig. 1; Sec. 3.3) and the
-// tail append (gfx950, wave64).  Pure byte movement: no arithmetic on values.
+// Key compaction K_pruned[s][t] = K[s][idx[t]] (Fig. 1; Sec. 3.3), full-width row
+// copies and the tail append (gfx950, wave64).  Pure byte movement: no arithmetic
+// on values.
 #include <type_traits>
 
 #include "thk_prune_device.h"
 
 namespace thk {
 
-// Flat path: K_pruned rows dense (ld_keep == T) and every unit of K_pruned
-// starting on a 16-byte boundary, so that a slab of whole rows is a run of whole
-// 16-byte chunks (see compact_rows).
+// Flat path: K_pruned rows dense (ld_keep == T) and the destination slab of every
+// unit starting on a 16-byte boundary, so that a run of whole rows is a run of
+// whole 16-byte chunks (see compact_rows).
 template <int DT>
-__global__ __launch_bounds__(256) void k_compact_flat(const void *__restrict__ k,
-                                                      const int16_t *__restrict__ idx,
-                                                      void *__restrict__ kp, int64_t S, int T,
-                                                      int blocks_per_unit, int64_t rows_per_block) {
+__global__ __launch_bounds__(256) void k_compact_flat(CompactArgs a) {
   using E = Elem<DT>;
   extern __shared__ u32x4 smem[];
   uint16_t *tab = (uint16_t *)smem;                       // [8 * T], padded to 2 KiB
-  const int64_t u = blockIdx.x / blocks_per_unit;
-  const int blk = (int)(blockIdx.x % blocks_per_unit);
-  const int64_t s0 = (int64_t)blk * rows_per_block;
-  const int64_t s1 = min(S, s0 + rows_per_block);
-  compact_build_tab(tab, idx + (size_t)u * T, T);
+  const int64_t u = blockIdx.x / a.blocks_per_unit;
+  const int blk = (int)(blockIdx.x % a.blocks_per_unit);
+  const int64_t s0 = (int64_t)blk * a.rows_per_block;
+  const int64_t s1 = min(a.n_rows, s0 + a.rows_per_block);
+  compact_build_tab(tab, a.idx + (size_t)u * a.T, a.T);
   __syncthreads();
-  compact_rows<DT>((const u32x4 *)((const char *)k + (size_t)u * S * kD * E::EB),
-                   (u32x4 *)((char *)kp + (size_t)u * S * T * E::EB), s0, s1, T, tab, smem + 128);
+  compact_rows<DT>((const u32x4 *)((const char *)a.src + ((size_t)u * a.src_unit_rows + a.src_row0) * kD * E::EB),
+                   (u32x4 *)((char *)a.dst + ((size_t)u * a.dst_unit_rows + a.dst_row0) * a.T * E::EB),
+                   s0, s1, a.T, tab, smem + 128);
 }
 
 // Element-wise path for padded or unaligned K_pruned layouts.
 template <int DT>
-__global__ __launch_bounds__(256) void k_compact_generic(const void *__restrict__ k,
-                                                         const int16_t *__restrict__ idx,
-                                                         void *__restrict__ kp, int64_t S, int T,
-                                                         int ld, int blocks_per_unit,
-                                                         int64_t rows_per_block) {
+__global__ __launch_bounds__(256) void k_compact_generic(CompactArgs a) {
   using ET = typename std::conditional<DT == THK_BF16, uint16_t, uint32_t>::type;
-  const int64_t u = blockIdx.x / blocks_per_unit;
-  const int blk = (int)(blockIdx.x % blocks_per_unit);
-  const int64_t s0 = (int64_t)blk * rows_per_block;
-  const int64_t s1 = min(S, s0 + rows_per_block);
-  const ET *src = (const ET *)k + (size_t)u * S * kD;
-  ET *dst = (ET *)kp + (size_t)u * S * ld;
-  const int16_t *uidx = idx + (size_t)u * T;
-  const int64_t n = (s1 - s0) * T;
+  const int64_t u = blockIdx.x / a.blocks_per_unit;
+  const int blk = (int)(blockIdx.x % a.blocks_per_unit);
+  const int64_t s0 = (int64_t)blk * a.rows_per_block;
+  const int64_t s1 = min(a.n_rows, s0 + a.rows_per_block);
+  const ET *src = (const ET *)a.src + ((size_t)u * a.src_unit_rows + a.src_row0) * kD;
+  ET *dst = (ET *)a.dst + ((size_t)u * a.dst_unit_rows + a.dst_row0) * a.ld;
+  const int16_t *uidx = a.idx + (size_t)u * a.T;
+  const int64_t n = (s1 - s0) * a.T;
   for (int64_t e = threadIdx.x; e < n; e += 256) {
-    const int64_t s = s0 + e / T;
-    const int t = (int)(e % T);
-    dst[(size_t)s * ld + t] = src[(size_t)s * kD + uidx[t]];
+    const int64_t s = s0 + e / a.T;
+    const int t = (int)(e % a.T);
+    dst[(size_t)s * a.ld + t] = src[(size_t)s * kD + uidx[t]];
   }
 }
 
+// Full-width row copy dst[u][dst_row0 + r][:] = src[u][src_row0 + r][:], r < n_rows.
+// One block per unit; rows move in ascending chunks, each chunk loaded completely
+// before any of it is stored, so a downward shift inside one buffer
+// (dst_row0 <= src_row0) is safe.
+template <int DT>
+__global__ __launch_bounds__(256) void k_copy_rows(const void *__restrict__ src, void *dst,
+                                                   int64_t src_unit_rows, int64_t src_row0,
+                                                   int64_t dst_unit_rows, int64_t dst_row0,
+                                                   int64_t n_rows) {
+  using E = Elem<DT>;
+  constexpr int CPR = kD / E::VEC;     // 16-byte chunks per row
+  constexpr int PER = 8;               // chunks per thread per pass
+  const int64_t u = blockIdx.x;
+  const u32x4 *s = (const u32x4 *)src + ((size_t)u * src_unit_rows + src_row0) * CPR;
+  u32x4 *d = (u32x4 *)dst + ((size_t)u * dst_unit_rows + dst_row0) * CPR;
+  const int64_t total = n_rows * CPR;
+  for (int64_t c0 = 0; c0 < total; c0 += 256 * PER) {
+    u32x4 r[PER];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int64_t c = c0 + (int64_t)j * 256 + threadIdx.x;
+      if (c < total) r[j] = s[c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int64_t c = c0 + (int64_t)j * 256 + threadIdx.x;
+      if (c < total) d[c] = r[j];
+    }
+    __syncthreads();
+  }
+}
+
+// One new token per unit: K_tail[u][k_row] = k_new[u], Vdst[u][v_row] = v_new[u].
 template <int DT>
 __global__ __launch_bounds__(256) void k_tail_append(const void *__restrict__ k_new,
                                                      const void *__restrict__ v_new,
-                                                     void *__restrict__ k_tail,
-                                                     void *__restrict__ v_tail, int64_t U,
-                                                     int s_tail, int cap) {
+                                                     void *__restrict__ k_dst, void *__restrict__ v_dst,
+                                                     int64_t U, int64_t k_unit_rows, int64_t k_row,
+                                                     int64_t v_unit_rows, int64_t v_row) {
   using E = Elem<DT>;
   constexpr int CPR = kD / E::VEC;   // 16-byte chunks per row
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= U * CPR) return;
   const int64_t u = i / CPR;
   const int c = (int)(i % CPR);
-  const size_t d = ((size_t)u * cap + s_tail) * CPR + c;
-  ((uint4 *)k_tail)[d] = ((const uint4 *)k_new)[i];
-  ((uint4 *)v_tail)[d] = ((const uint4 *)v_new)[i];
+  ((u32x4 *)k_dst)[((size_t)u * k_unit_rows + k_row) * CPR + c] = ((const u32x4 *)k_new)[i];
+  ((u32x4 *)v_dst)[((size_t)u * v_unit_rows + v_row) * CPR + c] = ((const u32x4 *)v_new)[i];
 }
 
-hipError_t launch_compact(int dtype, const void *k, const int16_t *idx, void *kp, int64_t U,
-                          int64_t S, int T, int ld_keep, hipStream_t st) {
+bool compact_is_flat(int dtype, int T, int ld_keep, int64_t dst_unit_rows, int64_t dst_row0, int64_t n_rows) {
+  const size_t rowb = (size_t)T * (dtype == THK_BF16 ? 2 : 4);
+  return ld_keep == T && (dst_unit_rows * rowb) % 16 == 0 && (dst_row0 * rowb) % 16 == 0 &&
+         (n_rows * rowb) % 16 == 0;
+}
+
+hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0,
+                          const int16_t *idx, void *dst, int64_t dst_unit_rows, int64_t dst_row0,
+                          int64_t U, int64_t n_rows, int T, int ld_keep, hipStream_t st) {
+  if (n_rows <= 0) return hipSuccess;
   const int eb = dtype == THK_BF16 ? 2 : 4;
-  const bool flat = ld_keep == T && ((size_t)S * T * eb) % 16 == 0;
-  // 512 rows per block (4 waves x 4 tiles), fewer blocks per unit when S is short
-  const int64_t rows_per_block = 512;
-  const int bpu = (int)((S + rows_per_block - 1) / rows_per_block);
-  const dim3 grid((unsigned)(U * bpu)), block(256);
-  if (flat) {
-    const size_t lds = 2048 + 4 * (size_t)32 * kD * eb;
-    if (dtype == THK_BF16)
-      hipLaunchKernelGGL((k_compact_flat<THK_BF16>), grid, block, lds, st, k, idx, kp, S, T, bpu, rows_per_block);
-    else
-      hipLaunchKernelGGL((k_compact_flat<THK_F32>), grid, block, lds, st, k, idx, kp, S, T, bpu, rows_per_block);
+  CompactArgs a;
+  a.src = src; a.dst = dst; a.idx = idx;
+  a.src_unit_rows = src_unit_rows; a.src_row0 = src_row0;
+  a.dst_unit_rows = dst_unit_rows; a.dst_row0 = dst_row0; a.n_rows = n_rows;
+  a.T = T; a.ld = ld_keep;
+  a.rows_per_block = 512;   // 4 waves x 4 tiles; fewer blocks per unit when the run is short
+  a.blocks_per_unit = (int)((n_rows + a.rows_per_block - 1) / a.rows_per_block);
+  const dim3 grid((unsigned)(U * a.blocks_per_unit)), block(256);
+  if (compact_is_flat(dtype, T, ld_keep, dst_unit_rows, dst_row0, n_rows)) {
+    const size_t lds = 2048 + 4 * (size_t)kCompactTileRows * kD * eb;
+    if (dtype == THK_BF16) hipLaunchKernelGGL((k_compact_flat<THK_BF16>), grid, block, lds, st, a);
+    else                   hipLaunchKernelGGL((k_compact_flat<THK_F32>), grid, block, lds, st, a);
   } else {
-    if (dtype == THK_BF16)
-      hipLaunchKernelGGL((k_compact_generic<THK_BF16>), grid, block, 0, st, k, idx, kp, S, T, ld_keep, bpu, rows_per_block);
-    else
-      hipLaunchKernelGGL((k_compact_generic<THK_F32>), grid, block, 0, st, k, idx, kp, S, T, ld_keep, bpu, rows_per_block);
+    if (dtype == THK_BF16) hipLaunchKernelGGL((k_compact_generic<THK_BF16>), grid, block, 0, st, a);
+    else                   hipLaunchKernelGGL((k_compact_generic<THK_F32>), grid, block, 0, st, a);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_tail_append(int dtype, const void *k_new, const void *v_new, void *k_tail,
-                              void *v_tail, int64_t U, int s_tail, int cap, hipStream_t st) {
+hipError_t launch_copy_rows(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0, void *dst,
+                            int64_t dst_unit_rows, int64_t dst_row0, int64_t U, int64_t n_rows,
+                            hipStream_t st) {
+  if (n_rows <= 0) return hipSuccess;
+  const dim3 grid((unsigned)U), block(256);
+  if (dtype == THK_BF16)
+    hipLaunchKernelGGL((k_copy_rows<THK_BF16>), grid, block, 0, st, src, dst, src_unit_rows, src_row0, dst_unit_rows, dst_row0, n_rows);
+  else
+    hipLaunchKernelGGL((k_copy_rows<THK_F32>), grid, block, 0, st, src, dst, src_unit_rows, src_row0, dst_unit_rows, dst_row0, n_rows);
+  return hipGetLastError();
+}
+
+hipError_t launch_tail_append(int dtype, const void *k_new, const void *v_new, void *k_dst, void *v_dst,
+                              int64_t U, int64_t k_unit_rows, int64_t k_row, int64_t v_unit_rows,
+                              int64_t v_row, hipStream_t st) {
   const int cpr = dtype == THK_BF16 ? 16 : 32;
   const dim3 grid((unsigned)((U * cpr + 255) / 256)), block(256);
   if (dtype == THK_BF16)
-    hipLaunchKernelGGL((k_tail_append<THK_BF16>), grid, block, 0, st, k_new, v_new, k_tail, v_tail, U, s_tail, cap);
+    hipLaunchKernelGGL((k_tail_append<THK_BF16>), grid, block, 0, st, k_new, v_new, k_dst, v_dst, U, k_unit_rows, k_row, v_unit_rows, v_row);
   else
-    hipLaunchKernelGGL((k_tail_append<THK_F32>), grid, block, 0, st, k_new, v_new, k_tail, v_tail, U, s_tail, cap);
+    hipLaunchKernelGGL((k_tail_append<THK_F32>), grid, block, 0, st, k_new, v_new, k_dst, v_dst, U, k_unit_rows, k_row, v_unit_rows, v_row);
   return hipGetLastError();
 }
 

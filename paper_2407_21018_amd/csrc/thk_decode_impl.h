@@ -346,7 +346,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   const char *kpg = (const char *)a.kp;
 
   constexpr int NV = VS::NV;
-  const size_t krow0 = (size_t)u * a.S + s0;             // first K_pruned / V row of this block
+  const size_t krow0 = (size_t)u * a.unit_rows + s0;     // first K_pruned / V row of this block
   const u32x4 *vbase = (const u32x4 *)a.v + krow0 * LPR;
 
   // the first tile's key and value bytes start moving before anything else happens
@@ -411,7 +411,9 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     const size_t row0 = (size_t)u * a.s_tail_cap + j0;
     u32x4 kt[KBT];
     k_issue<DT, KBT>(kt, (const char *)a.kt, row0 * kD * EB, nrows, kD, kD, lane);
-    const u32x4 *vg = (const u32x4 *)a.vt + row0 * LPR;
+    // the tail's value rows: a buffer of their own, or the rows that follow row S in v
+    const u32x4 *vg = a.unified_v ? (const u32x4 *)a.v + ((size_t)u * a.unit_rows + a.S + j0) * LPR
+                                  : (const u32x4 *)a.vt + row0 * LPR;
     v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
     k_commit<KBT>(kt, kbuf, lane);
     wave_sync_lds();

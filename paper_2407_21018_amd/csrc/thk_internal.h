@@ -64,14 +64,31 @@ hipError_t launch_finalize(int dtype, int mode, const double *partial, const voi
 
 hipError_t launch_select(const float *score, int16_t *idx, int64_t U, int T, hipStream_t st);
 
-hipError_t launch_compact(int dtype, const void *k, const int16_t *idx, void *kp, int64_t U,
-                          int64_t S, int T, int ld_keep, hipStream_t st);
+// K_pruned[u][dst_row0 + r][t] = src[u][src_row0 + r][idx[u][t]], r < n_rows; src has
+// src_unit_rows rows of 128 per unit, K_pruned dst_unit_rows rows of ld_keep per unit.
+struct CompactArgs {
+  const void *src;
+  void *dst;
+  const int16_t *idx;
+  int64_t src_unit_rows, src_row0, dst_unit_rows, dst_row0, n_rows, rows_per_block;
+  int32_t T, ld, blocks_per_unit;
+};
+bool compact_is_flat(int dtype, int T, int ld_keep, int64_t dst_unit_rows, int64_t dst_row0, int64_t n_rows);
+hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0,
+                          const int16_t *idx, void *dst, int64_t dst_unit_rows, int64_t dst_row0,
+                          int64_t U, int64_t n_rows, int T, int ld_keep, hipStream_t st);
+hipError_t launch_copy_rows(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0, void *dst,
+                            int64_t dst_unit_rows, int64_t dst_row0, int64_t U, int64_t n_rows,
+                            hipStream_t st);
 
 // One-launch prune (flat K_pruned layout only).  ws: prune_fused_ws_bytes(U, NB) bytes.
 size_t prune_fused_ws_bytes(int64_t U, int NB);
+// S rows per unit are scored; rows [0, S_keep) are compacted into K_pruned, whose units are
+// kp_unit_rows rows apart.
 hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float *score, int16_t *idx,
-                              void *kp, void *ws, int64_t U, int64_t S, int G, int S_obs, int T,
-                              int NB, int64_t RB, int spin_limit, hipStream_t st);
+                              void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
+                              int64_t kp_unit_rows, int G, int S_obs, int T, int NB, int64_t RB,
+                              int spin_limit, hipStream_t st);
 
 struct DecodeArgs {
   const void *q, *kp, *v, *kt, *vt;
@@ -79,14 +96,16 @@ struct DecodeArgs {
   void *out;
   float *ws;
   int64_t S, rows_per_split;
-  size_t kp_bytes;            // total bytes of K_pruned (bounds the flat tile loads)
+  int64_t unit_rows;          // rows between units in K_pruned and V (cache capacity per unit)
+  int32_t unified_v;          // tail values continue in v after row S (no separate v_tail)
   int32_t T, ldk, N_q, N_kv, s_tail, s_tail_cap, n_split, dtype;
   int64_t units;              // L * B * N_kv
   float scale_log2;           // log2(e) / sqrt(D)
 };
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t st);
 
-hipError_t launch_tail_append(int dtype, const void *k_new, const void *v_new, void *k_tail,
-                              void *v_tail, int64_t U, int s_tail, int cap, hipStream_t st);
+hipError_t launch_tail_append(int dtype, const void *k_new, const void *v_new, void *k_dst, void *v_dst,
+                              int64_t U, int64_t k_unit_rows, int64_t k_row, int64_t v_unit_rows,
+                              int64_t v_row, hipStream_t st);
 
 }  // namespace thk

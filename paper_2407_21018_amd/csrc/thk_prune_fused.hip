@@ -42,6 +42,8 @@ struct PruneFusedArgs {
   uint32_t *idx_pub;      // [U][64]  the index list, two entries per word, for the waiting blocks
   unsigned char *done;    // [U * NB]
   int64_t S, RB;          // rows per unit, rows per block
+  int64_t S_keep;         // rows [0, S_keep) of every unit are compacted
+  int64_t kp_unit_rows;   // rows between units of K_pruned
   int32_t T, G, S_obs, NB, spin_limit;
 };
 
@@ -152,7 +154,9 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   // ---- C. compact this block's rows -------------------------------------------
   compact_build_tab(tab, s_idx, a.T);
   __syncthreads();
-  compact_rows<DT>(src, (u32x4 *)((char *)a.kp + (size_t)u * a.S * a.T * E::EB), s0, s1, a.T, tab, tiles);
+  const int64_t s1c = min(s1, a.S_keep);   // rows past S_keep stay at full width with the caller
+  if (s0 < s1c)
+    compact_rows<DT>(src, (u32x4 *)((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB), s0, s1c, a.T, tab, tiles);
   if (tid == 0) a.done[item] = 1;
 }
 
@@ -176,11 +180,12 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
   compact_build_tab(tab, a.idx + (size_t)u * a.T, a.T);
   __syncthreads();
   const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
-  u32x4 *dst = (u32x4 *)((char *)a.kp + (size_t)u * a.S * a.T * E::EB);
+  u32x4 *dst = (u32x4 *)((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
   for (int blk = 0; blk < a.NB; ++blk) {
     if (done[blk]) continue;   // block-uniform: every thread reads the same byte
     const int64_t s0 = (int64_t)blk * a.RB;
-    compact_rows<DT>(src, dst, s0, min(a.S, s0 + a.RB), a.T, tab, tiles);
+    const int64_t s1c = min(a.S_keep, s0 + a.RB);
+    if (s0 < s1c) compact_rows<DT>(src, dst, s0, s1c, a.T, tab, tiles);
   }
 }
 
@@ -195,8 +200,9 @@ size_t prune_fused_ws_bytes(int64_t U, int NB) {
 }
 
 hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float *score, int16_t *idx,
-                              void *kp, void *ws, int64_t U, int64_t S, int G, int S_obs, int T,
-                              int NB, int64_t RB, int spin_limit, hipStream_t st) {
+                              void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
+                              int64_t kp_unit_rows, int G, int S_obs, int T, int NB, int64_t RB,
+                              int spin_limit, hipStream_t st) {
   PruneFusedArgs a;
   a.k = k; a.q_obs = q_obs; a.kp = kp; a.score = score; a.idx = idx;
   char *w = (char *)ws;
@@ -207,7 +213,7 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
   w = (char *)(((uintptr_t)w + 15) & ~(uintptr_t)15);
   a.idx_pub = (uint32_t *)w; w += (size_t)U * kWave * sizeof(uint32_t);
   a.done = (unsigned char *)w;
-  a.S = S; a.RB = RB; a.T = T; a.G = G; a.S_obs = S_obs; a.NB = NB; a.spin_limit = spin_limit;
+  a.S = S; a.S_keep = S_keep; a.kp_unit_rows = kp_unit_rows; a.RB = RB; a.T = T; a.G = G; a.S_obs = S_obs; a.NB = NB; a.spin_limit = spin_limit;
   const int eb = dtype == THK_BF16 ? 2 : 4;
   const size_t lds = 2048 + 4 * (size_t)kCompactTileRows * kD * eb;
   const dim3 gu((unsigned)U), gi((unsigned)(U * NB));

@@ -113,3 +113,22 @@ def test_binding_refuses_short_tensors():
     k = torch.zeros(10, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         thk.thk_compact_keys(s, k, A, A, stream=0)
+
+
+def test_cache_growth_argument_checks():
+    s = _shape(S=1000, S_recent=32, S_cap=1100)
+    assert _status(thk.thk_prune, _shape(S_recent=1000), A, A, A, A, A, (A, BIG), stream=0) == 2   # S_recent >= S
+    assert _status(thk.thk_prune, _shape(S=1000, S_recent=32, S_cap=900), A, A, A, A, A, (A, BIG), stream=0) == 2
+    assert _status(thk.thk_compact_rows, s, A, 64, 0, A, A, 1090, 20, stream=0) == 2       # past the capacity
+    assert _status(thk.thk_compact_rows, s, A, 64, 60, A, A, 0, 20, stream=0) == 2         # past the source
+    assert _status(thk.thk_compact_rows, s, None, 64, 0, A, A, 0, 20, stream=0) == 1
+    assert _status(thk.thk_copy_rows, s, A, 64, 0, A, 64, 1, 10, stream=0) == 2            # upward shift in place
+    assert _status(thk.thk_copy_rows, s, A, 64, 0, A + 8, 64, 0, 10, stream=0) == 4
+    assert _status(thk.thk_cache_append, _shape(S=1000, S_cap=1001), A, A, A, A, 1, 8, stream=0) == 2   # value cache full
+    assert _status(thk.thk_cache_append, s, A, A, A, A, 8, 8, stream=0) == 2               # tail full
+    assert _status(thk.thk_tail_flush, s, A, A, A, None, None, 10, 8, 4, stream=0) == 2    # s_tail > cap
+    assert _status(thk.thk_tail_flush, s, A, A, A, None, None, 8, 8, 9, stream=0) == 2     # flush more than held
+    assert _status(thk.thk_tail_flush, s, A, A, A, A, None, 8, 8, 4, stream=0) == 1        # v without v_tail
+    assert _status(thk.thk_tail_flush, _shape(S=1000, S_cap=1002), A, A, A, None, None, 8, 8, 4, stream=0) == 2
+    # unified value cache at decode needs room for the tail rows
+    assert _status(thk.thk_decode_attn, _shape(S=1000, S_cap=1003), A, A, A, A, A, None, 4, 8, A, (A, BIG), stream=0) == 2
