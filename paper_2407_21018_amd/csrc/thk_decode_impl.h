@@ -40,22 +40,32 @@ __device__ inline void wave_sync_lds() {
 // Cross-lane reductions over the 64 lanes with DPP row shifts and row
 // broadcasts: after the four row_shr steps lane 15 of every 16-lane row holds
 // the row's result, row_bcast:15 folds rows 0->1 and 2->3, row_bcast:31 folds
-// the lower half into rows 2 and 3, and lane 63 holds the total.
+// the lower half into rows 2 and 3, and lane 63 holds the total.  A lane whose
+// DPP source does not exist receives `old`; passing the lane's own value as
+// `old` makes the step a no-op there (max(x, x); x + 0 needs the identity 0)
+// and lets the compiler fold the move into the arithmetic instruction.
 template <int CTRL, int ROW_MASK>
-__device__ inline float dpp_move(float identity, float x) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(x), CTRL,
+__device__ inline float dpp_move(float old, float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(x), CTRL,
                                                     ROW_MASK, 0xf, false));
 }
+// Wave-wide maximum with the DPP step folded into v_max_f32 (one instruction per
+// step, written out because the compiler keeps a separate v_mov_dpp).  In-place
+// form: a lane whose DPP source does not exist, or whose row is masked off, is
+// not written and keeps its value.  The s_nop covers the two wait states a DPP
+// read needs after the VALU write of the same register.
+#define THK_DPP_MAX(x, ctrl) \
+  asm volatile("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 " ctrl : "+v"(x))
 __device__ inline float wave_max(float x) {
-  const float id = -INFINITY;
-  x = fmaxf(x, dpp_move<0x111, 0xf>(id, x));   // row_shr:1
-  x = fmaxf(x, dpp_move<0x112, 0xf>(id, x));   // row_shr:2
-  x = fmaxf(x, dpp_move<0x114, 0xf>(id, x));   // row_shr:4
-  x = fmaxf(x, dpp_move<0x118, 0xf>(id, x));   // row_shr:8
-  x = fmaxf(x, dpp_move<0x142, 0xa>(id, x));   // row_bcast:15 into rows 1, 3
-  x = fmaxf(x, dpp_move<0x143, 0xc>(id, x));   // row_bcast:31 into rows 2, 3
+  THK_DPP_MAX(x, "row_shr:1 row_mask:0xf bank_mask:0xf");
+  THK_DPP_MAX(x, "row_shr:2 row_mask:0xf bank_mask:0xf");
+  THK_DPP_MAX(x, "row_shr:4 row_mask:0xf bank_mask:0xf");
+  THK_DPP_MAX(x, "row_shr:8 row_mask:0xf bank_mask:0xf");
+  THK_DPP_MAX(x, "row_bcast:15 row_mask:0xa bank_mask:0xf");
+  THK_DPP_MAX(x, "row_bcast:31 row_mask:0xc bank_mask:0xf");
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
+__device__ inline float max_nn(float a, float b) { return a > b ? a : b; }   // inputs are never NaN
 __device__ inline float wave_sum(float x) {
   x += dpp_move<0x111, 0xf>(0.f, x);
   x += dpp_move<0x112, 0xf>(0.f, x);
@@ -261,7 +271,7 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
 #pragma unroll
   for (int g = 0; g < GT; ++g) {
     const float zz = r < nrows ? z[g] * scale : -INFINITY;
-    const float m_new = fmaxf(st.m[g], wave_max(zz));   // finite: the tile has >= 1 row
+    const float m_new = max_nn(st.m[g], wave_max(zz));   // finite: the tile has >= 1 row
     if (m_new != st.m[g]) {                             // wave-uniform; rare after the first tiles
       const float corr = __builtin_amdgcn_exp2f(st.m[g] - m_new);
       st.l[g] *= corr;
