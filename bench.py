@@ -27,6 +27,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload id (synth.CONFIGS); 2 = the metric's")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--graph", action="store_true",
+                    help="additionally time the step replayed from a HIP graph (reported as graph_ms_per_step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference dispatches of known size "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -187,6 +189,26 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = e0.elapsed_time(e1) / args.steps
 
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            step()
+        gr.replay()
+        torch.cuda.synchronize()
+        g0 = torch.cuda.Event(enable_timing=True); g1 = torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(args.steps):
+            gr.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        graph_ms = g0.elapsed_time(g1) / args.steps
+
     # main-kernel durations measured inside the timed region
     prune_kernel_us = [p[0][0].elapsed_time(p[0][1]) * 1e3 for p in pairs]
     dec_kernel_us = [a.elapsed_time(b) * 1e3 for (a, b) in used_pairs]
@@ -234,7 +256,7 @@ def main():
         "prune_frac": prune_bytes / prune_ms_layer / 1e6 / HBM_PEAK_GBS,
         "decode_us_per_step": dec_us_step, "decode_GBps": decode_bytes / dec_us_step / 1e3,
         "decode_frac": decode_bytes / dec_us_step / 1e3 / HBM_PEAK_GBS,
-        "host_wall_s": wall,
+        "host_wall_s": wall, "graph_ms_per_step": graph_ms,
         "kernels": kernels,
         "roofline": roof,
     }
