@@ -54,6 +54,12 @@ def lib():
         L.thko_decode_attn.restype = None
         L.thko_decode_attn.argtypes = [ctypes.c_int, i32, i32, i32, i32, i64, i32, i32,
                                        vp, vp, vp, vp, vp, vp, i32, i32, vp]
+        L.thko_score_value.restype = None
+        L.thko_score_value.argtypes = [ctypes.c_int, i32, i32, i32, i32, i32, i64, i32, i32,
+                                       vp, vp, vp, vp]
+        L.thko_decode_attn_kv.restype = None
+        L.thko_decode_attn_kv.argtypes = [ctypes.c_int, i32, i32, i32, i32, i64, i32, i32, i32, i32,
+                                          vp, vp, vp, vp, vp, vp, vp, i32, i32, vp]
         L.thko_objective.restype = dbl
         L.thko_objective.argtypes = [i32, i64, i32, vp, vp, vp]
         _lib = L
@@ -149,6 +155,45 @@ def decode_attn(q, k_pruned, idx, v, dtype, k_tail=None, v_tail=None, s_tail=0):
     lib().thko_decode_attn(_DT[dtype], B, N_q, N_kv, D, S, T, ld, _p(q), _p(k_pruned), _p(idx),
                            _p(v), _p(k_tail) if s_tail else None,
                            _p(v_tail) if s_tail else None, s_tail, cap, _p(out))
+    return out
+
+
+def score_value(q_obs, k, v, dtype, causal=False):
+    """q_obs [L,B,N_q,S_obs,D], k and v [L,B,N_kv,S,D] -> value-channel score
+    float64 [L,B,N_kv,D] (column norms of softmax(Q_obs K^T / sqrt(D)) V, summed over
+    the query heads of a group)."""
+    q_obs, k, v = _arr(q_obs, dtype), _arr(k, dtype), _arr(v, dtype)
+    L, B, N_q, S_obs, D = q_obs.shape
+    L2, B2, N_kv, S, D2 = k.shape
+    assert (L, B, D) == (L2, B2, D2) and N_q % N_kv == 0 and 1 <= S_obs <= S
+    assert v.shape == k.shape
+    out = np.empty((L, B, N_kv, D), np.float64)
+    lib().thko_score_value(_DT[dtype], L, B, N_q, N_kv, D, S, S_obs, int(bool(causal)),
+                           _p(q_obs), _p(k), _p(v), _p(out))
+    return out
+
+
+def decode_attn_kv(q, k_pruned, idx, v_pruned, idx_v, dtype, k_tail=None, v_tail=None, s_tail=0):
+    """As decode_attn with a channel-pruned value cache: v_pruned [B,N_kv,S,ld_v],
+    idx_v [B,N_kv,T_v]; the tail keeps full-width rows.  out float64 [B,N_q,D]."""
+    q, k_pruned, v_pruned = _arr(q, dtype), _arr(k_pruned, dtype), _arr(v_pruned, dtype)
+    idx = np.ascontiguousarray(idx, np.int16)
+    idx_v = np.ascontiguousarray(idx_v, np.int16)
+    B, N_q, D = q.shape
+    B2, N_kv, S, ld = k_pruned.shape
+    T, T_v, ld_v = idx.shape[-1], idx_v.shape[-1], v_pruned.shape[-1]
+    assert v_pruned.shape[:3] == (B, N_kv, S) and B2 == B and ld >= T and ld_v >= T_v
+    assert N_q % N_kv == 0 and idx_v.shape[:2] == (B, N_kv)
+    cap = 0
+    if s_tail > 0:
+        k_tail, v_tail = _arr(k_tail, dtype), _arr(v_tail, dtype)
+        cap = k_tail.shape[2]
+        assert k_tail.shape == (B, N_kv, cap, D) == v_tail.shape and s_tail <= cap
+    out = np.empty((B, N_q, D), np.float64)
+    lib().thko_decode_attn_kv(_DT[dtype], B, N_q, N_kv, D, S, T, ld, T_v, ld_v, _p(q),
+                              _p(k_pruned), _p(idx), _p(v_pruned), _p(idx_v),
+                              _p(k_tail) if s_tail else None, _p(v_tail) if s_tail else None,
+                              s_tail, cap, _p(out))
     return out
 
 

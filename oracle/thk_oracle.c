@@ -25,10 +25,17 @@
  * numpy.take, the pruning objective's triangle bound and its exact T = D-1
  * case (Sec. 3.2, Eq. 2), textbook attention at T = D and on channel-masked
  * keys, and the paper's KV-size example (Sec. 3.1) and Table 7 memory column.
+ * The value-cache routines (tests/test_oracle_pins_value.py): library fp64
+ * attention followed by library column norms, the uniform-attention and
+ * one-hot closed forms with and without the causal mask, shift / permutation
+ * / scaling invariances, and the reduction of the pruned-value decode to the
+ * key-only decode on channel-masked values.
  * Parity unpinned by any value printed in the paper: the GQA aggregation
  * (sum over the G query heads of per-head Frobenius norms), the ascending
  * order of the index list, and the attention error metric are conventions of
- * this build; the paper prints no numeric score, index set or output.
+ * this build; the paper prints no numeric score, index set or output.  The
+ * same holds for the value score's optional causal mask and for reading a
+ * removed value channel as a zero in the attention output.
  */
 #include <math.h>
 #include <stdint.h>
@@ -297,4 +304,144 @@ double thko_objective(int32_t S_q, int64_t S_k, int32_t D, const double *Q,
       fro2 += (full - kept) * (full - kept);
     }
   return sqrt(fro2);
+}
+
+/*
+ * Query-driven VALUE channel score (Appendix "Value Cache Pruning",
+ * Score_{v,i}[j]).  For one query head: A = softmax(Q_obs K^T / sqrt(D)) is
+ * S_obs x S, row-wise; column j of A V is one S_obs-vector and the Frobenius
+ * norm of a vector is its 2-norm.  Written out as defined: logits, softmax
+ * with the row maximum subtracted, the product with V, then the column norm.
+ * K is the un-pruned key cache.  For grouped-query attention the per-head
+ * norms of the G query heads that read one KV head are added (the same
+ * convention as the key score).
+ *
+ * causal = 0: the equation as printed, every window row sees all S keys.
+ * causal = 1: window row i sits at absolute position S - S_obs + i and sees
+ *             keys 0 .. S - S_obs + i only, as in the prefill's own attention
+ *             (the paper does not say which is meant; both are offered).
+ * Requires S_obs <= S when causal.  score [L][B][N_kv][D], double.
+ */
+void thko_score_value(int dtype, int32_t L, int32_t B, int32_t N_q,
+                      int32_t N_kv, int32_t D, int64_t S, int32_t S_obs,
+                      int32_t causal, const void *q_obs, const void *k,
+                      const void *v, double *score) {
+  const int32_t G = N_q / N_kv;
+  const int64_t U = (int64_t)L * B * N_kv;
+  const double inv_sqrt_d = 1.0 / sqrt((double)D);
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t u = 0; u < U; ++u) {
+    const int64_t lb = u / N_kv;
+    const int32_t h = (int32_t)(u % N_kv);
+    const size_t kvbase = (size_t)u * (size_t)S * D;
+    double *a = (double *)malloc((size_t)S * sizeof(double));
+    double *o = (double *)malloc((size_t)S_obs * D * sizeof(double));
+    double *sc = score + (size_t)u * D;
+    for (int32_t j = 0; j < D; ++j) sc[j] = 0.0;
+    for (int32_t g = 0; g < G; ++g) {
+      const int64_t n = (int64_t)h * G + g;
+      const size_t qbase = (size_t)(lb * N_q + n) * (size_t)S_obs * D;
+      for (int32_t i = 0; i < S_obs; ++i) {
+        const int64_t n_vis = causal ? (S - S_obs + i + 1) : S;
+        for (int64_t s = 0; s < n_vis; ++s) {
+          double dot = 0.0;
+          for (int32_t c = 0; c < D; ++c)
+            dot += ld(q_obs, dtype, qbase + (size_t)i * D + c) *
+                   ld(k, dtype, kvbase + (size_t)s * D + c);
+          a[s] = dot * inv_sqrt_d;
+        }
+        double amax = a[0];
+        for (int64_t s = 1; s < n_vis; ++s)
+          if (a[s] > amax) amax = a[s];
+        double denom = 0.0;
+        for (int64_t s = 0; s < n_vis; ++s) {
+          a[s] = exp(a[s] - amax);
+          denom += a[s];
+        }
+        for (int32_t j = 0; j < D; ++j) {
+          double acc = 0.0;
+          for (int64_t s = 0; s < n_vis; ++s)
+            acc += a[s] * ld(v, dtype, kvbase + (size_t)s * D + j);
+          o[(size_t)i * D + j] = acc / denom;
+        }
+      }
+      for (int32_t j = 0; j < D; ++j) {
+        double ss = 0.0;
+        for (int32_t i = 0; i < S_obs; ++i)
+          ss += o[(size_t)i * D + j] * o[(size_t)i * D + j];
+        sc[j] += sqrt(ss);
+      }
+    }
+    free(a);
+    free(o);
+  }
+}
+
+/*
+ * Decode attention with BOTH caches channel-pruned (Sec. 3.3 for the keys;
+ * Appendix "Value Cache Pruning" for the values).  Logits and softmax are
+ * those of thko_decode_attn.  The value rows of the pruned segment hold only
+ * the T_v kept channels idx_v[0..T_v); a removed value channel contributes
+ * nothing, so for output channel c
+ *   out[c] = ( sum_s p_s * V_pruned[s][t]  if c == idx_v[t] for some t, else 0
+ *            + sum_j p_{S+j} * V_tail[j][c] ) / denom.
+ * The un-pruned tail keeps full-width value rows.
+ *   V_pruned [B][N_kv][S][ld_v]; idx_v [B][N_kv][T_v]; the rest as in
+ *   thko_decode_attn.  out [B][N_q][D], double.
+ */
+void thko_decode_attn_kv(int dtype, int32_t B, int32_t N_q, int32_t N_kv,
+                         int32_t D, int64_t S, int32_t T, int32_t ld_keep,
+                         int32_t T_v, int32_t ld_v, const void *q,
+                         const void *k_pruned, const int16_t *idx,
+                         const void *v_pruned, const int16_t *idx_v,
+                         const void *k_tail, const void *v_tail,
+                         int32_t S_tail, int32_t S_tail_cap, double *out) {
+  const int32_t G = N_q / N_kv;
+  const int64_t n_heads = (int64_t)B * N_q;
+  const double inv_sqrt_d = 1.0 / sqrt((double)D);
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t bn = 0; bn < n_heads; ++bn) {
+    const int64_t b = bn / N_q;
+    const int32_t n = (int32_t)(bn % N_q);
+    const int64_t u = b * N_kv + n / G;
+    const size_t qb = (size_t)bn * D;
+    const int64_t n_keys = S + S_tail;
+    double *z = (double *)malloc((size_t)n_keys * sizeof(double));
+    for (int64_t s = 0; s < S; ++s) {
+      double dot = 0.0;
+      for (int32_t t = 0; t < T; ++t)
+        dot += ld(q, dtype, qb + (size_t)idx[(size_t)u * T + t]) *
+               ld(k_pruned, dtype, ((size_t)u * S + s) * ld_keep + t);
+      z[s] = dot * inv_sqrt_d;
+    }
+    for (int32_t j = 0; j < S_tail; ++j) {
+      double dot = 0.0;
+      for (int32_t c = 0; c < D; ++c)
+        dot += ld(q, dtype, qb + c) *
+               ld(k_tail, dtype, ((size_t)u * S_tail_cap + j) * D + c);
+      z[S + j] = dot * inv_sqrt_d;
+    }
+    double zmax = z[0];
+    for (int64_t s = 1; s < n_keys; ++s)
+      if (z[s] > zmax) zmax = z[s];
+    double denom = 0.0;
+    for (int64_t s = 0; s < n_keys; ++s) {
+      z[s] = exp(z[s] - zmax);
+      denom += z[s];
+    }
+    for (int32_t c = 0; c < D; ++c) out[qb + c] = 0.0;
+    for (int32_t t = 0; t < T_v; ++t) {
+      double acc = 0.0;
+      for (int64_t s = 0; s < S; ++s)
+        acc += z[s] * ld(v_pruned, dtype, ((size_t)u * S + s) * ld_v + t);
+      out[qb + (size_t)idx_v[(size_t)u * T_v + t]] = acc;
+    }
+    for (int32_t c = 0; c < D; ++c) {
+      double acc = out[qb + c];
+      for (int32_t j = 0; j < S_tail; ++j)
+        acc += z[S + j] * ld(v_tail, dtype, ((size_t)u * S_tail_cap + j) * D + c);
+      out[qb + c] = acc / denom;
+    }
+    free(z);
+  }
 }
