@@ -52,7 +52,8 @@ typedef enum { THK_F32 = 0, THK_BF16 = 1 } thk_dtype;
 typedef enum {
   THK_OP_SCORE = 0,  /* thk_score                       */
   THK_OP_DECODE = 1, /* thk_decode_attn                 */
-  THK_OP_PRUNE = 2   /* thk_prune                       */
+  THK_OP_PRUNE = 2,  /* thk_prune                       */
+  THK_OP_SCORE_VALUE = 3 /* thk_score_value             */
 } thk_op;
 
 /* Problem statement in the paper's B x S x L x N x D terms (Sec. 1). */
@@ -122,6 +123,27 @@ thk_status thk_score(const thk_shape *shape, const void *q_obs, const void *k,
 thk_status thk_score_magnitude(const thk_shape *shape, const void *k, int32_t p,
                                float *score, void *ws, size_t ws_bytes,
                                void *stream);
+
+/*
+ * Query-driven VALUE channel score (Appendix "Value Cache Pruning"):
+ *   Score_v[j] = || softmax(Q_obs K^T / sqrt(D)) V[:, j] ||_2 ,
+ * the norm of channel j of the observation window's attention output, added
+ * over the N_q / N_kv query heads that read one KV head.  K is the un-pruned
+ * key cache.  causal = 0 is the equation as printed (every window row sees all
+ * S keys); causal = 1 lets window row i, the token at position S - S_obs + i,
+ * see keys 0 .. S - S_obs + i as in the prefill's own attention.  Logits are
+ * accumulated in fp32 on the matrix cores, the softmax runs in fp32, and the
+ * probabilities are rounded to bf16 once before they multiply V (their row sum
+ * is taken over the rounded values); column norms are summed in fp64 and
+ * rounded once to float.  Feed the result to thk_select_topk for the value
+ * index list and to thk_compact_keys (which copies channels of any [S][D]
+ * cache) for the pruned values.  bf16 only (THK_ERR_UNSUPPORTED for fp32).
+ *   in : q_obs, k, v (device)        out: score_v (device, float, [L][B][N_kv][D])
+ *   ws : THK_OP_SCORE_VALUE bytes.
+ */
+thk_status thk_score_value(const thk_shape *shape, const void *q_obs, const void *k,
+                           const void *v, int32_t causal, float *score_v, void *ws,
+                           size_t ws_bytes, void *stream);
 
 /*
  * Top_T selection (Sec. 3.1 I = Top_T(M, T); Sec. 3.2 I_i): per unit the T

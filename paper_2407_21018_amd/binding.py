@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libthk.so")
 
 THK_F32, THK_BF16 = 0, 1
-THK_OP_SCORE, THK_OP_DECODE, THK_OP_PRUNE = 0, 1, 2
+THK_OP_SCORE, THK_OP_DECODE, THK_OP_PRUNE, THK_OP_SCORE_VALUE = 0, 1, 2, 3
 
 
 class ThkError(RuntimeError):
@@ -58,6 +58,8 @@ def load():
     L.thk_prune_is_fused.argtypes = [sp]
     L.thk_score.restype = ctypes.c_int
     L.thk_score.argtypes = [sp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.thk_score_value.restype = ctypes.c_int
+    L.thk_score_value.argtypes = [sp, vp, vp, vp, i32, vp, vp, ctypes.c_size_t, vp]
     L.thk_score_magnitude.restype = ctypes.c_int
     L.thk_score_magnitude.argtypes = [sp, vp, i32, vp, vp, ctypes.c_size_t, vp]
     L.thk_select_topk.restype = ctypes.c_int
@@ -176,6 +178,17 @@ def thk_score(shape, q_obs, k, score, ws, stream=None):
     _need(score, U * shape.D, "score", "thk_score")
     _check(load().thk_score(ctypes.byref(shape), _ptr(q_obs), _ptr(k), _ptr(score), _ws(ws),
                             _nbytes(ws), _stream(stream)), "thk_score")
+
+
+def thk_score_value(shape, q_obs, k, v, causal, score_v, ws, stream=None):
+    U, H, _ = _dims(shape)
+    _need(q_obs, H * shape.S_obs * shape.D, "q_obs", "thk_score_value")
+    _need(k, U * shape.S * shape.D, "k", "thk_score_value")
+    _need(v, U * shape.S * shape.D, "v", "thk_score_value")
+    _need(score_v, U * shape.D, "score_v", "thk_score_value")
+    _check(load().thk_score_value(ctypes.byref(shape), _ptr(q_obs), _ptr(k), _ptr(v), int(causal),
+                                  _ptr(score_v), _ws(ws), _nbytes(ws), _stream(stream)),
+           "thk_score_value")
 
 
 def thk_score_magnitude(shape, k, p, score, ws, stream=None):

@@ -149,6 +149,29 @@ FusedPlan fused_plan(const thk_shape *s) {
   return p;
 }
 
+// Split of the S axis for the value score: pieces are whole 128-row chunks of at least 512
+// rows, enough of them for ~4 blocks per compute unit, and few enough that the merge kernel's
+// weight table (pieces x key lanes per block <= 256) fits.
+Split value_split(const thk_shape *s) {
+  const int G = s->N_q / s->N_kv;
+  const int QT = value_attn_qt(G, s->S_obs);
+  const int nqt = (G * s->S_obs + 31) / 32;
+  const int64_t blocks1 = units_of(s) * ceil_div(nqt, QT);
+  int n = s->n_split;
+  if (n == 0) {
+    n = (int)ceil_div((int64_t)kCUs * 4, blocks1);
+    const int64_t cap = ceil_div(s->S, 512);
+    if (n > cap) n = (int)cap;
+    if (n < 1) n = 1;
+  }
+  const int max_n = 256 / (4 / QT);
+  if (n > max_n) n = max_n;
+  int64_t rows = ceil_div(s->S, n);
+  rows = ceil_div(rows, 128) * 128;
+  n = (int)ceil_div(s->S, rows);   // drop empty pieces
+  return {n, rows};
+}
+
 size_t score_ws_bytes(const thk_shape *s, int64_t units) {
   return (size_t)units * score_split(s, units).n * kD * sizeof(double);
 }
@@ -189,6 +212,7 @@ int32_t thk_default_split(const thk_shape *s, int32_t op) {
   if (op == THK_OP_DECODE) return decode_split(&t).n;
   if (op == THK_OP_SCORE) return score_split(&t, units_of(&t)).n;
   if (op == THK_OP_PRUNE) return score_split(&t, prune_group_units(&t)).n;
+  if (op == THK_OP_SCORE_VALUE) return (t.S_obs >= 1 && t.S_obs <= t.S) ? value_split(&t).n : 0;
   return 0;
 }
 
@@ -207,6 +231,9 @@ size_t thk_workspace_bytes(const thk_shape *s, int32_t op) {
       if (sp.n == 1) return 16;
       return (size_t)s->L * s->B * s->N_q * sp.n * (kD + 2) * sizeof(float);
     }
+    case THK_OP_SCORE_VALUE:
+      if (s->S_obs < 1 || (int64_t)s->S_obs > s->S) return 0;
+      return value_part_bytes(units_of(s), s->N_q / s->N_kv, s->S_obs, value_split(s).n);
     case THK_OP_PRUNE: {
       // a score array for the whole call + the larger of the two paths' scratch
       const FusedPlan fp = fused_plan(s);
@@ -402,6 +429,28 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
     profile_mark(false, hs);
     if (ce != hipSuccess) return THK_ERR_HIP;
   }
+  return THK_OK;
+}
+
+thk_status thk_score_value(const thk_shape *s, const void *q_obs, const void *k, const void *v,
+                           int32_t causal, float *score_v, void *ws, size_t ws_bytes, void *stream) {
+  thk_status st = check_shape(s, true);
+  if (st != THK_OK) return st;
+  if (q_obs == nullptr || k == nullptr || v == nullptr || score_v == nullptr) return THK_ERR_NULL;
+  if (!aligned16(q_obs) || !aligned16(k) || !aligned16(v) || !aligned16(score_v)) return THK_ERR_ALIGN;
+  if (causal != 0 && causal != 1) return THK_ERR_SHAPE;
+  if (s->dtype != THK_BF16) return THK_ERR_UNSUPPORTED;
+  const int G = s->N_q / s->N_kv;
+  if ((int64_t)G * s->S_obs > 32 * 1024) return THK_ERR_SHAPE;
+  const Split sp = value_split(s);
+  const int QT = value_attn_qt(G, s->S_obs);
+  const int64_t grid = units_of(s) * sp.n * ceil_div((G * s->S_obs + 31) / 32, QT);
+  if (grid > kMaxGrid) return THK_ERR_SHAPE;
+  if (ws == nullptr || !aligned16(ws) || ws_bytes < thk_workspace_bytes(s, THK_OP_SCORE_VALUE))
+    return THK_ERR_WORKSPACE;
+  if (launch_value_score(s->dtype, q_obs, k, v, (float *)ws, score_v, units_of(s), s->S, G, s->S_obs, causal,
+                         sp.n, sp.rows, (hipStream_t)stream) != hipSuccess)
+    return THK_ERR_HIP;
   return THK_OK;
 }
 

@@ -108,4 +108,18 @@ hipError_t launch_tail_append(int dtype, const void *k_new, const void *v_new, v
                               int64_t U, int64_t k_unit_rows, int64_t k_row, int64_t v_unit_rows,
                               int64_t v_row, hipStream_t st);
 
+// ---- value-channel score (Appendix "Value Cache Pruning") ----
+struct ValueAttnArgs {
+  const void *q_obs, *k, *v;
+  float *part;                 // partial records, value_part_bytes() bytes
+  int64_t S, rows_per_split;   // rows_per_split is a multiple of 128
+  int32_t G, S_obs, n_split, causal, n_qblk;
+  float scale_log2;            // log2(e) / sqrt(D)
+};
+int value_attn_qt(int G, int S_obs);   // query tiles of 32 rows carried by one block: 1, 2 or 4
+size_t value_part_bytes(int64_t U, int G, int S_obs, int n_split);
+hipError_t launch_value_score(int dtype, const void *q_obs, const void *k, const void *v, float *part,
+                              float *score, int64_t U, int64_t S, int G, int S_obs, int causal,
+                              int n_split, int64_t rows_per_split, hipStream_t st);
+
 }  // namespace thk

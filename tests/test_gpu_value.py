@@ -1,0 +1,146 @@
+"""GPU parity of the value-cache path (Appendix "Value Cache Pruning"): value-channel score
+on the matrix cores, selection and compaction of value channels, against the CPU fp64 oracle.
+
+Tolerance of the score.  The kernel rounds each softmax probability to bf16 once (relative
+error <= 2^-9) and normalises by the sum of the rounded values, so every row of A stays a
+convex combination: |o_ij - o_ij(exact)| <= 2^-9 * sum_s p_s |v_sj - o_ij| / sum_s p_s
+<= 2^-8 max_s |V[s, j]|, hence |Score_v[j] - exact| <= G sqrt(S_obs) 2^-8 max_s |V[s, j]| in the
+worst case (HARD_TOL, checked on every channel).  The errors of different keys are independent
+and mostly cancel; the typical deviation is a few 1e-4 of the score, and the test also bounds the
+median relative error by MEDIAN_TOL.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_21018_amd as thk
+from oracle import oracle as O
+from paper_2407_21018_amd.synth import as_numpy
+from helpers import DT, TDT, gpu_compact, gpu_select, ws_tensor
+
+pytestmark = pytest.mark.gpu
+D = 128
+MEDIAN_TOL = 1e-3
+
+
+def _randn(shape, dtype, seed, sigma=0.0):
+    g = torch.Generator(device="cuda"); g.manual_seed(seed)
+    x = torch.randn(*shape, generator=g, device="cuda")
+    if sigma:
+        x = x * torch.exp(sigma * torch.randn(shape[-1], generator=g, device="cuda"))
+    return x.to(TDT[dtype])
+
+
+def gpu_score_value(shape, q_obs, k, v, causal):
+    U = shape.L * shape.B * shape.N_kv
+    score = torch.full((U, shape.D), float("nan"), dtype=torch.float32, device=k.device)
+    ws = ws_tensor(thk.thk_workspace_bytes(shape, thk.THK_OP_SCORE_VALUE))
+    thk.thk_score_value(shape, q_obs, k, v, causal, score, ws)
+    torch.cuda.synchronize()
+    return score
+
+
+def check_score(got, want, v_np_f64, G, S_obs, tag):
+    """got, want [U, D]; v_np_f64 [U, S, D]."""
+    err = np.abs(got - want)
+    hard = G * np.sqrt(S_obs) * 2.0 ** -8 * np.abs(v_np_f64).max(axis=1) + 1e-6 * want
+    rel = err / np.maximum(want, 1e-30)
+    print(f"{tag}: max rel {rel.max():.3e} median rel {np.median(rel):.3e} "
+          f"max err/hard bound {(err / hard).max():.3e}", flush=True)
+    assert np.all(np.isfinite(got))
+    assert np.all(err <= hard)
+    assert np.median(rel) <= MEDIAN_TOL
+
+
+CASES = [
+    # G, S_obs, S, n_split, causal, sigma
+    (1, 32, 1037, 0, 0, 0.5),
+    (1, 32, 1037, 0, 1, 0.5),
+    (4, 32, 1037, 3, 1, 0.5),
+    (2, 32, 600, 2, 0, 1.0),
+    (4, 64, 777, 0, 1, 0.5),     # 8 query tiles: two blocks per unit
+    (3, 16, 300, 0, 1, 0.0),     # heads share a query tile; last tile partly empty
+    (1, 8, 129, 1, 1, 0.0),
+    (1, 32, 32, 1, 1, 0.0),      # the window is the whole sequence
+    (1, 1, 1, 1, 0, 0.0),        # one key, one query
+    (2, 5, 40, 0, 1, 0.0),
+    (4, 32, 4100, 0, 0, 1.0),
+    (1, 32, 4100, 8, 1, 1.0),
+]
+
+
+@pytest.mark.parametrize("G,S_obs,S,n_split,causal,sigma", CASES)
+def test_value_score_matches_oracle(G, S_obs, S, n_split, causal, sigma):
+    L, B, N_kv = 1, 2, 2
+    seed = 1000 + 7 * S + G
+    q_obs = _randn((L, B, N_kv * G, S_obs, D), "bf16", seed, sigma)
+    k = _randn((L, B, N_kv, S, D), "bf16", seed + 1, sigma)
+    v = _randn((L, B, N_kv, S, D), "bf16", seed + 2)
+    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, 64, 0, thk.THK_BF16, n_split)
+    print(f"value score G={G} S_obs={S_obs} S={S} n_split={n_split} causal={causal}", flush=True)
+    got = gpu_score_value(shape, q_obs, k, v, causal).cpu().numpy().astype(np.float64)
+    want = O.score_value(as_numpy(q_obs), as_numpy(k), as_numpy(v), "bf16", causal=bool(causal))
+    v64 = v.cpu().to(torch.float64).numpy().reshape(-1, S, D)
+    check_score(got, want.reshape(-1, D), v64, G, S_obs, f"G={G} S_obs={S_obs} S={S}")
+
+
+def test_value_score_split_count_changes_only_rounding():
+    """Any cut of the key axis gives the same score up to fp32 merge rounding."""
+    L, B, N_kv, G, S, S_obs = 1, 1, 2, 2, 3000, 32
+    q_obs = _randn((L, B, N_kv * G, S_obs, D), "bf16", 5, 0.5)
+    k = _randn((L, B, N_kv, S, D), "bf16", 6, 0.5)
+    v = _randn((L, B, N_kv, S, D), "bf16", 7)
+    ref = None
+    for n in (1, 2, 5, 24):
+        shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, 64, 0, thk.THK_BF16, n)
+        got = gpu_score_value(shape, q_obs, k, v, 1).cpu().numpy().astype(np.float64)
+        if ref is None:
+            ref = got
+        # the probabilities are rounded relative to the running maximum of their own piece, so
+        # a different cut rounds differently: same tolerance class as against the oracle
+        assert np.median(np.abs(got - ref) / ref) <= MEDIAN_TOL
+
+
+def test_value_prune_select_and_compact():
+    """score_v -> Top_T -> compaction of V.  The selection is taken in the kernel's precision
+    on both sides (the oracle selects from the float scores the GPU produced) and must agree
+    exactly; the compacted values are a bit copy."""
+    L, B, N_kv, G, S, S_obs, T_v = 1, 2, 2, 4, 900, 32, 77
+    q_obs = _randn((L, B, N_kv * G, S_obs, D), "bf16", 21, 0.5)
+    k = _randn((L, B, N_kv, S, D), "bf16", 22, 0.5)
+    # give the value channels unequal magnitudes so that the ranking is not all near-ties
+    v = _randn((L, B, N_kv, S, D), "bf16", 23, 0.7)
+    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T_v, 0, thk.THK_BF16, 0)
+    score = gpu_score_value(shape, q_obs, k, v, 1)
+    idx = gpu_select(shape, score)
+    want_idx = O.select_topk(score.cpu().numpy().astype(np.float64), T_v)
+    np.testing.assert_array_equal(idx.cpu().numpy(), want_idx)
+    vp = gpu_compact(shape, v, idx)
+    want_vp = O.compact_keys(as_numpy(v).reshape(-1, S, D), want_idx, "bf16")
+    np.testing.assert_array_equal(as_numpy(vp), want_vp)
+    # the oracle's own ranking differs only where its scores are within the score tolerance
+    ora = O.score_value(as_numpy(q_obs), as_numpy(k), as_numpy(v), "bf16", causal=True).reshape(-1, D)
+    ora_idx = O.select_topk(ora, T_v)
+    for u in range(ora.shape[0]):
+        diff = set(ora_idx[u].tolist()) ^ set(want_idx[u].tolist())
+        thr = np.sort(ora[u])[::-1][T_v - 1]
+        for c in diff:
+            assert abs(ora[u, c] - thr) <= 4e-3 * thr, (u, c, ora[u, c], thr)
+
+
+def test_value_score_argument_errors():
+    A = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    s = thk.make_shape(1, 1, 1, 1, D, 64, 32, 64, 0, thk.THK_BF16, 0)
+    def st(*a):
+        try:
+            thk.thk_score_value(*a)
+        except thk.ThkError as e:
+            return e.status
+        return 0
+    big = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    assert st(s, big, big, big, 2, big, big) == 2                      # causal flag out of range
+    sf = thk.make_shape(1, 1, 1, 1, D, 64, 32, 64, 0, thk.THK_F32, 0)
+    assert st(sf, big, big, big, 0, big, big) == 3                     # fp32 not built
+    assert st(s, big, big, big, 0, big, A[:16]) == 5                   # workspace too small
+    s2 = thk.make_shape(1, 1, 1, 1, D, 16, 32, 64, 0, thk.THK_BF16, 0)
+    assert st(s2, big, big, big, 0, big, big) == 2                     # S_obs > S
