@@ -132,12 +132,13 @@ thk_status thk_score_magnitude(const thk_shape *shape, const void *k, int32_t p,
  * key cache.  causal = 0 is the equation as printed (every window row sees all
  * S keys); causal = 1 lets window row i, the token at position S - S_obs + i,
  * see keys 0 .. S - S_obs + i as in the prefill's own attention.  Logits are
- * accumulated in fp32 on the matrix cores, the softmax runs in fp32, and the
- * probabilities are rounded to bf16 once before they multiply V (their row sum
- * is taken over the rounded values); column norms are summed in fp64 and
- * rounded once to float.  Feed the result to thk_select_topk for the value
- * index list and to thk_compact_keys (which copies channels of any [S][D]
- * cache) for the pruned values.  bf16 only (THK_ERR_UNSUPPORTED for fp32).
+ * accumulated in fp32 on the matrix cores and the softmax runs in fp32.  For
+ * bf16 tensors the probabilities are rounded to bf16 once before they multiply
+ * V (their row sum is taken over the rounded values); for fp32 tensors every
+ * product is fp32.  Column norms are summed in fp64 and rounded once to float.
+ * Feed the result to thk_select_topk for the value index list and to
+ * thk_compact_keys (which copies channels of any [S][D] cache) for the pruned
+ * values.
  *   in : q_obs, k, v (device)        out: score_v (device, float, [L][B][N_kv][D])
  *   ws : THK_OP_SCORE_VALUE bytes.
  */

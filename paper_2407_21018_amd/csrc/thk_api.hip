@@ -151,7 +151,7 @@ FusedPlan fused_plan(const thk_shape *s) {
 
 // Split of the S axis for the value score: pieces are whole 128-row chunks of at least 512
 // rows, enough of them for ~4 blocks per compute unit, and few enough that the merge kernel's
-// weight table (pieces x key lanes per block <= 256) fits.
+// weight table (at most 256 pieces) fits.
 Split value_split(const thk_shape *s) {
   const int G = s->N_q / s->N_kv;
   const int QT = value_attn_qt(G, s->S_obs);
@@ -164,8 +164,7 @@ Split value_split(const thk_shape *s) {
     if (n > cap) n = (int)cap;
     if (n < 1) n = 1;
   }
-  const int max_n = 256 / (4 / QT);
-  if (n > max_n) n = max_n;
+  if (n > 256) n = 256;
   int64_t rows = ceil_div(s->S, n);
   rows = ceil_div(rows, 128) * 128;
   n = (int)ceil_div(s->S, rows);   // drop empty pieces
@@ -439,7 +438,6 @@ thk_status thk_score_value(const thk_shape *s, const void *q_obs, const void *k,
   if (q_obs == nullptr || k == nullptr || v == nullptr || score_v == nullptr) return THK_ERR_NULL;
   if (!aligned16(q_obs) || !aligned16(k) || !aligned16(v) || !aligned16(score_v)) return THK_ERR_ALIGN;
   if (causal != 0 && causal != 1) return THK_ERR_SHAPE;
-  if (s->dtype != THK_BF16) return THK_ERR_UNSUPPORTED;
   const int G = s->N_q / s->N_kv;
   if ((int64_t)G * s->S_obs > 32 * 1024) return THK_ERR_SHAPE;
   const Split sp = value_split(s);

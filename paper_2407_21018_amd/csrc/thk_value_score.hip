@@ -30,6 +30,56 @@ namespace {
 constexpr int kRec = 32 * kD + 64;   // floats per partial record: O^T [128][32], m [32], l [32]
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no key seen yet"
 
+// One 32-key sub-tile of the running-maximum softmax in the MFMA accumulator layout: lane
+// (n, h) holds, for query column n, the 16 keys kb + (r / 4) * 8 + h * 4 + r % 4.  Scales the
+// logits into the log2 domain, hides keys past `lim`, updates the running maximum (rescaling
+// the row sum and the output accumulators when some query's maximum moved) and leaves the
+// probabilities exp2(s - m) in s.
+__device__ __forceinline__ void softmax_step(f32x16 &s, int64_t kb, int h, int64_t lim, int64_t lim_min,
+                                             float scale_log2, float &m_run, float &l_run, f32x16 (&o)[4]) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s[r] *= scale_log2;
+  if (kb + 31 > lim_min) {   // wave-uniform: only the sub-tiles that reach the window or the end
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int64_t key = kb + (r >> 2) * 8 + h * 4 + (r & 3);
+      if (key > lim) s[r] = -INFINITY;
+    }
+  }
+  float mt = s[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) mt = fmaxf(mt, s[r]);
+  mt = fmaxf(mt, __shfl_xor(mt, 32));
+  const float m_new = fmaxf(m_run, mt);
+  if (__any(m_new > m_run)) {
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    l_run *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+    m_run = m_new;
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(s[r] - m_run);
+}
+
+// Partial record of one (unit, split, query tile): O^T [128][32], then m [32] and l [32].
+__device__ __forceinline__ void write_record(float *rec, const f32x16 (&o)[4], float m_run, float l_tot, int n,
+                                             int h) {
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int d = dt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+      rec[d * 32 + n] = o[dt][r];
+    }
+  if (h == 0) {
+    rec[32 * kD + n] = m_run;
+    rec[32 * kD + 32 + n] = l_tot;
+  }
+}
+
 // ---------------------------------------------------------------- bf16 ----
 constexpr int kKst = 272;  // LDS bytes per key row: 16-lane b128 reads of 16 rows hit 64 distinct banks
 constexpr int kVst = 320;  // LDS bytes per value row: the 4-row x 32-byte transposing reads of a
@@ -40,8 +90,8 @@ __global__ __launch_bounds__(256, 2) void k_value_attn_bf16(ValueAttnArgs a) {
   constexpr int KW = 4 / QT;     // key sub-tiles per chunk
   constexpr int CR = KW * 32;    // rows per chunk
   constexpr int NP = 2 * KW;     // 16-row staging passes per chunk
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[CR * kKst];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[CR * kVst];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[CR * (kKst + kVst)];
+  unsigned char *Ks = smem, *Vs = smem + CR * kKst;
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int qt = w % QT, ksub = w / QT;
@@ -128,35 +178,12 @@ __global__ __launch_bounds__(256, 2) void k_value_attn_bf16(ValueAttnArgs a) {
         const bf16x8 ka = *(const bf16x8 *)(ka_p + ks * 32);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[ks], s, 0, 0, 0);
       }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] *= a.scale_log2;
-      if (kb + 31 > lim_min) {   // wave-uniform: only the chunks that reach the window or the end
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int64_t key = kb + (r >> 2) * 8 + h * 4 + (r & 3);
-          if (key > lim) s[r] = -INFINITY;
-        }
-      }
-      float mt = s[0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mt = fmaxf(mt, s[r]);
-      mt = fmaxf(mt, __shfl_xor(mt, 32));
-      const float m_new = fmaxf(m_run, mt);
-      if (__any(m_new > m_run)) {
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        l_run *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-        m_run = m_new;
-      }
+      softmax_step(s, kb, h, lim, lim_min, a.scale_log2, m_run, l_run, o);
       // probabilities, rounded to bf16 once; the same rounded values feed the row sum
       bf16x8 pb[2];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(s[r] - m_run);
-        const __bf16 pr = (__bf16)p;
+        const __bf16 pr = (__bf16)s[r];
         pb[r >> 3][r & 7] = pr;
         l_run += (float)pr;
       }
@@ -180,76 +207,230 @@ __global__ __launch_bounds__(256, 2) void k_value_attn_bf16(ValueAttnArgs a) {
     __syncthreads();
   }
 
-  // partial record of (unit, split, key sub-tile lane, query tile)
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  const int n_part = a.n_split * KW;
+  // The waves that carried the same query tile over different key sub-tiles meet in LDS (the
+  // staging buffers are free after the loop's last barrier): common maximum, rescale, and the
+  // wave of sub-tile 0 adds the others up.
+  float l_tot = l_run + __shfl_xor(l_run, 32);
+  if constexpr (KW > 1) {
+    float *mx = (float *)smem;                 // [KW][QT][32] maxima, then [KW][QT][32] sums
+    float *ox = mx + 2 * KW * QT * 32;         // [KW - 1][QT][64 registers][64 lanes]
+    if (h == 0) mx[(ksub * QT + qt) * 32 + n] = m_run;
+    __syncthreads();
+    float M = m_run;
+#pragma unroll
+    for (int k = 0; k < KW; ++k) M = fmaxf(M, mx[(k * QT + qt) * 32 + n]);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - M);
+    l_tot *= alpha;
+    m_run = M;
+    if (ksub > 0) {
+      float *dst = ox + (size_t)((ksub - 1) * QT + qt) * 64 * 64 + lane;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dst[(dt * 16 + r) * 64] = o[dt][r] * alpha;
+      if (h == 0) mx[(KW + ksub) * QT * 32 + qt * 32 + n] = l_tot;
+    }
+    __syncthreads();
+    if (ksub > 0) return;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+#pragma unroll
+    for (int k = 1; k < KW; ++k) {
+      const float *src = ox + (size_t)((k - 1) * QT + qt) * 64 * 64 + lane;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] += src[(dt * 16 + r) * 64];
+      l_tot += mx[(KW + k) * QT * 32 + qt * 32 + n];
+    }
+  }
+  // partial record of (unit, split, query tile)
   const int nqt = a.n_qblk * QT;
-  float *rec = a.part + (((size_t)u * n_part + (size_t)sp * KW + ksub) * nqt + qtile) * kRec;
+  write_record(a.part + (((size_t)u * a.n_split + sp) * nqt + qtile) * kRec, o, m_run, l_tot, n, h);
+}
+
+// ---------------------------------------------------------------- fp32 ----
+// The same streaming attention in full fp32 on v_mfma_f32_32x32x2_f32 (one 32-key tile per
+// step, one wave per query tile, QT waves per block).  The contraction index of an MFMA step is
+// the lane half h: step j of the logits multiplies channel 8 * (j / 4) + 4 * h + j % 4, so a
+// lane reads its four channels of four consecutive steps as one 16-byte LDS word; step j of
+// O^T += V^T P^T multiplies key (j / 4) * 8 + 4 * h + j % 4, which is accumulator register j of
+// P^T.  Probabilities stay fp32.
+constexpr int kKstF = 528;  // LDS bytes per key row (b128 reads of 16 rows: 64 distinct banks)
+constexpr int kVstF = 544;  // LDS bytes per value row (the two halves read rows 4 apart: 32 banks apart)
+
+template <int QT>
+__global__ __launch_bounds__(64 * QT) void k_value_attn_f32(ValueAttnArgs a) {
+  __shared__ __attribute__((aligned(16))) unsigned char Ks[32 * kKstF];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs[32 * kVstF];
+  constexpr int NT = 64 * QT;
+  const int tid = threadIdx.x, lane = tid & 63, qt = tid >> 6;
+  const int n = lane & 31, h = lane >> 5;
+
+  int64_t bid = blockIdx.x;
+  const int qb = (int)(bid % a.n_qblk);
+  bid /= a.n_qblk;
+  const int sp = (int)(bid % a.n_split);
+  const int64_t u = bid / a.n_split;
+
+  const int rows_q = a.G * a.S_obs;
+  const int qtile = qb * QT + qt;
+  const int row = qtile * 32 + n;
+  const int64_t S = a.S;
+
+  float4 qreg[16];   // channels 8 * jj + 4 * h .. + 3 of this lane's query row
+  {
+    const float *qp = (const float *)a.q_obs + ((size_t)u * rows_q + (row < rows_q ? row : 0)) * kD + h * 4;
+#pragma unroll
+    for (int jj = 0; jj < 16; ++jj) {
+      qreg[jj] = *(const float4 *)(qp + jj * 8);
+      if (row >= rows_q) qreg[jj] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  const int64_t lim = a.causal ? S - a.S_obs + (row % a.S_obs) : S - 1;
+  const int64_t lim_min = a.causal ? S - a.S_obs : S - 1;
+  const int64_t k0 = (int64_t)sp * a.rows_per_split;
+  const int64_t k1 = (k0 + a.rows_per_split < S) ? k0 + a.rows_per_split : S;
+
+  const unsigned char *kg = (const unsigned char *)a.k + (size_t)u * S * (kD * 4);
+  const unsigned char *vg = (const unsigned char *)a.v + (size_t)u * S * (kD * 4);
+
+  f32x16 o[4];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int d = dt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-      rec[d * 32 + n] = o[dt][r];
+    for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+  float m_run = kNegBig, l_run = 0.f;
+
+  const unsigned char *ka_p = Ks + n * kKstF + h * 16;
+  const unsigned char *va_p = Vs + (h * 4) * kVstF + n * 4;
+
+  for (int64_t kb = k0; kb < k1; kb += 32) {
+    __syncthreads();   // the previous tile is no longer read
+    // 32 rows of 512 bytes each: 1024 16-byte pieces per tensor
+#pragma unroll 4
+    for (int i = tid; i < 1024; i += NT) {
+      const int r = i >> 5, c = (i & 31) * 16;
+      int64_t gr = kb + r;
+      gr = gr < S ? gr : S - 1;   // rows past the end repeat the last one; their weights are zero
+      *(u32x4 *)(Ks + r * kKstF + c) = *(const u32x4 *)(kg + gr * (kD * 4) + c);
+      *(u32x4 *)(Vs + r * kVstF + c) = *(const u32x4 *)(vg + gr * (kD * 4) + c);
     }
-  if (h == 0) {
-    rec[32 * kD + n] = m_run;
-    rec[32 * kD + 32 + n] = l_tot;
+    __syncthreads();
+    f32x16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int jj = 0; jj < 16; ++jj) {
+      const float4 ka = *(const float4 *)(ka_p + jj * 32);
+      s = __builtin_amdgcn_mfma_f32_32x32x2f32(ka.x, qreg[jj].x, s, 0, 0, 0);
+      s = __builtin_amdgcn_mfma_f32_32x32x2f32(ka.y, qreg[jj].y, s, 0, 0, 0);
+      s = __builtin_amdgcn_mfma_f32_32x32x2f32(ka.z, qreg[jj].z, s, 0, 0, 0);
+      s = __builtin_amdgcn_mfma_f32_32x32x2f32(ka.w, qreg[jj].w, s, 0, 0, 0);
+    }
+    softmax_step(s, kb, h, lim, lim_min, a.scale_log2, m_run, l_run, o);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) l_run += s[r];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const unsigned char *vp = va_p + ((j >> 2) * 8 + (j & 3)) * kVstF;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        const float va = *(const float *)(vp + dt * 128);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x2f32(va, s[j], o[dt], 0, 0, 0);
+      }
+    }
   }
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const int nqt = a.n_qblk * QT;
+  write_record(a.part + (((size_t)u * a.n_split + sp) * nqt + qtile) * kRec, o, m_run, l_tot, n, h);
 }
 
-// Merge the partial records of one unit, normalise, and take the column norms per query head.
-// 128 threads = the 128 value channels.
-__global__ __launch_bounds__(128) void k_value_finalize(const float *part, float *score, int G, int S_obs,
-                                                        int n_part, int nqt) {
-  extern __shared__ float wts[];   // [n_part][32] merge weights of the current query tile
-  const int64_t u = blockIdx.x;
-  const int d = threadIdx.x;
+// Merge the partial records of one 32-row query tile of one unit and normalise.  256 threads:
+// thread (d, half) sums the records p = half, half + 2, ... for value channel d; the halves meet
+// in LDS.  A unit with a single tile gets its score here (each thread holds all of its rows);
+// otherwise the squared outputs go to sq[u][row][d] for k_value_norms.
+__global__ __launch_bounds__(256) void k_value_merge(const float *part, float *sq, float *score, int G, int S_obs,
+                                                     int n_part, int nqt, int nt) {
+  extern __shared__ float wts[];   // [n_part][32] merge weights, then [128][33] for the halves
+  const int64_t u = blockIdx.x / nt;
+  const int t = (int)(blockIdx.x % nt);
+  const int d = threadIdx.x & 127, half = threadIdx.x >> 7;
   const int rows_q = G * S_obs;
   const float *pu = part + (size_t)u * n_part * nqt * kRec;
-  double ss = 0.0, total = 0.0;   // running sum of squares of the current head; sum of finished heads
-  for (int t = 0; t * 32 < rows_q; ++t) {
-    __syncthreads();
-    if (d < 32) {
-      float M = kNegBig;
-      for (int p = 0; p < n_part; ++p) M = fmaxf(M, pu[((size_t)p * nqt + t) * kRec + 32 * kD + d]);
-      float L = 0.f;
-      for (int p = 0; p < n_part; ++p) {
-        const float *r = pu + ((size_t)p * nqt + t) * kRec + 32 * kD;
-        const float wv = __builtin_amdgcn_exp2f(r[d] - M);
-        wts[p * 32 + d] = wv;
-        L += wv * r[32 + d];
-      }
-      const float inv = L > 0.f ? 1.f / L : 0.f;
-      for (int p = 0; p < n_part; ++p) wts[p * 32 + d] *= inv;
-    }
-    __syncthreads();
-    float acc[32];
-#pragma unroll
-    for (int q = 0; q < 32; ++q) acc[q] = 0.f;
+  if (threadIdx.x < 32) {
+    const int q = threadIdx.x;
+    float M = kNegBig;
+    for (int p = 0; p < n_part; ++p) M = fmaxf(M, pu[((size_t)p * nqt + t) * kRec + 32 * kD + q]);
+    float L = 0.f;
     for (int p = 0; p < n_part; ++p) {
-      const float4 *src = (const float4 *)(pu + ((size_t)p * nqt + t) * kRec + d * 32);
-      const float *wp = wts + p * 32;
-#pragma unroll
-      for (int q4 = 0; q4 < 8; ++q4) {
-        const float4 x = src[q4];
-        acc[q4 * 4 + 0] += wp[q4 * 4 + 0] * x.x;
-        acc[q4 * 4 + 1] += wp[q4 * 4 + 1] * x.y;
-        acc[q4 * 4 + 2] += wp[q4 * 4 + 2] * x.z;
-        acc[q4 * 4 + 3] += wp[q4 * 4 + 3] * x.w;
-      }
+      const float *r = pu + ((size_t)p * nqt + t) * kRec + 32 * kD;
+      const float wv = __builtin_amdgcn_exp2f(r[q] - M);
+      wts[p * 32 + q] = wv;
+      L += wv * r[32 + q];
     }
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    for (int p = 0; p < n_part; ++p) wts[p * 32 + q] *= inv;
+  }
+  __syncthreads();
+  float acc[32];
+#pragma unroll
+  for (int q = 0; q < 32; ++q) acc[q] = 0.f;
+  for (int p = half; p < n_part; p += 2) {
+    const float4 *src = (const float4 *)(pu + ((size_t)p * nqt + t) * kRec + d * 32);
+    const float *wp = wts + p * 32;
+#pragma unroll
+    for (int q4 = 0; q4 < 8; ++q4) {
+      const float4 x = src[q4];
+      acc[q4 * 4 + 0] += wp[q4 * 4 + 0] * x.x;
+      acc[q4 * 4 + 1] += wp[q4 * 4 + 1] * x.y;
+      acc[q4 * 4 + 2] += wp[q4 * 4 + 2] * x.z;
+      acc[q4 * 4 + 3] += wp[q4 * 4 + 3] * x.w;
+    }
+  }
+  __syncthreads();               // the weights are no longer read
+  float *xch = wts;              // [128][33]
+  if (half == 1) {
+#pragma unroll
+    for (int q = 0; q < 32; ++q) xch[d * 33 + q] = acc[q];
+  }
+  __syncthreads();
+  if (half == 1) return;
+#pragma unroll
+  for (int q = 0; q < 32; ++q) acc[q] += xch[d * 33 + q];
+  if (nt == 1) {
+    double ss = 0.0, total = 0.0;
 #pragma unroll
     for (int q = 0; q < 32; ++q) {
-      const int row = t * 32 + q;
-      if (row < rows_q) {
+      if (q < rows_q) {
         ss += (double)acc[q] * (double)acc[q];
-        if ((row + 1) % S_obs == 0) {   // last window row of a head
+        if ((q + 1) % S_obs == 0) {   // last window row of a head
           total += sqrt(ss);
           ss = 0.0;
         }
       }
     }
+    score[(size_t)u * kD + d] = (float)total;
+  } else {
+    float *dst = sq + ((size_t)u * nt + t) * 32 * kD;
+#pragma unroll
+    for (int q = 0; q < 32; ++q) dst[q * kD + d] = acc[q] * acc[q];
+  }
+}
+
+// Column norms per query head from the squared outputs: thread d walks the unit's rows in
+// (head, window row) order and closes a head at its last row.
+__global__ __launch_bounds__(128) void k_value_norms(const float *sq, float *score, int G, int S_obs, int nt) {
+  const int64_t u = blockIdx.x;
+  const int d = threadIdx.x;
+  const float *src = sq + (size_t)u * nt * 32 * kD + d;
+  double total = 0.0;
+  for (int g = 0; g < G; ++g) {
+    double ss = 0.0;
+    for (int i = 0; i < S_obs; ++i) ss += (double)src[(size_t)(g * S_obs + i) * kD];
+    total += sqrt(ss);
   }
   score[(size_t)u * kD + d] = (float)total;
 }
@@ -265,13 +446,13 @@ size_t value_part_bytes(int64_t U, int G, int S_obs, int n_split) {
   const int QT = value_attn_qt(G, S_obs);
   const int nqt = (G * S_obs + 31) / 32;
   const int n_qblk = (nqt + QT - 1) / QT;
-  return (size_t)U * n_split * (4 / QT) * n_qblk * QT * kRec * sizeof(float);
+  const size_t sq = nqt > 1 ? (size_t)U * nqt * 32 * kD * sizeof(float) : 0;
+  return (size_t)U * n_split * n_qblk * QT * kRec * sizeof(float) + sq;
 }
 
 hipError_t launch_value_score(int dtype, const void *q_obs, const void *k, const void *v, float *part,
                               float *score, int64_t U, int64_t S, int G, int S_obs, int causal,
                               int n_split, int64_t rows_per_split, hipStream_t st) {
-  if (dtype != THK_BF16) return hipErrorInvalidValue;
   const int QT = value_attn_qt(G, S_obs);
   const int nqt_real = (G * S_obs + 31) / 32;
   ValueAttnArgs a;
@@ -282,15 +463,28 @@ hipError_t launch_value_score(int dtype, const void *q_obs, const void *k, const
   a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)kD));
   const unsigned grid = (unsigned)(U * n_split * a.n_qblk);
   profile_mark(true, st);
-  if (QT == 4) hipLaunchKernelGGL(k_value_attn_bf16<4>, dim3(grid), dim3(256), 0, st, a);
-  else if (QT == 2) hipLaunchKernelGGL(k_value_attn_bf16<2>, dim3(grid), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL(k_value_attn_bf16<1>, dim3(grid), dim3(256), 0, st, a);
+  if (dtype == THK_BF16) {
+    if (QT == 4) hipLaunchKernelGGL(k_value_attn_bf16<4>, dim3(grid), dim3(256), 0, st, a);
+    else if (QT == 2) hipLaunchKernelGGL(k_value_attn_bf16<2>, dim3(grid), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(k_value_attn_bf16<1>, dim3(grid), dim3(256), 0, st, a);
+  } else {
+    if (QT == 4) hipLaunchKernelGGL(k_value_attn_f32<4>, dim3(grid), dim3(256), 0, st, a);
+    else if (QT == 2) hipLaunchKernelGGL(k_value_attn_f32<2>, dim3(grid), dim3(128), 0, st, a);
+    else hipLaunchKernelGGL(k_value_attn_f32<1>, dim3(grid), dim3(64), 0, st, a);
+  }
   profile_mark(false, st);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int n_part = n_split * (4 / QT);
-  hipLaunchKernelGGL(k_value_finalize, dim3((unsigned)U), dim3(128), (size_t)n_part * 32 * sizeof(float), st,
-                     part, score, G, S_obs, n_part, a.n_qblk * QT);
+  const int n_part = n_split;
+  const int nqt = a.n_qblk * QT;
+  float *sq = part + (size_t)U * n_part * nqt * kRec;   // behind the partial records
+  size_t lds = (size_t)n_part * 32 * sizeof(float);
+  if (lds < 128 * 33 * sizeof(float)) lds = 128 * 33 * sizeof(float);
+  hipLaunchKernelGGL(k_value_merge, dim3((unsigned)(U * nqt_real)), dim3(256), lds, st, part, sq, score, G, S_obs,
+                     n_part, nqt, nqt_real);
+  e = hipGetLastError();
+  if (e != hipSuccess || nqt_real == 1) return e;
+  hipLaunchKernelGGL(k_value_norms, dim3((unsigned)U), dim3(128), 0, st, sq, score, G, S_obs, nqt_real);
   return hipGetLastError();
 }
 
