@@ -202,6 +202,26 @@ thk_status thk_decode_attn(const thk_shape *shape, const void *q,
                            size_t ws_bytes, void *stream);
 
 /*
+ * Decode attention with the VALUE cache channel-pruned as well (Appendix "Value
+ * Cache Pruning"; keys as in thk_decode_attn).  V_pruned [L][B][N_kv][S_cap][ld_v]
+ * holds, per row, the T_v channels idx_v[0 .. T_v) of the values (what
+ * thk_compact_keys writes from V with the value index list and ld_keep = ld_v).
+ * A removed channel contributes nothing:
+ *   out[n][c] = ( sum_s p_s V_pruned[h][s][t]   if c == idx_v[h][t], else 0
+ *               + sum_j p_{S+j} V_tail[h][j][c] ) / sum p
+ * The tail keeps full-width rows (v_tail is required when s_tail > 0).
+ * 1 <= T_v <= ld_v <= D; ld_v must be a multiple of 4 (THK_ERR_UNSUPPORTED
+ * otherwise); idx_v [L][B][N_kv][T_v] int16, ascending, 16-byte aligned.
+ *   ws : THK_OP_DECODE bytes.
+ */
+thk_status thk_decode_attn_kv(const thk_shape *shape, const void *q, const void *k_pruned,
+                              const int16_t *idx, const void *v_pruned,
+                              const int16_t *idx_v, int32_t T_v, int32_t ld_v,
+                              const void *k_tail, const void *v_tail, int32_t s_tail,
+                              int32_t s_tail_cap, void *out, void *ws, size_t ws_bytes,
+                              void *stream);
+
+/*
  * Append one newly decoded token per (layer, batch, KV head) to the unpruned
  * tail segment (Sec. 3.3: new keys stay at full D):
  *   K_tail[..][s_tail][:] = k_new[..][:],  V_tail[..][s_tail][:] = v_new[..][:]

@@ -71,6 +71,9 @@ def load():
     L.thk_decode_attn.restype = ctypes.c_int
     L.thk_decode_attn.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
     i64 = ctypes.c_int64
+    L.thk_decode_attn_kv.restype = ctypes.c_int
+    L.thk_decode_attn_kv.argtypes = [sp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, i32, vp, vp,
+                                     ctypes.c_size_t, vp]
     L.thk_compact_rows.restype = ctypes.c_int
     L.thk_compact_rows.argtypes = [sp, vp, i64, i64, vp, vp, i64, i64, vp]
     L.thk_copy_rows.restype = ctypes.c_int
@@ -243,6 +246,26 @@ def thk_decode_attn(shape, q, k_pruned, idx, v, k_tail, v_tail, s_tail, s_tail_c
     _check(load().thk_decode_attn(ctypes.byref(shape), _ptr(q), _ptr(k_pruned), _ptr(idx), _ptr(v),
                                   _ptr(k_tail), _ptr(v_tail), s_tail, s_tail_cap, _ptr(out),
                                   _ws(ws), _nbytes(ws), _stream(stream)), "thk_decode_attn")
+
+
+def thk_decode_attn_kv(shape, q, k_pruned, idx, v_pruned, idx_v, T_v, ld_v, k_tail, v_tail, s_tail,
+                       s_tail_cap, out, ws, stream=None):
+    U, H, ld = _dims(shape)
+    w = "thk_decode_attn_kv"
+    _need(q, H * shape.D, "q", w)
+    _need(out, H * shape.D, "out", w)
+    rows = _cache_rows(shape, shape.S)
+    _need(k_pruned, U * rows * ld, "k_pruned", w)
+    _need(idx, U * shape.T, "idx", w)
+    _need(v_pruned, U * rows * max(ld_v, 0), "v_pruned", w)
+    _need(idx_v, U * max(T_v, 0), "idx_v", w)
+    if s_tail > 0:
+        _need(k_tail, U * s_tail_cap * shape.D, "k_tail", w)
+        _need(v_tail, U * s_tail_cap * shape.D, "v_tail", w)
+    _check(load().thk_decode_attn_kv(ctypes.byref(shape), _ptr(q), _ptr(k_pruned), _ptr(idx),
+                                     _ptr(v_pruned), _ptr(idx_v), T_v, ld_v, _ptr(k_tail), _ptr(v_tail),
+                                     s_tail, s_tail_cap, _ptr(out), _ws(ws), _nbytes(ws),
+                                     _stream(stream)), w)
 
 
 def thk_tail_append(shape, k_new, v_new, k_tail, v_tail, s_tail, s_tail_cap, stream=None):

@@ -452,15 +452,22 @@ thk_status thk_score_value(const thk_shape *s, const void *q_obs, const void *k,
   return THK_OK;
 }
 
-thk_status thk_decode_attn(const thk_shape *s, const void *q, const void *k_pruned,
-                           const int16_t *idx, const void *v, const void *k_tail,
-                           const void *v_tail, int32_t s_tail, int32_t s_tail_cap, void *out,
-                           void *ws, size_t ws_bytes, void *stream) {
+static thk_status decode_common(const thk_shape *s, const void *q, const void *k_pruned,
+                                const int16_t *idx, const void *v, const int16_t *idx_v, int32_t T_v,
+                                int32_t ld_v, const void *k_tail, const void *v_tail, int32_t s_tail,
+                                int32_t s_tail_cap, void *out, void *ws, size_t ws_bytes, void *stream) {
   thk_status st = check_shape(s, false);
   if (st != THK_OK) return st;
   if (q == nullptr || k_pruned == nullptr || idx == nullptr || v == nullptr || out == nullptr) return THK_ERR_NULL;
   if (s_tail < 0 || s_tail_cap < 0 || s_tail > s_tail_cap) return THK_ERR_SHAPE;
   if (s_tail > 0 && k_tail == nullptr) return THK_ERR_NULL;
+  const bool pruned_v = T_v > 0;
+  if (pruned_v) {
+    if (idx_v == nullptr || (s_tail > 0 && v_tail == nullptr)) return THK_ERR_NULL;
+    if (T_v > s->D || ld_v < T_v || ld_v > s->D) return THK_ERR_SHAPE;
+    if (ld_v % 4 != 0) return THK_ERR_UNSUPPORTED;
+    if (!aligned16(idx_v)) return THK_ERR_ALIGN;
+  }
   const bool unified_v = s_tail > 0 && v_tail == nullptr;   // tail values follow row S in v
   const int64_t unit_rows = cache_rows(s, s->S);
   if (unit_rows < s->S + (unified_v ? s_tail : 0)) return THK_ERR_SHAPE;
@@ -482,8 +489,27 @@ thk_status thk_decode_attn(const thk_shape *s, const void *q, const void *k_prun
   a.unit_rows = unit_rows;
   a.unified_v = unified_v ? 1 : 0;
   a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)s->D));
+  a.idx_v = idx_v; a.T_v = pruned_v ? T_v : 0; a.ld_v = pruned_v ? ld_v : 0;
   if (launch_decode(a, (hipStream_t)stream) != hipSuccess) return THK_ERR_HIP;
   return THK_OK;
+}
+
+thk_status thk_decode_attn(const thk_shape *s, const void *q, const void *k_pruned,
+                           const int16_t *idx, const void *v, const void *k_tail,
+                           const void *v_tail, int32_t s_tail, int32_t s_tail_cap, void *out,
+                           void *ws, size_t ws_bytes, void *stream) {
+  return decode_common(s, q, k_pruned, idx, v, nullptr, 0, 0, k_tail, v_tail, s_tail, s_tail_cap, out, ws,
+                       ws_bytes, stream);
+}
+
+thk_status thk_decode_attn_kv(const thk_shape *s, const void *q, const void *k_pruned,
+                              const int16_t *idx, const void *v_pruned, const int16_t *idx_v,
+                              int32_t T_v, int32_t ld_v, const void *k_tail, const void *v_tail,
+                              int32_t s_tail, int32_t s_tail_cap, void *out, void *ws,
+                              size_t ws_bytes, void *stream) {
+  if (T_v < 1) return s == nullptr ? THK_ERR_NULL : THK_ERR_SHAPE;
+  return decode_common(s, q, k_pruned, idx, v_pruned, idx_v, T_v, ld_v, k_tail, v_tail, s_tail, s_tail_cap, out,
+                       ws, ws_bytes, stream);
 }
 
 thk_status thk_tail_append(const thk_shape *s, const void *k_new, const void *v_new, void *k_tail,

@@ -132,6 +132,18 @@ struct TileState {
   float m[GT];                       // running max (log2 domain)
   float l[GT];                       // per-lane partial sum of probabilities
   float acc[GT][Elem<DT>::VEC];      // per-lane partial output channels
+  float accp[GT][4];                 // channel-pruned values only: partial sums of 4 kept channels
+};
+
+// A lane's view of a tile of channel-pruned value rows staged in its wave's LDS slab: rows are
+// ld elements apart, groups of 4 kept channels go to lanes (col), and rpw rows are handled per
+// step (rsub = this lane's row within a step).
+struct VPruned {
+  char *vbuf;
+  int shift;        // bytes from the slab start to the tile's first row
+  int ld;
+  int rpw, rsub, col;
+  bool active;
 };
 
 // Issue the global loads of a tile of `nrows` rows, W elements wide with row
@@ -195,13 +207,18 @@ __device__ __forceinline__ void v_issue(u32x4 (&vr)[NV], const u32x4 *__restrict
 // acc += p.V.  vg: the tile's value rows (16-byte chunks, 128 elements per row).
 // qs: [GT][kQS] floats, entries 128..135 of every vector are zero; qp: the same
 // vectors as packed bf16 pairs, [GT][kQS / 2] words (bf16 inputs only).
-template <int DT, int GT, int RA, int TR, int NV>
+// PV = 0: value rows are full width (vg, vr).  PV = 1: value rows are channel-pruned; their
+// bytes are in vrp (KBV staged chunks per lane) and are walked out of LDS as described by vp.
+// PV = 2: a full-width tile (the tail) of a kernel that also carries pruned-value sums, which
+// follow every change of the running maximum.
+template <int DT, int GT, int RA, int TR, int NV, int PV = 0, int KBV = 1>
 __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld,
                                              const float *__restrict__ qs,
                                              const uint32_t *__restrict__ qp,
                                              const u32x4 *__restrict__ vg,
                                              u32x4 (&vr)[NV], const char *kbuf,
-                                             float *ps, TileState<DT, GT> &st, float scale, int lane) {
+                                             float *ps, TileState<DT, GT> &st, float scale, int lane,
+                                             const u32x4 (*vrp)[KBV] = nullptr, const VPruned *vp = nullptr) {
   using E = Elem<DT>;
   using VS = VShape<DT, TR>;
   constexpr int VEC = E::VEC, EB = E::EB;
@@ -277,6 +294,10 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
       st.l[g] *= corr;
 #pragma unroll
       for (int v = 0; v < VEC; ++v) st.acc[g][v] *= corr;
+      if constexpr (PV != 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) st.accp[g][e] *= corr;
+      }
       st.m[g] = m_new;
     }
     pr[g] = __builtin_amdgcn_exp2f(zz - m_new);
@@ -291,6 +312,33 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
 #pragma unroll
     for (int g = 0; g < GT; ++g) ps[r * GT + g] = pr[g];
   }
+  if constexpr (PV == 1) {
+    // ---- accp += p . V_pruned: value bytes to LDS, then 4 kept channels per lane ----------
+    k_commit<KBV>(*vrp, vp->vbuf, lane);
+    wave_sync_lds();
+    const char *vrow = vp->vbuf + vp->shift + ((size_t)vp->rsub * vp->ld + vp->col * 4) * EB;
+    const size_t step = (size_t)vp->rpw * vp->ld * EB;
+    for (int r0 = 0; r0 < nrows; r0 += vp->rpw, vrow += step) {
+      const int row = r0 + vp->rsub;
+      if (vp->active && row < nrows) {
+        float f[4];
+        if constexpr (DT == THK_BF16) {
+          const uint2 w = *(const uint2 *)vrow;
+          f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xffff0000u);
+          f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xffff0000u);
+        } else {
+          const float4 w = *(const float4 *)vrow;
+          f[0] = w.x; f[1] = w.y; f[2] = w.z; f[3] = w.w;
+        }
+#pragma unroll
+        for (int g = 0; g < GT; ++g) {
+          const float pg = ps[row * GT + g];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) st.accp[g][e] = fmaf(pg, f[e], st.accp[g][e]);
+        }
+      }
+    }
+  } else {
   wave_sync_lds();
 
   // ---- acc += p . V --------------------------------------------------------
@@ -319,12 +367,18 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
     }
     if (b + 1 < VS::NB) v_issue<DT, TR, NV>(vr, vg, nrows, b + 1, lane);
   }
+  }
   wave_sync_lds();   // ps and kbuf are rewritten by the next tile
 }
 
 // KB: 16-byte K chunks a lane may have to stage for one TR-row pruned tile.
 // WPE: resident waves per SIMD the register budget is set for.
-template <int DT, int GT, int RA, int KB, int TR, int WPE>
+// VP = 1: the value rows of the pruned segment hold only the T_v kept channels (a.v is
+// V_pruned with rows a.ld_v elements apart, a.idx_v lists the channels).  Their bytes are staged
+// like the key bytes (KB chunks per lane, the class is chosen for the wider of the two) and
+// each lane accumulates 4 kept channels; at the end the sums are scattered to their channels.
+// The tail keeps full-width value rows.
+template <int DT, int GT, int RA, int KB, int TR, int WPE, int VP = 0>
 __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, int kbuf_bytes) {
   using E = Elem<DT>;
   using VS = VShape<DT, TR>;
@@ -338,9 +392,20 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   float *mrg = (float *)(qfp + GT * (kQS / 2));  // [4][GT][130] per-wave states for the final merge
   char *wbase = (char *)(mrg + 4 * GT * (kD + 2));
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-  const int wstride = kbuf_bytes + GT * TR * 4;
+  const int wstride = kbuf_bytes + GT * TR * 4 + (VP ? kbuf_bytes : 0);
   char *kbuf = wbase + (size_t)wave * wstride;
   float *ps = (float *)(kbuf + kbuf_bytes);
+  VPruned vpd;
+  vpd.vbuf = (char *)(ps + GT * TR);
+  vpd.shift = 0;
+  vpd.ld = a.ld_v;
+  {
+    const int lprv = VP ? (a.T_v + 3) / 4 : 1;          // lanes per value row, <= 32
+    vpd.rpw = min(kWave / lprv, 8);
+    vpd.rsub = lane / lprv;
+    vpd.col = lane % lprv;
+    vpd.active = vpd.rsub < vpd.rpw;
+  }
 
   const int sp = (int)(blockIdx.x % a.n_split);
   const int64_t ug = blockIdx.x / a.n_split;
@@ -362,11 +427,16 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   // the first tile's key and value bytes start moving before anything else happens
   u32x4 kr[KB];
   u32x4 vr[NV];
+  u32x4 vrp[VP ? KB : 1];
   int shift_next = 0;
   if (wave < nt_p) {
     const int nr = (int)min((int64_t)TR, s1 - s0 - (int64_t)wave * TR);
     shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)wave * TR) * a.ldk * EB, nr, a.T, a.ldk, lane);
-    v_issue<DT, TR, NV>(vr, vbase + (size_t)wave * TR * LPR, nr, 0, lane);
+    if constexpr (VP)
+      vpd.shift = k_issue<DT, KB>(vrp, (const char *)a.v, (krow0 + (size_t)wave * TR) * a.ld_v * EB, nr, a.T_v,
+                                  a.ld_v, lane);
+    else
+      v_issue<DT, TR, NV>(vr, vbase + (size_t)wave * TR * LPR, nr, 0, lane);
   }
 
   // query: gather the kept channels (Sec. 3.3: the query is pruned with the stored mask)
@@ -396,6 +466,8 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     st.m[g] = -INFINITY; st.l[g] = 0.f;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) st.acc[g][v] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) st.accp[g][e] = 0.f;
   }
 
   // ---- pruned segment: the K bytes of this wave's next tile are in flight while
@@ -405,13 +477,23 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     const u32x4 *vg = vbase + (size_t)ti * TR * LPR;
     const int shift = shift_next;
     k_commit<KB>(kr, kbuf, lane);
-    if (ti != wave) v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
+    if (ti != wave) {
+      if constexpr (VP)
+        vpd.shift = k_issue<DT, KB>(vrp, (const char *)a.v, (krow0 + (size_t)ti * TR) * a.ld_v * EB, nrows,
+                                    a.T_v, a.ld_v, lane);
+      else
+        v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
+    }
     if (ti + 4 < nt_p) {
       const int nr = (int)min((int64_t)TR, s1 - s0 - (int64_t)(ti + 4) * TR);
       shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)(ti + 4) * TR) * a.ldk * EB, nr, a.T, a.ldk, lane);
     }
     wave_sync_lds();
-    tile_compute<DT, GT, RA, TR, NV>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st, a.scale_log2, lane);
+    if constexpr (VP)
+      tile_compute<DT, GT, RA, TR, NV, 1, KB>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st,
+                                              a.scale_log2, lane, &vrp, &vpd);
+    else
+      tile_compute<DT, GT, RA, TR, NV>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st, a.scale_log2, lane);
   }
 
   // ---- unpruned tail segment (full-width keys, full query) ------------------
@@ -427,7 +509,8 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
     k_commit<KBT>(kt, kbuf, lane);
     wave_sync_lds();
-    tile_compute<DT, GT, 16, TR, NV>(0, nrows, kD, kD, qf, qfp, vg, vr, kbuf, ps, st, a.scale_log2, lane);
+    tile_compute<DT, GT, 16, TR, NV, (VP ? 2 : 0)>(0, nrows, kD, kD, qf, qfp, vg, vr, kbuf, ps, st, a.scale_log2,
+                                                    lane);
   }
 
   // ---- wave state -> LDS ---------------------------------------------------
@@ -443,6 +526,24 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     if (lane < LPR)
 #pragma unroll
       for (int v = 0; v < VEC; ++v) rec[2 + lane * VEC + v] = st.acc[g][v];
+  }
+  if constexpr (VP) {
+    // the sums over the pruned rows go to their channels, one row-within-step group at a time
+    const int16_t *uidv = a.idx_v + (size_t)u * a.T_v;
+    for (int rs = 0; rs < vpd.rpw; ++rs) {
+      wave_sync_lds();
+      if (vpd.active && vpd.rsub == rs) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int t = vpd.col * 4 + e;
+          if (t < a.T_v) {
+            const int c = uidv[t];
+#pragma unroll
+            for (int g = 0; g < GT; ++g) mrg[(size_t)(wave * GT + g) * (kD + 2) + 2 + c] += st.accp[g][e];
+          }
+        }
+      }
+    }
   }
   __syncthreads();
 
@@ -490,44 +591,50 @@ inline DecodeLaunch decode_launch_params(const DecodeArgs &a, int tr) {
   return p;
 }
 
-template <int DT, int GT, int RA, int KB, int TR, int WPE>
+template <int DT, int GT, int RA, int KB, int TR, int WPE, int VP>
 inline hipError_t decode_launch_one(const DecodeArgs &a, int groups, hipStream_t st) {
   constexpr int eb = Elem<DT>::EB;
   int kbuf = KB * kWave * 16;                      // every staged chunk has an LDS slot
   const int tailbuf = kTailRows * kD * eb;
   if (kbuf < tailbuf) kbuf = tailbuf;
-  const size_t lds = (size_t)(3 * GT * kQS + 4 * GT * (kD + 2)) * 4 + 4 * ((size_t)kbuf + GT * TR * 4);
+  const size_t lds = (size_t)(3 * GT * kQS + 4 * GT * (kD + 2)) * 4 +
+                     4 * ((size_t)kbuf * (VP ? 2 : 1) + GT * TR * 4);
   const dim3 grid((unsigned)(a.units * groups * a.n_split)), block(256);
   if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void *)k_decode<DT, GT, RA, KB, TR, WPE>,
+    hipError_t e = hipFuncSetAttribute((const void *)k_decode<DT, GT, RA, KB, TR, WPE, VP>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((k_decode<DT, GT, RA, KB, TR, WPE>), grid, block, lds, st, a, groups, kbuf);
+  hipLaunchKernelGGL((k_decode<DT, GT, RA, KB, TR, WPE, VP>), grid, block, lds, st, a, groups, kbuf);
   return hipGetLastError();
 }
 
-template <int DT, int GT, int KB, int TR, int WPE>
+template <int DT, int GT, int KB, int TR, int WPE, int VP>
 inline hipError_t decode_launch_ra(const DecodeArgs &a, int ra, int groups, hipStream_t st) {
-  if (ra == 16) return decode_launch_one<DT, GT, 16, KB, TR, WPE>(a, groups, st);
-  if (ra == 8) return decode_launch_one<DT, GT, 8, KB, TR, WPE>(a, groups, st);
-  if (ra == 4) return decode_launch_one<DT, GT, 4, KB, TR, WPE>(a, groups, st);
+  if (ra == 16) return decode_launch_one<DT, GT, 16, KB, TR, WPE, VP>(a, groups, st);
+  if (ra == 8) return decode_launch_one<DT, GT, 8, KB, TR, WPE, VP>(a, groups, st);
+  if (ra == 4) return decode_launch_one<DT, GT, 4, KB, TR, WPE, VP>(a, groups, st);
   if constexpr (DT == THK_BF16) {
-    if (ra == 2) return decode_launch_one<DT, GT, 2, KB, TR, WPE>(a, groups, st);
+    if (ra == 2) return decode_launch_one<DT, GT, 2, KB, TR, WPE, VP>(a, groups, st);
   }
   return hipErrorInvalidValue;
 }
 
 // Tiles of 32 rows: two lanes share a key row, waves stay light (4 per SIMD when
 // K staging is narrow and at most two query heads share the block, else 3).
-template <int DT, int GT>
+template <int DT, int GT, int VP = 0>
 hipError_t decode_launch_gt(const DecodeArgs &a, int groups, hipStream_t st) {
   constexpr int TR = 32;
-  const DecodeLaunch p = decode_launch_params<DT>(a, TR);
+  DecodeLaunch p = decode_launch_params<DT>(a, TR);
+  if constexpr (VP) {
+    // the value tile is staged with the same chunk count: size the class for the wider of the two
+    const int kbv = (int)((TR * (size_t)a.ld_v * Elem<DT>::EB + 15 + 15) / 16 + kWave - 1) / kWave;
+    if (kbv > p.kb) p.kb = kbv;
+  }
   constexpr int KBN = (DT == THK_BF16) ? 5 : 10;   // T <= 79
   constexpr int KBW = (DT == THK_BF16) ? 9 : 17;   // up to ld_keep = 128
-  if (p.kb <= KBN) return decode_launch_ra<DT, GT, KBN, TR, (GT <= 2 ? 4 : 3)>(a, p.ra, groups, st);
-  if (p.kb <= KBW) return decode_launch_ra<DT, GT, KBW, TR, 3>(a, p.ra, groups, st);
+  if (p.kb <= KBN) return decode_launch_ra<DT, GT, KBN, TR, (VP ? 3 : (GT <= 2 ? 4 : 3)), VP>(a, p.ra, groups, st);
+  if (p.kb <= KBW) return decode_launch_ra<DT, GT, KBW, TR, (VP ? 2 : 3), VP>(a, p.ra, groups, st);
   return hipErrorInvalidValue;
 }
 

@@ -1,0 +1,8 @@
+// Decode kernels over channel-pruned keys AND values, f32 inputs, 2 query head(s) per block.
+#include "thk_decode_impl.h"
+
+namespace thk {
+hipError_t decode_kv_launch_f32_g2(const DecodeArgs &a, int groups, hipStream_t st) {
+  return decode_launch_gt<THK_F32, 2, 1>(a, groups, st);
+}
+}  // namespace thk

@@ -24,9 +24,12 @@
 // invalidate a whole L2 per block.  Instead, everything one block hands to
 // another (partial sums, the index list, the counter and the flag) moves through
 // relaxed device-scope atomic loads and stores, which go to the coherence point
-// themselves; a producer only waits for its own stores to complete
-// (workgroup-scope release) before it bumps the counter or raises the flag, and
-// a consumer only reads after it has seen the counter or flag value.
+// themselves; a producer waits until its own stores have been acknowledged
+// (s_waitcnt vmcnt(0) in every wave, then the block barrier) before it bumps the
+// counter or raises the flag, and a consumer only reads after it has seen the
+// counter or flag value.  The wait is written out: a workgroup-scope release
+// fence compiles to nothing here (a block's waves share one L1), and without it
+// the flag can overtake the data on its way to memory.
 #include "thk_prune_device.h"
 
 namespace thk {
@@ -55,10 +58,10 @@ __device__ inline double pub_load_f64(const double *p) {
   return __longlong_as_double((long long)__hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED,
                                                            __HIP_MEMORY_SCOPE_AGENT));
 }
-// the block's own stores have completed (no cache maintenance): what a producer needs before
-// it signals through a device-scope atomic
+// Every store the block has issued so far has been acknowledged by the memory system (no cache
+// maintenance): what a producer needs before it signals through a device-scope atomic.
 __device__ inline void block_stores_done() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 }
 

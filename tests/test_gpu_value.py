@@ -151,3 +151,99 @@ def test_value_score_argument_errors():
     assert st(s, big, big, big, 0, big, A[:16]) == 5                   # workspace too small
     s2 = thk.make_shape(1, 1, 1, 1, D, 16, 32, 64, 0, thk.THK_BF16, 0)
     assert st(s2, big, big, big, 0, big, big) == 2                     # S_obs > S
+
+
+# ------------------------------------------------ decode over pruned K and V ----
+def _rand_idx(U, T, seed):
+    g = torch.Generator(device="cpu"); g.manual_seed(seed)
+    idx = torch.stack([torch.randperm(D, generator=g)[:T].sort().values for _ in range(U)])
+    return idx.to(torch.int16).cuda()
+
+
+DECODE_CASES = [
+    # dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split
+    ("bf16", 1, 1037, 76, 76, 76, 0, 0, 0),
+    ("bf16", 1, 1037, 76, 51, 52, 5, 16, 3),
+    ("bf16", 4, 2100, 64, 64, 64, 17, 32, 0),
+    ("bf16", 2, 600, 51, 89, 92, 0, 0, 1),      # wide value rows
+    ("bf16", 4, 333, 128, 128, 128, 3, 8, 2),   # nothing removed: the widest rows
+    ("bf16", 1, 45, 64, 1, 4, 2, 4, 1),         # a single kept value channel
+    ("bf16", 8, 777, 38, 102, 104, 1, 1, 0),
+    ("f32", 1, 1037, 64, 64, 64, 0, 0, 0),
+    ("f32", 4, 900, 76, 51, 52, 9, 16, 4),
+    ("f32", 2, 333, 51, 128, 128, 0, 0, 1),
+    ("f32", 1, 5, 3, 7, 8, 0, 0, 1),
+]
+
+
+@pytest.mark.parametrize("dtype,G,S,T,T_v,ld_v,s_tail,cap,n_split", DECODE_CASES)
+def test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split):
+    from helpers import ATTN_TOL, attn_rel_err
+    L, B, N_kv = 1, 2, 2
+    U = L * B * N_kv
+    seed = 50 + S + T_v
+    q = _randn((L * B * N_kv * G, D), dtype, seed, 0.5)
+    kp = _randn((U, S, T), dtype, seed + 1, 0.5)
+    vp = _randn((U, S, ld_v), dtype, seed + 2)
+    if ld_v > T_v:
+        vp[:, :, T_v:] = float("nan")          # the padding of a value row must never be used
+    idx, idx_v = _rand_idx(U, T, seed + 3), _rand_idx(U, T_v, seed + 4)
+    kt = _randn((U, max(cap, 1), D), dtype, seed + 5, 0.5)
+    vt = _randn((U, max(cap, 1), D), dtype, seed + 6)
+    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, 1, T, 0, DT[dtype], n_split)
+    out = torch.full((U * G, D), float("nan"), dtype=TDT[dtype], device="cuda")
+    ws = ws_tensor(thk.thk_workspace_bytes(shape, thk.THK_OP_DECODE))
+    print(f"decode kv {dtype} G={G} S={S} T={T} T_v={T_v} ld_v={ld_v} tail={s_tail} split={n_split}", flush=True)
+    thk.thk_decode_attn_kv(shape, q, kp, idx, vp, idx_v, T_v, ld_v, kt if s_tail else None,
+                           vt if s_tail else None, s_tail, cap, out, ws)
+    torch.cuda.synchronize()
+    vp_np = as_numpy(vp[:, :, :T_v].contiguous()).reshape(B, N_kv, S, T_v)
+    want = O.decode_attn_kv(as_numpy(q).reshape(B, N_kv * G, D), as_numpy(kp).reshape(B, N_kv, S, T),
+                            as_numpy(idx).reshape(B, N_kv, T), vp_np, as_numpy(idx_v).reshape(B, N_kv, T_v),
+                            dtype, as_numpy(kt).reshape(B, N_kv, -1, D) if s_tail else None,
+                            as_numpy(vt).reshape(B, N_kv, -1, D) if s_tail else None, s_tail)
+    err = attn_rel_err(out, want.reshape(-1, D))
+    print(f"   max rel err {err.max():.3e}", flush=True)
+    assert err.max() <= ATTN_TOL[dtype]
+    if s_tail == 0:   # removed channels are exactly zero
+        o = out.float().cpu().numpy().reshape(U, G, D)
+        keep = np.zeros((U, D), bool)
+        np.put_along_axis(keep, idx_v.cpu().numpy().astype(np.int64), True, axis=1)
+        assert np.all(o[~np.broadcast_to(keep[:, None, :], o.shape)] == 0.0)
+
+
+def test_decode_attn_kv_with_identity_value_index_equals_key_only_decode():
+    """T_v = D, idx_v = 0..D-1: the same arithmetic order is not promised, the same result to
+    the attention tolerance is."""
+    from helpers import ATTN_TOL, gpu_decode
+    L, B, N_kv, G, S, T = 1, 2, 2, 4, 1500, 64
+    U = L * B * N_kv
+    q = _randn((U * G, D), "bf16", 91, 0.5)
+    kp = _randn((U, S, T), "bf16", 92, 0.5)
+    v = _randn((U, S, D), "bf16", 93)
+    idx = _rand_idx(U, T, 94)
+    ident = torch.arange(D, dtype=torch.int16, device="cuda").repeat(U, 1).contiguous()
+    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, 1, T, 0, thk.THK_BF16, 0)
+    ref = gpu_decode(shape, q, kp, idx, v).float()
+    out = torch.empty_like(q)
+    ws = ws_tensor(thk.thk_workspace_bytes(shape, thk.THK_OP_DECODE))
+    thk.thk_decode_attn_kv(shape, q, kp, idx, v, ident, D, D, None, None, 0, 0, out, ws)
+    torch.cuda.synchronize()
+    rel = (out.float() - ref).abs().amax(1) / ref.abs().amax(1)
+    assert rel.max().item() <= ATTN_TOL["bf16"]
+
+
+def test_decode_attn_kv_argument_errors():
+    big = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    s = thk.make_shape(1, 1, 1, 1, D, 64, 1, 64, 0, thk.THK_BF16, 1)
+    def st(*a):
+        try:
+            thk.thk_decode_attn_kv(*a)
+        except thk.ThkError as e:
+            return e.status
+        return 0
+    assert st(s, big, big, big, big, big, 0, 0, None, None, 0, 0, big, big) == 2      # T_v < 1
+    assert st(s, big, big, big, big, big, 65, 64, None, None, 0, 0, big, big) == 2    # ld_v < T_v
+    assert st(s, big, big, big, big, big, 63, 63, None, None, 0, 0, big, big) == 3    # ld_v % 4 != 0
+    assert st(s, big, big, big, big, None, 64, 64, None, None, 0, 0, big, big) == 1   # idx_v missing
+    assert st(s, big, big, big, big, big, 64, 64, big, None, 2, 4, big, big) == 1     # tail without v_tail
