@@ -53,7 +53,8 @@ typedef enum {
   THK_OP_SCORE = 0,  /* thk_score                       */
   THK_OP_DECODE = 1, /* thk_decode_attn                 */
   THK_OP_PRUNE = 2,  /* thk_prune                       */
-  THK_OP_SCORE_VALUE = 3 /* thk_score_value             */
+  THK_OP_SCORE_VALUE = 3, /* thk_score_value            */
+  THK_OP_PRUNE_VALUE = 4  /* thk_prune_value            */
 } thk_op;
 
 /* Problem statement in the paper's B x S x L x N x D terms (Sec. 1). */
@@ -80,6 +81,12 @@ int32_t thk_version(void);
 
 /* Static string for a status code. */
 const char *thk_status_string(thk_status st);
+
+/* The HIP runtime's message for the launch error behind the calling thread's most recent
+ * THK_ERR_HIP ("no error" if there was none).  An entry point that launches first consumes
+ * any error the thread's earlier HIP calls left pending, so THK_ERR_HIP is about its own
+ * launches only. */
+const char *thk_last_hip_error(void);
 
 /*
  * T = floor((1 - lambda) * D): the number of channels kept at pruning ratio
@@ -145,6 +152,19 @@ thk_status thk_score_magnitude(const thk_shape *shape, const void *k, int32_t p,
 thk_status thk_score_value(const thk_shape *shape, const void *q_obs, const void *k,
                            const void *v, int32_t causal, float *score_v, void *ws,
                            size_t ws_bytes, void *stream);
+
+/*
+ * End-of-prefill prune of the VALUE cache (Appendix "Value Cache Pruning"):
+ * thk_score_value + thk_select_topk + thk_compact_keys applied to V in one call.
+ * The shape's T, ld_keep, S_recent and S_cap describe the pruned VALUE cache here
+ * (T = channels kept, the paper's T for I_i = Top_T(Score_v, T)).  `score_v` may
+ * be NULL (then it lives in ws).
+ *   in : q_obs, k, v (device)   out: score_v (float), idx_v (int16), v_pruned
+ *   ws : THK_OP_PRUNE_VALUE bytes.
+ */
+thk_status thk_prune_value(const thk_shape *shape, const void *q_obs, const void *k,
+                           const void *v, int32_t causal, float *score_v, int16_t *idx_v,
+                           void *v_pruned, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Top_T selection (Sec. 3.1 I = Top_T(M, T); Sec. 3.2 I_i): per unit the T

@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libthk.so")
 
 THK_F32, THK_BF16 = 0, 1
-THK_OP_SCORE, THK_OP_DECODE, THK_OP_PRUNE, THK_OP_SCORE_VALUE = 0, 1, 2, 3
+THK_OP_SCORE, THK_OP_DECODE, THK_OP_PRUNE, THK_OP_SCORE_VALUE, THK_OP_PRUNE_VALUE = 0, 1, 2, 3, 4
 
 
 class ThkError(RuntimeError):
@@ -42,12 +42,18 @@ def load():
         return _lib
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: build it with __graft_entry__.build()")
+    # PyTorch's wheel carries its own copy of the HIP runtime.  Loading torch first makes libthk
+    # bind to that same copy; loaded the other way round the process ends up with two runtimes
+    # and the second one finds no device.
+    import torch  # noqa: F401
     L = ctypes.CDLL(_LIB_PATH)
     sp, vp, i32 = ctypes.POINTER(thk_shape), ctypes.c_void_p, ctypes.c_int32
     L.thk_version.restype = i32
     L.thk_version.argtypes = []
     L.thk_status_string.restype = ctypes.c_char_p
     L.thk_status_string.argtypes = [ctypes.c_int]
+    L.thk_last_hip_error.restype = ctypes.c_char_p
+    L.thk_last_hip_error.argtypes = []
     L.thk_keep_count.restype = i32
     L.thk_keep_count.argtypes = [i32, ctypes.c_double]
     L.thk_workspace_bytes.restype = ctypes.c_size_t
@@ -60,6 +66,8 @@ def load():
     L.thk_score.argtypes = [sp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.thk_score_value.restype = ctypes.c_int
     L.thk_score_value.argtypes = [sp, vp, vp, vp, i32, vp, vp, ctypes.c_size_t, vp]
+    L.thk_prune_value.restype = ctypes.c_int
+    L.thk_prune_value.argtypes = [sp, vp, vp, vp, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.thk_score_magnitude.restype = ctypes.c_int
     L.thk_score_magnitude.argtypes = [sp, vp, i32, vp, vp, ctypes.c_size_t, vp]
     L.thk_select_topk.restype = ctypes.c_int
@@ -145,7 +153,13 @@ def _cache_rows(s, used):
     return s.S_cap or used
 
 
+def thk_last_hip_error():
+    return load().thk_last_hip_error().decode()
+
+
 def _check(st, where):
+    if st == 6:
+        raise ThkError(st, f"{where} [{thk_last_hip_error()}]")
     if st != 0:
         raise ThkError(st, where)
 
@@ -192,6 +206,20 @@ def thk_score_value(shape, q_obs, k, v, causal, score_v, ws, stream=None):
     _check(load().thk_score_value(ctypes.byref(shape), _ptr(q_obs), _ptr(k), _ptr(v), int(causal),
                                   _ptr(score_v), _ws(ws), _nbytes(ws), _stream(stream)),
            "thk_score_value")
+
+
+def thk_prune_value(shape, q_obs, k, v, causal, score_v, idx_v, v_pruned, ws, stream=None):
+    U, H, ld = _dims(shape)
+    w = "thk_prune_value"
+    _need(q_obs, H * shape.S_obs * shape.D, "q_obs", w)
+    _need(k, U * shape.S * shape.D, "k", w)
+    _need(v, U * shape.S * shape.D, "v", w)
+    _need(score_v, U * shape.D, "score_v", w)
+    _need(idx_v, U * shape.T, "idx_v", w)
+    _need(v_pruned, U * _cache_rows(shape, shape.S - shape.S_recent) * ld, "v_pruned", w)
+    _check(load().thk_prune_value(ctypes.byref(shape), _ptr(q_obs), _ptr(k), _ptr(v), int(causal),
+                                  _ptr(score_v), _ptr(idx_v), _ptr(v_pruned), _ws(ws), _nbytes(ws),
+                                  _stream(stream)), w)
 
 
 def thk_score_magnitude(shape, k, p, score, ws, stream=None):

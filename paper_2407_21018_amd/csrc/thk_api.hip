@@ -24,6 +24,12 @@ void profile_mark(bool start, hipStream_t st) {
 
 namespace {
 
+thread_local hipError_t g_last_hip = hipSuccess;   // the launch error behind the last THK_ERR_HIP
+inline bool failed(hipError_t e) {
+  if (e != hipSuccess) g_last_hip = e;
+  return e != hipSuccess;
+}
+
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 inline int elem_bytes(int dtype) { return dtype == THK_BF16 ? 2 : 4; }
 inline int64_t units_of(const thk_shape *s) { return (int64_t)s->L * s->B * s->N_kv; }
@@ -186,6 +192,8 @@ void thk_profile_next(void *ev_start, void *ev_stop) {
   g_prof_stop = (ev_start != nullptr && ev_stop != nullptr) ? (hipEvent_t)ev_stop : nullptr;
 }
 
+const char *thk_last_hip_error(void) { return hipGetErrorString(g_last_hip); }
+
 const char *thk_status_string(thk_status st) {
   switch (st) {
     case THK_OK: return "ok";
@@ -211,7 +219,7 @@ int32_t thk_default_split(const thk_shape *s, int32_t op) {
   if (op == THK_OP_DECODE) return decode_split(&t).n;
   if (op == THK_OP_SCORE) return score_split(&t, units_of(&t)).n;
   if (op == THK_OP_PRUNE) return score_split(&t, prune_group_units(&t)).n;
-  if (op == THK_OP_SCORE_VALUE) return (t.S_obs >= 1 && t.S_obs <= t.S) ? value_split(&t).n : 0;
+  if (op == THK_OP_SCORE_VALUE || op == THK_OP_PRUNE_VALUE) return (t.S_obs >= 1 && t.S_obs <= t.S) ? value_split(&t).n : 0;
   return 0;
 }
 
@@ -233,6 +241,11 @@ size_t thk_workspace_bytes(const thk_shape *s, int32_t op) {
     case THK_OP_SCORE_VALUE:
       if (s->S_obs < 1 || (int64_t)s->S_obs > s->S) return 0;
       return value_part_bytes(units_of(s), s->N_q / s->N_kv, s->S_obs, value_split(s).n);
+    case THK_OP_PRUNE_VALUE: {
+      if (s->S_obs < 1 || (int64_t)s->S_obs > s->S) return 0;
+      const size_t a = value_part_bytes(units_of(s), s->N_q / s->N_kv, s->S_obs, value_split(s).n);
+      return ((a + 15) & ~(size_t)15) + (size_t)units_of(s) * kD * sizeof(float);
+    }
     case THK_OP_PRUNE: {
       // a score array for the whole call + the larger of the two paths' scratch
       const FusedPlan fp = fused_plan(s);
@@ -258,10 +271,10 @@ static thk_status score_common(const thk_shape *s, int mode, const void *q_obs, 
   if (U * sp.n > kMaxGrid) return THK_ERR_SHAPE;
   if (ws == nullptr || !aligned16(ws) || ws_bytes < score_ws_bytes(s, U)) return THK_ERR_WORKSPACE;
   hipStream_t hs = (hipStream_t)stream;
-  if (launch_colsum(s->dtype, k, (double *)ws, U, s->S, sp.n, sp.rows, mode == 1 ? 1 : 2, hs) != hipSuccess)
+  if (failed(launch_colsum(s->dtype, k, (double *)ws, U, s->S, sp.n, sp.rows, mode == 1 ? 1 : 2, hs)))
     return THK_ERR_HIP;
-  if (launch_finalize(s->dtype, mode, (const double *)ws, q_obs, score, nullptr, U, s->N_q / s->N_kv,
-                      s->S_obs, sp.n, s->T, hs) != hipSuccess)
+  if (failed(launch_finalize(s->dtype, mode, (const double *)ws, q_obs, score, nullptr, U, s->N_q / s->N_kv,
+                      s->S_obs, sp.n, s->T, hs)))
     return THK_ERR_HIP;
   return THK_OK;
 }
@@ -282,7 +295,7 @@ thk_status thk_select_topk(const thk_shape *s, const float *score, int16_t *idx,
   if (st != THK_OK) return st;
   if (score == nullptr || idx == nullptr) return THK_ERR_NULL;
   if (!aligned16(score) || !aligned16(idx)) return THK_ERR_ALIGN;
-  if (launch_select(score, idx, units_of(s), s->T, (hipStream_t)stream) != hipSuccess) return THK_ERR_HIP;
+  if (failed(launch_select(score, idx, units_of(s), s->T, (hipStream_t)stream))) return THK_ERR_HIP;
   return THK_OK;
 }
 
@@ -294,8 +307,8 @@ thk_status thk_compact_keys(const thk_shape *s, const void *k, const int16_t *id
   if (!aligned16(k) || !aligned16(idx) || !aligned16(k_pruned)) return THK_ERR_ALIGN;
   if (units_of(s) * ceil_div(s->S, 512) > kMaxGrid) return THK_ERR_SHAPE;
   if (s->S_cap != 0 && s->S_cap < keep_rows(s)) return THK_ERR_SHAPE;
-  if (launch_compact(s->dtype, k, s->S, 0, idx, k_pruned, cache_rows(s, keep_rows(s)), 0, units_of(s),
-                     keep_rows(s), s->T, ld_of(s), (hipStream_t)stream) != hipSuccess)
+  if (failed(launch_compact(s->dtype, k, s->S, 0, idx, k_pruned, cache_rows(s, keep_rows(s)), 0, units_of(s),
+                            keep_rows(s), s->T, ld_of(s), (hipStream_t)stream)))
     return THK_ERR_HIP;
   return THK_OK;
 }
@@ -312,8 +325,8 @@ thk_status thk_compact_rows(const thk_shape *s, const void *src, int64_t src_uni
     return THK_ERR_SHAPE;
   if (!aligned16(src) || !aligned16(idx) || !aligned16(k_pruned)) return THK_ERR_ALIGN;
   if (units_of(s) * ceil_div(n_rows > 0 ? n_rows : 1, 512) > kMaxGrid) return THK_ERR_SHAPE;
-  if (launch_compact(s->dtype, src, src_unit_rows, src_row0, idx, k_pruned, dst_unit_rows, dst_row0,
-                     units_of(s), n_rows, s->T, ld_of(s), (hipStream_t)stream) != hipSuccess)
+  if (failed(launch_compact(s->dtype, src, src_unit_rows, src_row0, idx, k_pruned, dst_unit_rows, dst_row0,
+                     units_of(s), n_rows, s->T, ld_of(s), (hipStream_t)stream)))
     return THK_ERR_HIP;
   return THK_OK;
 }
@@ -329,8 +342,8 @@ thk_status thk_copy_rows(const thk_shape *s, const void *src, int64_t src_unit_r
     return THK_ERR_SHAPE;
   if (src == dst && (dst_unit_rows != src_unit_rows || dst_row0 > src_row0)) return THK_ERR_SHAPE;
   if (!aligned16(src) || !aligned16(dst)) return THK_ERR_ALIGN;
-  if (launch_copy_rows(s->dtype, src, src_unit_rows, src_row0, dst, dst_unit_rows, dst_row0, units_of(s),
-                       n_rows, (hipStream_t)stream) != hipSuccess)
+  if (failed(launch_copy_rows(s->dtype, src, src_unit_rows, src_row0, dst, dst_unit_rows, dst_row0, units_of(s),
+                       n_rows, (hipStream_t)stream)))
     return THK_ERR_HIP;
   return THK_OK;
 }
@@ -343,8 +356,8 @@ thk_status thk_cache_append(const thk_shape *s, const void *k_new, const void *v
   if (s_tail < 0 || s_tail >= s_tail_cap) return THK_ERR_SHAPE;
   if (s->S + s_tail >= cache_rows(s, s->S)) return THK_ERR_SHAPE;   // the value cache is full
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_tail) || !aligned16(v)) return THK_ERR_ALIGN;
-  if (launch_tail_append(s->dtype, k_new, v_new, k_tail, v, units_of(s), s_tail_cap, s_tail,
-                         cache_rows(s, s->S), s->S + s_tail, (hipStream_t)stream) != hipSuccess)
+  if (failed(launch_tail_append(s->dtype, k_new, v_new, k_tail, v, units_of(s), s_tail_cap, s_tail,
+                         cache_rows(s, s->S), s->S + s_tail, (hipStream_t)stream)))
     return THK_ERR_HIP;
   return THK_OK;
 }
@@ -364,17 +377,17 @@ thk_status thk_tail_flush(const thk_shape *s, const int16_t *idx, void *k_pruned
     return THK_ERR_ALIGN;
   hipStream_t hs = (hipStream_t)stream;
   const int64_t U = units_of(s);
-  if (launch_compact(s->dtype, k_tail, s_tail_cap, 0, idx, k_pruned, unit_rows, s->S, U, n_flush, s->T,
-                     ld_of(s), hs) != hipSuccess)
+  if (failed(launch_compact(s->dtype, k_tail, s_tail_cap, 0, idx, k_pruned, unit_rows, s->S, U, n_flush, s->T,
+                     ld_of(s), hs)))
     return THK_ERR_HIP;
-  if (launch_copy_rows(s->dtype, k_tail, s_tail_cap, n_flush, k_tail, s_tail_cap, 0, U, s_tail - n_flush,
-                       hs) != hipSuccess)
+  if (failed(launch_copy_rows(s->dtype, k_tail, s_tail_cap, n_flush, k_tail, s_tail_cap, 0, U, s_tail - n_flush,
+                       hs)))
     return THK_ERR_HIP;
   if (v != nullptr) {
-    if (launch_copy_rows(s->dtype, v_tail, s_tail_cap, 0, v, unit_rows, s->S, U, n_flush, hs) != hipSuccess)
+    if (failed(launch_copy_rows(s->dtype, v_tail, s_tail_cap, 0, v, unit_rows, s->S, U, n_flush, hs)))
       return THK_ERR_HIP;
-    if (launch_copy_rows(s->dtype, v_tail, s_tail_cap, n_flush, v_tail, s_tail_cap, 0, U, s_tail - n_flush,
-                         hs) != hipSuccess)
+    if (failed(launch_copy_rows(s->dtype, v_tail, s_tail_cap, n_flush, v_tail, s_tail_cap, 0, U, s_tail - n_flush,
+                         hs)))
       return THK_ERR_HIP;
   }
   return THK_OK;
@@ -397,9 +410,9 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
   const FusedPlan fp = fused_plan(s);
   if (fp.ok) {
     const int spin = (int)env_long("THK_PRUNE_SPIN_LIMIT", 4096);
-    if (launch_prune_fused(s->dtype, q_obs, k, sc, idx, k_pruned, ws, U, s->S, keep_rows(s),
-                           cache_rows(s, keep_rows(s)), G, s->S_obs, s->T, fp.NB, fp.RB, spin < 0 ? 0 : spin,
-                           hs) != hipSuccess)
+    if (failed(launch_prune_fused(s->dtype, q_obs, k, sc, idx, k_pruned, ws, U, s->S, keep_rows(s),
+                                  cache_rows(s, keep_rows(s)), G, s->S_obs, s->T, fp.NB, fp.RB,
+                                  spin < 0 ? 0 : spin, hs)))
       return THK_ERR_HIP;
     return THK_OK;
   }
@@ -415,18 +428,18 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
   for (int64_t u0 = 0; u0 < U; u0 += gu) {
     const int64_t nu = (U - u0 < gu) ? U - u0 : gu;
     const char *kg = (const char *)k + (size_t)u0 * s->S * kD * eb;
-    if (launch_colsum(s->dtype, kg, partial, nu, s->S, sp.n, sp.rows, 2, hs) != hipSuccess) return THK_ERR_HIP;
+    if (failed(launch_colsum(s->dtype, kg, partial, nu, s->S, sp.n, sp.rows, 2, hs))) return THK_ERR_HIP;
     // unit u reads query heads u * G .. u * G + G - 1, so a group starting at u0 starts u0 * G heads in
     const char *qg = (const char *)q_obs + (size_t)u0 * G * s->S_obs * kD * eb;
-    if (launch_finalize(s->dtype, 0, partial, qg, sc + (size_t)u0 * kD, idx + (size_t)u0 * s->T, nu, G,
-                        s->S_obs, sp.n, s->T, hs) != hipSuccess)
+    if (failed(launch_finalize(s->dtype, 0, partial, qg, sc + (size_t)u0 * kD, idx + (size_t)u0 * s->T, nu, G,
+                        s->S_obs, sp.n, s->T, hs)))
       return THK_ERR_HIP;
     profile_mark(true, hs);
     const hipError_t ce = launch_compact(s->dtype, kg, s->S, 0, idx + (size_t)u0 * s->T,
                                          (char *)k_pruned + (size_t)u0 * kp_rows * ld * eb, kp_rows, 0, nu,
                                          keep_rows(s), s->T, ld, hs);
     profile_mark(false, hs);
-    if (ce != hipSuccess) return THK_ERR_HIP;
+    if (failed(ce)) return THK_ERR_HIP;
   }
   return THK_OK;
 }
@@ -446,10 +459,29 @@ thk_status thk_score_value(const thk_shape *s, const void *q_obs, const void *k,
   if (grid > kMaxGrid) return THK_ERR_SHAPE;
   if (ws == nullptr || !aligned16(ws) || ws_bytes < thk_workspace_bytes(s, THK_OP_SCORE_VALUE))
     return THK_ERR_WORKSPACE;
-  if (launch_value_score(s->dtype, q_obs, k, v, (float *)ws, score_v, units_of(s), s->S, G, s->S_obs, causal,
-                         sp.n, sp.rows, (hipStream_t)stream) != hipSuccess)
+  if (failed(launch_value_score(s->dtype, q_obs, k, v, (float *)ws, score_v, units_of(s), s->S, G, s->S_obs, causal,
+                         sp.n, sp.rows, (hipStream_t)stream)))
     return THK_ERR_HIP;
   return THK_OK;
+}
+
+thk_status thk_prune_value(const thk_shape *s, const void *q_obs, const void *k, const void *v,
+                           int32_t causal, float *score_v, int16_t *idx_v, void *v_pruned, void *ws,
+                           size_t ws_bytes, void *stream) {
+  thk_status st = check_shape(s, true);
+  if (st != THK_OK) return st;
+  if (idx_v == nullptr || v_pruned == nullptr) return THK_ERR_NULL;
+  if (!aligned16(idx_v) || !aligned16(v_pruned) || (score_v != nullptr && !aligned16(score_v)))
+    return THK_ERR_ALIGN;
+  const size_t need = thk_workspace_bytes(s, THK_OP_PRUNE_VALUE);
+  if (ws == nullptr || !aligned16(ws) || ws_bytes < need) return THK_ERR_WORKSPACE;
+  // the score array sits behind the value score's own scratch unless the caller wants it
+  float *sc = score_v != nullptr ? score_v : (float *)((char *)ws + need - (size_t)units_of(s) * kD * sizeof(float));
+  st = thk_score_value(s, q_obs, k, v, causal, sc, ws, thk_workspace_bytes(s, THK_OP_SCORE_VALUE), stream);
+  if (st != THK_OK) return st;
+  st = thk_select_topk(s, sc, idx_v, stream);
+  if (st != THK_OK) return st;
+  return thk_compact_keys(s, v, idx_v, v_pruned, stream);
 }
 
 static thk_status decode_common(const thk_shape *s, const void *q, const void *k_pruned,
@@ -490,7 +522,7 @@ static thk_status decode_common(const thk_shape *s, const void *q, const void *k
   a.unified_v = unified_v ? 1 : 0;
   a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)s->D));
   a.idx_v = idx_v; a.T_v = pruned_v ? T_v : 0; a.ld_v = pruned_v ? ld_v : 0;
-  if (launch_decode(a, (hipStream_t)stream) != hipSuccess) return THK_ERR_HIP;
+  if (failed(launch_decode(a, (hipStream_t)stream))) return THK_ERR_HIP;
   return THK_OK;
 }
 
@@ -519,8 +551,8 @@ thk_status thk_tail_append(const thk_shape *s, const void *k_new, const void *v_
   if (k_new == nullptr || v_new == nullptr || k_tail == nullptr || v_tail == nullptr) return THK_ERR_NULL;
   if (s_tail < 0 || s_tail >= s_tail_cap) return THK_ERR_SHAPE;
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_tail) || !aligned16(v_tail)) return THK_ERR_ALIGN;
-  if (launch_tail_append(s->dtype, k_new, v_new, k_tail, v_tail, units_of(s), s_tail_cap, s_tail, s_tail_cap,
-                         s_tail, (hipStream_t)stream) != hipSuccess)
+  if (failed(launch_tail_append(s->dtype, k_new, v_new, k_tail, v_tail, units_of(s), s_tail_cap, s_tail, s_tail_cap,
+                         s_tail, (hipStream_t)stream)))
     return THK_ERR_HIP;
   return THK_OK;
 }

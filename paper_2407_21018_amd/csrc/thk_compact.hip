@@ -104,6 +104,7 @@ bool compact_is_flat(int dtype, int T, int ld_keep, int64_t dst_unit_rows, int64
 hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0,
                           const int16_t *idx, void *dst, int64_t dst_unit_rows, int64_t dst_row0,
                           int64_t U, int64_t n_rows, int T, int ld_keep, hipStream_t st) {
+  clear_stale_hip_error();
   if (n_rows <= 0) return hipSuccess;
   const int eb = dtype == THK_BF16 ? 2 : 4;
   CompactArgs a;
@@ -128,6 +129,7 @@ hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int
 hipError_t launch_copy_rows(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0, void *dst,
                             int64_t dst_unit_rows, int64_t dst_row0, int64_t U, int64_t n_rows,
                             hipStream_t st) {
+  clear_stale_hip_error();
   if (n_rows <= 0) return hipSuccess;
   const dim3 grid((unsigned)U), block(256);
   if (dtype == THK_BF16)
@@ -140,6 +142,7 @@ hipError_t launch_copy_rows(int dtype, const void *src, int64_t src_unit_rows, i
 hipError_t launch_tail_append(int dtype, const void *k_new, const void *v_new, void *k_dst, void *v_dst,
                               int64_t U, int64_t k_unit_rows, int64_t k_row, int64_t v_unit_rows,
                               int64_t v_row, hipStream_t st) {
+  clear_stale_hip_error();
   const int cpr = dtype == THK_BF16 ? 16 : 32;
   const dim3 grid((unsigned)((U * cpr + 255) / 256)), block(256);
   if (dtype == THK_BF16)

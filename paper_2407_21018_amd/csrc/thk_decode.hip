@@ -70,6 +70,7 @@ __global__ __launch_bounds__(128) void k_decode_merge(const float *__restrict__ 
 }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t st) {
+  clear_stale_hip_error();
   const int G = a.N_q / a.N_kv;
   const int gt = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
   const int groups = G / gt;

@@ -316,27 +316,35 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
     // ---- accp += p . V_pruned: value bytes to LDS, then 4 kept channels per lane ----------
     k_commit<KBV>(*vrp, vp->vbuf, lane);
     wave_sync_lds();
-    const char *vrow = vp->vbuf + vp->shift + ((size_t)vp->rsub * vp->ld + vp->col * 4) * EB;
-    const size_t step = (size_t)vp->rpw * vp->ld * EB;
-    for (int r0 = 0; r0 < nrows; r0 += vp->rpw, vrow += step) {
-      const int row = r0 + vp->rsub;
-      if (vp->active && row < nrows) {
-        float f[4];
+    // Rows r0 + rsub, r0 = 0, rpw, 2 rpw, ...; four steps are read before they are used.  A row
+    // past the tile's end is read as the tile's last row with weight 0, so nothing branches.
+    const char *vbase = vp->vbuf + vp->shift + (size_t)vp->col * 4 * EB;
+    const int rowb = vp->ld * EB;
+    for (int r0 = 0; r0 < nrows; r0 += 4 * vp->rpw) {
+      float f[4][4], pg[4][GT];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = r0 + i * vp->rpw + vp->rsub;
+        const bool live = row < nrows;
+        const int rr = live ? row : nrows - 1;
+        const char *vrow = vbase + rr * rowb;
         if constexpr (DT == THK_BF16) {
           const uint2 w = *(const uint2 *)vrow;
-          f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xffff0000u);
-          f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xffff0000u);
+          f[i][0] = __uint_as_float(w.x << 16); f[i][1] = __uint_as_float(w.x & 0xffff0000u);
+          f[i][2] = __uint_as_float(w.y << 16); f[i][3] = __uint_as_float(w.y & 0xffff0000u);
         } else {
           const float4 w = *(const float4 *)vrow;
-          f[0] = w.x; f[1] = w.y; f[2] = w.z; f[3] = w.w;
+          f[i][0] = w.x; f[i][1] = w.y; f[i][2] = w.z; f[i][3] = w.w;
         }
 #pragma unroll
-        for (int g = 0; g < GT; ++g) {
-          const float pg = ps[row * GT + g];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) st.accp[g][e] = fmaf(pg, f[e], st.accp[g][e]);
-        }
+        for (int g = 0; g < GT; ++g) pg[i][g] = live ? ps[rr * GT + g] : 0.f;
       }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int g = 0; g < GT; ++g)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) st.accp[g][e] = fmaf(pg[i][g], f[i][e], st.accp[g][e]);
     }
   } else {
   wave_sync_lds();

@@ -50,6 +50,11 @@ template <> struct Elem<THK_BF16> {
 // ---- one-shot timing hook (thk_profile_next): record around a call's main kernel ----
 void profile_mark(bool start, hipStream_t st);   // no-op unless a pair is pending; stop consumes it
 
+// hipGetLastError() reports the calling thread's most recent unconsumed error, whoever caused
+// it; a launcher consumes whatever is pending first so that what it returns is about its own
+// launches only.
+inline void clear_stale_hip_error() { (void)hipGetLastError(); }
+
 // ---- launchers (one per kernel family; each returns hipGetLastError()) ----
 // Column sums of squares (p == 2) or of absolute values (p == 1) of K per
 // unit, cut into n_split pieces of rows_per_split rows: partial[U][n_split][D].

@@ -206,6 +206,7 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
                               void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
                               int64_t kp_unit_rows, int G, int S_obs, int T, int NB, int64_t RB,
                               int spin_limit, hipStream_t st) {
+  clear_stale_hip_error();
   PruneFusedArgs a;
   a.k = k; a.q_obs = q_obs; a.kp = kp; a.score = score; a.idx = idx;
   char *w = (char *)ws;

@@ -96,6 +96,7 @@ __global__ __launch_bounds__(kFinThreads) void k_finalize(int mode, const double
 // ---------------------------------------------------------------------------
 hipError_t launch_colsum(int dtype, const void *k, double *partial, int64_t U, int64_t S,
                          int n_split, int64_t rows_per_split, int p, hipStream_t st) {
+  clear_stale_hip_error();
   const dim3 grid((unsigned)(U * n_split)), block(256);
   if (dtype == THK_BF16) {
     if (p == 2) hipLaunchKernelGGL((k_colsum<THK_BF16, 2>), grid, block, 0, st, k, partial, S, n_split, rows_per_split);
@@ -110,6 +111,7 @@ hipError_t launch_colsum(int dtype, const void *k, double *partial, int64_t U, i
 hipError_t launch_finalize(int dtype, int mode, const double *partial, const void *q_obs,
                            float *score, int16_t *idx, int64_t U, int G, int S_obs,
                            int n_split, int T, hipStream_t st) {
+  clear_stale_hip_error();
   const dim3 grid((unsigned)U), block(kFinThreads);
   if (dtype == THK_BF16)
     hipLaunchKernelGGL((k_finalize<THK_BF16>), grid, block, 0, st, mode, partial, q_obs, score, idx, G, S_obs, n_split, T);
@@ -119,6 +121,7 @@ hipError_t launch_finalize(int dtype, int mode, const double *partial, const voi
 }
 
 hipError_t launch_select(const float *score, int16_t *idx, int64_t U, int T, hipStream_t st) {
+  clear_stale_hip_error();
   const dim3 grid((unsigned)((U + 3) / 4)), block(256);
   hipLaunchKernelGGL(k_select, grid, block, 0, st, score, idx, U, T);
   return hipGetLastError();

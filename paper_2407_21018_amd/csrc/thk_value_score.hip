@@ -453,6 +453,7 @@ size_t value_part_bytes(int64_t U, int G, int S_obs, int n_split) {
 hipError_t launch_value_score(int dtype, const void *q_obs, const void *k, const void *v, float *part,
                               float *score, int64_t U, int64_t S, int G, int S_obs, int causal,
                               int n_split, int64_t rows_per_split, hipStream_t st) {
+  clear_stale_hip_error();
   const int QT = value_attn_qt(G, S_obs);
   const int nqt_real = (G * S_obs + 31) / 32;
   ValueAttnArgs a;

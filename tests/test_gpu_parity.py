@@ -164,6 +164,42 @@ PRUNE_CASES = [("bf16", 1, 2048, 76, 1.5), ("bf16", 4, 4096 + 64, 64, 1.0), ("f3
                ("bf16", 1, 1024, 51, 2.0), ("f32", 2, 2048, 64, 1.0), ("bf16", 1, 40, 64, 1.0)]
 
 
+def test_prune_fused_repeated_calls_on_one_workspace(monkeypatch):
+    """The one-launch form hands the index list from the block that selects to the blocks
+    that wait through the workspace.  Calls that alternate between two inputs on the SAME
+    workspace leave the other input's list behind each time: a block that picked up a stale
+    list (or a list that had not fully arrived) would compact the wrong channels.  Checked
+    on the GPU against a plain gather with the index list the call returned, and against the
+    oracle's list for the first call of each input."""
+    monkeypatch.setenv("THK_PRUNE_PATH", "fused")
+    L, B, N, S, S_obs, T = 4, 4, 16, 4096, 32, 76
+    U = L * B * N
+    shape = thk.make_shape(L, B, N, N, D, S, S_obs, T, 0, thk.THK_BF16, 0)
+    assert thk.thk_prune_is_fused(shape) == 1
+    inputs = [(_randn((L, B, N, S_obs, D), "bf16", 71 + i, 1.0), _randn((L, B, N, S, D), "bf16", 81 + i, 1.0))
+              for i in range(2)]
+    ws = ws_tensor(thk.thk_workspace_bytes(shape, thk.THK_OP_PRUNE))
+    ws.fill_(0xA5)
+    score = torch.empty(U, D, dtype=torch.float32, device="cuda")
+    idx = torch.empty(U, T, dtype=torch.int16, device="cuda")
+    kp = torch.empty(U, S, T, dtype=torch.bfloat16, device="cuda")
+    first_idx = {}
+    for rep in range(8):
+        q_obs, k = inputs[rep % 2]
+        kp.fill_(-7.0)
+        thk.thk_prune(shape, q_obs, k, score, idx, kp, ws)
+        torch.cuda.synchronize()
+        want = torch.gather(k.reshape(U, S, D), 2, idx.to(torch.int64)[:, None, :].expand(U, S, T))
+        assert torch.equal(kp.view(torch.int16), want.view(torch.int16)), f"call {rep}"
+        if rep < 2:
+            first_idx[rep] = idx.clone()
+            o_sc = O.score(as_numpy(q_obs), as_numpy(k), "bf16").reshape(U, D)
+            check_idx_with_tie_rule(idx.cpu().numpy(), O.select_topk(o_sc, T), o_sc, T)
+        else:
+            assert torch.equal(idx, first_idx[rep % 2]), f"call {rep}"
+    assert not torch.equal(first_idx[0], first_idx[1])
+
+
 @pytest.mark.parametrize("path", ["fused", "fused-small-blocks", "fused-no-wait", "staged", "staged-groups"])
 @pytest.mark.parametrize("dtype,G,S,T,sigma", PRUNE_CASES)
 def test_prune_pipeline_matches_oracle(dtype, G, S, T, sigma, path, monkeypatch):

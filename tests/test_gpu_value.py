@@ -247,3 +247,56 @@ def test_decode_attn_kv_argument_errors():
     assert st(s, big, big, big, big, big, 63, 63, None, None, 0, 0, big, big) == 3    # ld_v % 4 != 0
     assert st(s, big, big, big, big, None, 64, 64, None, None, 0, 0, big, big) == 1   # idx_v missing
     assert st(s, big, big, big, big, big, 64, 64, big, None, 2, 4, big, big) == 1     # tail without v_tail
+
+
+# -------------------------------------------- the whole path: prune K, prune V, decode ----
+@pytest.mark.parametrize("dtype,G,S,lam_k,lam_v,causal", [("bf16", 1, 1500, 0.4, 0.4, 1), ("bf16", 4, 2300, 0.5, 0.3, 1),
+                                                         ("f32", 2, 700, 0.5, 0.5, 0)])
+def test_prune_keys_and_values_then_decode(dtype, G, S, lam_k, lam_v, causal):
+    """End of prefill: thk_prune for the keys, thk_prune_value for the values; then one decode
+    step over both pruned caches with a short un-pruned tail.  Every stage is checked against the
+    oracle fed with the GPU's own upstream results (so one tie-swap cannot cascade)."""
+    from helpers import ATTN_TOL, attn_rel_err, gpu_prune
+    L, B, N_kv, S_obs, cap, s_tail = 1, 2, 2, 32, 8, 3
+    U = L * B * N_kv
+    T, T_v = thk.thk_keep_count(D, lam_k), thk.thk_keep_count(D, lam_v)
+    ld_v = (T_v + 3) // 4 * 4
+    q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, 301, 0.5)
+    k = _randn((L, B, N_kv, S, D), dtype, 302, 0.5)
+    v = _randn((L, B, N_kv, S, D), dtype, 303, 0.7)
+    shape_k = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T, 0, DT[dtype], 0)
+    _, idx, kp = gpu_prune(shape_k, q_obs, k)
+    shape_v = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T_v, ld_v, DT[dtype], 0)
+    score_v = torch.empty(U, D, dtype=torch.float32, device="cuda")
+    idx_v = torch.full((U, T_v), -1, dtype=torch.int16, device="cuda")
+    vp = torch.zeros(U, S, ld_v, dtype=TDT[dtype], device="cuda")
+    ws = ws_tensor(thk.thk_workspace_bytes(shape_v, thk.THK_OP_PRUNE_VALUE))
+    thk.thk_prune_value(shape_v, q_obs, k, v, causal, score_v, idx_v, vp, ws)
+    torch.cuda.synchronize()
+    # stage checks
+    want_sc = O.score_value(as_numpy(q_obs), as_numpy(k), as_numpy(v), dtype, causal=bool(causal)).reshape(U, D)
+    check_score(score_v.cpu().numpy().astype(np.float64), want_sc,
+                v.cpu().to(torch.float64).numpy().reshape(U, S, D), G, S_obs, "pipeline", dtype)
+    want_idx_v = O.select_topk(score_v.cpu().numpy().astype(np.float64), T_v)
+    np.testing.assert_array_equal(idx_v.cpu().numpy(), want_idx_v)
+    want_vp = O.compact_keys(as_numpy(v).reshape(U, S, D), want_idx_v, dtype)
+    np.testing.assert_array_equal(as_numpy(vp[:, :, :T_v].contiguous()), want_vp)
+    # the same call with the score left in the workspace gives the same index list
+    idx_v2 = torch.full_like(idx_v, -1)
+    thk.thk_prune_value(shape_v, q_obs, k, v, causal, None, idx_v2, vp, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(idx_v, idx_v2)
+    # decode
+    q = _randn((U * G, D), dtype, 304, 0.5)
+    kt = _randn((U, cap, D), dtype, 305, 0.5)
+    vt = _randn((U, cap, D), dtype, 306)
+    shape_d = thk.make_shape(L, B, N_kv * G, N_kv, D, S, 1, T, 0, DT[dtype], 0)
+    out = torch.empty(U * G, D, dtype=TDT[dtype], device="cuda")
+    wsd = ws_tensor(thk.thk_workspace_bytes(shape_d, thk.THK_OP_DECODE))
+    thk.thk_decode_attn_kv(shape_d, q, kp, idx, vp, idx_v, T_v, ld_v, kt, vt, s_tail, cap, out, wsd)
+    torch.cuda.synchronize()
+    want = O.decode_attn_kv(as_numpy(q).reshape(B, N_kv * G, D), as_numpy(kp).reshape(B, N_kv, S, T),
+                            as_numpy(idx).reshape(B, N_kv, T), want_vp.reshape(B, N_kv, S, T_v),
+                            want_idx_v.reshape(B, N_kv, T_v), dtype, as_numpy(kt).reshape(B, N_kv, cap, D),
+                            as_numpy(vt).reshape(B, N_kv, cap, D), s_tail)
+    assert attn_rel_err(out, want.reshape(-1, D)).max() <= ATTN_TOL[dtype]
