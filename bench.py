@@ -27,6 +27,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload id (synth.CONFIGS); 2 = the metric's")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-value-cache", action="store_true",
+                    help="skip the value-cache extension leg (value score, value prune, decode over both caches)")
     ap.add_argument("--graph", action="store_true",
                     help="additionally time the step replayed from a HIP graph (reported as graph_ms_per_step)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -69,6 +71,69 @@ def cpu_baseline(cfg_id, cfg, T, device, budget_s=20.0):
             "sample": f"{layers} of {cfg['L']} layers, all {U} units each: prune + 1 decode step per layer "
                       f"({t_prune + t_dec:.1f} s of oracle time)",
             "prune_ms_per_layer": t_prune / layers * 1e3, "decode_us_per_step": t_dec / layers * 1e6}
+
+
+def value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k, v, kp, idx, dec, kt, vt, out, reps):
+    """The value-cache extension (not part of `value`): prune V with the same ratio as K
+    (value score on the matrix cores -> Top_T -> compaction) over all layers in one call, then
+    one decode step per layer over both pruned caches.  Reports the score kernel against the
+    HBM roofline (it streams K and V once) with its matrix-core rate beside it."""
+    L, B, N_q, N_kv, D, S, S_obs = (cfg[n] for n in ("L", "B", "N_q", "N_kv", "D", "S", "S_obs"))
+    U, G, dev = B * N_kv, N_q // N_kv, q_obs.device
+    cap, spl = cfg["tail_cap"], cfg["steps"]
+    T_v = T
+    ld_v = (T_v + 3) // 4 * 4
+    shape_v = thk.make_shape(L, B, N_q, N_kv, D, S, S_obs, T_v, ld_v, tdt, 0)
+    shape_1 = thk.make_shape(1, B, N_q, N_kv, D, S, S_obs, T, 0, tdt, 0)
+    score_v = torch.empty(L * U, D, dtype=torch.float32, device=dev)
+    idx_v = torch.empty(L * U, T_v, dtype=torch.int16, device=dev)
+    vp = torch.empty(L, U, S, ld_v, dtype=dt, device=dev)
+    ws = torch.empty(max(thk.thk_workspace_bytes(shape_v, thk.THK_OP_PRUNE_VALUE),
+                         thk.thk_workspace_bytes(shape_1, thk.THK_OP_DECODE), 16), dtype=torch.uint8, device=dev)
+
+    def ev():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()
+        return e
+
+    def prune_v(pair=None):
+        if pair is not None:
+            thk.thk_profile_next(*pair)
+        thk.thk_prune_value(shape_v, q_obs, k, v, 1, score_v, idx_v, vp, ws)
+
+    def decode_all():
+        for l in range(L):
+            q = dec[l][0][0]
+            thk.thk_decode_attn_kv(shape_1, q, kp[l], idx[l * U:(l + 1) * U], vp[l], idx_v[l * U:(l + 1) * U],
+                                   T_v, ld_v, kt[l] if cap else None, vt[l] if cap else None,
+                                   1 if cap else 0, cap, out[l], ws)
+
+    prune_v(); decode_all()
+    pairs = [(ev(), ev()) for _ in range(reps)]
+    marks = [ev() for _ in range(3)]
+    torch.cuda.synchronize()
+    marks[0].record()
+    for i in range(reps):
+        prune_v(pairs[i])
+    marks[1].record()
+    for i in range(reps):
+        decode_all()
+    marks[2].record()
+    torch.cuda.synchronize()
+    score_us = sum(a.elapsed_time(b) for a, b in pairs) / reps * 1e3
+    prune_ms_layer = marks[0].elapsed_time(marks[1]) / reps / L
+    dec_us = marks[1].elapsed_time(marks[2]) / reps / L * 1e3
+    score_bytes = L * (2 * U * S * D * eb + B * N_q * S_obs * D * eb)
+    score_flops = 4.0 * L * U * G * S_obs * S * D
+    prune_v_bytes = score_bytes + L * U * S * eb * (D + T_v)
+    dec_bytes = U * eb * (S * (T + T_v) + (2 * D if cap else 0))
+    return {"T_v": T_v, "causal": 1,
+            "score_kernel": "k_value_attn", "score_us": score_us, "score_bytes": score_bytes,
+            "score_GBps": score_bytes / score_us / 1e3, "score_frac_of_hbm_peak": score_bytes / score_us / 1e3 / HBM_PEAK_GBS,
+            "score_TFLOPs": score_flops / score_us / 1e6,
+            "prune_value_ms_per_layer": prune_ms_layer, "prune_value_GBps": prune_v_bytes / L / prune_ms_layer / 1e6,
+            "decode_kv_us_per_step": dec_us, "decode_kv_GBps": dec_bytes / dec_us / 1e3,
+            "decode_kv_bytes_vs_k_only": (T + T_v) / (T + D)}
 
 
 def measured_traffic(kernel):
@@ -260,6 +325,9 @@ def main():
         "kernels": kernels,
         "roofline": roof,
     }
+    if not args.no_value_cache:
+        res["value_cache"] = value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k, v, kp, idx, dec, kt, vt, out,
+                                             args.steps)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg_id, cfg, T, dev)
     print(json.dumps(res))
