@@ -291,8 +291,9 @@ def main():
     step_bytes = L * (prune_bytes + steps_per_layer * decode_bytes)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    fused = bool(thk.thk_prune_is_fused(shape_all))
-    prune_kernel = "k_prune_fused" if fused else "k_compact_flat"
+    form = thk.thk_prune_is_fused(shape_all)
+    fused = form != 0
+    prune_kernel = {2: "k_prune_onepass", 1: "k_prune_fused", 0: "k_compact_flat"}[form]
     prune_kernel_bytes = L * prune_bytes if fused else L * U * S * eb * (D + T)
     kernels = {
         prune_kernel: {"launches_per_step": 1, "avg_us": prune_k_us, "bytes_per_launch": prune_kernel_bytes,

@@ -106,8 +106,9 @@ size_t thk_workspace_bytes(const thk_shape *shape, int32_t op);
 /* The n_split the library would use for `op` when shape->n_split == 0. */
 int32_t thk_default_split(const thk_shape *shape, int32_t op);
 
-/* 1 if thk_prune would run `shape` as one fused launch, 0 for the staged three-kernel form
- * (or an invalid shape).  Host-only. */
+/* How thk_prune would run `shape`: 2 = one launch that keeps the rows on chip between the
+ * score and the compaction (K read once), 1 = one launch that reads the rows twice, 0 = the
+ * staged three-kernel form (or an invalid shape).  Host-only. */
 int32_t thk_prune_is_fused(const thk_shape *shape);
 
 /*
@@ -187,11 +188,16 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
 /*
  * End-of-prefill prune = thk_score + thk_select_topk + thk_compact_keys in one
  * call.  When K_pruned is dense (ld_keep == T) and S * T * sizeof(element) is a
- * multiple of 16, a single kernel does all three steps per row block, so that
- * the compaction re-reads K from cache rather than HBM; otherwise the three
- * kernels run one after the other.  Scores agree with thk_score to fp64
- * summation order (the last float bit can differ).  `score` may be NULL (then
- * it lives in ws).
+ * multiple of 16, a single kernel does all three steps: a block takes 512 rows of
+ * a unit (fewer for small calls), keeps them on chip while the unit's index list
+ * is being decided, and compacts them from there, so K is read from memory once;
+ * otherwise (and for units of more than 64 such blocks) the three kernels run one
+ * after the other.  Scores agree with thk_score to fp64 summation order (the
+ * last float bit can differ).  `score` may be NULL (then it lives in ws).
+ * Environment (read per call, for experiments and tests): THK_PRUNE_PATH =
+ * staged | fused | reread (the one-kernel form with the rows read twice),
+ * THK_PRUNE_BLOCK_ROWS, THK_PRUNE_HOLD_ROWS, THK_PRUNE_SPIN_LIMIT,
+ * THK_PRUNE_GROUP_MIB.
  *   ws : THK_OP_PRUNE bytes.
  */
 thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,

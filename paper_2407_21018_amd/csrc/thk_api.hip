@@ -124,14 +124,14 @@ long env_long(const char *name, long dflt) {
   return atol(e);
 }
 
-struct FusedPlan { bool ok; int NB; int64_t RB; };
+struct FusedPlan { bool ok; int NB; int64_t RB; int hold; };
 
 // The fused kernel needs the flat K_pruned layout (dense rows, 16-byte aligned
 // units).  Its blocks take 512 rows each (measured best on MI355X) and the
 // blocks of a unit wait for each other, so units of more than 64 blocks (long
 // sequences spread over few units) go through the staged path instead.
 FusedPlan fused_plan(const thk_shape *s) {
-  FusedPlan p{false, 0, 0};
+  FusedPlan p{false, 0, 0, 0};
   const char *path = getenv("THK_PRUNE_PATH");
   if (path != nullptr && path[0] == 's') return p;   // "staged": the three-kernel path
   const int eb = elem_bytes(s->dtype);
@@ -140,14 +140,20 @@ FusedPlan fused_plan(const thk_shape *s) {
   (void)eb;
   int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 0);
   if (rb <= 0) {
-    // 512 rows per block; small calls get shorter blocks until the launch has ~4 blocks per CU
-    rb = 512;
+    // the default block size, halved for small calls until the launch has ~4 blocks per CU
+    rb = env_long("THK_PRUNE_HOLD_ROWS", 512);
     while (rb > 64 && units_of(s) * ceil_div(s->S, rb) < (int64_t)kCUs * 4) rb /= 2;
+    // a unit may have at most 64 blocks: long sequences take larger blocks
+    while (rb < 512 && ceil_div(s->S, rb) > 64) rb *= 2;
   }
   if (rb < 32) rb = 32;
   rb = ceil_div(rb, 32) * 32;
+  // blocks of 128, 256 or 512 rows (fp32: 128 or 256) keep their rows on chip between the
+  // column sums and the compaction; other sizes, or THK_PRUNE_PATH=reread, read them twice
+  const bool reread = path != nullptr && path[0] == 'r';
+  if (!reread && (rb == 128 || rb == 256 || (rb == 512 && s->dtype == THK_BF16))) p.hold = (int)(rb / 128);
   const int64_t nb = ceil_div(s->S, rb);
-  const bool forced = path != nullptr && path[0] == 'f';   // "fused": regardless of block count
+  const bool forced = path != nullptr && (path[0] == 'f' || path[0] == 'r');   // regardless of block count
   if (nb > (forced ? 256 : 64)) return p;
   p.RB = rb;
   p.NB = (int)nb;
@@ -225,7 +231,8 @@ int32_t thk_default_split(const thk_shape *s, int32_t op) {
 
 int32_t thk_prune_is_fused(const thk_shape *s) {
   if (check_shape(s, true) != THK_OK) return 0;
-  return fused_plan(s).ok ? 1 : 0;
+  const FusedPlan fp = fused_plan(s);
+  return !fp.ok ? 0 : fp.hold != 0 ? 2 : 1;
 }
 
 size_t thk_workspace_bytes(const thk_shape *s, int32_t op) {
@@ -411,7 +418,7 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
   if (fp.ok) {
     const int spin = (int)env_long("THK_PRUNE_SPIN_LIMIT", 4096);
     if (failed(launch_prune_fused(s->dtype, q_obs, k, sc, idx, k_pruned, ws, U, s->S, keep_rows(s),
-                                  cache_rows(s, keep_rows(s)), G, s->S_obs, s->T, fp.NB, fp.RB,
+                                  cache_rows(s, keep_rows(s)), G, s->S_obs, s->T, fp.NB, fp.RB, fp.hold,
                                   spin < 0 ? 0 : spin, hs)))
       return THK_ERR_HIP;
     return THK_OK;

@@ -89,11 +89,12 @@ hipError_t launch_copy_rows(int dtype, const void *src, int64_t src_unit_rows, i
 // One-launch prune (flat K_pruned layout only).  ws: prune_fused_ws_bytes(U, NB) bytes.
 size_t prune_fused_ws_bytes(int64_t U, int NB);
 // S rows per unit are scored; rows [0, S_keep) are compacted into K_pruned, whose units are
-// kp_unit_rows rows apart.
+// kp_unit_rows rows apart.  hold = 0: blocks of RB rows re-read their rows for the compaction;
+// hold = 1, 2, 4 (fp32: 1, 2): RB = 128 * hold and the rows stay on chip in between.
 hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float *score, int16_t *idx,
                               void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
                               int64_t kp_unit_rows, int G, int S_obs, int T, int NB, int64_t RB,
-                              int spin_limit, hipStream_t st);
+                              int hold, int spin_limit, hipStream_t st);
 
 struct DecodeArgs {
   const void *q, *kp, *v, *kt, *vt;

@@ -197,6 +197,40 @@ __device__ __forceinline__ void compact_build_tab(uint16_t *tab, const int16_t *
   }
 }
 
+// Step 2 of compact_rows for one tile that is already in LDS: rows r0 .. r0 + nr of the unit.
+template <int DT>
+__device__ __forceinline__ void compact_emit_tile(const u32x4 *tile, u32x4 *__restrict__ dst, int64_t r0, int nr,
+                                                  int T, const uint16_t *tab, int lane) {
+  using E = Elem<DT>;
+  constexpr int VEC = E::VEC;
+  const int period = 8 * T;
+  const int nchunks = nr * T / VEC;
+  u32x4 *o = dst + (size_t)r0 * T / VEC;
+  for (int c = lane; c < nchunks; c += kWave) {
+    const int e0 = c * VEC;
+    const int pb = e0 / period;
+    const int pe = e0 - pb * period;
+    const int rowbase = pb * 8 * kD;
+    u32x4 w;
+    if constexpr (DT == THK_BF16) {
+      const uint16_t *tl = (const uint16_t *)tile + rowbase;
+      const u32x4 offs = *(const u32x4 *)(tab + pe);   // 8 offsets
+      const uint32_t o0 = offs.x & 0xffffu, o1 = offs.x >> 16, o2 = offs.y & 0xffffu, o3 = offs.y >> 16;
+      const uint32_t o4 = offs.z & 0xffffu, o5 = offs.z >> 16, o6 = offs.w & 0xffffu, o7 = offs.w >> 16;
+      w.x = (uint32_t)tl[o0] | ((uint32_t)tl[o1] << 16);
+      w.y = (uint32_t)tl[o2] | ((uint32_t)tl[o3] << 16);
+      w.z = (uint32_t)tl[o4] | ((uint32_t)tl[o5] << 16);
+      w.w = (uint32_t)tl[o6] | ((uint32_t)tl[o7] << 16);
+    } else {
+      const uint32_t *tl = (const uint32_t *)tile + rowbase;
+      const uint2 offs = *(const uint2 *)(tab + pe);   // 4 offsets
+      w.x = tl[offs.x & 0xffffu]; w.y = tl[offs.x >> 16];
+      w.z = tl[offs.y & 0xffffu]; w.w = tl[offs.y >> 16];
+    }
+    o[c] = w;
+  }
+}
+
 template <int DT>
 __device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
                                              int64_t s0, int64_t s1, int T, const uint16_t *tab,
@@ -221,31 +255,7 @@ __device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, u32x
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    const int nchunks = nr * T / VEC;
-    u32x4 *o = dst + (size_t)r0 * T / VEC;
-    for (int c = lane; c < nchunks; c += kWave) {
-      const int e0 = c * VEC;
-      const int pb = e0 / period;
-      const int pe = e0 - pb * period;
-      const int rowbase = pb * 8 * kD;
-      u32x4 w;
-      if constexpr (DT == THK_BF16) {
-        const uint16_t *tl = (const uint16_t *)tile + rowbase;
-        const u32x4 offs = *(const u32x4 *)(tab + pe);   // 8 offsets
-        const uint32_t o0 = offs.x & 0xffffu, o1 = offs.x >> 16, o2 = offs.y & 0xffffu, o3 = offs.y >> 16;
-        const uint32_t o4 = offs.z & 0xffffu, o5 = offs.z >> 16, o6 = offs.w & 0xffffu, o7 = offs.w >> 16;
-        w.x = (uint32_t)tl[o0] | ((uint32_t)tl[o1] << 16);
-        w.y = (uint32_t)tl[o2] | ((uint32_t)tl[o3] << 16);
-        w.z = (uint32_t)tl[o4] | ((uint32_t)tl[o5] << 16);
-        w.w = (uint32_t)tl[o6] | ((uint32_t)tl[o7] << 16);
-      } else {
-        const uint32_t *tl = (const uint32_t *)tile + rowbase;
-        const uint2 offs = *(const uint2 *)(tab + pe);   // 4 offsets
-        w.x = tl[offs.x & 0xffffu]; w.y = tl[offs.x >> 16];
-        w.z = tl[offs.y & 0xffffu]; w.w = tl[offs.y >> 16];
-      }
-      o[c] = w;
-    }
+    compact_emit_tile<DT>(tile, dst, r0, nr, T, tab, lane);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }

@@ -1,16 +1,18 @@
-// One-launch prune: score -> Top_T -> compaction with K read from HBM once
-// (Sec. 3.2 selection, Fig. 1 storage) -- gfx950, wave64.
+// One-launch prune: score -> Top_T -> compaction (Sec. 3.2 selection, Fig. 1 storage) --
+// gfx950, wave64.
 //
 // Every 256-thread block owns one (unit, row block) item and does three things:
 //   A. column sums of squares of its rows -> partial[item] (fp64), then it
 //      announces itself on the unit's arrival counter;
 //   B. the block that arrives LAST for a unit merges the unit's partials in
 //      row-block order, forms the scores with the pre-computed query norms,
-//      runs the Top_T selection, publishes idx and raises the unit's ready
-//      flag; the other blocks of the unit wait for that flag (bounded spin);
-//   C. every block compacts ITS OWN rows with the published index list.  The
-//      rows were streamed moments ago by the same block, so this second read is
-//      served by the L2 / memory-side cache instead of HBM.
+//      runs the Top_T selection and publishes the index list; the other blocks
+//      of the unit wait for the list (bounded spin);
+//   C. every block compacts ITS OWN rows with the published index list.
+// Two forms: k_prune_onepass keeps the block's rows on chip (registers and the
+// LDS tiles) from A to C, so K is read from memory once; k_prune_fused streams
+// the rows in A and reads them again in C (any block size; the second read comes
+// from the memory-side cache or HBM).
 //
 // Waiting is safe: a block only waits for blocks of its own unit, which have
 // lower or neighbouring block numbers and are dispatched with it; the wait is
@@ -22,14 +24,15 @@
 // Cross-block traffic.  The L2 caches of the eight XCDs are not coherent with
 // each other, and a device-scope release/acquire fence would write back /
 // invalidate a whole L2 per block.  Instead, everything one block hands to
-// another (partial sums, the index list, the counter and the flag) moves through
-// relaxed device-scope atomic loads and stores, which go to the coherence point
-// themselves; a producer waits until its own stores have been acknowledged
-// (s_waitcnt vmcnt(0) in every wave, then the block barrier) before it bumps the
-// counter or raises the flag, and a consumer only reads after it has seen the
-// counter or flag value.  The wait is written out: a workgroup-scope release
-// fence compiles to nothing here (a block's waves share one L1), and without it
-// the flag can overtake the data on its way to memory.
+// another (partial sums, the counter, the index list) moves through relaxed
+// device-scope atomic loads and stores, which go to the coherence point
+// themselves.  Before it bumps the counter a producer waits until its partial
+// sums have been acknowledged (s_waitcnt vmcnt(0) in every wave, then the block
+// barrier): a workgroup-scope release fence compiles to nothing here (a block's
+// waves share one L1), and without the wait the counter can overtake the data on
+// its way to memory.  The index list needs no such ordering: each of its 32-bit
+// words carries its own validity mark, the waiting blocks poll the words
+// themselves, and k_prune_prep clears them before every call.
 #include "thk_prune_device.h"
 
 namespace thk {
@@ -41,7 +44,7 @@ struct PruneFusedArgs {
   int16_t *idx;
   double *partial;        // [U][NB][128]
   double *qn;             // [U][128]   sum_g ||Q_obs,g[:, c]||
-  int *arrived, *ready;   // [U] each
+  int *arrived, *ready;   // [U] each (ready: unused slot kept for the workspace layout)
   uint32_t *idx_pub;      // [U][64]  the index list, two entries per word, for the waiting blocks
   unsigned char *done;    // [U * NB]
   int64_t S, RB;          // rows per unit, rows per block
@@ -58,6 +61,10 @@ __device__ inline double pub_load_f64(const double *p) {
   return __longlong_as_double((long long)__hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED,
                                                            __HIP_MEMORY_SCOPE_AGENT));
 }
+// Mark of a published index-list word (channel numbers are below 128, so bit 15 of each half
+// is free); k_prune_prep clears the words.
+constexpr uint32_t kPubValid = 0x80008000u;
+
 // Every store the block has issued so far has been acknowledged by the memory system (no cache
 // maintenance): what a producer needs before it signals through a device-scope atomic.
 __device__ inline void block_stores_done() {
@@ -72,10 +79,85 @@ __global__ __launch_bounds__(512) void k_prune_prep(PruneFusedArgs a) {
   const int64_t u = blockIdx.x;
   const double tot = unit_query_norm<DT, 512>(a.q_obs, u, a.G, a.S_obs, red);
   if (threadIdx.x < kD) a.qn[(size_t)u * kD + threadIdx.x] = tot;
-  if (threadIdx.x == 0) { a.arrived[u] = 0; a.ready[u] = 0; }
+  if (threadIdx.x == 0) a.arrived[u] = 0;
+  if (threadIdx.x < kWave) a.idx_pub[(size_t)u * kWave + threadIdx.x] = 0u;
   for (int i = threadIdx.x; i < a.NB; i += 512) a.done[(size_t)u * a.NB + i] = 0;
 }
 
+// Phases A' (publish, arrive), B (the last block of the unit merges, scores, selects, publishes)
+// and the bounded wait of the others.  s_part: the block's 128 column sums in LDS.  On return
+// s_idx holds the unit's index list, or the result is false: the block gives up and leaves its
+// rows to k_prune_repair.  All 256 threads must call.
+__device__ __forceinline__ bool unit_index_list(const PruneFusedArgs &a, int64_t u, int64_t item,
+                                                double *s_part, float *s_sc, int16_t *s_idx,
+                                                int *s_flag) {
+  const int tid = threadIdx.x;
+  if (tid < kD) pub_store_f64(a.partial + (size_t)item * kD + tid, s_part[tid]);
+  block_stores_done();
+  if (tid == 0) *s_flag = (atomicAdd(&a.arrived[u], 1) == a.NB - 1);
+  __syncthreads();
+  const bool last = *s_flag != 0;
+  __syncthreads();   // everyone has read the flag before the waiting path reuses it
+
+  if (last) {
+    // merge the unit's partials in block order: the two halves of the block list are summed by
+    // two thread groups (eight loads in flight each) and added, first half first
+    {
+      const int c = tid & (kD - 1), half = tid >> 7;
+      const int b_mid = (a.NB + 1) / 2;
+      const int b0 = half ? b_mid : 0, b1 = half ? a.NB : b_mid;
+      const double *p = a.partial + (size_t)u * a.NB * kD + c;
+      double kss = 0.0;
+      for (int b = b0; b < b1; b += 8) {   // a short last batch re-reads its last entry, unused
+        double x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = pub_load_f64(p + (size_t)min(b + j, b1 - 1) * kD);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) kss += (b + j < b1) ? x[j] : 0.0;
+      }
+      double *xch = (double *)s_part;   // the block's own sums are published already
+      if (half) xch[c] = kss;
+      __syncthreads();
+      if (!half) {
+        kss += xch[c];
+        const float scf = (float)(a.qn[(size_t)u * kD + c] * sqrt(kss));
+        a.score[(size_t)u * kD + c] = scf;
+        s_sc[c] = scf;
+      }
+    }
+    __syncthreads();
+    if (tid < kWave) select_wave(s_sc[tid], s_sc[tid + 64], a.T, s_idx, tid);
+    __syncthreads();
+    if (tid < a.T) a.idx[(size_t)u * a.T + tid] = s_idx[tid];
+    if (tid < kWave) {
+      const uint32_t lo = 2 * tid < a.T ? (uint16_t)s_idx[2 * tid] : 0u;
+      const uint32_t hi = 2 * tid + 1 < a.T ? (uint16_t)s_idx[2 * tid + 1] : 0u;
+      __hip_atomic_store(a.idx_pub + (size_t)u * kWave + tid, lo | (hi << 16) | kPubValid, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return true;
+  }
+  // ---- wait (bounded) for the unit's index list: every word carries its own validity mark, so
+  // the list needs no separate flag and no ordering between its words
+  if (tid < kWave) {
+    const uint32_t *p = a.idx_pub + (size_t)u * kWave + tid;
+    uint32_t w = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int n = 0; __any((w & kPubValid) == 0) && n < a.spin_limit; ++n) {
+      __builtin_amdgcn_s_sleep(16);
+      if ((w & kPubValid) == 0) w = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const bool ok = __all((w & kPubValid) != 0);
+    if (ok) {
+      s_idx[2 * tid] = (int16_t)(w & 0x7fffu);
+      s_idx[2 * tid + 1] = (int16_t)((w >> 16) & 0x7fffu);
+    }
+    if (tid == 0) *s_flag = ok;
+  }
+  __syncthreads();
+  return *s_flag != 0;
+}
+
+// Form 1: stream the rows for the column sums, re-read them for the compaction.
 template <int DT>
 __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   using E = Elem<DT>;
@@ -83,7 +165,9 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   uint16_t *tab = (uint16_t *)smem;          // 2 KiB
   u32x4 *tiles = smem + 128;                 // 4 x [32][128] elements
   __shared__ double red[4][kD];
+  __shared__ double s_part[kD];
   __shared__ float s_sc[kD];
+  __shared__ int16_t s_idx[kD];
   __shared__ int s_flag;
   const int tid = threadIdx.x;
   const int64_t item = blockIdx.x;
@@ -93,73 +177,128 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   const int64_t s1 = min(a.S, s0 + a.RB);
   const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
 
-  // ---- A. partial column sums, then arrive -----------------------------------
-  __shared__ double s_part[kD];
-  __shared__ int16_t s_idx[kD];
   colsum_block<DT, 2>(src, s0, s1, s_part, red);
   __syncthreads();
-  if (tid < kD) pub_store_f64(a.partial + (size_t)item * kD + tid, s_part[tid]);
-  block_stores_done();
-  if (tid == 0) s_flag = (atomicAdd(&a.arrived[u], 1) == a.NB - 1);
-  __syncthreads();
+  if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag)) return;
 
-  if (s_flag) {
-    // ---- B. last block of the unit: merge, score, select, publish ------------
-    if (tid < kD) {
-      const double *p = a.partial + (size_t)u * a.NB * kD + tid;
-      double kss = 0.0;
-      int b = 0;
-      for (; b + 8 <= a.NB; b += 8) {
-        double x[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) x[j] = pub_load_f64(p + (size_t)(b + j) * kD);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) kss += x[j];
-      }
-      for (; b < a.NB; ++b) kss += pub_load_f64(p + (size_t)b * kD);
-      const float scf = (float)(a.qn[(size_t)u * kD + tid] * sqrt(kss));
-      a.score[(size_t)u * kD + tid] = scf;
-      s_sc[tid] = scf;
-    }
-    __syncthreads();
-    if (tid < kWave) select_wave(s_sc[tid], s_sc[tid + 64], a.T, s_idx, tid);
-    __syncthreads();
-    if (tid < a.T) a.idx[(size_t)u * a.T + tid] = s_idx[tid];
-    if (tid < kWave) {
-      const uint32_t lo = 2 * tid < a.T ? (uint16_t)s_idx[2 * tid] : 0u;
-      const uint32_t hi = 2 * tid + 1 < a.T ? (uint16_t)s_idx[2 * tid + 1] : 0u;
-      __hip_atomic_store(a.idx_pub + (size_t)u * kWave + tid, lo | (hi << 16), __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
-    }
-    block_stores_done();
-    if (tid == 0) __hip_atomic_store(&a.ready[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  } else {
-    // ---- wait (bounded) for the unit's index list ----------------------------
-    if (tid == 0) {
-      int ok = __hip_atomic_load(&a.ready[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      for (int n = 0; ok == 0 && n < a.spin_limit; ++n) {
-        __builtin_amdgcn_s_sleep(16);
-        ok = __hip_atomic_load(&a.ready[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      s_flag = ok;
-    }
-    __syncthreads();
-    if (s_flag == 0) return;   // whole block leaves; k_prune_repair compacts these rows
-    if (tid < kWave) {
-      const uint32_t w = __hip_atomic_load(a.idx_pub + (size_t)u * kWave + tid, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-      s_idx[2 * tid] = (int16_t)(w & 0xffffu);
-      s_idx[2 * tid + 1] = (int16_t)(w >> 16);
-    }
-    __syncthreads();
-  }
-
-  // ---- C. compact this block's rows -------------------------------------------
   compact_build_tab(tab, s_idx, a.T);
   __syncthreads();
   const int64_t s1c = min(s1, a.S_keep);   // rows past S_keep stay at full width with the caller
   if (s0 < s1c)
     compact_rows<DT>(src, (u32x4 *)((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB), s0, s1c, a.T, tab, tiles);
+  if (tid == 0) a.done[item] = 1;
+}
+
+// Form 2: K is read from memory ONCE.  The block's rows (NTW tiles of 32 rows per wave, RB =
+// 128 * NTW rows) are held from the column sums until the index list arrives: the first
+// NTW - NLT tiles of a wave in registers, the last NLT in the wave's LDS tiles, which are idle
+// until the compaction anyway.  The compaction then empties the LDS tiles first and stages the
+// register tiles through the freed slot.  What hides the wait for the list is the other blocks
+// resident on the compute unit; the bytes they hold together cover the bandwidth-delay
+// product of the stream.
+// registers that hold rows: (NTW - NLT) tiles x 32 (bf16) or 64 (fp32) per lane
+template <int DT, int NTW, int NLT>
+__global__ __launch_bounds__(256, (NTW - NLT) * 16 * Elem<DT>::EB <= 32 ? 4 : (NTW - NLT) * 16 * Elem<DT>::EB <= 96 ? 3 : 2)
+void k_prune_onepass(PruneFusedArgs a) {
+  using E = Elem<DT>;
+  constexpr int VEC = E::VEC, CPR = kD / VEC, TR = kCompactTileRows, NLD = TR * CPR / kWave;
+  constexpr int NRT = NTW - NLT;             // tiles per wave held in registers
+  extern __shared__ u32x4 smem[];
+  uint16_t *tab = (uint16_t *)smem;          // 2 KiB
+  u32x4 *tiles = smem + 128;                 // [4 waves][NLT] x [32][128] elements
+  __shared__ double red[4][kD];
+  __shared__ double s_part[kD];
+  __shared__ float s_sc[kD];
+  __shared__ int16_t s_idx[kD];
+  __shared__ int s_flag;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int64_t item = blockIdx.x;
+  const int64_t u = item / a.NB;
+  const int blk = (int)(item % a.NB);
+  const int64_t s0 = (int64_t)blk * a.RB;   // a.RB == 128 * NTW
+  const int64_t s1 = min(a.S, s0 + a.RB);
+  const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
+  u32x4 *wtile = tiles + (size_t)wave * NLT * (TR * CPR);   // this wave's NLT tiles
+
+  // tile n of this wave = rows s0 + (4 n + wave) * 32 .. + 32, nr of them inside [s0, hi)
+  auto tile_row0 = [&](int n) { return s0 + (int64_t)(4 * n + wave) * TR; };
+  auto tile_rows = [&](int n, int64_t hi) { return (int)max((int64_t)0, min((int64_t)TR, hi - tile_row0(n))); };
+
+  // ---- load: every chunk of the block's rows is in flight at once ----------------------------
+  u32x4 r[NTW][NLD];
+#pragma unroll
+  for (int n = 0; n < NTW; ++n) {
+    const int nr = tile_rows(n, s1);
+    const u32x4 *tsrc = src + (size_t)tile_row0(n) * CPR;
+    const int cmax = nr * CPR - 1;
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      // chunks past a ragged tile's end repeat its last chunk (in bounds; excluded below)
+      r[n][j] = nr > 0 ? tsrc[min(j * kWave + lane, cmax)] : zero;
+    }
+  }
+
+  // ---- column sums of squares; the last NLT tiles then move to LDS -----------------------------
+  double dacc[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) dacc[v] = 0.0;
+#pragma unroll
+  for (int nn = 0; nn < NTW; ++nn) {
+    const int n = (nn + NRT) % NTW;          // LDS-bound tiles first: their registers free up early
+    const int nr = tile_rows(n, s1);
+    float facc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) facc[v] = 0.f;
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+      float f[VEC];
+      E::unpack(r[n][j], f);
+      const bool valid = (j * kWave + lane) / CPR < nr;
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) facc[v] = valid ? fmaf(f[v], f[v], facc[v]) : facc[v];
+      if (n >= NRT) wtile[(size_t)(n - NRT) * (TR * CPR) + j * kWave + lane] = r[n][j];
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) dacc[v] += (double)facc[v];
+  }
+#pragma unroll
+  for (int off = CPR; off < kWave; off <<= 1)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) dacc[v] += __shfl_xor(dacc[v], off);
+  if (lane < CPR)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) red[wave][lane * VEC + v] = dacc[v];
+  __syncthreads();
+  if (tid < kD) s_part[tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
+  __syncthreads();
+
+  if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag)) return;
+
+  // ---- compaction: the LDS tiles first, then the register tiles through slot 0 ---------------
+  compact_build_tab(tab, s_idx, a.T);
+  __syncthreads();
+  const int64_t s1c = min(s1, a.S_keep);
+  u32x4 *dst = (u32x4 *)((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
+#pragma unroll
+  for (int n = NRT; n < NTW; ++n) {
+    const int nr = tile_rows(n, s1c);
+    if (nr > 0) compact_emit_tile<DT>(wtile + (size_t)(n - NRT) * (TR * CPR), dst, tile_row0(n), nr, a.T, tab, lane);
+  }
+#pragma unroll
+  for (int n = 0; n < NRT; ++n) {
+    const int nr = tile_rows(n, s1c);
+    if (nr > 0) {   // wave-uniform
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();       // the slot's previous tile has been read
+#pragma unroll
+      for (int j = 0; j < NLD; ++j) wtile[j * kWave + lane] = r[n][j];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      compact_emit_tile<DT>(wtile, dst, tile_row0(n), nr, a.T, tab, lane);
+    }
+  }
   if (tid == 0) a.done[item] = 1;
 }
 
@@ -205,7 +344,7 @@ size_t prune_fused_ws_bytes(int64_t U, int NB) {
 hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float *score, int16_t *idx,
                               void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
                               int64_t kp_unit_rows, int G, int S_obs, int T, int NB, int64_t RB,
-                              int spin_limit, hipStream_t st) {
+                              int hold, int spin_limit, hipStream_t st) {
   clear_stale_hip_error();
   PruneFusedArgs a;
   a.k = k; a.q_obs = q_obs; a.kp = kp; a.score = score; a.idx = idx;
@@ -221,25 +360,47 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
   const int eb = dtype == THK_BF16 ? 2 : 4;
   const size_t lds = 2048 + 4 * (size_t)kCompactTileRows * kD * eb;
   const dim3 gu((unsigned)U), gi((unsigned)(U * NB));
+  // hold == 0: the re-reading form; otherwise RB == 128 * hold and the rows are held on chip
+  const void *main_fn = nullptr;
+  int nlt = 1;   // LDS tiles per wave
   if (dtype == THK_BF16) {
-    hipLaunchKernelGGL((k_prune_prep<THK_BF16>), gu, dim3(512), 0, st, a);
-    profile_mark(true, st);
-    hipLaunchKernelGGL((k_prune_fused<THK_BF16>), gi, dim3(256), lds, st, a);
-    profile_mark(false, st);
-    hipLaunchKernelGGL((k_prune_repair<THK_BF16>), gu, dim3(256), lds, st, a);
+    switch (hold) {
+      case 0: main_fn = (const void *)k_prune_fused<THK_BF16>; break;
+      case 1: main_fn = (const void *)k_prune_onepass<THK_BF16, 1, 1>; break;
+      case 2: main_fn = (const void *)k_prune_onepass<THK_BF16, 2, 1>; break;
+      case 4: main_fn = (const void *)k_prune_onepass<THK_BF16, 4, 1>; break;
+    }
   } else {
-    hipError_t e = hipFuncSetAttribute((const void *)k_prune_fused<THK_F32>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void *)k_prune_repair<THK_F32>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((k_prune_prep<THK_F32>), gu, dim3(512), 0, st, a);
-    profile_mark(true, st);
-    hipLaunchKernelGGL((k_prune_fused<THK_F32>), gi, dim3(256), lds, st, a);
-    profile_mark(false, st);
-    hipLaunchKernelGGL((k_prune_repair<THK_F32>), gu, dim3(256), lds, st, a);
+    switch (hold) {
+      case 0: main_fn = (const void *)k_prune_fused<THK_F32>; break;
+      case 1: main_fn = (const void *)k_prune_onepass<THK_F32, 1, 1>; break;
+      case 2: main_fn = (const void *)k_prune_onepass<THK_F32, 2, 1>; break;
+    }
   }
+  if (main_fn == nullptr || (hold != 0 && RB != 128 * hold)) return hipErrorInvalidValue;
+  const size_t lds_main = 2048 + 4 * (size_t)nlt * kCompactTileRows * kD * eb;
+  if (lds_main > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(main_fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_main);
+    if (e != hipSuccess) return e;
+  }
+  if (lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void *)k_prune_repair<THK_F32>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  void *kargs[] = {(void *)&a};
+  if (dtype == THK_BF16)
+    hipLaunchKernelGGL((k_prune_prep<THK_BF16>), gu, dim3(512), 0, st, a);
+  else
+    hipLaunchKernelGGL((k_prune_prep<THK_F32>), gu, dim3(512), 0, st, a);
+  profile_mark(true, st);
+  hipError_t le = hipLaunchKernel(main_fn, gi, dim3(256), kargs, lds_main, st);
+  profile_mark(false, st);
+  if (le != hipSuccess) return le;
+  if (dtype == THK_BF16)
+    hipLaunchKernelGGL((k_prune_repair<THK_BF16>), gu, dim3(256), lds, st, a);
+  else
+    hipLaunchKernelGGL((k_prune_repair<THK_F32>), gu, dim3(256), lds, st, a);
   return hipGetLastError();
 }
 

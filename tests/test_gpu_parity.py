@@ -175,7 +175,7 @@ def test_prune_fused_repeated_calls_on_one_workspace(monkeypatch):
     L, B, N, S, S_obs, T = 4, 4, 16, 4096, 32, 76
     U = L * B * N
     shape = thk.make_shape(L, B, N, N, D, S, S_obs, T, 0, thk.THK_BF16, 0)
-    assert thk.thk_prune_is_fused(shape) == 1
+    assert thk.thk_prune_is_fused(shape) == 2      # the form that keeps the rows on chip
     inputs = [(_randn((L, B, N, S_obs, D), "bf16", 71 + i, 1.0), _randn((L, B, N, S, D), "bf16", 81 + i, 1.0))
               for i in range(2)]
     ws = ws_tensor(thk.thk_workspace_bytes(shape, thk.THK_OP_PRUNE))
@@ -200,14 +200,22 @@ def test_prune_fused_repeated_calls_on_one_workspace(monkeypatch):
     assert not torch.equal(first_idx[0], first_idx[1])
 
 
-@pytest.mark.parametrize("path", ["fused", "fused-small-blocks", "fused-no-wait", "staged", "staged-groups"])
+@pytest.mark.parametrize("path", ["fused", "fused-small-blocks", "fused-no-wait", "hold-128", "hold-256", "hold-512",
+                                  "hold-256-no-wait", "reread-256", "staged", "staged-groups"])
 @pytest.mark.parametrize("dtype,G,S,T,sigma", PRUNE_CASES)
 def test_prune_pipeline_matches_oracle(dtype, G, S, T, sigma, path, monkeypatch):
     """thk_prune in its one-launch form (default row blocks, 32-row blocks, and with
     the wait for the index list switched off from the host so that the repair
     kernel does every compaction) and in its staged form (one group, many groups)."""
-    if path.startswith("fused"):
+    if path.startswith("fused") or path.startswith("hold"):
         monkeypatch.setenv("THK_PRUNE_PATH", "fused")
+    if path.startswith("hold"):      # row blocks that stay in registers between score and compaction
+        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", path.split("-")[1])
+    if path == "hold-256-no-wait":
+        monkeypatch.setenv("THK_PRUNE_SPIN_LIMIT", "0")
+    if path == "reread-256":         # the same blocking with the rows read twice
+        monkeypatch.setenv("THK_PRUNE_PATH", "reread")
+        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", "256")
     if path == "fused-small-blocks":
         monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", "32")
     if path == "fused-no-wait":
