@@ -240,7 +240,6 @@ __device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, u32x
   constexpr int NLD = TR * CPR / kWave;   // 16-byte loads per lane per tile
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   u32x4 *tile = tiles + wave * (TR * CPR);
-  const int period = 8 * T;
   for (int64_t r0 = s0 + (int64_t)wave * TR; r0 < s1; r0 += 4 * TR) {
     const int nr = (int)min((int64_t)TR, s1 - r0);
     // rows past the end of a ragged last tile re-read its last row (kept in bounds, never gathered)

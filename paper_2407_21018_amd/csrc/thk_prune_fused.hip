@@ -44,7 +44,7 @@ struct PruneFusedArgs {
   int16_t *idx;
   double *partial;        // [U][NB][128]
   double *qn;             // [U][128]   sum_g ||Q_obs,g[:, c]||
-  int *arrived, *ready;   // [U] each (ready: unused slot kept for the workspace layout)
+  int *arrived;           // [U] blocks of the unit that have published their partial sums
   uint32_t *idx_pub;      // [U][64]  the index list, two entries per word, for the waiting blocks
   unsigned char *done;    // [U * NB]
   int64_t S, RB;          // rows per unit, rows per block
@@ -334,7 +334,7 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
 size_t prune_fused_ws_bytes(int64_t U, int NB) {
   size_t b = (size_t)U * NB * kD * sizeof(double);   // partial
   b += (size_t)U * kD * sizeof(double);              // qn
-  b += (size_t)U * 2 * sizeof(int);                  // arrived, ready
+  b += (size_t)U * sizeof(int);                      // arrived
   b = (b + 15) & ~(size_t)15;
   b += (size_t)U * kWave * sizeof(uint32_t);         // idx_pub
   b += ((size_t)U * NB + 15) & ~(size_t)15;          // done
@@ -352,7 +352,6 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
   a.partial = (double *)w; w += (size_t)U * NB * kD * sizeof(double);
   a.qn = (double *)w;      w += (size_t)U * kD * sizeof(double);
   a.arrived = (int *)w;    w += (size_t)U * sizeof(int);
-  a.ready = (int *)w;      w += (size_t)U * sizeof(int);
   w = (char *)(((uintptr_t)w + 15) & ~(uintptr_t)15);
   a.idx_pub = (uint32_t *)w; w += (size_t)U * kWave * sizeof(uint32_t);
   a.done = (unsigned char *)w;

@@ -132,3 +132,65 @@ def test_cache_growth_argument_checks():
     assert _status(thk.thk_tail_flush, _shape(S=1000, S_cap=1002), A, A, A, None, None, 8, 8, 4, stream=0) == 2
     # unified value cache at decode needs room for the tail rows
     assert _status(thk.thk_decode_attn, _shape(S=1000, S_cap=1003), A, A, A, A, A, None, 4, 8, A, (A, BIG), stream=0) == 2
+
+
+def test_value_cache_entry_points_reject_bad_arguments():
+    s = _shape()
+    ws = (A, BIG)
+    # thk_score_value
+    assert _status(thk.thk_score_value, s, A, A, A, 2, A, ws, stream=0) == 2          # causal flag
+    assert _status(thk.thk_score_value, s, A, None, A, 0, A, ws, stream=0) == 1       # k missing
+    assert _status(thk.thk_score_value, s, A, A, A + 8, 0, A, ws, stream=0) == 4      # v misaligned
+    assert _status(thk.thk_score_value, s, A, A, A, 0, A, (A, 16), stream=0) == 5     # workspace too small
+    assert _status(thk.thk_score_value, _shape(S_obs=1001), A, A, A, 0, A, ws, stream=0) == 2
+    assert _status(thk.thk_score_value, _shape(N_q=2048, N_kv=1, S_obs=32, S=100), A, A, A, 0, A, ws, stream=0) == 2
+    # thk_prune_value
+    assert _status(thk.thk_prune_value, s, A, A, A, 0, A, None, A, ws, stream=0) == 1     # idx_v missing
+    assert _status(thk.thk_prune_value, s, A, A, A, 0, A, A, A, (A, 16), stream=0) == 5
+    assert _status(thk.thk_prune_value, s, A, A, A, 3, None, A, A, ws, stream=0) == 2     # causal flag
+    # thk_decode_attn_kv
+    d = (s, A, A, A, A)
+    assert _status(thk.thk_decode_attn_kv, *d, A, 0, 0, None, None, 0, 0, A, ws, stream=0) == 2     # T_v < 1
+    assert _status(thk.thk_decode_attn_kv, *d, A, 65, 64, None, None, 0, 0, A, ws, stream=0) == 2   # ld_v < T_v
+    assert _status(thk.thk_decode_attn_kv, *d, A, 64, 132, None, None, 0, 0, A, ws, stream=0) == 2  # ld_v > D
+    assert _status(thk.thk_decode_attn_kv, *d, A, 63, 63, None, None, 0, 0, A, ws, stream=0) == 3   # ld_v % 4
+    assert _status(thk.thk_decode_attn_kv, *d, None, 64, 64, None, None, 0, 0, A, ws, stream=0) == 1
+    assert _status(thk.thk_decode_attn_kv, *d, A + 2, 64, 64, None, None, 0, 0, A, ws, stream=0) == 4
+    assert _status(thk.thk_decode_attn_kv, *d, A, 64, 64, A, None, 2, 4, A, ws, stream=0) == 1      # tail without v_tail
+
+
+def test_value_workspace_and_split_sizes():
+    """Workspace of the value score = partial attention records (one per unit, split and 32-row
+    query tile: 128 x 32 outputs + 32 maxima + 32 sums, fp32) + the squared outputs when a unit
+    has more than one query tile; the value prune adds the score array."""
+    rec = (32 * 128 + 64) * 4
+    for G, S_obs, S in [(1, 32, 4096), (4, 32, 32768), (4, 64, 131072), (3, 16, 300), (1, 1, 1)]:
+        s = _shape(L=2, B=1, N_q=2 * G, N_kv=2, S=S, S_obs=S_obs)
+        U = 4
+        n = thk.thk_default_split(s, thk.THK_OP_SCORE_VALUE)
+        assert 1 <= n <= 256 and (n == 1 or S // n >= 128)
+        nqt = -(-G * S_obs // 32)
+        qt = 4 if nqt >= 4 else 2 if nqt >= 2 else 1
+        nqt_pad = -(-nqt // qt) * qt
+        want = U * n * nqt_pad * rec + (U * nqt * 32 * 128 * 4 if nqt > 1 else 0)
+        assert thk.thk_workspace_bytes(s, thk.THK_OP_SCORE_VALUE) == want
+        assert thk.thk_workspace_bytes(s, thk.THK_OP_PRUNE_VALUE) == (want + 15) // 16 * 16 + U * 128 * 4
+        s.n_split = 3
+        assert thk.thk_default_split(s, thk.THK_OP_SCORE_VALUE) == n     # the library's own choice
+    assert thk.thk_workspace_bytes(_shape(S_obs=0), thk.THK_OP_SCORE_VALUE) == 0
+
+
+def test_prune_plan_by_shape(monkeypatch):
+    """Which form thk_prune takes (2 = rows held on chip, 1 = rows read twice, 0 = staged)."""
+    for v in ("THK_PRUNE_PATH", "THK_PRUNE_BLOCK_ROWS", "THK_PRUNE_HOLD_ROWS"):
+        monkeypatch.delenv(v, raising=False)
+    cfg2 = thk.make_shape(32, 4, 32, 32, 128, 4096, 32, 76, 0, thk.THK_BF16, 0)
+    assert thk.thk_prune_is_fused(cfg2) == 2
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 131072, 64, 64, 0, thk.THK_BF16, 0)) == 0  # 256 blocks per unit
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 8, 32, 8, 128, 32768, 32, 64, 0, thk.THK_BF16, 0)) == 2
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 0, thk.THK_F32, 0)) == 1     # tiny: 64-row blocks
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 72, thk.THK_F32, 0)) == 0    # padded rows: not flat
+    monkeypatch.setenv("THK_PRUNE_PATH", "reread")
+    assert thk.thk_prune_is_fused(cfg2) == 1
+    monkeypatch.setenv("THK_PRUNE_PATH", "staged")
+    assert thk.thk_prune_is_fused(cfg2) == 0
