@@ -8,8 +8,8 @@
 //
 // k_value_attn (bf16): 4 waves per block.  The G * S_obs query rows of one KV head are cut into
 // tiles of 32 rows; a block carries QT of them (1, 2 or 4) and streams the keys in chunks of
-// (4 / QT) * 32 rows, so wave w works on query tile w % QT and key sub-tile w / QT of every
-// chunk.  Per 32-key sub-tile a wave computes
+// 128 rows; wave w works on query tile w % QT and on the QT consecutive 32-key sub-tiles
+// number w / QT of every chunk.  Per 32-key sub-tile a wave computes
 //   S^T = K_sub Q^T        8 x v_mfma_f32_32x32x16_bf16 (A = keys from LDS, B = queries in VGPRs)
 //   P^T = exp2(S^T - m)    in the accumulator layout, which already is the B-operand layout
 //   O^T += V_sub^T P^T     8 x MFMA; the A operand (values transposed) comes from row-major LDS
@@ -21,7 +21,7 @@
 namespace thk {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -31,14 +31,11 @@ constexpr int kRec = 32 * kD + 64;   // floats per partial record: O^T [128][32]
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no key seen yet"
 
 // One 32-key sub-tile of the running-maximum softmax in the MFMA accumulator layout: lane
-// (n, h) holds, for query column n, the 16 keys kb + (r / 4) * 8 + h * 4 + r % 4.  Scales the
-// logits into the log2 domain, hides keys past `lim`, updates the running maximum (rescaling
-// the row sum and the output accumulators when some query's maximum moved) and leaves the
-// probabilities exp2(s - m) in s.
+// (n, h) holds, for query column n, the 16 keys kb + (r / 4) * 8 + h * 4 + r % 4.  Hides keys
+// past `lim`, updates the running maximum (rescaling the row sum and the output accumulators
+// when some query's maximum moved) and leaves the probabilities exp2(s * scale_log2 - m) in s.
 __device__ __forceinline__ void softmax_step(f32x16 &s, int64_t kb, int h, int64_t lim, int64_t lim_min,
                                              float scale_log2, float &m_run, float &l_run, f32x16 (&o)[4]) {
-#pragma unroll
-  for (int r = 0; r < 16; ++r) s[r] *= scale_log2;
   if (kb + 31 > lim_min) {   // wave-uniform: only the sub-tiles that reach the window or the end
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -50,7 +47,8 @@ __device__ __forceinline__ void softmax_step(f32x16 &s, int64_t kb, int h, int64
 #pragma unroll
   for (int r = 1; r < 16; ++r) mt = fmaxf(mt, s[r]);
   mt = fmaxf(mt, __shfl_xor(mt, 32));
-  const float m_new = fmaxf(m_run, mt);
+  // the running maximum lives in the log2 domain (scale_log2 > 0 keeps the order)
+  const float m_new = fmaxf(m_run, mt * scale_log2);
   if (__any(m_new > m_run)) {
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     l_run *= alpha;
@@ -61,7 +59,7 @@ __device__ __forceinline__ void softmax_step(f32x16 &s, int64_t kb, int h, int64
     m_run = m_new;
   }
 #pragma unroll
-  for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(s[r] - m_run);
+  for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -m_run));
 }
 
 // Partial record of one (unit, split, query tile): O^T [128][32], then m [32] and l [32].
@@ -87,9 +85,10 @@ constexpr int kVst = 320;  // LDS bytes per value row: the 4-row x 32-byte trans
 
 template <int QT>
 __global__ __launch_bounds__(256, 2) void k_value_attn_bf16(ValueAttnArgs a) {
-  constexpr int KW = 4 / QT;     // key sub-tiles per chunk
-  constexpr int CR = KW * 32;    // rows per chunk
-  constexpr int NP = 2 * KW;     // 16-row staging passes per chunk
+  constexpr int KW = 4 / QT;     // waves that share a query tile, each on its own key sub-tiles
+  constexpr int KT = QT;         // 32-key sub-tiles per wave and chunk
+  constexpr int CR = 128;        // rows per chunk = KW * KT * 32
+  constexpr int NP = 8;          // 16-row staging passes per chunk
   __shared__ __attribute__((aligned(16))) unsigned char smem[CR * (kKst + kVst)];
   unsigned char *Ks = smem, *Vs = smem + CR * kKst;
 
@@ -132,13 +131,17 @@ __global__ __launch_bounds__(256, 2) void k_value_attn_bf16(ValueAttnArgs a) {
   const int srow = tid >> 4, scol = (tid & 15) * 16;
 
   u32x4 pk[NP], pv[NP];
-  auto fetch = [&](int c) {
+  // quarter q of the next chunk's loads: q = 0, 1 the two halves of the key rows, q = 2, 3 of
+  // the value rows
+  auto fetch_part = [&](int c, int q) {
+    const unsigned char *g = q < 2 ? kg : vg;
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
+    for (int pp = 0; pp < NP / 2; ++pp) {
+      const int p = (q & 1) * (NP / 2) + pp;
       int64_t gr = k0 + (int64_t)c * CR + p * 16 + srow;
       gr = gr < S ? gr : S - 1;   // rows past the end repeat the last one; their weights are zero
-      pk[p] = *(const u32x4 *)(kg + gr * (kD * 2) + scol);
-      pv[p] = *(const u32x4 *)(vg + gr * (kD * 2) + scol);
+      const u32x4 x = *(const u32x4 *)(g + gr * (kD * 2) + scol);
+      if (q < 2) pk[p] = x; else pv[p] = x;
     }
   };
   auto stash = [&]() {
@@ -157,41 +160,55 @@ __global__ __launch_bounds__(256, 2) void k_value_attn_bf16(ValueAttnArgs a) {
   float m_run = kNegBig, l_run = 0.f;
 
   // LDS addresses of this lane's operands inside a sub-tile
-  const unsigned char *ka_p = Ks + (ksub * 32 + n) * kKst + h * 16;
+  const unsigned char *ka_p = Ks + (ksub * KT * 32 + n) * kKst + h * 16;
   const int j = lane & 15, gsub = (lane >> 4) & 1;
-  const unsigned char *va_p = Vs + (ksub * 32 + h * 4 + (j >> 2)) * kVst + (gsub * 16 + 4 * (j & 3)) * 2;
+  const unsigned char *va_p = Vs + (ksub * KT * 32 + h * 4 + (j >> 2)) * kVst + (gsub * 16 + 4 * (j & 3)) * 2;
 
   if (nchunks > 0) {
-    fetch(0);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) fetch_part(0, q);
     stash();
   }
   __syncthreads();
   for (int c = 0; c < nchunks; ++c) {
-    if (c + 1 < nchunks) fetch(c + 1);
-    const int64_t kb = k0 + (int64_t)c * CR + ksub * 32;   // first key of this wave's sub-tile
-    if (kb < k1) {
+    // the next chunk's loads are issued in four parts spread over this chunk's work, so that the
+    // memory system has requests in flight throughout the compute phase
+    const bool more = c + 1 < nchunks;
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+      if (more) {
+#pragma unroll
+        for (int q = t * (4 / KT); q < (t + 1) * (4 / KT); ++q) fetch_part(c + 1, q);
+      }
+      const int64_t kb = k0 + (int64_t)c * CR + (ksub * KT + t) * 32;   // first key of the sub-tile
+      if (kb >= k1) continue;
+      const unsigned char *ka_t = ka_p + t * 32 * kKst, *va_t = va_p + t * 32 * kVst;
       f32x16 s;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 ka = *(const bf16x8 *)(ka_p + ks * 32);
+        const bf16x8 ka = *(const bf16x8 *)(ka_t + ks * 32);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[ks], s, 0, 0, 0);
       }
       softmax_step(s, kb, h, lim, lim_min, a.scale_log2, m_run, l_run, o);
       // probabilities, rounded to bf16 once; the same rounded values feed the row sum
+      // (v_dot2_f32_bf16 against a pair of ones adds two of them per instruction)
       bf16x8 pb[2];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const __bf16 pr = (__bf16)s[r];
-        pb[r >> 3][r & 7] = pr;
-        l_run += (float)pr;
-      }
+      for (int r = 0; r < 16; ++r) pb[r >> 3][r & 7] = (__bf16)s[r];
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bf16x2 pr = {pb[k2][2 * i], pb[k2][2 * i + 1]};
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l_run, false);
+        }
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) {
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2) {
-          const unsigned char *vp = va_p + (k2 * 16) * kVst + dt * 64;
+          const unsigned char *vp = va_t + (k2 * 16) * kVst + dt * 64;
           const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
               (__attribute__((address_space(3))) s16x4 *)(vp));
           const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -348,16 +365,23 @@ __global__ __launch_bounds__(64 * QT) void k_value_attn_f32(ValueAttnArgs a) {
   write_record(a.part + (((size_t)u * a.n_split + sp) * nqt + qtile) * kRec, o, m_run, l_tot, n, h);
 }
 
-// Merge the partial records of one 32-row query tile of one unit and normalise.  256 threads:
-// thread (d, half) sums the records p = half, half + 2, ... for value channel d; the halves meet
-// in LDS.  A unit with a single tile gets its score here (each thread holds all of its rows);
-// otherwise the squared outputs go to sq[u][row][d] for k_value_norms.
+// Merge the partial records of one 32-row query tile of one unit and normalise.  A block of
+// 256 threads covers DQ = 256 / PG value channels: thread (d, pg) sums the records p = pg,
+// pg + PG, ... for channel d; the PG groups meet in LDS and are added in group order.  A unit
+// with a single tile gets its score here (each thread holds all of its rows); otherwise the
+// squared outputs go to sq[u][row][d] for k_value_norms.  PG = 2 for few records, 8 for many.
+template <int PG>
 __global__ __launch_bounds__(256) void k_value_merge(const float *part, float *sq, float *score, int G, int S_obs,
                                                      int n_part, int nqt, int nt) {
-  extern __shared__ float wts[];   // [n_part][32] merge weights, then [128][33] for the halves
-  const int64_t u = blockIdx.x / nt;
-  const int t = (int)(blockIdx.x % nt);
-  const int d = threadIdx.x & 127, half = threadIdx.x >> 7;
+  constexpr int DQ = 256 / PG, NDB = kD / DQ;   // channels per block, blocks per (unit, tile)
+  extern __shared__ float wts[];   // [n_part][32] merge weights, then [PG - 1][DQ][33] for the groups
+  int64_t bid = blockIdx.x;
+  const int db = (int)(bid % NDB);
+  bid /= NDB;
+  const int64_t u = bid / nt;
+  const int t = (int)(bid % nt);
+  const int dl = threadIdx.x % DQ, pg = threadIdx.x / DQ;
+  const int d = db * DQ + dl;
   const int rows_q = G * S_obs;
   const float *pu = part + (size_t)u * n_part * nqt * kRec;
   if (threadIdx.x < 32) {
@@ -378,7 +402,7 @@ __global__ __launch_bounds__(256) void k_value_merge(const float *part, float *s
   float acc[32];
 #pragma unroll
   for (int q = 0; q < 32; ++q) acc[q] = 0.f;
-  for (int p = half; p < n_part; p += 2) {
+  for (int p = pg; p < n_part; p += PG) {
     const float4 *src = (const float4 *)(pu + ((size_t)p * nqt + t) * kRec + d * 32);
     const float *wp = wts + p * 32;
 #pragma unroll
@@ -391,15 +415,17 @@ __global__ __launch_bounds__(256) void k_value_merge(const float *part, float *s
     }
   }
   __syncthreads();               // the weights are no longer read
-  float *xch = wts;              // [128][33]
-  if (half == 1) {
+  float *xch = wts;              // [PG - 1][DQ][33]
+  if (pg > 0) {
 #pragma unroll
-    for (int q = 0; q < 32; ++q) xch[d * 33 + q] = acc[q];
+    for (int q = 0; q < 32; ++q) xch[((pg - 1) * DQ + dl) * 33 + q] = acc[q];
   }
   __syncthreads();
-  if (half == 1) return;
+  if (pg > 0) return;
 #pragma unroll
-  for (int q = 0; q < 32; ++q) acc[q] += xch[d * 33 + q];
+  for (int g2 = 1; g2 < PG; ++g2)
+#pragma unroll
+    for (int q = 0; q < 32; ++q) acc[q] += xch[((g2 - 1) * DQ + dl) * 33 + q];
   if (nt == 1) {
     double ss = 0.0, total = 0.0;
 #pragma unroll
@@ -420,19 +446,35 @@ __global__ __launch_bounds__(256) void k_value_merge(const float *part, float *s
   }
 }
 
-// Column norms per query head from the squared outputs: thread d walks the unit's rows in
-// (head, window row) order and closes a head at its last row.
-__global__ __launch_bounds__(128) void k_value_norms(const float *sq, float *score, int G, int S_obs, int nt) {
+// Column norms per query head from the squared outputs.  1024 threads = 128 channels x 8 head
+// groups: thread (d, hg) sums the squares of heads hg, hg + 8, ... (eight rows in flight), takes
+// the roots, and the groups are added in group order.
+__global__ __launch_bounds__(1024) void k_value_norms(const float *sq, float *score, int G, int S_obs, int nt) {
+  __shared__ double tot[8][kD];
   const int64_t u = blockIdx.x;
-  const int d = threadIdx.x;
+  const int d = threadIdx.x & (kD - 1), hg = threadIdx.x >> 7;
   const float *src = sq + (size_t)u * nt * 32 * kD + d;
   double total = 0.0;
-  for (int g = 0; g < G; ++g) {
+  for (int g = hg; g < G; g += 8) {
+    const float *hs = src + (size_t)g * S_obs * kD;
     double ss = 0.0;
-    for (int i = 0; i < S_obs; ++i) ss += (double)src[(size_t)(g * S_obs + i) * kD];
+    for (int i0 = 0; i0 < S_obs; i0 += 8) {
+      float x[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[j] = hs[(size_t)min(i0 + j, S_obs - 1) * kD];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) ss += (i0 + j < S_obs) ? (double)x[j] : 0.0;
+    }
     total += sqrt(ss);
   }
-  score[(size_t)u * kD + d] = (float)total;
+  tot[hg][d] = total;
+  __syncthreads();
+  if (hg == 0) {
+    double t = tot[0][d];
+#pragma unroll
+    for (int g2 = 1; g2 < 8; ++g2) t += tot[g2][d];
+    score[(size_t)u * kD + d] = (float)t;
+  }
 }
 
 }  // namespace
@@ -479,13 +521,20 @@ hipError_t launch_value_score(int dtype, const void *q_obs, const void *k, const
   const int n_part = n_split;
   const int nqt = a.n_qblk * QT;
   float *sq = part + (size_t)U * n_part * nqt * kRec;   // behind the partial records
+  // few records: 2 groups x 128 channels per block; many: 8 groups x 32 channels, 4 blocks
+  const int PG = n_part > 8 ? 8 : 2;
+  const int DQ = 256 / PG;
   size_t lds = (size_t)n_part * 32 * sizeof(float);
-  if (lds < 128 * 33 * sizeof(float)) lds = 128 * 33 * sizeof(float);
-  hipLaunchKernelGGL(k_value_merge, dim3((unsigned)(U * nqt_real)), dim3(256), lds, st, part, sq, score, G, S_obs,
-                     n_part, nqt, nqt_real);
+  const size_t xch = (size_t)(PG - 1) * DQ * 33 * sizeof(float);
+  if (lds < xch) lds = xch;
+  const dim3 mg((unsigned)(U * nqt_real * (kD / DQ)));
+  if (PG == 8)
+    hipLaunchKernelGGL(k_value_merge<8>, mg, dim3(256), lds, st, part, sq, score, G, S_obs, n_part, nqt, nqt_real);
+  else
+    hipLaunchKernelGGL(k_value_merge<2>, mg, dim3(256), lds, st, part, sq, score, G, S_obs, n_part, nqt, nqt_real);
   e = hipGetLastError();
   if (e != hipSuccess || nqt_real == 1) return e;
-  hipLaunchKernelGGL(k_value_norms, dim3((unsigned)U), dim3(128), 0, st, sq, score, G, S_obs, nqt_real);
+  hipLaunchKernelGGL(k_value_norms, dim3((unsigned)U), dim3(1024), 0, st, sq, score, G, S_obs, nqt_real);
   return hipGetLastError();
 }
 
