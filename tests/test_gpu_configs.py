@@ -132,3 +132,102 @@ def test_config5_prune_and_tail_decode():
         worst = max(worst, err.max())
     print(f"config 5: attention max rel err {worst:.3e}")
     assert worst <= ATTN_TOL["bf16"]
+
+
+# ------------------------------------------------------------------ value cache ----
+VALUE_SAMPLES = {1: 8, 2: 48, 3: 8, 4: 2, 5: 12}    # units whose value score the oracle recomputes
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
+def test_config_value_prune_and_decode(cfg_id):
+    """The value-cache path at full size, in the launch configuration the benchmark uses: one
+    thk_prune_value call over all layers (causal window), then thk_decode_attn_kv per layer.
+    The fp64 oracle recomputes the value score on a fixed sample of units spread over the call
+    (an S_obs x S attention per unit and head); the selection is checked on EVERY unit in the
+    kernel's precision, the compacted values bit for bit on the sampled units, and the decode
+    output on the sampled units' heads."""
+    _value_cfg_body(cfg_id)
+
+
+def _value_cfg_body(cfg_id):
+    cfg = synth.CONFIGS[cfg_id]
+    L, B, N_q, N_kv, D, S, S_obs = (cfg[k] for k in ("L", "B", "N_q", "N_kv", "D", "S", "S_obs"))
+    dtn = cfg["dtype"]
+    G, U = N_q // N_kv, B * N_kv
+    T = thk.thk_keep_count(D, cfg["lam"])
+    T_v, ld_v = T, (T + 3) // 4 * 4
+    dt = synth.torch_dtype(dtn)
+    q_obs = torch.empty(L, B, N_q, S_obs, D, dtype=dt, device=DEV)
+    k = torch.empty(L, B, N_kv, S, D, dtype=dt, device=DEV)
+    v = torch.empty(L, B, N_kv, S, D, dtype=dt, device=DEV)
+    for l in range(L):
+        q_obs[l], k[l], v[l] = (t[0] for t in synth.gen_prefill(cfg_id, l, DEV, **cfg))
+    shape_v = thk.make_shape(L, B, N_q, N_kv, D, S, S_obs, T_v, ld_v, DT[dtn], 0)
+    score_v = torch.empty(L * U, D, dtype=torch.float32, device=DEV)
+    idx_v = torch.full((L * U, T_v), -1, dtype=torch.int16, device=DEV)
+    vp = torch.zeros(L, U, S, ld_v, dtype=dt, device=DEV)
+    ws = torch.empty(thk.thk_workspace_bytes(shape_v, thk.THK_OP_PRUNE_VALUE), dtype=torch.uint8, device=DEV)
+    thk.thk_prune_value(shape_v, q_obs, k, v, 1, score_v, idx_v, vp, ws)
+    torch.cuda.synchronize()
+
+    # selection on every unit, from the scores the GPU produced
+    g_sc = score_v.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(g_sc)) and np.all(g_sc > 0)
+    want_idx = O.select_topk(g_sc, T_v)
+    np.testing.assert_array_equal(idx_v.cpu().numpy(), want_idx)
+
+    # sampled units: score against the oracle, compacted values bit for bit
+    n_s = VALUE_SAMPLES[cfg_id]
+    units = sorted({int(round(i * (L * U - 1) / max(1, n_s - 1))) for i in range(n_s)})
+    qf = q_obs.reshape(L * U, G, S_obs, D)
+    kf, vf = k.reshape(L * U, S, D), v.reshape(L * U, S, D)
+    worst_med, worst_hard = 0.0, 0.0
+    ui = torch.tensor(units, device=DEV)
+    # one oracle call for all sampled units (its OpenMP loop runs over units)
+    want_all = O.score_value(as_numpy(qf[ui])[:, None], as_numpy(kf[ui])[:, None, None],
+                             as_numpy(vf[ui])[:, None, None], dtn, causal=True)[:, 0, 0]
+    for j, u in enumerate(units):
+        want = want_all[j]
+        err = np.abs(g_sc[u] - want)
+        v64 = vf[u].cpu().to(torch.float64).numpy()
+        if dtn == "bf16":
+            hard = G * np.sqrt(S_obs) * 2.0 ** -8 * np.abs(v64).max(axis=0) + 1e-6 * want
+            assert np.all(err <= hard), f"unit {u}"
+            worst_hard = max(worst_hard, float((err / hard).max()))
+            worst_med = max(worst_med, float(np.median(err / want)))
+        else:
+            scale = np.maximum(want, G * np.sqrt(S_obs) * np.abs(v64).mean(axis=0))
+            assert np.all(err <= 1e-5 * scale), f"unit {u}"
+        got_vp = as_numpy(vp.reshape(L * U, S, ld_v)[u][:, :T_v].contiguous())
+        np.testing.assert_array_equal(got_vp, O.compact_keys(as_numpy(vf[u])[None], want_idx[u][None], dtn)[0])
+    assert worst_med <= 1e-3
+    print(f"config {cfg_id} value score on units {units}: worst median rel err {worst_med:.2e}, "
+          f"worst err / hard bound {worst_hard:.2e}", flush=True)
+
+    # decode over both pruned caches: prune the keys as the benchmark does, then one step per
+    # sampled layer, checked on the batch rows that hold sampled units
+    shape_k = thk.make_shape(L, B, N_q, N_kv, D, S, S_obs, T, 0, DT[dtn], 0)
+    score = torch.empty(L * U, D, dtype=torch.float32, device=DEV)
+    idx = torch.full((L * U, T), -1, dtype=torch.int16, device=DEV)
+    kp = torch.zeros(L, U, S, T, dtype=dt, device=DEV)
+    wsk = torch.empty(max(thk.thk_workspace_bytes(shape_k, thk.THK_OP_PRUNE), 16), dtype=torch.uint8, device=DEV)
+    thk.thk_prune(shape_k, q_obs, k, score, idx, kp, wsk)
+    del k, q_obs
+    shape_1 = thk.make_shape(1, B, N_q, N_kv, D, S, 1, T, 0, DT[dtn], 0)
+    wsd = torch.empty(max(thk.thk_workspace_bytes(shape_1, thk.THK_OP_DECODE), 16), dtype=torch.uint8, device=DEV)
+    out = torch.empty(B * N_q, D, dtype=dt, device=DEV)
+    worst = 0.0
+    for l in sorted({u // U for u in units})[:3]:
+        q, _, _ = synth.gen_decode(cfg_id, l, 0, DEV, **cfg)
+        sl = slice(l * U, (l + 1) * U)
+        thk.thk_decode_attn_kv(shape_1, q, kp[l], idx[sl], vp[l], idx_v[sl], T_v, ld_v, None, None, 0, 0, out, wsd)
+        torch.cuda.synchronize()
+        rows = sorted({(u % U) // N_kv for u in units if u // U == l})[:2]     # batch rows
+        kp_np = as_numpy(kp[l]).reshape(B, N_kv, S, T)[rows]
+        vp_np = as_numpy(vp[l][:, :, :T_v].contiguous()).reshape(B, N_kv, S, T_v)[rows]
+        ref = O.decode_attn_kv(as_numpy(q)[0][rows], kp_np, idx[sl].cpu().numpy().reshape(B, N_kv, T)[rows], vp_np,
+                               idx_v[sl].cpu().numpy().reshape(B, N_kv, T_v)[rows], dtn)
+        err = attn_rel_err(out.reshape(B, N_q, D)[rows].reshape(-1, D), ref.reshape(-1, D))
+        worst = max(worst, float(err.max()))
+    print(f"config {cfg_id}: attention over pruned keys and values, max rel err {worst:.3e}", flush=True)
+    assert worst <= ATTN_TOL[dtn]
