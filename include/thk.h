@@ -191,13 +191,13 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
  * multiple of 16, a single kernel does all three steps: a block takes 512 rows of
  * a unit (fewer for small calls), keeps them on chip while the unit's index list
  * is being decided, and compacts them from there, so K is read from memory once;
- * otherwise (and for units of more than 64 such blocks) the three kernels run one
+ * otherwise (and for units of more than 256 such blocks) the three kernels run one
  * after the other.  Scores agree with thk_score to fp64 summation order (the
  * last float bit can differ).  `score` may be NULL (then it lives in ws).
  * Environment (read per call, for experiments and tests): THK_PRUNE_PATH =
  * staged | fused | reread (the one-kernel form with the rows read twice),
- * THK_PRUNE_BLOCK_ROWS, THK_PRUNE_HOLD_ROWS, THK_PRUNE_SPIN_LIMIT,
- * THK_PRUNE_GROUP_MIB.
+ * THK_PRUNE_BLOCK_ROWS, THK_PRUNE_HOLD_ROWS, THK_PRUNE_MAX_BLOCKS,
+ * THK_PRUNE_SPIN_LIMIT, THK_PRUNE_GROUP_MIB.
  *   ws : THK_OP_PRUNE bytes.
  */
 thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,

@@ -126,10 +126,10 @@ long env_long(const char *name, long dflt) {
 
 struct FusedPlan { bool ok; int NB; int64_t RB; int hold; };
 
-// The fused kernel needs the flat K_pruned layout (dense rows, 16-byte aligned
-// units).  Its blocks take 512 rows each (measured best on MI355X) and the
-// blocks of a unit wait for each other, so units of more than 64 blocks (long
-// sequences spread over few units) go through the staged path instead.
+// The one-launch forms need the flat K_pruned layout (dense rows, 16-byte aligned units).
+// Their blocks take 512 rows each (measured best on MI355X; fewer for small calls) and the
+// blocks of a unit wait for each other; a unit may have up to 256 of them (above 64 they
+// arrive in two levels), longer sequences go through the staged path instead.
 FusedPlan fused_plan(const thk_shape *s) {
   FusedPlan p{false, 0, 0, 0};
   const char *path = getenv("THK_PRUNE_PATH");
@@ -154,7 +154,7 @@ FusedPlan fused_plan(const thk_shape *s) {
   if (!reread && (rb == 128 || rb == 256 || (rb == 512 && s->dtype == THK_BF16))) p.hold = (int)(rb / 128);
   const int64_t nb = ceil_div(s->S, rb);
   const bool forced = path != nullptr && (path[0] == 'f' || path[0] == 'r');   // regardless of block count
-  if (nb > (forced ? 256 : 64)) return p;
+  if (nb > (forced ? 256 : env_long("THK_PRUNE_MAX_BLOCKS", 256))) return p;
   p.RB = rb;
   p.NB = (int)nb;
   p.ok = units_of(s) * p.NB <= kMaxGrid;

@@ -37,6 +37,8 @@
 
 namespace thk {
 
+constexpr int kMaxGroups = 16;   // groups per unit in the two-level arrival
+
 struct PruneFusedArgs {
   const void *k, *q_obs;
   void *kp;
@@ -44,7 +46,10 @@ struct PruneFusedArgs {
   int16_t *idx;
   double *partial;        // [U][NB][128]
   double *qn;             // [U][128]   sum_g ||Q_obs,g[:, c]||
-  int *arrived;           // [U] blocks of the unit that have published their partial sums
+  int *arrived;           // [U] blocks (or groups) of the unit that have published their sums
+  int *arrived_g;         // [U][kMaxGroups] blocks of a group that have published (two-level form)
+  double *gpartial;       // [U][kMaxGroups][128] group sums (two-level form)
+  int32_t GS;             // blocks per group; 0 = one level
   uint32_t *idx_pub;      // [U][64]  the index list, two entries per word, for the waiting blocks
   unsigned char *done;    // [U * NB]
   int64_t S, RB;          // rows per unit, rows per block
@@ -80,6 +85,7 @@ __global__ __launch_bounds__(512) void k_prune_prep(PruneFusedArgs a) {
   const double tot = unit_query_norm<DT, 512>(a.q_obs, u, a.G, a.S_obs, red);
   if (threadIdx.x < kD) a.qn[(size_t)u * kD + threadIdx.x] = tot;
   if (threadIdx.x == 0) a.arrived[u] = 0;
+  if (a.GS > 0 && threadIdx.x < kMaxGroups) a.arrived_g[(size_t)u * kMaxGroups + threadIdx.x] = 0;
   if (threadIdx.x < kWave) a.idx_pub[(size_t)u * kWave + threadIdx.x] = 0u;
   for (int i = threadIdx.x; i < a.NB; i += 512) a.done[(size_t)u * a.NB + i] = 0;
 }
@@ -88,42 +94,72 @@ __global__ __launch_bounds__(512) void k_prune_prep(PruneFusedArgs a) {
 // and the bounded wait of the others.  s_part: the block's 128 column sums in LDS.  On return
 // s_idx holds the unit's index list, or the result is false: the block gives up and leaves its
 // rows to k_prune_repair.  All 256 threads must call.
+// Sum of n partial vectors (128 doubles each, consecutive) for channel tid % 128: the two halves
+// of the list are summed by two thread groups (eight loads in flight each) and added, first
+// half first.  The result is valid in the threads of the first group.  xch: 128 doubles of LDS.
+__device__ __forceinline__ double merge_partials(const double *base, int n, double *xch) {
+  const int tid = threadIdx.x;
+  const int c = tid & (kD - 1), half = tid >> 7;
+  const int b_mid = (n + 1) / 2;
+  const int b0 = half ? b_mid : 0, b1 = half ? n : b_mid;
+  const double *p = base + c;
+  double sum = 0.0;
+  for (int b = b0; b < b1; b += 8) {   // a short last batch re-reads its last entry, unused
+    double x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = pub_load_f64(p + (size_t)min(b + j, b1 - 1) * kD);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sum += (b + j < b1) ? x[j] : 0.0;
+  }
+  if (half) xch[c] = sum;
+  __syncthreads();
+  if (!half) sum += xch[c];
+  return sum;
+}
+
+// One arrival: thread 0 bumps the counter; true in every thread of the block that makes it `full`.
+__device__ __forceinline__ bool arrive(int *counter, int full, int *s_flag) {
+  if (threadIdx.x == 0) *s_flag = (atomicAdd(counter, 1) == full - 1);
+  __syncthreads();
+  const bool last = *s_flag != 0;
+  __syncthreads();   // everyone has read the flag before it is reused
+  return last;
+}
+
 __device__ __forceinline__ bool unit_index_list(const PruneFusedArgs &a, int64_t u, int64_t item,
                                                 double *s_part, float *s_sc, int16_t *s_idx,
                                                 int *s_flag) {
   const int tid = threadIdx.x;
   if (tid < kD) pub_store_f64(a.partial + (size_t)item * kD + tid, s_part[tid]);
   block_stores_done();
-  if (tid == 0) *s_flag = (atomicAdd(&a.arrived[u], 1) == a.NB - 1);
-  __syncthreads();
-  const bool last = *s_flag != 0;
-  __syncthreads();   // everyone has read the flag before the waiting path reuses it
+
+  // Units of many blocks arrive in two levels: the last block of a group of a.GS consecutive
+  // blocks merges the group's sums into one vector and arrives for the group, so that nobody
+  // ever has to walk more than a.GS or NB / a.GS vectors.
+  const double *src = a.partial + (size_t)u * a.NB * kD;
+  int n_src = a.NB;
+  bool last = true;
+  if (a.GS > 0) {
+    const int blk = (int)(item - u * a.NB);
+    const int g = blk / a.GS;
+    const int gsize = min(a.GS, a.NB - g * a.GS);
+    last = arrive(a.arrived_g + (size_t)u * kMaxGroups + g, gsize, s_flag);
+    if (last) {
+      const double gs = merge_partials(src + (size_t)g * a.GS * kD, gsize, s_part);
+      if (tid < kD) pub_store_f64(a.gpartial + ((size_t)u * kMaxGroups + g) * kD + tid, gs);
+      block_stores_done();
+      src = a.gpartial + (size_t)u * kMaxGroups * kD;
+      n_src = (a.NB + a.GS - 1) / a.GS;
+    }
+  }
+  if (last) last = arrive(a.arrived + u, n_src, s_flag);
 
   if (last) {
-    // merge the unit's partials in block order: the two halves of the block list are summed by
-    // two thread groups (eight loads in flight each) and added, first half first
-    {
-      const int c = tid & (kD - 1), half = tid >> 7;
-      const int b_mid = (a.NB + 1) / 2;
-      const int b0 = half ? b_mid : 0, b1 = half ? a.NB : b_mid;
-      const double *p = a.partial + (size_t)u * a.NB * kD + c;
-      double kss = 0.0;
-      for (int b = b0; b < b1; b += 8) {   // a short last batch re-reads its last entry, unused
-        double x[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) x[j] = pub_load_f64(p + (size_t)min(b + j, b1 - 1) * kD);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) kss += (b + j < b1) ? x[j] : 0.0;
-      }
-      double *xch = (double *)s_part;   // the block's own sums are published already
-      if (half) xch[c] = kss;
-      __syncthreads();
-      if (!half) {
-        kss += xch[c];
-        const float scf = (float)(a.qn[(size_t)u * kD + c] * sqrt(kss));
-        a.score[(size_t)u * kD + c] = scf;
-        s_sc[c] = scf;
-      }
+    const double kss = merge_partials(src, n_src, s_part);   // s_part: its sums are published already
+    if (tid < kD) {
+      const float scf = (float)(a.qn[(size_t)u * kD + tid] * sqrt(kss));
+      a.score[(size_t)u * kD + tid] = scf;
+      s_sc[tid] = scf;
     }
     __syncthreads();
     if (tid < kWave) select_wave(s_sc[tid], s_sc[tid + 64], a.T, s_idx, tid);
@@ -331,8 +367,15 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
   }
 }
 
+// blocks per group for a unit of NB blocks (0 = one-level arrival)
+static int group_size(int NB) { return NB > 64 ? (NB + kMaxGroups - 1) / kMaxGroups : 0; }
+
 size_t prune_fused_ws_bytes(int64_t U, int NB) {
   size_t b = (size_t)U * NB * kD * sizeof(double);   // partial
+  if (group_size(NB) > 0) {
+    b += (size_t)U * kMaxGroups * kD * sizeof(double);   // gpartial
+    b += (size_t)U * kMaxGroups * sizeof(int);           // arrived_g
+  }
   b += (size_t)U * kD * sizeof(double);              // qn
   b += (size_t)U * sizeof(int);                      // arrived
   b = (b + 15) & ~(size_t)15;
@@ -350,6 +393,12 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
   a.k = k; a.q_obs = q_obs; a.kp = kp; a.score = score; a.idx = idx;
   char *w = (char *)ws;
   a.partial = (double *)w; w += (size_t)U * NB * kD * sizeof(double);
+  a.GS = group_size(NB);
+  a.gpartial = nullptr; a.arrived_g = nullptr;
+  if (a.GS > 0) {
+    a.gpartial = (double *)w; w += (size_t)U * kMaxGroups * kD * sizeof(double);
+    a.arrived_g = (int *)w;   w += (size_t)U * kMaxGroups * sizeof(int);
+  }
   a.qn = (double *)w;      w += (size_t)U * kD * sizeof(double);
   a.arrived = (int *)w;    w += (size_t)U * sizeof(int);
   w = (char *)(((uintptr_t)w + 15) & ~(uintptr_t)15);

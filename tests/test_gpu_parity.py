@@ -200,6 +200,26 @@ def test_prune_fused_repeated_calls_on_one_workspace(monkeypatch):
     assert not torch.equal(first_idx[0], first_idx[1])
 
 
+@pytest.mark.parametrize("block_rows", [128, 64])
+def test_prune_two_level_arrival(block_rows, monkeypatch):
+    """Units of more than 64 row blocks: the blocks arrive group by group and the group sums are
+    merged a second time (102 blocks of 128 rows held on chip; 204 blocks of 64 rows read twice)."""
+    monkeypatch.setenv("THK_PRUNE_PATH", "fused")
+    monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", str(block_rows))
+    L, B, N_kv, G, S, S_obs, T = 1, 2, 2, 2, 13008, 32, 64
+    q_obs = _randn((L, B, N_kv * G, S_obs, D), "bf16", 41, 1.0)
+    k = _randn((L, B, N_kv, S, D), "bf16", 42, 1.0)
+    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T, 0, thk.THK_BF16, 0)
+    assert thk.thk_prune_is_fused(shape) == (2 if block_rows == 128 else 1)
+    score, idx, kp = gpu_prune(shape, q_obs, k)
+    o_sc, o_idx, o_kp = oracle_prune(q_obs, k, "bf16", T)
+    U = L * B * N_kv
+    rel = np.abs(score.cpu().numpy().astype(np.float64) - o_sc.reshape(U, D)) / o_sc.reshape(U, D)
+    assert rel.max() <= SCORE_TOL
+    check_idx_with_tie_rule(idx.cpu().numpy(), o_idx, o_sc, T)
+    np.testing.assert_array_equal(as_numpy(kp), O.compact_keys(as_numpy(k).reshape(U, S, D), idx.cpu().numpy(), "bf16"))
+
+
 @pytest.mark.parametrize("path", ["fused", "fused-small-blocks", "fused-no-wait", "hold-128", "hold-256", "hold-512",
                                   "hold-256-no-wait", "reread-256", "staged", "staged-groups"])
 @pytest.mark.parametrize("dtype,G,S,T,sigma", PRUNE_CASES)
