@@ -129,6 +129,54 @@ __device__ __forceinline__ double unit_query_norm(const void *__restrict__ q_obs
 }
 
 // ---------------------------------------------------------------------------
+// The same quantity, sum_g ||Q_obs,g[:, c]||_2, computed by ONE wavefront without LDS or
+// barriers: the wave loads 64 / LPR window rows per step (eight steps in flight), every lane
+// squares its VEC channels in fp64, the row groups are folded by shuffles, and lanes
+// 0 .. LPR-1 write the unit's 128 values to qn_u.
+// ---------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ void wave_query_norm(const void *__restrict__ q_obs, int64_t u, int G, int S_obs,
+                                                double *__restrict__ qn_u, int lane) {
+  using E = Elem<DT>;
+  constexpr int VEC = E::VEC, LPR = kD / VEC, RG = kWave / LPR, UNR = 8;
+  const int cl = lane % LPR, rg = lane / LPR;
+  const u32x4 *qbase = (const u32x4 *)((const char *)q_obs + (size_t)u * G * S_obs * kD * E::EB);
+  double tot[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) tot[v] = 0.0;
+  for (int g = 0; g < G; ++g) {
+    double qa[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) qa[v] = 0.0;
+    for (int i0 = 0; i0 < S_obs; i0 += RG * UNR) {
+      u32x4 r[UNR];
+#pragma unroll
+      for (int j = 0; j < UNR; ++j) {
+        const int i = i0 + j * RG + rg;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        r[j] = i < S_obs ? qbase[((size_t)g * S_obs + i) * LPR + cl] : zero;
+      }
+#pragma unroll
+      for (int j = 0; j < UNR; ++j) {
+        float f[VEC];
+        E::unpack(r[j], f);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) qa[v] += (double)f[v] * (double)f[v];
+      }
+    }
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) qa[v] += __shfl_xor(qa[v], off);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) tot[v] += sqrt(qa[v]);
+  }
+  if (rg == 0)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) qn_u[cl * VEC + v] = tot[v];
+}
+
+// ---------------------------------------------------------------------------
 // Top_T of 128 scores with one wavefront: two keys per lane, bitonic sort of
 // 64-bit keys (order-preserving score bits << 32 | 127 - channel, so that equal
 // scores rank the lower channel first and all keys are distinct), then every

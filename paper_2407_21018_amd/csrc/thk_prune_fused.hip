@@ -77,23 +77,20 @@ __device__ inline void block_stores_done() {
   __syncthreads();
 }
 
-// Per unit: query norms, and the counters / flags back to zero.
+// Per unit: query norms, and the counters, index-list words and done marks back to zero.  One
+// wavefront per unit (four units per block), nothing shared between them.
 template <int DT>
-__global__ __launch_bounds__(512) void k_prune_prep(PruneFusedArgs a) {
-  __shared__ double red[kQnHeads][512 / kWave][kD];
-  const int64_t u = blockIdx.x;
-  const double tot = unit_query_norm<DT, 512>(a.q_obs, u, a.G, a.S_obs, red);
-  if (threadIdx.x < kD) a.qn[(size_t)u * kD + threadIdx.x] = tot;
-  if (threadIdx.x == 0) a.arrived[u] = 0;
-  if (a.GS > 0 && threadIdx.x < kMaxGroups) a.arrived_g[(size_t)u * kMaxGroups + threadIdx.x] = 0;
-  if (threadIdx.x < kWave) a.idx_pub[(size_t)u * kWave + threadIdx.x] = 0u;
-  for (int i = threadIdx.x; i < a.NB; i += 512) a.done[(size_t)u * a.NB + i] = 0;
+__global__ __launch_bounds__(256) void k_prune_prep(PruneFusedArgs a, int64_t U) {
+  const int lane = threadIdx.x % kWave;
+  const int64_t u = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave;
+  if (u >= U) return;
+  wave_query_norm<DT>(a.q_obs, u, a.G, a.S_obs, a.qn + (size_t)u * kD, lane);
+  if (lane == 0) a.arrived[u] = 0;
+  if (a.GS > 0 && lane < kMaxGroups) a.arrived_g[(size_t)u * kMaxGroups + lane] = 0;
+  a.idx_pub[(size_t)u * kWave + lane] = 0u;
+  for (int i = lane; i < a.NB; i += kWave) a.done[(size_t)u * a.NB + i] = 0;
 }
 
-// Phases A' (publish, arrive), B (the last block of the unit merges, scores, selects, publishes)
-// and the bounded wait of the others.  s_part: the block's 128 column sums in LDS.  On return
-// s_idx holds the unit's index list, or the result is false: the block gives up and leaves its
-// rows to k_prune_repair.  All 256 threads must call.
 // Sum of n partial vectors (128 doubles each, consecutive) for channel tid % 128: the two halves
 // of the list are summed by two thread groups (eight loads in flight each) and added, first
 // half first.  The result is valid in the threads of the first group.  xch: 128 doubles of LDS.
@@ -438,9 +435,9 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
   }
   void *kargs[] = {(void *)&a};
   if (dtype == THK_BF16)
-    hipLaunchKernelGGL((k_prune_prep<THK_BF16>), gu, dim3(512), 0, st, a);
+    hipLaunchKernelGGL((k_prune_prep<THK_BF16>), dim3((unsigned)((U + 3) / 4)), dim3(256), 0, st, a, U);
   else
-    hipLaunchKernelGGL((k_prune_prep<THK_F32>), gu, dim3(512), 0, st, a);
+    hipLaunchKernelGGL((k_prune_prep<THK_F32>), dim3((unsigned)((U + 3) / 4)), dim3(256), 0, st, a, U);
   profile_mark(true, st);
   hipError_t le = hipLaunchKernel(main_fn, gi, dim3(256), kargs, lds_main, st);
   profile_mark(false, st);
