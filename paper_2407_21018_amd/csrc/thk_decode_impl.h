@@ -166,7 +166,7 @@ __device__ __forceinline__ int k_issue(u32x4 (&kr)[KB], const char *__restrict__
   const int last = (int)((kend - a0 + 15) >> 4) - 1;
   const char *p = kg + a0;
 #pragma unroll
-  for (int j = 0; j < KB; ++j) kr[j] = *(const u32x4 *)(p + (size_t)min(j * kWave + lane, last) * 16);
+  for (int j = 0; j < KB; ++j) kr[j] = ld_stream((const u32x4 *)(p + (size_t)min(j * kWave + lane, last) * 16));
   return (int)(kbeg - a0);
 }
 
@@ -194,12 +194,12 @@ __device__ __forceinline__ void v_issue(u32x4 (&vr)[NV], const u32x4 *__restrict
   using VS = VShape<DT, TR>;
   if (nrows == TR) {
 #pragma unroll
-    for (int i = 0; i < VS::NV; ++i) vr[i] = vg[(size_t)(b * VS::NV + i) * kWave + lane];
+    for (int i = 0; i < VS::NV; ++i) vr[i] = ld_stream(vg + (size_t)(b * VS::NV + i) * kWave + lane);
   } else {
     const int vrow = lane / VS::LPR, vcol = lane % VS::LPR;
 #pragma unroll
     for (int i = 0; i < VS::NV; ++i)
-      vr[i] = vg[(size_t)min((b * VS::NV + i) * VS::RPL + vrow, nrows - 1) * VS::LPR + vcol];
+      vr[i] = ld_stream(vg + (size_t)min((b * VS::NV + i) * VS::RPL + vrow, nrows - 1) * VS::LPR + vcol);
   }
 }
 

@@ -15,6 +15,14 @@ constexpr int kCUs = 256;   // compute units of an MI355X
 // (arrays of the uint4 class type are copied member-wise through memcpy and can end up in scratch).
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// A 16-byte load of data that is read once and never again (the K and V streams): the
+// non-temporal hint keeps it from allocating in the L2 and the memory-side cache, which on
+// MI355X lifts a pure read stream from ~6.3 to ~7.1 TB/s.
+__device__ __forceinline__ u32x4 ld_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+// ... and the matching store for data this launch will not read back (a few percent on mixed
+// read / write streams).
+__device__ __forceinline__ void st_stream(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+
 // ---- element access ------------------------------------------------------
 // A 16-byte chunk holds VEC elements; unpack() widens them to float exactly.
 template <int DT> struct Elem;

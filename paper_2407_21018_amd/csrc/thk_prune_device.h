@@ -14,7 +14,9 @@ namespace thk {
 // exact in fp32; fp32 chains are UNR terms long and are then folded into fp64
 // accumulators, which carry every later merge.  red: LDS, 4 x 128 doubles.
 // ---------------------------------------------------------------------------
-template <int DT, int P>
+// STREAM: the rows are not read again soon (non-temporal loads); the one-launch prune that
+// re-reads its rows for the compaction wants them cached instead.
+template <int DT, int P, bool STREAM = true>
 __device__ __forceinline__ void colsum_block(const u32x4 *__restrict__ base, int64_t s0, int64_t s1,
                                              double *__restrict__ out, double (*red)[kD]) {
   using E = Elem<DT>;
@@ -31,7 +33,7 @@ __device__ __forceinline__ void colsum_block(const u32x4 *__restrict__ base, int
     for (int j = 0; j < UNR; ++j) {
       const int64_t row = s + (int64_t)j * RPB;
       const u32x4 zero = {0u, 0u, 0u, 0u};
-      r[j] = row < s1 ? base[row * LPR + cl] : zero;
+      r[j] = row >= s1 ? zero : STREAM ? ld_stream(base + row * LPR + cl) : base[row * LPR + cl];
     }
     float facc[VEC];
 #pragma unroll
@@ -275,7 +277,7 @@ __device__ __forceinline__ void compact_emit_tile(const u32x4 *tile, u32x4 *__re
       w.x = tl[offs.x & 0xffffu]; w.y = tl[offs.x >> 16];
       w.z = tl[offs.y & 0xffffu]; w.w = tl[offs.y >> 16];
     }
-    o[c] = w;
+    st_stream(o + c, w);
   }
 }
 
@@ -295,7 +297,7 @@ __device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, u32x
     const u32x4 *tsrc = src + (size_t)r0 * CPR;
     const int cmax = nr * CPR - 1;
 #pragma unroll
-    for (int j = 0; j < NLD; ++j) r[j] = tsrc[min(j * kWave + lane, cmax)];
+    for (int j = 0; j < NLD; ++j) r[j] = ld_stream(tsrc + min(j * kWave + lane, cmax));
 #pragma unroll
     for (int j = 0; j < NLD; ++j) tile[j * kWave + lane] = r[j];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

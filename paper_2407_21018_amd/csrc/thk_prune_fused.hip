@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   const int64_t s1 = min(a.S, s0 + a.RB);
   const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
 
-  colsum_block<DT, 2>(src, s0, s1, s_part, red);
+  colsum_block<DT, 2, false>(src, s0, s1, s_part, red);
   __syncthreads();
   if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag)) return;
 
@@ -268,7 +268,7 @@ void k_prune_onepass(PruneFusedArgs a) {
     for (int j = 0; j < NLD; ++j) {
       const u32x4 zero = {0u, 0u, 0u, 0u};
       // chunks past a ragged tile's end repeat its last chunk (in bounds; excluded below)
-      r[n][j] = nr > 0 ? tsrc[min(j * kWave + lane, cmax)] : zero;
+      r[n][j] = nr > 0 ? ld_stream(tsrc + min(j * kWave + lane, cmax)) : zero;
     }
   }
 

@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256, 2) void k_value_attn_bf16(ValueAttnArgs a) {
       const int p = (q & 1) * (NP / 2) + pp;
       int64_t gr = k0 + (int64_t)c * CR + p * 16 + srow;
       gr = gr < S ? gr : S - 1;   // rows past the end repeat the last one; their weights are zero
-      const u32x4 x = *(const u32x4 *)(g + gr * (kD * 2) + scol);
+      const u32x4 x = ld_stream((const u32x4 *)(g + gr * (kD * 2) + scol));
       if (q < 2) pk[p] = x; else pv[p] = x;
     }
   };
