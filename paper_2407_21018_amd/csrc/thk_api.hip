@@ -88,7 +88,7 @@ Split decode_split(const thk_shape *s) {
     // pieces per unit, each at least 256 rows; big calls still get two pieces per unit so
     // that the last blocks to finish are short
     n = 1;
-    while ((int64_t)n * 2 * wgs <= (int64_t)kCUs * 4) n *= 2;
+    while ((int64_t)n * 2 * wgs <= (int64_t)kCUs * 4 && n < 64) n *= 2;   // the merge grows with n
     if (n == 1 && s->S >= 2048) n = 2;
     const int64_t cap = ceil_div(s->S, 256);
     if (n > cap) n = (int)cap;
