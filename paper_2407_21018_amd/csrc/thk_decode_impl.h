@@ -400,11 +400,11 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   float *mrg = (float *)(qfp + GT * (kQS / 2));  // [4][GT][130] per-wave states for the final merge
   char *wbase = (char *)(mrg + 4 * GT * (kD + 2));
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-  const int wstride = kbuf_bytes + GT * TR * 4 + (VP ? kbuf_bytes : 0);
+  const int wstride = kbuf_bytes + GT * TR * 4;
   char *kbuf = wbase + (size_t)wave * wstride;
   float *ps = (float *)(kbuf + kbuf_bytes);
   VPruned vpd;
-  vpd.vbuf = (char *)(ps + GT * TR);
+  vpd.vbuf = kbuf;   // the key bytes of a tile are consumed before its value bytes are staged
   vpd.shift = 0;
   vpd.ld = a.ld_v;
   {
@@ -605,8 +605,7 @@ inline hipError_t decode_launch_one(const DecodeArgs &a, int groups, hipStream_t
   int kbuf = KB * kWave * 16;                      // every staged chunk has an LDS slot
   const int tailbuf = kTailRows * kD * eb;
   if (kbuf < tailbuf) kbuf = tailbuf;
-  const size_t lds = (size_t)(3 * GT * kQS + 4 * GT * (kD + 2)) * 4 +
-                     4 * ((size_t)kbuf * (VP ? 2 : 1) + GT * TR * 4);
+  const size_t lds = (size_t)(3 * GT * kQS + 4 * GT * (kD + 2)) * 4 + 4 * ((size_t)kbuf + GT * TR * 4);
   const dim3 grid((unsigned)(a.units * groups * a.n_split)), block(256);
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void *)k_decode<DT, GT, RA, KB, TR, WPE, VP>,
@@ -641,7 +640,9 @@ hipError_t decode_launch_gt(const DecodeArgs &a, int groups, hipStream_t st) {
   }
   constexpr int KBN = (DT == THK_BF16) ? 5 : 10;   // T <= 79
   constexpr int KBW = (DT == THK_BF16) ? 9 : 17;   // up to ld_keep = 128
-  if (p.kb <= KBN) return decode_launch_ra<DT, GT, KBN, TR, (VP ? 3 : (GT <= 2 ? 4 : 3)), VP>(a, p.ra, groups, st);
+  // fp32 with pruned values stages twice as many registers: three waves per SIMD there
+  if (p.kb <= KBN)
+    return decode_launch_ra<DT, GT, KBN, TR, ((GT <= 2 && !(VP && DT == THK_F32)) ? 4 : 3), VP>(a, p.ra, groups, st);
   if (p.kb <= KBW) return decode_launch_ra<DT, GT, KBW, TR, (VP ? 2 : 3), VP>(a, p.ra, groups, st);
   return hipErrorInvalidValue;
 }
