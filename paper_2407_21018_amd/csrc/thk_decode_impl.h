@@ -383,9 +383,10 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
 // WPE: resident waves per SIMD the register budget is set for.
 // VP = 1: the value rows of the pruned segment hold only the T_v kept channels (a.v is
 // V_pruned with rows a.ld_v elements apart, a.idx_v lists the channels).  Their bytes are staged
-// like the key bytes (KB chunks per lane, the class is chosen for the wider of the two) and
-// each lane accumulates 4 kept channels; at the end the sums are scattered to their channels.
-// The tail keeps full-width value rows.
+// like the key bytes (KB chunks per lane, the class is chosen for the wider of the two), into the
+// same wave-private LDS slab once the tile's key bytes have been consumed, and each lane
+// accumulates 4 kept channels; at the end the sums are scattered to their channels.  The tail
+// keeps full-width value rows.
 template <int DT, int GT, int RA, int KB, int TR, int WPE, int VP = 0>
 __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, int kbuf_bytes) {
   using E = Elem<DT>;
