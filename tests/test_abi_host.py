@@ -195,3 +195,25 @@ def test_prune_plan_by_shape(monkeypatch):
     assert thk.thk_prune_is_fused(cfg2) == 1
     monkeypatch.setenv("THK_PRUNE_PATH", "staged")
     assert thk.thk_prune_is_fused(cfg2) == 0
+
+
+def test_plain_c_program_uses_the_boundary(tmp_path):
+    """thk.h is a C header and libthk.so a C library: a gcc-built program with no C++ and no
+    Python in it includes the one and links the other."""
+    import subprocess
+    exe = tmp_path / "abi_host_check"
+    libdir = os.path.dirname(thk.lib_path())
+    subprocess.check_call(["gcc", "-std=c11", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "c", "abi_host_check.c"), "-o", str(exe),
+                           "-L", libdir, "-lthk", f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert "abi host check ok" in out.stdout
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                         text=True, timeout=120)
+    assert out.returncode == 2 and "ONE GPU" in out.stderr
