@@ -33,6 +33,8 @@
 // its way to memory.  The index list needs no such ordering: each of its 32-bit
 // words carries its own validity mark, the waiting blocks poll the words
 // themselves, and k_prune_prep clears them before every call.
+#include <stdlib.h>
+
 #include "thk_prune_device.h"
 
 namespace thk {
@@ -50,6 +52,9 @@ struct PruneFusedArgs {
   int *arrived_g;         // [U][kMaxGroups] blocks of a group that have published (two-level form)
   double *gpartial;       // [U][kMaxGroups][128] group sums (two-level form)
   int32_t GS;             // blocks per group; 0 = one level
+  // graded start of a short launch's first round: block `item` < stagger_blocks of unit u first
+  // sleeps (u % stagger_units) * stagger_ticks times 64 cycles
+  int32_t stagger_blocks, stagger_units, stagger_ticks;
   uint32_t *idx_pub;      // [U][64]  the index list, two entries per word, for the waiting blocks
   unsigned char *done;    // [U * NB]
   int64_t S, RB;          // rows per unit, rows per block
@@ -257,6 +262,16 @@ void k_prune_onepass(PruneFusedArgs a) {
   auto tile_row0 = [&](int n) { return s0 + (int64_t)(4 * n + wave) * TR; };
   auto tile_rows = [&](int n, int64_t hi) { return (int)max((int64_t)0, min((int64_t)TR, hi - tile_row0(n))); };
 
+  // A launch of only a few rounds of resident blocks would run in lock-step (everybody loads,
+  // everybody waits for the index lists, everybody stores).  The first round's units therefore
+  // start one after the other, a unit's transfer time apart; the later rounds inherit the
+  // spacing because a unit's blocks leave, and their successors start, together.
+  if (item < a.stagger_blocks) {
+    int ticks = (int)(u % a.stagger_units) * a.stagger_ticks;
+    for (; ticks >= 127; ticks -= 127) __builtin_amdgcn_s_sleep(127);
+    for (; ticks >= 16; ticks -= 16) __builtin_amdgcn_s_sleep(16);
+  }
+
   // ---- load: every chunk of the block's rows is in flight at once ----------------------------
   u32x4 r[NTW][NLD];
 #pragma unroll
@@ -387,10 +402,27 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
                               int hold, int spin_limit, hipStream_t st) {
   clear_stale_hip_error();
   PruneFusedArgs a;
+  const int eb = dtype == THK_BF16 ? 2 : 4;
   a.k = k; a.q_obs = q_obs; a.kp = kp; a.score = score; a.idx = idx;
   char *w = (char *)ws;
   a.partial = (double *)w; w += (size_t)U * NB * kD * sizeof(double);
   a.GS = group_size(NB);
+  a.stagger_blocks = 0; a.stagger_units = 1; a.stagger_ticks = 0;
+  if (hold != 0) {
+    // resident blocks: 3 per compute unit for 512-row blocks, 4 otherwise
+    const int64_t resident = (int64_t)kCUs * (hold == 4 ? 3 : 4);
+    const int64_t total = U * NB;
+    const int64_t res_units = resident / NB;
+    double ns = -1.0;
+    if (const char *e = getenv("THK_PRUNE_STAGGER_NS")) ns = atof(e);
+    else if (res_units >= 2 && total >= 2 * resident && total <= 12 * resident)
+      ns = (double)S * kD * eb * 1.5 / 5.7e3;     // a unit's rows in and compacted rows out at 5.7 TB/s
+    if (ns > 0.0 && res_units >= 2) {
+      a.stagger_blocks = (int32_t)(res_units * NB);
+      a.stagger_units = (int32_t)res_units;
+      a.stagger_ticks = (int32_t)(ns * 2.4 / 64.0) + 1;   // 2.4 GHz, s_sleep counts 64-cycle ticks
+    }
+  }
   a.gpartial = nullptr; a.arrived_g = nullptr;
   if (a.GS > 0) {
     a.gpartial = (double *)w; w += (size_t)U * kMaxGroups * kD * sizeof(double);
@@ -402,7 +434,6 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
   a.idx_pub = (uint32_t *)w; w += (size_t)U * kWave * sizeof(uint32_t);
   a.done = (unsigned char *)w;
   a.S = S; a.S_keep = S_keep; a.kp_unit_rows = kp_unit_rows; a.RB = RB; a.T = T; a.G = G; a.S_obs = S_obs; a.NB = NB; a.spin_limit = spin_limit;
-  const int eb = dtype == THK_BF16 ? 2 : 4;
   const size_t lds = 2048 + 4 * (size_t)kCompactTileRows * kD * eb;
   const dim3 gu((unsigned)U), gi((unsigned)(U * NB));
   // hold == 0: the re-reading form; otherwise RB == 128 * hold and the rows are held on chip
