@@ -136,11 +136,43 @@ __device__ __forceinline__ double unit_query_norm(const void *__restrict__ q_obs
 // squares its VEC channels in fp64, the row groups are folded by shuffles, and lanes
 // 0 .. LPR-1 write the unit's 128 values to qn_u.
 // ---------------------------------------------------------------------------
+// Sum over the window rows of one head of the squared entries, per channel, in every lane that
+// owns the channel (lane % LPR picks VEC consecutive channels).
+template <int DT>
+__device__ __forceinline__ void wave_head_sumsq(const u32x4 *__restrict__ qhead, int S_obs, int lane,
+                                                double (&qa)[Elem<DT>::VEC]) {
+  using E = Elem<DT>;
+  constexpr int VEC = E::VEC, LPR = kD / VEC, RG = kWave / LPR, UNR = 8;
+  const int cl = lane % LPR, rg = lane / LPR;
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) qa[v] = 0.0;
+  for (int i0 = 0; i0 < S_obs; i0 += RG * UNR) {
+    u32x4 r[UNR];
+#pragma unroll
+    for (int j = 0; j < UNR; ++j) {
+      const int i = i0 + j * RG + rg;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      r[j] = i < S_obs ? qhead[(size_t)i * LPR + cl] : zero;
+    }
+#pragma unroll
+    for (int j = 0; j < UNR; ++j) {
+      float f[VEC];
+      E::unpack(r[j], f);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) qa[v] += (double)f[v] * (double)f[v];
+    }
+  }
+#pragma unroll
+  for (int off = LPR; off < kWave; off <<= 1)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) qa[v] += __shfl_xor(qa[v], off);
+}
+
 template <int DT>
 __device__ __forceinline__ void wave_query_norm(const void *__restrict__ q_obs, int64_t u, int G, int S_obs,
                                                 double *__restrict__ qn_u, int lane) {
   using E = Elem<DT>;
-  constexpr int VEC = E::VEC, LPR = kD / VEC, RG = kWave / LPR, UNR = 8;
+  constexpr int VEC = E::VEC, LPR = kD / VEC;
   const int cl = lane % LPR, rg = lane / LPR;
   const u32x4 *qbase = (const u32x4 *)((const char *)q_obs + (size_t)u * G * S_obs * kD * E::EB);
   double tot[VEC];
@@ -148,32 +180,45 @@ __device__ __forceinline__ void wave_query_norm(const void *__restrict__ q_obs, 
   for (int v = 0; v < VEC; ++v) tot[v] = 0.0;
   for (int g = 0; g < G; ++g) {
     double qa[VEC];
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) qa[v] = 0.0;
-    for (int i0 = 0; i0 < S_obs; i0 += RG * UNR) {
-      u32x4 r[UNR];
-#pragma unroll
-      for (int j = 0; j < UNR; ++j) {
-        const int i = i0 + j * RG + rg;
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        r[j] = i < S_obs ? qbase[((size_t)g * S_obs + i) * LPR + cl] : zero;
-      }
-#pragma unroll
-      for (int j = 0; j < UNR; ++j) {
-        float f[VEC];
-        E::unpack(r[j], f);
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) qa[v] += (double)f[v] * (double)f[v];
-      }
-    }
-#pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1)
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) qa[v] += __shfl_xor(qa[v], off);
+    wave_head_sumsq<DT>(qbase + (size_t)g * S_obs * LPR, S_obs, lane, qa);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) tot[v] += sqrt(qa[v]);
   }
   if (rg == 0)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) qn_u[cl * VEC + v] = tot[v];
+}
+
+// The same for a unit with several query heads, by a block of NW wavefronts: NW heads at a time,
+// one per wave, their norms handed to wave 0 through LDS and added there in head order (the
+// result equals wave_query_norm's bit for bit).  hn: NW * 128 doubles of LDS.
+template <int DT, int NW>
+__device__ __forceinline__ void block_query_norm(const void *__restrict__ q_obs, int64_t u, int G, int S_obs,
+                                                 double *__restrict__ qn_u, double *hn) {
+  using E = Elem<DT>;
+  constexpr int VEC = E::VEC, LPR = kD / VEC;
+  const int lane = threadIdx.x % kWave, w = threadIdx.x / kWave;
+  const int cl = lane % LPR, rg = lane / LPR;
+  const u32x4 *qbase = (const u32x4 *)((const char *)q_obs + (size_t)u * G * S_obs * kD * E::EB);
+  double tot[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) tot[v] = 0.0;
+  for (int g0 = 0; g0 < G; g0 += NW) {
+    if (g0 + w < G) {
+      double qa[VEC];
+      wave_head_sumsq<DT>(qbase + (size_t)(g0 + w) * S_obs * LPR, S_obs, lane, qa);
+      if (rg == 0)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) hn[w * kD + cl * VEC + v] = sqrt(qa[v]);
+    }
+    __syncthreads();
+    if (w == 0 && rg == 0)
+      for (int j = 0; j < NW && g0 + j < G; ++j)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) tot[v] += hn[j * kD + cl * VEC + v];
+    __syncthreads();
+  }
+  if (w == 0 && rg == 0)
 #pragma unroll
     for (int v = 0; v < VEC; ++v) qn_u[cl * VEC + v] = tot[v];
 }

@@ -82,14 +82,26 @@ __device__ inline void block_stores_done() {
   __syncthreads();
 }
 
-// Per unit: query norms, and the counters, index-list words and done marks back to zero.  One
-// wavefront per unit (four units per block), nothing shared between them.
+// Per unit: query norms, and the counters, index-list words and done marks back to zero.  With
+// one query head per unit a wavefront takes a unit (four units per block, nothing shared between
+// them); with several, a block takes a unit and its waves share the heads.
 template <int DT>
 __global__ __launch_bounds__(256) void k_prune_prep(PruneFusedArgs a, int64_t U) {
+  __shared__ double hn[4 * kD];
   const int lane = threadIdx.x % kWave;
-  const int64_t u = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave;
-  if (u >= U) return;
-  wave_query_norm<DT>(a.q_obs, u, a.G, a.S_obs, a.qn + (size_t)u * kD, lane);
+  int64_t u;
+  bool clear;
+  if (a.G > 1) {
+    u = blockIdx.x;
+    block_query_norm<DT, 4>(a.q_obs, u, a.G, a.S_obs, a.qn + (size_t)u * kD, hn);
+    clear = threadIdx.x < kWave;
+  } else {
+    u = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave;
+    if (u >= U) return;
+    wave_query_norm<DT>(a.q_obs, u, 1, a.S_obs, a.qn + (size_t)u * kD, lane);
+    clear = true;
+  }
+  if (!clear) return;
   if (lane == 0) a.arrived[u] = 0;
   if (a.GS > 0 && lane < kMaxGroups) a.arrived_g[(size_t)u * kMaxGroups + lane] = 0;
   a.idx_pub[(size_t)u * kWave + lane] = 0u;
@@ -465,10 +477,11 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
     if (e != hipSuccess) return e;
   }
   void *kargs[] = {(void *)&a};
+  const unsigned prep_blocks = (unsigned)(a.G > 1 ? U : (U + 3) / 4);
   if (dtype == THK_BF16)
-    hipLaunchKernelGGL((k_prune_prep<THK_BF16>), dim3((unsigned)((U + 3) / 4)), dim3(256), 0, st, a, U);
+    hipLaunchKernelGGL((k_prune_prep<THK_BF16>), dim3(prep_blocks), dim3(256), 0, st, a, U);
   else
-    hipLaunchKernelGGL((k_prune_prep<THK_F32>), dim3((unsigned)((U + 3) / 4)), dim3(256), 0, st, a, U);
+    hipLaunchKernelGGL((k_prune_prep<THK_F32>), dim3(prep_blocks), dim3(256), 0, st, a, U);
   profile_mark(true, st);
   hipError_t le = hipLaunchKernel(main_fn, gi, dim3(256), kargs, lds_main, st);
   profile_mark(false, st);
