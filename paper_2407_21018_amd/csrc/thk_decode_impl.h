@@ -379,6 +379,37 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
   wave_sync_lds();   // ps and kbuf are rewritten by the next tile
 }
 
+// Merge of the four waves' softmax states (mrg: [GT][130] floats per wave, wstride floats from
+// wave to wave, in LDS, complete and visible to the block): the output row of every query head,
+// or this split's state record.
+template <int DT, int GT>
+__device__ __forceinline__ void block_merge_store(const float *mrg, int wstride, const DecodeArgs &a,
+                                                  int64_t bn0, int sp) {
+  using E = Elem<DT>;
+  for (int o = threadIdx.x; o < GT * kD; o += 256) {
+    const int g = o / kD, c = o % kD;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, mrg[(size_t)w * wstride + g * (kD + 2)]);
+    float Lsum = 0.f, A = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float *rec = mrg + (size_t)w * wstride + g * (kD + 2);
+      const float wgt = rec[0] == -INFINITY ? 0.f : exp2f(rec[0] - M);
+      Lsum = fmaf(rec[1], wgt, Lsum);
+      A = fmaf(rec[2 + c], wgt, A);
+    }
+    const size_t bn = (size_t)(bn0 + g);
+    if (a.n_split == 1) {
+      E::store1(a.out, bn * kD + c, A / Lsum);
+    } else {
+      float *rec = a.ws + (bn * a.n_split + sp) * (kD + 2);
+      rec[2 + c] = A;
+      if (c == 0) { rec[0] = M; rec[1] = Lsum; }
+    }
+  }
+}
+
 // KB: 16-byte K chunks a lane may have to stage for one TR-row pruned tile.
 // WPE: resident waves per SIMD the register budget is set for.
 // VP = 1: the value rows of the pruned segment hold only the T_v kept channels (a.v is
@@ -556,29 +587,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   }
   __syncthreads();
 
-  // ---- merge the four waves; write the output or this split's state --------
-  for (int o = tid; o < GT * kD; o += 256) {
-    const int g = o / kD, c = o % kD;
-    float M = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, mrg[(size_t)(w * GT + g) * (kD + 2)]);
-    float Lsum = 0.f, A = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float *rec = mrg + (size_t)(w * GT + g) * (kD + 2);
-      const float wgt = rec[0] == -INFINITY ? 0.f : exp2f(rec[0] - M);
-      Lsum = fmaf(rec[1], wgt, Lsum);
-      A = fmaf(rec[2 + c], wgt, A);
-    }
-    const size_t bn = (size_t)(bn0 + g);
-    if (a.n_split == 1) {
-      E::store1(a.out, bn * kD + c, A / Lsum);
-    } else {
-      float *rec = a.ws + (bn * a.n_split + sp) * (kD + 2);
-      rec[2 + c] = A;
-      if (c == 0) { rec[0] = M; rec[1] = Lsum; }
-    }
-  }
+  block_merge_store<DT, GT>(mrg, GT * (kD + 2), a, bn0, sp);
 }
 
 // ---- host side: pick the instantiation for a shape --------------------------

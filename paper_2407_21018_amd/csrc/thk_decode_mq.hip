@@ -1,0 +1,331 @@
+// Decode attention over the pruned key cache for bf16 caches whose KV heads serve four query
+// heads each (Sec. 3.3, Fig. 2; attention formula of Sec. 3.2) -- gfx950, wave64.
+//
+// With four query heads per key row the two products of a tile are skinny matrix products
+// (4 x T by T x 32, then 4 x 32 by 32 x 128) and go to the matrix cores as batches of 4 x 4
+// blocks (v_mfma_f32_4x4x4_16B_bf16: 16 independent blocks per instruction; lane 4 b + x holds
+// row x of A_b, column x of B_b and column x of D_b).  Work split, tile size, staging of the key
+// bytes, split records and the final merge are those of k_decode; what differs is one tile:
+//
+//   logits   block b <-> key rows 4 (b % 8) .. + 3 and one half (b / 8) of the kept channels.
+//            A_b = four key rows x four channels, 8 bytes per lane straight from the staged
+//            bytes in LDS; B_b = the four query heads' same four channels; D_b[i][j] is the
+//            partial logit of row i and head j.  The blocks of one half walk the channel chunks
+//            in rotated order so that the row reads spread over the LDS banks; the two halves
+//            are added with one cross-half exchange.
+//   softmax  lane 4 b + j owns head j and four rows: the running maximum is a per-lane scalar,
+//            reduced over the lanes of equal j.  A probability is split into two bf16 terms
+//            (p = hi + lo, exact to 2^-16), so that the matrix product loses nothing against
+//            the fp32 arithmetic of the other kernels.
+//   values   block b <-> output channels 4 b .. + 3 (two instructions cover 128 channels).
+//            A_b = the four heads' probabilities of four rows, the same for every block (read
+//            back from a 512-byte LDS line); B_b = four value rows x four channels, which is a
+//            transposed read of the row-major value tile: ds_read_b64_tr_b16 out of LDS, where
+//            the tile is staged with the two 128-byte halves of odd rows swapped (the four rows
+//            of one read then cover all banks).  D_b[i][j] accumulates head i, channel 4 b + j:
+//            lane l ends with channels l and 64 + l of all four heads.
+#include <stdlib.h>
+
+#include "thk_decode_impl.h"
+
+namespace thk {
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMqRows = 32;                       // rows per tile
+constexpr int kMqVBytes = kMqRows * kD * 2;       // a value tile in LDS
+constexpr int kMqVChunks = kMqVBytes / 16 / kWave;   // 16-byte value chunks per lane and tile
+
+struct MqState {
+  float m;        // running maximum of this lane's head (lane % 4), log2 domain
+  float l;        // this lane's share of its head's probability sum
+  f32x4 acc[2];   // acc[h][i]: head i, channel 64 h + lane
+};
+
+__device__ __forceinline__ f32x4 mfma4(s16x4 a, s16x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, c, 0, 0, 0);
+}
+
+// x combined over the lanes of equal lane % 4 inside each half of the wave (rotations by 4 and 8
+// inside the 16-lane rows, then the neighbouring row).
+template <bool MAX>
+__device__ __forceinline__ float quad_column_reduce(float x) {
+  float y = dpp_move<0x124, 0xf>(x, x);   // row_ror:4
+  x = MAX ? max_nn(x, y) : x + y;
+  y = dpp_move<0x128, 0xf>(x, x);         // row_ror:8
+  x = MAX ? max_nn(x, y) : x + y;
+  y = __shfl_xor(x, 16);
+  return MAX ? max_nn(x, y) : x + y;
+}
+
+// Value rows of a tile into registers: chunk j * 64 + lane is 16 bytes of row 4 j + lane / 16.
+// Rows past a ragged tile's end re-read its last row (their probability is 0).
+__device__ __forceinline__ void mq_v_issue(u32x4 (&vr)[kMqVChunks], const u32x4 *__restrict__ vg, int nrows,
+                                           int lane) {
+  const int rsub = lane >> 4, col = lane & 15;
+#pragma unroll
+  for (int j = 0; j < kMqVChunks; ++j) vr[j] = ld_stream(vg + (size_t)min(4 * j + rsub, nrows - 1) * 16 + col);
+}
+
+// ... and into the slab: rows 256 bytes apart, the two halves of odd rows swapped.
+__device__ __forceinline__ void mq_v_commit(const u32x4 (&vr)[kMqVChunks], char *slab, int lane) {
+  const int rsub = lane >> 4, col = (lane & 15) ^ ((rsub & 1) << 3);
+#pragma unroll
+  for (int j = 0; j < kMqVChunks; ++j) *(u32x4 *)(slab + (4 * j + rsub) * 256 + col * 16) = vr[j];
+}
+
+// Logits of a tile whose key bytes are in the slab.  nch: 4-channel chunks per row; qrow: this
+// lane's head as packed bf16, zero from chunk nch on.  Returns, in both halves of the wave, the
+// dot products of rows 4 ((lane / 4) % 8) + r, r = 0 .. 3, with head lane % 4.
+__device__ __forceinline__ f32x4 mq_logits(const char *slab, int shift, int nrows, int nch, int pitch_bytes,
+                                           const uint32_t *qrow, int lane) {
+  const int b = lane >> 2, x = lane & 3, half = b >> 3, bb = b & 7;
+  const char *rowp = slab + shift + min(4 * bb + x, nrows - 1) * pitch_bytes;
+  const int nst = (nch + 1) >> 1;          // chunks per half = matrix instructions
+  int rel = bb % nst;
+  f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+  auto step = [&](f32x4 &d) {
+    const int c = half * nst + rel;
+    // a chunk past the row's end: the row's first chunk against the zero chunk of the query
+    const bool valid = c < nch;
+    const s16x4 ka = *(const s16x4 *)(rowp + (valid ? c : 0) * 8);
+    const s16x4 qb = *(const s16x4 *)((const char *)qrow + (valid ? c : nch) * 8);
+    d = mfma4(ka, qb, d);
+    rel = rel + 1 == nst ? 0 : rel + 1;
+  };
+  int ks = 0;
+  for (; ks + 2 <= nst; ks += 2) { step(d0); step(d1); }
+  if (ks < nst) step(d0);
+  f32x4 d;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const float t = d0[r] + d1[r];
+    d[r] = t + __shfl_xor(t, 32);
+  }
+  return d;
+}
+
+// Running softmax over the tile's logits; the probabilities go to pline as two bf16 terms:
+// bytes [0, 256) the leading terms, [256, 512) the remainders, entry 4 ks + head holding the
+// four rows 4 ks .. 4 ks + 3.
+__device__ __forceinline__ void mq_softmax(const f32x4 &d, int nrows, float scale, MqState &st, char *pline,
+                                           int lane) {
+  const int bb = (lane >> 2) & 7;
+  float zz[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) zz[r] = 4 * bb + r < nrows ? d[r] * scale : -INFINITY;
+  const float mx = quad_column_reduce<true>(max_nn(max_nn(zz[0], zz[1]), max_nn(zz[2], zz[3])));
+  const float m_new = max_nn(st.m, mx);             // finite: the tile has at least one row
+  if (__builtin_amdgcn_ballot_w64(m_new != st.m) != 0) {   // rare after the first tiles
+    const float corr = __builtin_amdgcn_exp2f(st.m - m_new);
+    st.l *= corr;
+    st.m = m_new;
+    // every lane carries channels of all four heads: the heads' factors sit in the lane's quad
+    const float c0 = dpp_move<0x00, 0xf>(corr, corr), c1 = dpp_move<0x55, 0xf>(corr, corr);
+    const float c2 = dpp_move<0xAA, 0xf>(corr, corr), c3 = dpp_move<0xFF, 0xf>(corr, corr);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      st.acc[h][0] *= c0; st.acc[h][1] *= c1; st.acc[h][2] *= c2; st.acc[h][3] *= c3;
+    }
+  }
+  uint32_t hi[4], lo[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const float p = __builtin_amdgcn_exp2f(zz[r] - m_new);
+    st.l += p;
+    hi[r] = __float_as_uint(p) & 0xffff0000u;
+    lo[r] = __float_as_uint(p - __uint_as_float(hi[r])) & 0xffff0000u;
+  }
+  // the lower half of the wave writes the leading terms, the upper half the remainders
+  const bool up = lane >= 32;
+  uint2 w;
+  w.x = up ? ((lo[0] >> 16) | lo[1]) : ((hi[0] >> 16) | hi[1]);
+  w.y = up ? ((lo[2] >> 16) | lo[3]) : ((hi[2] >> 16) | hi[3]);
+  *(uint2 *)(pline + lane * 8) = w;
+}
+
+// acc += P . V for the tile whose value rows are in the slab and probabilities in pline.
+__device__ __forceinline__ void mq_values(const char *slab, const char *pline, int nrows, MqState &st, int lane) {
+  const int x = lane & 3, grp = lane >> 4, j = lane & 15, r = j >> 2, seg = j & 3;
+  const int cc = 2 * grp + (seg >> 1), swz = (r & 1) << 3;
+  const char *vb0 = slab + r * 256 + ((cc ^ swz) << 4) + (seg & 1) * 8;        // channels 0 .. 63
+  const char *vb1 = slab + r * 256 + (((8 + cc) ^ swz) << 4) + (seg & 1) * 8;  // channels 64 .. 127
+  const char *pa = pline + x * 8;
+  const int nks = (nrows + 3) >> 2;
+#pragma unroll
+  for (int ks = 0; ks < kMqRows / 4; ++ks) {
+    if (ks < nks) {
+      const s16x4 a_hi = *(const s16x4 *)(pa + ks * 32), a_lo = *(const s16x4 *)(pa + 256 + ks * 32);
+      const s16x4 b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4 *)(vb0 + ks * 1024));
+      const s16x4 b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4 *)(vb1 + ks * 1024));
+      st.acc[0] = mfma4(a_hi, b0, st.acc[0]);
+      st.acc[1] = mfma4(a_hi, b1, st.acc[1]);
+      st.acc[0] = mfma4(a_lo, b0, st.acc[0]);
+      st.acc[1] = mfma4(a_lo, b1, st.acc[1]);
+    }
+  }
+}
+
+// KB: 16-byte key chunks a lane may have to stage for one tile.  slab_bytes: the wave's LDS slab,
+// which holds a tile's key bytes and, once the logits are done, its value rows.
+template <int KB, int WPE>
+__global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups, int slab_bytes) {
+  constexpr int DT = THK_BF16, GT = 4, EB = 2, TR = kMqRows, LPR = 16;
+  constexpr int KBT = kTailRows * kD * EB / 16 / kWave;   // chunks per lane of a tail tile
+  extern __shared__ uint4 smem[];
+  uint32_t *qkp = (uint32_t *)smem;                 // [GT][kQS/2] kept query channels, packed bf16, 0 beyond T
+  uint32_t *qfp = qkp + GT * (kQS / 2);             // [GT][kQS/2] full query
+  char *wbase = (char *)(qfp + GT * (kQS / 2));
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  char *slab = wbase + (size_t)wave * (slab_bytes + 512);
+  char *pline = slab + slab_bytes;
+
+  const int sp = (int)(blockIdx.x % a.n_split);
+  const int64_t ug = blockIdx.x / a.n_split;
+  const int gi = (int)(ug % groups);
+  const int64_t u = ug / groups;             // (layer, batch, KV head)
+  const int G = a.N_q / a.N_kv;
+  const int64_t bn0 = u * G + (int64_t)gi * GT;
+
+  const int64_t s0 = min(a.S, (int64_t)sp * a.rows_per_split);
+  const int64_t s1 = min(a.S, s0 + a.rows_per_split);
+  const int nt_p = (int)((s1 - s0 + TR - 1) / TR);
+  const int nt_t = (sp == a.n_split - 1) ? (a.s_tail + kTailRows - 1) / kTailRows : 0;
+  const char *kpg = (const char *)a.kp;
+  const size_t krow0 = (size_t)u * a.unit_rows + s0;     // first K_pruned / V row of this block
+  const u32x4 *vbase = (const u32x4 *)a.v + krow0 * LPR;
+
+  // the first tile's key and value bytes start moving before anything else happens
+  u32x4 kr[KB];
+  u32x4 vr[kMqVChunks];
+  int shift_next = 0;
+  if (wave < nt_p) {
+    const int nr = (int)min((int64_t)TR, s1 - s0 - (int64_t)wave * TR);
+    shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)wave * TR) * a.ldk * EB, nr, a.T, a.ldk, lane);
+    mq_v_issue(vr, vbase + (size_t)wave * TR * LPR, nr, lane);
+  }
+
+  // query: gather the kept channels (Sec. 3.3: the query is pruned with the stored mask)
+  {
+    const int16_t *uidx = a.idx + (size_t)u * a.T;
+    const uint16_t *q16 = (const uint16_t *)a.q;
+    for (int o = tid; o < GT * (kQS / 2); o += 256) {
+      const int g = o / (kQS / 2), c = 2 * (o % (kQS / 2));
+      const size_t qb = (size_t)(bn0 + g) * kD;
+      const uint32_t f0 = c < kD ? q16[qb + c] : 0u, f1 = c + 1 < kD ? q16[qb + c + 1] : 0u;
+      const uint32_t k0 = c < a.T ? q16[qb + uidx[c]] : 0u, k1 = c + 1 < a.T ? q16[qb + uidx[c + 1]] : 0u;
+      qfp[o] = f0 | (f1 << 16);
+      qkp[o] = k0 | (k1 << 16);
+    }
+  }
+  __syncthreads();
+
+  MqState st;
+  st.m = -INFINITY;
+  st.l = 0.f;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) st.acc[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int x = lane & 3;
+  const int pitch_bytes = a.ldk * EB, nch = a.T >> 2;
+
+  // ---- pruned segment: the bytes of this wave's next tile are in flight while the current
+  // one is computed
+  for (int ti = wave; ti < nt_p; ti += 4) {
+    const int nrows = (int)min((int64_t)TR, s1 - s0 - (int64_t)ti * TR);
+    const bool more = ti + 4 < nt_p;
+    const int nr4 = more ? (int)min((int64_t)TR, s1 - s0 - (int64_t)(ti + 4) * TR) : 0;
+    const int shift = shift_next;
+    k_commit<KB>(kr, slab, lane);
+    if (more)
+      shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)(ti + 4) * TR) * a.ldk * EB, nr4, a.T, a.ldk, lane);
+    wave_sync_lds();
+    const f32x4 d = mq_logits(slab, shift, nrows, nch, pitch_bytes, qkp + x * (kQS / 2), lane);
+    mq_softmax(d, nrows, a.scale_log2, st, pline, lane);
+    wave_sync_lds();   // the key bytes are consumed: the slab takes the value rows
+    mq_v_commit(vr, slab, lane);
+    if (more) mq_v_issue(vr, vbase + (size_t)(ti + 4) * TR * LPR, nr4, lane);
+    wave_sync_lds();
+    mq_values(slab, pline, nrows, st, lane);
+    wave_sync_lds();   // slab and pline are rewritten by the next tile
+  }
+
+  // ---- unpruned tail segment (full-width keys, full query) ------------------
+  for (int ti = wave; ti < nt_t; ti += 4) {
+    const int j0 = ti * kTailRows;
+    const int nrows = min(kTailRows, a.s_tail - j0);
+    const size_t row0 = (size_t)u * a.s_tail_cap + j0;
+    u32x4 kt[KBT];
+    k_issue<DT, KBT>(kt, (const char *)a.kt, row0 * kD * EB, nrows, kD, kD, lane);
+    // the tail's value rows: a buffer of their own, or the rows that follow row S in v
+    const u32x4 *vg = a.unified_v ? (const u32x4 *)a.v + ((size_t)u * a.unit_rows + a.S + j0) * LPR
+                                  : (const u32x4 *)a.vt + row0 * LPR;
+    mq_v_issue(vr, vg, nrows, lane);
+    k_commit<KBT>(kt, slab, lane);
+    wave_sync_lds();
+    const f32x4 d = mq_logits(slab, 0, nrows, kD / 4, kD * EB, qfp + x * (kQS / 2), lane);
+    mq_softmax(d, nrows, a.scale_log2, st, pline, lane);
+    wave_sync_lds();
+    mq_v_commit(vr, slab, lane);
+    wave_sync_lds();
+    mq_values(slab, pline, nrows, st, lane);
+    wave_sync_lds();
+  }
+
+  // ---- wave state -> LDS: [GT][130] floats at the start of the wave's own slab -------------
+  {
+    float *mrg = (float *)slab;
+    const float lt = quad_column_reduce<false>(st.l);   // both halves of the wave saw every row
+    if (lane < GT) {
+      float *rec = mrg + lane * (kD + 2);
+      rec[0] = st.m;
+      rec[1] = lt;
+    }
+#pragma unroll
+    for (int i = 0; i < GT; ++i) {
+      float *rec = mrg + i * (kD + 2) + 2;
+      rec[lane] = st.acc[0][i];
+      rec[64 + lane] = st.acc[1][i];
+    }
+  }
+  __syncthreads();
+  block_merge_store<DT, GT>((const float *)wbase, (slab_bytes + 512) / 4, a, bn0, sp);
+}
+
+// Four blocks per compute unit with the narrow staging class (37 KB of LDS and at most 128
+// registers per lane each), three with the wide one.
+template <int KB>
+static hipError_t mq_launch(const DecodeArgs &a, int groups, hipStream_t st) {
+  constexpr int WPE = KB <= 5 ? 4 : 3;
+  const int slab = KB * kWave * 16 > kMqVBytes ? KB * kWave * 16 : kMqVBytes;
+  const size_t lds = (size_t)(2 * 4 * (kQS / 2)) * 4 + 4 * ((size_t)slab + 512);
+  const dim3 grid((unsigned)(a.units * groups * a.n_split)), block(256);
+  if (lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void *)k_decode_mq<KB, WPE>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k_decode_mq<KB, WPE>), grid, block, lds, st, a, groups, slab);
+  return hipGetLastError();
+}
+
+// True when the shape is one this kernel serves: bf16, full-width values, query heads in groups
+// of four, and key rows whose length and pitch are multiples of four elements (8-byte operands).
+// THK_DECODE_MFMA=0 in the environment keeps such shapes on k_decode.
+bool decode_mq_serves(const DecodeArgs &a) {
+  if (a.dtype != THK_BF16 || a.T_v > 0 || a.N_kv <= 0) return false;
+  const int G = a.N_q / a.N_kv;
+  if (G % 4 != 0 || a.T % 4 != 0 || a.T < 4 || a.ldk % 4 != 0) return false;
+  if (decode_launch_params<THK_BF16>(a, kMqRows).kb > 9) return false;
+  const char *env = getenv("THK_DECODE_MFMA");
+  return !(env && env[0] == '0');
+}
+
+hipError_t decode_mq_launch(const DecodeArgs &a, int groups, hipStream_t st) {
+  if (decode_launch_params<THK_BF16>(a, kMqRows).kb <= 5) return mq_launch<5>(a, groups, st);
+  return mq_launch<9>(a, groups, st);
+}
+
+}  // namespace thk

@@ -132,6 +132,16 @@ DECODE_CASES = [
     (2, 3, 1, 4096, 76, 0, 0, 0, 0, 0.0),      # diffuse softmax: V accumulation dominates
     (1, 2, 4, 8192, 64, 0, 64, 0, 0, 0.0),
     (1, 2, 1, 5000, 64, 0, 0, 33, 64, 2.0),    # heavy-tailed scales: near one-hot softmax
+    # four query heads per KV head: bf16 takes the matrix-core kernel when T and ld are multiples of 4
+    (1, 2, 4, 1037, 76, 80, 0, 0, 0, 1.0),     # padded rows
+    (1, 1, 4, 333, 128, 0, 2, 7, 16, 1.0),     # nothing pruned: the wide staging class
+    (1, 2, 4, 100, 4, 0, 0, 0, 0, 1.0),        # one chunk per row
+    (1, 2, 4, 97, 8, 12, 0, 16, 16, 1.0),
+    (1, 1, 8, 2100, 64, 0, 5, 33, 64, 0.0),    # two groups of four heads
+    (1, 2, 4, 1, 64, 0, 0, 0, 0, 1.0),
+    (1, 2, 4, 1, 64, 0, 0, 1, 1, 1.0),
+    (1, 2, 4, 500, 64, 66, 0, 3, 8, 1.0),      # pitch not a multiple of 4: the general kernel
+    (1, 1, 4, 4096, 76, 0, 0, 64, 64, 2.0),
 ]
 
 
@@ -142,6 +152,19 @@ def test_decode_matches_oracle(dtype, case):
     err, _ = _decode_case(dtype, B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma, 1000 + S + T)
     print(f"decode {dtype} {case}: max rel err {err.max():.3e}")
     assert err.max() <= ATTN_TOL[dtype]
+
+
+@pytest.mark.parametrize("case", [c for c in DECODE_CASES if c[2] % 4 == 0], ids=lambda c: "-".join(map(str, c)))
+def test_decode_general_kernel_on_grouped_heads(case, monkeypatch):
+    """THK_DECODE_MFMA=0 keeps bf16 shapes with four query heads per KV head on the general kernel."""
+    monkeypatch.setenv("THK_DECODE_MFMA", "0")
+    B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma = case
+    err, out0 = _decode_case("bf16", B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma, 1000 + S + T)
+    assert err.max() <= ATTN_TOL["bf16"]
+    monkeypatch.setenv("THK_DECODE_MFMA", "1")
+    err1, out1 = _decode_case("bf16", B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma, 1000 + S + T)
+    print(f"decode bf16 {case}: max rel err general {err.max():.3e}, matrix cores {err1.max():.3e}")
+    assert err1.max() <= ATTN_TOL["bf16"]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
