@@ -142,6 +142,9 @@ DECODE_CASES = [
     (1, 2, 4, 1, 64, 0, 0, 1, 1, 1.0),
     (1, 2, 4, 500, 64, 66, 0, 3, 8, 1.0),      # pitch not a multiple of 4: the general kernel
     (1, 1, 4, 4096, 76, 0, 0, 64, 64, 2.0),
+    (1, 1, 4, 200, 124, 0, 0, 2, 4, 1.0),      # 248-byte rows: 8-byte aligned only
+    (1, 1, 4, 200, 128, 132, 2, 0, 0, 1.0),    # the widest tile the staging holds
+    (1, 2, 4, 555, 64, 128, 0, 5, 8, 0.0),     # kept channels at the front of full-width rows
 ]
 
 
