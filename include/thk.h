@@ -218,8 +218,8 @@ thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,
  * S_obs in the shape is ignored.  With n_split > 1 partial (max, sum, acc[D])
  * states go through ws and a second kernel merges them in split order without
  * atomics, so repeated calls give identical bits.
- * bf16 caches with N_q / N_kv a multiple of 4 and T, ld_keep multiples of 4 run the
- * two products on the matrix cores (probabilities as two bf16 terms, exact to
+ * bf16 caches with N_q / N_kv a multiple of 4 and T, ld_keep multiples of 4 (here
+ * and in thk_decode_attn_kv) run the two products on the matrix cores (probabilities as two bf16 terms, exact to
  * 2^-16; accumulation in fp32); THK_DECODE_MFMA=0 in the environment (read per
  * call, for experiments and tests) keeps them on the general kernel.
  *   ws : THK_OP_DECODE bytes.

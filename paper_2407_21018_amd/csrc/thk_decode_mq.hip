@@ -24,6 +24,10 @@
 //            the tile is staged with the two 128-byte halves of odd rows swapped (the four rows
 //            of one read then cover all banks).  D_b[i][j] accumulates head i, channel 4 b + j:
 //            lane l ends with channels l and 64 + l of all four heads.
+//   VP = 1   channel-pruned value rows (T_v kept channels, rows ld_v elements apart): their bytes
+//            are staged like the key bytes, as a flat range, and the same transposing reads walk
+//            them with the row pitch ld_v; lane l then sums kept channels l and 64 + l, which
+//            are scattered to their output channels at the end.  The tail keeps full-width rows.
 #include <stdlib.h>
 
 #include "thk_decode_impl.h"
@@ -41,6 +45,7 @@ struct MqState {
   float m;        // running maximum of this lane's head (lane % 4), log2 domain
   float l;        // this lane's share of its head's probability sum
   f32x4 acc[2];   // acc[h][i]: head i, channel 64 h + lane
+  f32x4 accp[2];  // channel-pruned values only: accp[h][i]: head i, kept channel number 64 h + lane
 };
 
 __device__ __forceinline__ f32x4 mfma4(s16x4 a, s16x4 b, f32x4 c) {
@@ -109,6 +114,7 @@ __device__ __forceinline__ f32x4 mq_logits(const char *slab, int shift, int nrow
 // Running softmax over the tile's logits; the probabilities go to pline as two bf16 terms:
 // bytes [0, 256) the leading terms, [256, 512) the remainders, entry 4 ks + head holding the
 // four rows 4 ks .. 4 ks + 3.
+template <int VP>
 __device__ __forceinline__ void mq_softmax(const f32x4 &d, int nrows, float scale, MqState &st, char *pline,
                                            int lane) {
   const int bb = (lane >> 2) & 7;
@@ -127,6 +133,9 @@ __device__ __forceinline__ void mq_softmax(const f32x4 &d, int nrows, float scal
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       st.acc[h][0] *= c0; st.acc[h][1] *= c1; st.acc[h][2] *= c2; st.acc[h][3] *= c3;
+      if constexpr (VP) {
+        st.accp[h][0] *= c0; st.accp[h][1] *= c1; st.accp[h][2] *= c2; st.accp[h][3] *= c3;
+      }
     }
   }
   uint32_t hi[4], lo[4];
@@ -169,9 +178,39 @@ __device__ __forceinline__ void mq_values(const char *slab, const char *pline, i
   }
 }
 
+// accp += P . V_pruned for the tile whose value bytes sit in the slab as staged (first row at
+// byte `shift`, rows pitch_bytes apart).  A read past a row's T_v channels lands in the next row,
+// or within the 512 bytes that follow every slab, and only feeds kept-channel numbers >= T_v,
+// which nobody collects; a row past a ragged tile's end is read as the tile's last row, with
+// probability 0.
+__device__ __forceinline__ void mq_values_pruned(const char *slab, int shift, int pitch_bytes, int T_v,
+                                                 const char *pline, int nrows, MqState &st, int lane) {
+  const int x = lane & 3, grp = lane >> 4, j = lane & 15, r = j >> 2, seg = j & 3;
+  const char *vb = slab + shift + (16 * grp + 4 * seg) * 2;
+  const char *pa = pline + x * 8;
+  const int nks = (nrows + 3) >> 2;
+  const bool wide = T_v > 64;
+  for (int ks = 0; ks < nks; ++ks) {
+    const char *vrow = vb + min(4 * ks + r, nrows - 1) * pitch_bytes;
+    const s16x4 a_hi = *(const s16x4 *)(pa + ks * 32), a_lo = *(const s16x4 *)(pa + 256 + ks * 32);
+    const s16x4 b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vrow));
+    st.accp[0] = mfma4(a_hi, b0, st.accp[0]);
+    if (wide) {
+      const s16x4 b1 =
+          __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vrow + 128));
+      st.accp[1] = mfma4(a_hi, b1, st.accp[1]);
+      st.accp[0] = mfma4(a_lo, b0, st.accp[0]);
+      st.accp[1] = mfma4(a_lo, b1, st.accp[1]);
+    } else {
+      st.accp[0] = mfma4(a_lo, b0, st.accp[0]);
+    }
+  }
+}
+
 // KB: 16-byte key chunks a lane may have to stage for one tile.  slab_bytes: the wave's LDS slab,
 // which holds a tile's key bytes and, once the logits are done, its value rows.
-template <int KB, int WPE>
+// VP = 1: the value rows of the pruned segment are channel-pruned (a.v = V_pruned, a.ld_v, a.idx_v).
+template <int KB, int WPE, int VP>
 __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups, int slab_bytes) {
   constexpr int DT = THK_BF16, GT = 4, EB = 2, TR = kMqRows, LPR = 16;
   constexpr int KBT = kTailRows * kD * EB / 16 / kWave;   // chunks per lane of a tail tile
@@ -201,11 +240,16 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
   // the first tile's key and value bytes start moving before anything else happens
   u32x4 kr[KB];
   u32x4 vr[kMqVChunks];
-  int shift_next = 0;
+  u32x4 vrp[VP ? KB : 1];
+  int shift_next = 0, vshift = 0;
   if (wave < nt_p) {
     const int nr = (int)min((int64_t)TR, s1 - s0 - (int64_t)wave * TR);
     shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)wave * TR) * a.ldk * EB, nr, a.T, a.ldk, lane);
-    mq_v_issue(vr, vbase + (size_t)wave * TR * LPR, nr, lane);
+    if constexpr (VP)
+      vshift = k_issue<DT, KB>(vrp, (const char *)a.v, (krow0 + (size_t)wave * TR) * a.ld_v * EB, nr, a.T_v, a.ld_v,
+                               lane);
+    else
+      mq_v_issue(vr, vbase + (size_t)wave * TR * LPR, nr, lane);
   }
 
   // query: gather the kept channels (Sec. 3.3: the query is pruned with the stored mask)
@@ -227,7 +271,10 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
   st.m = -INFINITY;
   st.l = 0.f;
 #pragma unroll
-  for (int h = 0; h < 2; ++h) st.acc[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int h = 0; h < 2; ++h) {
+    st.acc[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.accp[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   const int x = lane & 3;
   const int pitch_bytes = a.ldk * EB, nch = a.T >> 2;
 
@@ -243,12 +290,22 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
       shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)(ti + 4) * TR) * a.ldk * EB, nr4, a.T, a.ldk, lane);
     wave_sync_lds();
     const f32x4 d = mq_logits(slab, shift, nrows, nch, pitch_bytes, qkp + x * (kQS / 2), lane);
-    mq_softmax(d, nrows, a.scale_log2, st, pline, lane);
+    mq_softmax<VP>(d, nrows, a.scale_log2, st, pline, lane);
     wave_sync_lds();   // the key bytes are consumed: the slab takes the value rows
-    mq_v_commit(vr, slab, lane);
-    if (more) mq_v_issue(vr, vbase + (size_t)(ti + 4) * TR * LPR, nr4, lane);
-    wave_sync_lds();
-    mq_values(slab, pline, nrows, st, lane);
+    if constexpr (VP) {
+      const int vs = vshift;
+      k_commit<KB>(vrp, slab, lane);
+      if (more)
+        vshift = k_issue<DT, KB>(vrp, (const char *)a.v, (krow0 + (size_t)(ti + 4) * TR) * a.ld_v * EB, nr4, a.T_v,
+                                 a.ld_v, lane);
+      wave_sync_lds();
+      mq_values_pruned(slab, vs, a.ld_v * EB, a.T_v, pline, nrows, st, lane);
+    } else {
+      mq_v_commit(vr, slab, lane);
+      if (more) mq_v_issue(vr, vbase + (size_t)(ti + 4) * TR * LPR, nr4, lane);
+      wave_sync_lds();
+      mq_values(slab, pline, nrows, st, lane);
+    }
     wave_sync_lds();   // slab and pline are rewritten by the next tile
   }
 
@@ -266,7 +323,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
     k_commit<KBT>(kt, slab, lane);
     wave_sync_lds();
     const f32x4 d = mq_logits(slab, 0, nrows, kD / 4, kD * EB, qfp + x * (kQS / 2), lane);
-    mq_softmax(d, nrows, a.scale_log2, st, pline, lane);
+    mq_softmax<VP>(d, nrows, a.scale_log2, st, pline, lane);
     wave_sync_lds();
     mq_v_commit(vr, slab, lane);
     wave_sync_lds();
@@ -289,6 +346,20 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
       rec[lane] = st.acc[0][i];
       rec[64 + lane] = st.acc[1][i];
     }
+    if constexpr (VP) {
+      // the sums over the pruned rows go to their channels (distinct for distinct kept numbers)
+      wave_sync_lds();
+      const int16_t *uidv = a.idx_v + (size_t)u * a.T_v;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int t = 64 * h + lane;
+        if (t < a.T_v) {
+          const int c = uidv[t];
+#pragma unroll
+          for (int i = 0; i < GT; ++i) mrg[i * (kD + 2) + 2 + c] += st.accp[h][i];
+        }
+      }
+    }
   }
   __syncthreads();
   block_merge_store<DT, GT>((const float *)wbase, (slab_bytes + 512) / 4, a, bn0, sp);
@@ -296,36 +367,50 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
 
 // Four blocks per compute unit with the narrow staging class (37 KB of LDS and at most 128
 // registers per lane each), three with the wide one.
-template <int KB>
+template <int KB, int VP>
 static hipError_t mq_launch(const DecodeArgs &a, int groups, hipStream_t st) {
   constexpr int WPE = KB <= 5 ? 4 : 3;
   const int slab = KB * kWave * 16 > kMqVBytes ? KB * kWave * 16 : kMqVBytes;
   const size_t lds = (size_t)(2 * 4 * (kQS / 2)) * 4 + 4 * ((size_t)slab + 512);
   const dim3 grid((unsigned)(a.units * groups * a.n_split)), block(256);
   if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void *)k_decode_mq<KB, WPE>,
+    hipError_t e = hipFuncSetAttribute((const void *)k_decode_mq<KB, WPE, VP>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((k_decode_mq<KB, WPE>), grid, block, lds, st, a, groups, slab);
+  hipLaunchKernelGGL((k_decode_mq<KB, WPE, VP>), grid, block, lds, st, a, groups, slab);
   return hipGetLastError();
 }
 
-// True when the shape is one this kernel serves: bf16, full-width values, query heads in groups
-// of four, and key rows whose length and pitch are multiples of four elements (8-byte operands).
-// THK_DECODE_MFMA=0 in the environment keeps such shapes on k_decode.
+// Staged 16-byte chunks per lane for one tile: the wider of the key rows and, when they are
+// channel-pruned, the value rows.
+static int mq_chunks(const DecodeArgs &a) {
+  int kb = decode_launch_params<THK_BF16>(a, kMqRows).kb;
+  if (a.T_v > 0) {
+    const int kbv = (int)((kMqRows * (size_t)a.ld_v * 2 + 15 + 15) / 16 + kWave - 1) / kWave;
+    if (kbv > kb) kb = kbv;
+  }
+  return kb;
+}
+
+// True when the shape is one this kernel serves: bf16, query heads in groups of four, and rows
+// (keys, and values when they are channel-pruned) whose length and pitch are multiples of four
+// elements, so that every operand is 8 bytes.  THK_DECODE_MFMA=0 in the environment keeps such
+// shapes on k_decode.
 bool decode_mq_serves(const DecodeArgs &a) {
-  if (a.dtype != THK_BF16 || a.T_v > 0 || a.N_kv <= 0) return false;
+  if (a.dtype != THK_BF16 || a.N_kv <= 0) return false;
   const int G = a.N_q / a.N_kv;
   if (G % 4 != 0 || a.T % 4 != 0 || a.T < 4 || a.ldk % 4 != 0) return false;
-  if (decode_launch_params<THK_BF16>(a, kMqRows).kb > 9) return false;
+  if (a.T_v > 0 && a.ld_v % 4 != 0) return false;
+  if (mq_chunks(a) > 9) return false;
   const char *env = getenv("THK_DECODE_MFMA");
   return !(env && env[0] == '0');
 }
 
 hipError_t decode_mq_launch(const DecodeArgs &a, int groups, hipStream_t st) {
-  if (decode_launch_params<THK_BF16>(a, kMqRows).kb <= 5) return mq_launch<5>(a, groups, st);
-  return mq_launch<9>(a, groups, st);
+  const bool narrow = mq_chunks(a) <= 5;
+  if (a.T_v > 0) return narrow ? mq_launch<5, 1>(a, groups, st) : mq_launch<9, 1>(a, groups, st);
+  return narrow ? mq_launch<5, 0>(a, groups, st) : mq_launch<9, 0>(a, groups, st);
 }
 
 }  // namespace thk

@@ -169,6 +169,12 @@ DECODE_CASES = [
     ("bf16", 4, 333, 128, 128, 128, 3, 8, 2),   # nothing removed: the widest rows
     ("bf16", 1, 45, 64, 1, 4, 2, 4, 1),         # a single kept value channel
     ("bf16", 8, 777, 38, 102, 104, 1, 1, 0),
+    # bf16 with four query heads per KV head and T, ld_v multiples of 4: the matrix-core kernel
+    ("bf16", 4, 1037, 76, 51, 52, 5, 16, 3),
+    ("bf16", 4, 97, 64, 3, 4, 0, 0, 1),
+    ("bf16", 4, 500, 76, 100, 104, 0, 0, 0),
+    ("bf16", 4, 31, 64, 64, 64, 0, 0, 1),       # one ragged tile
+    ("bf16", 8, 1300, 64, 76, 76, 33, 64, 2),
     ("f32", 1, 1037, 64, 64, 64, 0, 0, 0),
     ("f32", 4, 900, 76, 51, 52, 9, 16, 4),
     ("f32", 2, 333, 51, 128, 128, 0, 0, 1),
@@ -210,6 +216,14 @@ def test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n
         keep = np.zeros((U, D), bool)
         np.put_along_axis(keep, idx_v.cpu().numpy().astype(np.int64), True, axis=1)
         assert np.all(o[~np.broadcast_to(keep[:, None, :], o.shape)] == 0.0)
+
+
+@pytest.mark.parametrize("dtype,G,S,T,T_v,ld_v,s_tail,cap,n_split",
+                         [c for c in DECODE_CASES if c[0] == "bf16" and c[1] % 4 == 0 and c[3] % 4 == 0])
+def test_decode_attn_kv_general_kernel_on_grouped_heads(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split, monkeypatch):
+    """THK_DECODE_MFMA=0: the shapes the matrix-core kernel serves, on the general kernel."""
+    monkeypatch.setenv("THK_DECODE_MFMA", "0")
+    test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split)
 
 
 def test_decode_attn_kv_with_identity_value_index_equals_key_only_decode():
