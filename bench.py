@@ -295,11 +295,12 @@ def main():
     fused = form != 0
     prune_kernel = {2: "k_prune_onepass", 1: "k_prune_fused", 0: "k_compact_flat"}[form]
     prune_kernel_bytes = L * prune_bytes if fused else L * U * S * eb * (D + T)
+    decode_kernel = "k_decode_mq" if thk.thk_decode_on_matrix_cores(shape_1) else "k_decode"
     kernels = {
         prune_kernel: {"launches_per_step": 1, "avg_us": prune_k_us, "bytes_per_launch": prune_kernel_bytes,
                        "GBps": prune_kernel_bytes / prune_k_us / 1e3},
-        "k_decode": {"launches_per_step": n_dec, "avg_us": dec_k_us, "bytes_per_launch": decode_bytes,
-                     "GBps": decode_bytes / dec_k_us / 1e3},
+        decode_kernel: {"launches_per_step": n_dec, "avg_us": dec_k_us, "bytes_per_launch": decode_bytes,
+                        "GBps": decode_bytes / dec_k_us / 1e3},
     }
     # the dominant kernel = most time inside a step
     dom = max(kernels, key=lambda n: kernels[n]["avg_us"] * kernels[n]["launches_per_step"])

@@ -111,6 +111,11 @@ int32_t thk_default_split(const thk_shape *shape, int32_t op);
  * staged three-kernel form (or an invalid shape).  Host-only. */
 int32_t thk_prune_is_fused(const thk_shape *shape);
 
+/* 1 if thk_decode_attn (T_v == 0) or thk_decode_attn_kv (value rows of T_v kept channels,
+ * ld_v elements apart) would run `shape` on the matrix-core kernel k_decode_mq, 0 if on the
+ * general kernel k_decode (or the shape is invalid).  Host-only; honours THK_DECODE_MFMA. */
+int32_t thk_decode_on_matrix_cores(const thk_shape *shape, int32_t T_v, int32_t ld_v);
+
 /*
  * Query-driven channel score (Sec. 3.2, Score_i[j] = ||Q_i[-S_obs:, j] K_i[:, j]^T||_F).
  * The matrix is an outer product of two columns, so the score is

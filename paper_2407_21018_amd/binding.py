@@ -62,6 +62,8 @@ def load():
     L.thk_default_split.argtypes = [sp, i32]
     L.thk_prune_is_fused.restype = i32
     L.thk_prune_is_fused.argtypes = [sp]
+    L.thk_decode_on_matrix_cores.restype = i32
+    L.thk_decode_on_matrix_cores.argtypes = [sp, i32, i32]
     L.thk_score.restype = ctypes.c_int
     L.thk_score.argtypes = [sp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.thk_score_value.restype = ctypes.c_int
@@ -186,6 +188,10 @@ def thk_default_split(shape, op):
 
 def thk_prune_is_fused(shape):
     return int(load().thk_prune_is_fused(ctypes.byref(shape)))
+
+
+def thk_decode_on_matrix_cores(shape, T_v=0, ld_v=0):
+    return int(load().thk_decode_on_matrix_cores(ctypes.byref(shape), T_v, ld_v))
 
 
 def thk_score(shape, q_obs, k, score, ws, stream=None):

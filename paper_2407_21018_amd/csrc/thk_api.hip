@@ -235,6 +235,15 @@ int32_t thk_prune_is_fused(const thk_shape *s) {
   return !fp.ok ? 0 : fp.hold != 0 ? 2 : 1;
 }
 
+int32_t thk_decode_on_matrix_cores(const thk_shape *s, int32_t T_v, int32_t ld_v) {
+  if (check_shape(s, false) != THK_OK) return 0;
+  if (T_v < 0 || T_v > kD || (T_v > 0 && (ld_v < T_v || ld_v > kD))) return 0;
+  DecodeArgs a = {};
+  a.T = s->T; a.ldk = ld_of(s); a.N_q = s->N_q; a.N_kv = s->N_kv; a.dtype = s->dtype;
+  a.T_v = T_v; a.ld_v = T_v > 0 ? ld_v : 0;
+  return decode_mq_serves(a) ? 1 : 0;
+}
+
 size_t thk_workspace_bytes(const thk_shape *s, int32_t op) {
   if (check_shape(s, false) != THK_OK) return 0;
   switch (op) {

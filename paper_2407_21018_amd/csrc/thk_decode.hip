@@ -19,7 +19,6 @@ hipError_t decode_kv_launch_f32_g1(const DecodeArgs &, int, hipStream_t);
 hipError_t decode_kv_launch_f32_g2(const DecodeArgs &, int, hipStream_t);
 hipError_t decode_kv_launch_f32_g4(const DecodeArgs &, int, hipStream_t);
 // four query heads per KV head on the matrix cores (bf16, full-width values)
-bool decode_mq_serves(const DecodeArgs &);
 hipError_t decode_mq_launch(const DecodeArgs &, int, hipStream_t);
 
 // Merge of the per-split states: m = max m_i, l = sum l_i 2^(m_i - m),

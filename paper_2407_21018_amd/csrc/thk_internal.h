@@ -120,6 +120,8 @@ struct DecodeArgs {
   int32_t T_v, ld_v;
 };
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t st);
+// the shape runs on the matrix-core kernel (needs dtype, T, ldk, N_q, N_kv, T_v, ld_v of a)
+bool decode_mq_serves(const DecodeArgs &a);
 
 hipError_t launch_tail_append(int dtype, const void *k_new, const void *v_new, void *k_dst, void *v_dst,
                               int64_t U, int64_t k_unit_rows, int64_t k_row, int64_t v_unit_rows,

@@ -197,6 +197,25 @@ def test_prune_plan_by_shape(monkeypatch):
     assert thk.thk_prune_is_fused(cfg2) == 0
 
 
+def test_decode_kernel_choice_by_shape(monkeypatch):
+    """bf16, query heads in groups of four, T and the row pitches multiples of 4: the matrix-core kernel."""
+    monkeypatch.delenv("THK_DECODE_MFMA", raising=False)
+    mk = lambda N_q, N_kv, T, ld, dt: thk.make_shape(1, 1, N_q, N_kv, 128, 4096, 1, T, ld, dt, 0)
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16)) == 1
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 76, 80, thk.THK_BF16)) == 1
+    assert thk.thk_decode_on_matrix_cores(mk(64, 8, 128, 0, thk.THK_BF16)) == 1       # two groups of four
+    assert thk.thk_decode_on_matrix_cores(mk(32, 32, 76, 0, thk.THK_BF16)) == 0       # one head per KV head
+    assert thk.thk_decode_on_matrix_cores(mk(16, 8, 64, 0, thk.THK_BF16)) == 0
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 51, 0, thk.THK_BF16)) == 0        # T not a multiple of 4
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 66, thk.THK_BF16)) == 0       # pitch not a multiple of 4
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_F32)) == 0
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16), 51, 52) == 1  # channel-pruned values
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16), 51, 51) == 0  # invalid pitch (below the ABI's multiple of 4)
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16), 200, 200) == 0
+    monkeypatch.setenv("THK_DECODE_MFMA", "0")
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16)) == 0
+
+
 def test_plain_c_program_uses_the_boundary(tmp_path):
     """thk.h is a C header and libthk.so a C library: a gcc-built program with no C++ and no
     Python in it includes the one and links the other."""
