@@ -270,6 +270,48 @@ __device__ inline void select_wave(float s_lo, float s_hi, int T, int16_t *out, 
 }
 
 // ---------------------------------------------------------------------------
+// The same selection by a 256-thread block, by counting: channel c is kept iff fewer than T
+// channels rank before it (larger score, or equal score and lower index).  Thread (c, h)
+// counts over one half of the channels, read as LDS broadcasts; the kept channels are emitted
+// in ascending order through ballot + prefix popcount.  A few hundred cycles, against the
+// ~5000 of the one-wave sort, which matters where other blocks wait for the list.
+// sc: 128 scores in LDS (complete and visible); scratch: 257 words of LDS; out: LDS, T entries,
+// visible to the block on return.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void select_block(const float *sc, int T, int16_t *out, uint32_t *scratch) {
+  const int tid = threadIdx.x, c = tid & (kD - 1), h = tid >> 7;
+  uint32_t *key = scratch, *part = scratch + kD, *cnt0 = scratch + 2 * kD;
+  if (tid < kD) {
+    const uint32_t b = __float_as_uint(sc[tid]);
+    key[tid] = (b & 0x80000000u) ? ~b : (b | 0x80000000u);   // unsigned order == float order
+  }
+  __syncthreads();
+  const uint32_t mine = key[c];
+  int before = 0;
+#pragma unroll 8
+  for (int j = h * 64; j < h * 64 + 64; ++j) {
+    const uint32_t kj = key[j];
+    before += (kj > mine) || (kj == mine && j < c);
+  }
+  if (h) part[c] = (uint32_t)before;
+  __syncthreads();
+  bool keep = false;
+  unsigned long long m = 0;
+  if (!h) {
+    keep = before + (int)part[c] < T;
+    m = __ballot(keep);
+    if (tid == 0) *cnt0 = (uint32_t)__popcll(m);   // kept among channels 0 .. 63
+  }
+  __syncthreads();
+  if (keep) {
+    const int lane = tid % kWave;
+    const int pos = __popcll(m & ((1ull << lane) - 1ull)) + (tid >= kWave ? (int)*cnt0 : 0);
+    out[pos] = (int16_t)c;
+  }
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
 // Compaction of rows [s0, s1) of one unit (K_pruned rows dense, unit start
 // 16-byte aligned) by a 256-thread block.  Each wavefront works alone on tiles
 // of 32 rows:

@@ -103,7 +103,10 @@ __global__ __launch_bounds__(256) void k_prune_prep(PruneFusedArgs a, int64_t U)
   }
   if (!clear) return;
   if (lane == 0) a.arrived[u] = 0;
-  if (a.GS > 0 && lane < kMaxGroups) a.arrived_g[(size_t)u * kMaxGroups + lane] = 0;
+  if (a.GS > 0) {
+    if (lane < kMaxGroups) a.arrived_g[(size_t)u * kMaxGroups + lane] = 0;
+    for (int i = lane; i < kMaxGroups * kD; i += kWave) a.gpartial[(size_t)u * kMaxGroups * kD + i] = 0.0;
+  }
   a.idx_pub[(size_t)u * kWave + lane] = 0u;
   for (int i = lane; i < a.NB; i += kWave) a.done[(size_t)u * a.NB + i] = 0;
 }
@@ -140,45 +143,91 @@ __device__ __forceinline__ bool arrive(int *counter, int full, int *s_flag) {
   return last;
 }
 
+// A group's sums as the group's last block publishes them: 64-bit words that carry their own
+// validity mark in the lowest mantissa bit (a change of at most 2^-52 relative; k_prune_prep
+// clears the words before every call), so that readers need no flag and no ordering.
+__device__ inline void pub_store_marked(double *p, double v) {
+  __hip_atomic_store((unsigned long long *)p, (unsigned long long)__double_as_longlong(v) | 1ull, __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline unsigned long long pub_load_bits(const double *p) {
+  return __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Scores of the unit from its column sums (kss, valid in threads < 128) and the index list;
+// `writer` also stores both for the caller.  scratch: 257 words of LDS.
+__device__ __forceinline__ void score_and_select(const PruneFusedArgs &a, int64_t u, double qn_c, double kss,
+                                                 float *s_sc, int16_t *s_idx, uint32_t *scratch, bool writer) {
+  const int tid = threadIdx.x;
+  if (tid < kD) {
+    const float scf = (float)(qn_c * sqrt(kss));
+    if (writer) a.score[(size_t)u * kD + tid] = scf;
+    s_sc[tid] = scf;
+  }
+  __syncthreads();
+  select_block(s_sc, a.T, s_idx, scratch);
+  if (writer && tid < a.T) a.idx[(size_t)u * a.T + tid] = s_idx[tid];
+}
+
 __device__ __forceinline__ bool unit_index_list(const PruneFusedArgs &a, int64_t u, int64_t item,
                                                 double *s_part, float *s_sc, int16_t *s_idx,
-                                                int *s_flag) {
+                                                int *s_flag, uint32_t *scratch) {
   const int tid = threadIdx.x;
+  // the query norms are needed last; their load travels with the stores below
+  const double qn_c = tid < kD ? a.qn[(size_t)u * kD + tid] : 0.0;
   if (tid < kD) pub_store_f64(a.partial + (size_t)item * kD + tid, s_part[tid]);
   block_stores_done();
 
-  // Units of many blocks arrive in two levels: the last block of a group of a.GS consecutive
-  // blocks merges the group's sums into one vector and arrives for the group, so that nobody
-  // ever has to walk more than a.GS or NB / a.GS vectors.
   const double *src = a.partial + (size_t)u * a.NB * kD;
-  int n_src = a.NB;
-  bool last = true;
   if (a.GS > 0) {
+    // Units of many blocks, two levels.  The last block of a group of a.GS consecutive blocks
+    // merges the group's sums into one vector and publishes it; EVERY block of the unit then
+    // reads the (at most 16) group vectors, adds them in group order and makes the index list
+    // for itself -- the same bits everywhere.  Nobody waits for a block that waits: the group
+    // vectors come from blocks that only had to finish their own rows.
     const int blk = (int)(item - u * a.NB);
     const int g = blk / a.GS;
     const int gsize = min(a.GS, a.NB - g * a.GS);
-    last = arrive(a.arrived_g + (size_t)u * kMaxGroups + g, gsize, s_flag);
-    if (last) {
+    double *gp = a.gpartial + (size_t)u * kMaxGroups * kD;
+    if (arrive(a.arrived_g + (size_t)u * kMaxGroups + g, gsize, s_flag)) {
       const double gs = merge_partials(src + (size_t)g * a.GS * kD, gsize, s_part);
-      if (tid < kD) pub_store_f64(a.gpartial + ((size_t)u * kMaxGroups + g) * kD + tid, gs);
-      block_stores_done();
-      src = a.gpartial + (size_t)u * kMaxGroups * kD;
-      n_src = (a.NB + a.GS - 1) / a.GS;
+      if (tid < kD) pub_store_marked(gp + (size_t)g * kD + tid, gs);
     }
+    const int n_grp = (a.NB + a.GS - 1) / a.GS;
+    // thread (c, half) polls channel c of groups 8 half .. 8 half + 7; all loads in flight at once
+    constexpr int HG = kMaxGroups / 2;
+    const int c = tid & (kD - 1), j0 = (tid >> 7) * HG;
+    unsigned long long w[HG];
+#pragma unroll
+    for (int j = 0; j < HG; ++j) w[j] = pub_load_bits(gp + (size_t)min(j0 + j, n_grp - 1) * kD + c);
+    bool ok;
+    for (int n = 0;; ++n) {
+      bool miss = false;
+#pragma unroll
+      for (int j = 0; j < HG; ++j) miss |= (w[j] & 1ull) == 0;
+      if (!__any(miss) || n >= a.spin_limit) { ok = !miss; break; }
+      __builtin_amdgcn_s_sleep(16);
+#pragma unroll
+      for (int j = 0; j < HG; ++j)
+        if ((w[j] & 1ull) == 0) w[j] = pub_load_bits(gp + (size_t)min(j0 + j, n_grp - 1) * kD + c);
+    }
+    double kss = 0.0;
+#pragma unroll
+    for (int j = 0; j < HG; ++j) kss += j0 + j < n_grp ? __longlong_as_double((long long)(w[j] & ~1ull)) : 0.0;
+    if (tid == 0) *s_flag = 1;
+    __syncthreads();
+    if (!ok) *s_flag = 0;      // any thread that ran out of polls
+    if (tid >= kD) s_part[c] = kss;
+    __syncthreads();
+    if (*s_flag == 0) return false;
+    if (tid < kD) kss += s_part[c];
+    score_and_select(a, u, qn_c, kss, s_sc, s_idx, scratch, blk == 0);
+    return true;
   }
-  if (last) last = arrive(a.arrived + u, n_src, s_flag);
 
-  if (last) {
-    const double kss = merge_partials(src, n_src, s_part);   // s_part: its sums are published already
-    if (tid < kD) {
-      const float scf = (float)(a.qn[(size_t)u * kD + tid] * sqrt(kss));
-      a.score[(size_t)u * kD + tid] = scf;
-      s_sc[tid] = scf;
-    }
-    __syncthreads();
-    if (tid < kWave) select_wave(s_sc[tid], s_sc[tid + 64], a.T, s_idx, tid);
-    __syncthreads();
-    if (tid < a.T) a.idx[(size_t)u * a.T + tid] = s_idx[tid];
+  if (arrive(a.arrived + u, a.NB, s_flag)) {
+    const double kss = merge_partials(src, a.NB, s_part);   // s_part: its sums are published already
+    score_and_select(a, u, qn_c, kss, s_sc, s_idx, scratch, true);
     if (tid < kWave) {
       const uint32_t lo = 2 * tid < a.T ? (uint16_t)s_idx[2 * tid] : 0u;
       const uint32_t hi = 2 * tid + 1 < a.T ? (uint16_t)s_idx[2 * tid + 1] : 0u;
@@ -218,6 +267,7 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   __shared__ double s_part[kD];
   __shared__ float s_sc[kD];
   __shared__ int16_t s_idx[kD];
+  __shared__ uint32_t s_scratch[2 * kD + 1];
   __shared__ int s_flag;
   const int tid = threadIdx.x;
   const int64_t item = blockIdx.x;
@@ -229,7 +279,7 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
 
   colsum_block<DT, 2, false>(src, s0, s1, s_part, red);
   __syncthreads();
-  if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag)) return;
+  if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
 
   compact_build_tab(tab, s_idx, a.T);
   __syncthreads();
@@ -260,6 +310,7 @@ void k_prune_onepass(PruneFusedArgs a) {
   __shared__ double s_part[kD];
   __shared__ float s_sc[kD];
   __shared__ int16_t s_idx[kD];
+  __shared__ uint32_t s_scratch[2 * kD + 1];
   __shared__ int s_flag;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int64_t item = blockIdx.x;
@@ -333,7 +384,7 @@ void k_prune_onepass(PruneFusedArgs a) {
   if (tid < kD) s_part[tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
   __syncthreads();
 
-  if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag)) return;
+  if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
 
   // ---- compaction: the LDS tiles first, then the register tiles through slot 0 ---------------
   compact_build_tab(tab, s_idx, a.T);
@@ -379,7 +430,28 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
   if (undone) s_any = 1;
   __syncthreads();
   if (s_any == 0) return;
-  compact_build_tab(tab, a.idx + (size_t)u * a.T, a.T);
+  if (a.GS > 0) {
+    // The blocks of a two-level unit make the list for themselves and block 0 stores the
+    // caller's copy, so the copy may be missing.  All group vectors are there by now: the same
+    // sums in the same order give the same list.
+    __shared__ float s_sc[kD];
+    __shared__ int16_t s_idx[kD];
+    __shared__ uint32_t s_scratch[2 * kD + 1];
+    const int tid = threadIdx.x;
+    const int n_grp = (a.NB + a.GS - 1) / a.GS;
+    const double *gp = a.gpartial + (size_t)u * kMaxGroups * kD;
+    double kss = 0.0;
+    if (tid < kD) {
+      double half[2] = {0.0, 0.0};
+      for (int j = 0; j < n_grp; ++j)
+        half[j / (kMaxGroups / 2)] += __longlong_as_double((long long)(pub_load_bits(gp + (size_t)j * kD + tid) & ~1ull));
+      kss = half[0] + half[1];
+    }
+    score_and_select(a, u, tid < kD ? a.qn[(size_t)u * kD + tid] : 0.0, kss, s_sc, s_idx, s_scratch, true);
+    compact_build_tab(tab, s_idx, a.T);
+  } else {
+    compact_build_tab(tab, a.idx + (size_t)u * a.T, a.T);
+  }
   __syncthreads();
   const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
   u32x4 *dst = (u32x4 *)((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);

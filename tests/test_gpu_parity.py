@@ -226,12 +226,18 @@ def test_prune_fused_repeated_calls_on_one_workspace(monkeypatch):
     assert not torch.equal(first_idx[0], first_idx[1])
 
 
+@pytest.mark.parametrize("spin_limit", [None, 0])
 @pytest.mark.parametrize("block_rows", [128, 64])
-def test_prune_two_level_arrival(block_rows, monkeypatch):
-    """Units of more than 64 row blocks: the blocks arrive group by group and the group sums are
-    merged a second time (102 blocks of 128 rows held on chip; 204 blocks of 64 rows read twice)."""
+def test_prune_two_level_arrival(block_rows, spin_limit, monkeypatch):
+    """Units of more than 64 row blocks: the blocks arrive group by group, the last block of a
+    group publishes the group's sums, and every block makes the index list from the group sums
+    (102 blocks of 128 rows held on chip; 204 blocks of 64 rows read twice).  With the wait
+    switched off from the host, blocks that find a group vector missing leave their rows, and
+    possibly the caller's copy of the list, to the repair kernel."""
     monkeypatch.setenv("THK_PRUNE_PATH", "fused")
     monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", str(block_rows))
+    if spin_limit is not None:
+        monkeypatch.setenv("THK_PRUNE_SPIN_LIMIT", str(spin_limit))
     L, B, N_kv, G, S, S_obs, T = 1, 2, 2, 2, 13008, 32, 64
     q_obs = _randn((L, B, N_kv * G, S_obs, D), "bf16", 41, 1.0)
     k = _randn((L, B, N_kv, S, D), "bf16", 42, 1.0)
