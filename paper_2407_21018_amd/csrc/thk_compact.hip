@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void k_compact_flat(CompactArgs a) {
   const int blk = (int)(blockIdx.x % a.blocks_per_unit);
   const int64_t s0 = (int64_t)blk * a.rows_per_block;
   const int64_t s1 = min(a.n_rows, s0 + a.rows_per_block);
-  compact_build_tab(tab, a.idx + (size_t)u * a.T, a.T);
+  compact_build_tab<DT>(tab, a.idx + (size_t)u * a.T, a.T);
   __syncthreads();
   compact_rows<DT>((const u32x4 *)((const char *)a.src + ((size_t)u * a.src_unit_rows + a.src_row0) * kD * E::EB),
                    (u32x4 *)((char *)a.dst + ((size_t)u * a.dst_unit_rows + a.dst_row0) * a.T * E::EB),
@@ -116,7 +116,7 @@ hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int
   a.blocks_per_unit = (int)((n_rows + a.rows_per_block - 1) / a.rows_per_block);
   const dim3 grid((unsigned)(U * a.blocks_per_unit)), block(256);
   if (compact_is_flat(dtype, T, ld_keep, dst_unit_rows, dst_row0, n_rows)) {
-    const size_t lds = 2048 + 4 * (size_t)kCompactTileRows * kD * eb;
+    const size_t lds = 2048 + 4 * compact_tile_bytes(eb);
     if (dtype == THK_BF16) hipLaunchKernelGGL((k_compact_flat<THK_BF16>), grid, block, lds, st, a);
     else                   hipLaunchKernelGGL((k_compact_flat<THK_F32>), grid, block, lds, st, a);
   } else {

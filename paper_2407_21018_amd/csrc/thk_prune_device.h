@@ -326,11 +326,26 @@ __device__ __forceinline__ void select_block(const float *sc, int T, int16_t *ou
 // ---------------------------------------------------------------------------
 constexpr int kCompactTileRows = 32;
 
+// A tile in LDS: 32 full-width rows, one 16-byte chunk of padding after each, so that
+// consecutive rows start four banks apart (rows 256 or 512 bytes apart would all start in the
+// same bank, and the gather below reads the same channels of up to eight rows in one step).
+template <int DT>
+struct Tile {
+  static constexpr int CPR = kD / Elem<DT>::VEC;          // 16-byte chunks per row
+  static constexpr int PITCH = CPR + 1;                   // chunks from row to row in LDS
+  static constexpr int CHUNKS = kCompactTileRows * PITCH; // chunks per tile
+  static constexpr int ROW_ELEMS = PITCH * Elem<DT>::VEC; // elements from row to row in LDS
+  // LDS chunk of the tile's id-th 16-byte chunk in memory order
+  __device__ static inline int slot(int id) { return (id / CPR) * PITCH + id % CPR; }
+};
+constexpr size_t compact_tile_bytes(int eb) { return (size_t)kCompactTileRows * (kD * eb + 16); }
+
+template <int DT>
 __device__ __forceinline__ void compact_build_tab(uint16_t *tab, const int16_t *uidx, int T) {
   const int period = 8 * T;
   for (int e = threadIdx.x; e < period; e += 256) {
     const int row = e / T, t = e - row * T;
-    tab[e] = (uint16_t)(row * kD + (int)uidx[t]);
+    tab[e] = (uint16_t)(row * Tile<DT>::ROW_ELEMS + (int)uidx[t]);
   }
 }
 
@@ -347,7 +362,7 @@ __device__ __forceinline__ void compact_emit_tile(const u32x4 *tile, u32x4 *__re
     const int e0 = c * VEC;
     const int pb = e0 / period;
     const int pe = e0 - pb * period;
-    const int rowbase = pb * 8 * kD;
+    const int rowbase = pb * 8 * Tile<DT>::ROW_ELEMS;
     u32x4 w;
     if constexpr (DT == THK_BF16) {
       const uint16_t *tl = (const uint16_t *)tile + rowbase;
@@ -376,7 +391,7 @@ __device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, u32x
   constexpr int VEC = E::VEC, CPR = kD / VEC, TR = kCompactTileRows;
   constexpr int NLD = TR * CPR / kWave;   // 16-byte loads per lane per tile
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-  u32x4 *tile = tiles + wave * (TR * CPR);
+  u32x4 *tile = tiles + wave * Tile<DT>::CHUNKS;
   for (int64_t r0 = s0 + (int64_t)wave * TR; r0 < s1; r0 += 4 * TR) {
     const int nr = (int)min((int64_t)TR, s1 - r0);
     // rows past the end of a ragged last tile re-read its last row (kept in bounds, never gathered)
@@ -386,7 +401,7 @@ __device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, u32x
 #pragma unroll
     for (int j = 0; j < NLD; ++j) r[j] = ld_stream(tsrc + min(j * kWave + lane, cmax));
 #pragma unroll
-    for (int j = 0; j < NLD; ++j) tile[j * kWave + lane] = r[j];
+    for (int j = 0; j < NLD; ++j) tile[Tile<DT>::slot(j * kWave + lane)] = r[j];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");

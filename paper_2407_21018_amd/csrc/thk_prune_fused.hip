@@ -281,7 +281,7 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   __syncthreads();
   if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
 
-  compact_build_tab(tab, s_idx, a.T);
+  compact_build_tab<DT>(tab, s_idx, a.T);
   __syncthreads();
   const int64_t s1c = min(s1, a.S_keep);   // rows past S_keep stay at full width with the caller
   if (s0 < s1c)
@@ -319,7 +319,7 @@ void k_prune_onepass(PruneFusedArgs a) {
   const int64_t s0 = (int64_t)blk * a.RB;   // a.RB == 128 * NTW
   const int64_t s1 = min(a.S, s0 + a.RB);
   const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
-  u32x4 *wtile = tiles + (size_t)wave * NLT * (TR * CPR);   // this wave's NLT tiles
+  u32x4 *wtile = tiles + (size_t)wave * NLT * Tile<DT>::CHUNKS;   // this wave's NLT tiles
 
   // tile n of this wave = rows s0 + (4 n + wave) * 32 .. + 32, nr of them inside [s0, hi)
   auto tile_row0 = [&](int n) { return s0 + (int64_t)(4 * n + wave) * TR; };
@@ -368,7 +368,7 @@ void k_prune_onepass(PruneFusedArgs a) {
       const bool valid = (j * kWave + lane) / CPR < nr;
 #pragma unroll
       for (int v = 0; v < VEC; ++v) facc[v] = valid ? fmaf(f[v], f[v], facc[v]) : facc[v];
-      if (n >= NRT) wtile[(size_t)(n - NRT) * (TR * CPR) + j * kWave + lane] = r[n][j];
+      if (n >= NRT) wtile[(size_t)(n - NRT) * Tile<DT>::CHUNKS + Tile<DT>::slot(j * kWave + lane)] = r[n][j];
     }
 #pragma unroll
     for (int v = 0; v < VEC; ++v) dacc[v] += (double)facc[v];
@@ -387,14 +387,14 @@ void k_prune_onepass(PruneFusedArgs a) {
   if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
 
   // ---- compaction: the LDS tiles first, then the register tiles through slot 0 ---------------
-  compact_build_tab(tab, s_idx, a.T);
+  compact_build_tab<DT>(tab, s_idx, a.T);
   __syncthreads();
   const int64_t s1c = min(s1, a.S_keep);
   u32x4 *dst = (u32x4 *)((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
 #pragma unroll
   for (int n = NRT; n < NTW; ++n) {
     const int nr = tile_rows(n, s1c);
-    if (nr > 0) compact_emit_tile<DT>(wtile + (size_t)(n - NRT) * (TR * CPR), dst, tile_row0(n), nr, a.T, tab, lane);
+    if (nr > 0) compact_emit_tile<DT>(wtile + (size_t)(n - NRT) * Tile<DT>::CHUNKS, dst, tile_row0(n), nr, a.T, tab, lane);
   }
 #pragma unroll
   for (int n = 0; n < NRT; ++n) {
@@ -403,7 +403,7 @@ void k_prune_onepass(PruneFusedArgs a) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();       // the slot's previous tile has been read
 #pragma unroll
-      for (int j = 0; j < NLD; ++j) wtile[j * kWave + lane] = r[n][j];
+      for (int j = 0; j < NLD; ++j) wtile[Tile<DT>::slot(j * kWave + lane)] = r[n][j];
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -448,9 +448,9 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
       kss = half[0] + half[1];
     }
     score_and_select(a, u, tid < kD ? a.qn[(size_t)u * kD + tid] : 0.0, kss, s_sc, s_idx, s_scratch, true);
-    compact_build_tab(tab, s_idx, a.T);
+    compact_build_tab<DT>(tab, s_idx, a.T);
   } else {
-    compact_build_tab(tab, a.idx + (size_t)u * a.T, a.T);
+    compact_build_tab<DT>(tab, a.idx + (size_t)u * a.T, a.T);
   }
   __syncthreads();
   const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
@@ -518,7 +518,7 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
   a.idx_pub = (uint32_t *)w; w += (size_t)U * kWave * sizeof(uint32_t);
   a.done = (unsigned char *)w;
   a.S = S; a.S_keep = S_keep; a.kp_unit_rows = kp_unit_rows; a.RB = RB; a.T = T; a.G = G; a.S_obs = S_obs; a.NB = NB; a.spin_limit = spin_limit;
-  const size_t lds = 2048 + 4 * (size_t)kCompactTileRows * kD * eb;
+  const size_t lds = 2048 + 4 * compact_tile_bytes(eb);
   const dim3 gu((unsigned)U), gi((unsigned)(U * NB));
   // hold == 0: the re-reading form; otherwise RB == 128 * hold and the rows are held on chip
   const void *main_fn = nullptr;
@@ -538,7 +538,7 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
     }
   }
   if (main_fn == nullptr || (hold != 0 && RB != 128 * hold)) return hipErrorInvalidValue;
-  const size_t lds_main = 2048 + 4 * (size_t)nlt * kCompactTileRows * kD * eb;
+  const size_t lds_main = 2048 + 4 * (size_t)nlt * compact_tile_bytes(eb);
   if (lds_main > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(main_fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_main);
     if (e != hipSuccess) return e;
