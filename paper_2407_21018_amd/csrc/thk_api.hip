@@ -79,16 +79,25 @@ Split score_split(const thk_shape *s, int64_t units) {
 
 int group_width(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
 
+// Query heads that share a block of the decode kernel the shape takes.
+int decode_heads_per_block(const thk_shape *s) {
+  DecodeArgs a = {};
+  a.T = s->T; a.ldk = ld_of(s); a.N_q = s->N_q; a.N_kv = s->N_kv; a.dtype = s->dtype;
+  return decode_mq_serves(a) ? decode_mq_heads(a) : group_width(s->N_q / s->N_kv);
+}
+
 Split decode_split(const thk_shape *s) {
   int n = s->n_split;
   const int G = s->N_q / s->N_kv;
-  const int64_t wgs = units_of(s) * (G / group_width(G));
+  const int64_t wgs = units_of(s) * (G / decode_heads_per_block(s));
   if (n == 0) {
     // about one resident set of blocks (4 per compute unit) over the call, a power of two
     // pieces per unit, each at least 256 rows; big calls still get two pieces per unit so
     // that the last blocks to finish are short
     n = 1;
-    while ((int64_t)n * 2 * wgs <= (int64_t)kCUs * 4 && n < 64) n *= 2;   // the merge grows with n
+    // (3 per compute unit where a block serves eight heads)
+    const int per_cu = decode_heads_per_block(s) == 8 ? 3 : 4;
+    while ((int64_t)n * 2 * wgs <= (int64_t)kCUs * per_cu && n < 64) n *= 2;   // the merge grows with n
     if (n == 1 && s->S >= 2048) n = 2;
     const int64_t cap = ceil_div(s->S, 256);
     if (n > cap) n = (int)cap;

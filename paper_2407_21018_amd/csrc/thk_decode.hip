@@ -19,7 +19,7 @@ hipError_t decode_kv_launch_f32_g1(const DecodeArgs &, int, hipStream_t);
 hipError_t decode_kv_launch_f32_g2(const DecodeArgs &, int, hipStream_t);
 hipError_t decode_kv_launch_f32_g4(const DecodeArgs &, int, hipStream_t);
 // four query heads per KV head on the matrix cores (bf16, full-width values)
-hipError_t decode_mq_launch(const DecodeArgs &, int, hipStream_t);
+hipError_t decode_mq_launch(const DecodeArgs &, hipStream_t);
 
 // Merge of the per-split states: m = max m_i, l = sum l_i 2^(m_i - m),
 // acc = sum acc_i 2^(m_i - m), out = acc / l.  One block of 128 * PG threads per query head:
@@ -99,7 +99,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st) {
   hipError_t e;
   profile_mark(true, st);
   if (decode_mq_serves(a))
-    e = decode_mq_launch(a, groups, st);
+    e = decode_mq_launch(a, st);
   else if (a.T_v > 0 && a.dtype == THK_BF16)
     e = gt == 4 ? decode_kv_launch_bf16_g4(a, groups, st)
                 : gt == 2 ? decode_kv_launch_bf16_g2(a, groups, st) : decode_kv_launch_bf16_g1(a, groups, st);

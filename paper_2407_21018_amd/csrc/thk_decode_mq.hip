@@ -1,5 +1,5 @@
-// Decode attention over the pruned key cache for bf16 caches whose KV heads serve four query
-// heads each (Sec. 3.3, Fig. 2; attention formula of Sec. 3.2) -- gfx950, wave64.
+// Decode attention over the pruned key cache for bf16 caches whose KV heads serve a multiple of
+// four query heads each (Sec. 3.3, Fig. 2; attention formula of Sec. 3.2) -- gfx950, wave64.
 //
 // With four query heads per key row the two products of a tile are skinny matrix products
 // (4 x T by T x 32, then 4 x 32 by 32 x 128) and go to the matrix cores as batches of 4 x 4
@@ -28,6 +28,8 @@
 //            are staged like the key bytes, as a flat range, and the same transposing reads walk
 //            them with the row pitch ld_v; lane l then sums kept channels l and 64 + l, which
 //            are scattered to their output channels at the end.  The tail keeps full-width rows.
+//   NH = 2   eight query heads per KV head in one block: two groups of four share every key
+//            and value operand read from LDS; queries, probabilities and accumulators double.
 #include <stdlib.h>
 
 #include "thk_decode_impl.h"
@@ -80,35 +82,44 @@ __device__ __forceinline__ void mq_v_commit(const u32x4 (&vr)[kMqVChunks], char 
   for (int j = 0; j < kMqVChunks; ++j) *(u32x4 *)(slab + (4 * j + rsub) * 256 + col * 16) = vr[j];
 }
 
-// Logits of a tile whose key bytes are in the slab.  nch: 4-channel chunks per row; qrow: this
-// lane's head as packed bf16, zero from chunk nch on.  Returns, in both halves of the wave, the
-// dot products of rows 4 ((lane / 4) % 8) + r, r = 0 .. 3, with head lane % 4.
-__device__ __forceinline__ f32x4 mq_logits(const char *slab, int shift, int nrows, int nch, int pitch_bytes,
-                                           const uint32_t *qrow, int lane) {
+// Logits of a tile whose key bytes are in the slab, for NH groups of four heads.  nch:
+// 4-channel chunks per row; qrow: this lane's head of the first group as packed bf16, zero from
+// chunk nch on (the same head of the next group follows 4 * kQS / 2 words later).  d[g] receives,
+// in both halves of the wave, the dot products of rows 4 ((lane / 4) % 8) + r, r = 0 .. 3, with
+// head 4 g + lane % 4: the key operand is read once for all groups.
+template <int NH>
+__device__ __forceinline__ void mq_logits(const char *slab, int shift, int nrows, int nch, int pitch_bytes,
+                                          const uint32_t *qrow, int lane, f32x4 (&d)[NH]) {
   const int b = lane >> 2, x = lane & 3, half = b >> 3, bb = b & 7;
   const char *rowp = slab + shift + min(4 * bb + x, nrows - 1) * pitch_bytes;
-  const int nst = (nch + 1) >> 1;          // chunks per half = matrix instructions
+  const int nst = (nch + 1) >> 1;          // chunks per half = matrix instructions per group
   int rel = bb % nst;
-  f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
-  auto step = [&](f32x4 &d) {
+  f32x4 d0[NH], d1[NH];
+#pragma unroll
+  for (int g = 0; g < NH; ++g) {
+    d0[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+    d1[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  auto step = [&](f32x4 (&acc)[NH]) {
     const int c = half * nst + rel;
     // a chunk past the row's end: the row's first chunk against the zero chunk of the query
     const bool valid = c < nch;
     const s16x4 ka = *(const s16x4 *)(rowp + (valid ? c : 0) * 8);
-    const s16x4 qb = *(const s16x4 *)((const char *)qrow + (valid ? c : nch) * 8);
-    d = mfma4(ka, qb, d);
+    const char *qp = (const char *)qrow + (valid ? c : nch) * 8;
+#pragma unroll
+    for (int g = 0; g < NH; ++g) acc[g] = mfma4(ka, *(const s16x4 *)(qp + g * 4 * (kQS / 2) * 4), acc[g]);
     rel = rel + 1 == nst ? 0 : rel + 1;
   };
   int ks = 0;
   for (; ks + 2 <= nst; ks += 2) { step(d0); step(d1); }
   if (ks < nst) step(d0);
-  f32x4 d;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const float t = d0[r] + d1[r];
-    d[r] = t + __shfl_xor(t, 32);
-  }
-  return d;
+  for (int g = 0; g < NH; ++g)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float t = d0[g][r] + d1[g][r];
+      d[g][r] = t + __shfl_xor(t, 32);
+    }
 }
 
 // Running softmax over the tile's logits; the probabilities go to pline as two bf16 terms:
@@ -154,8 +165,11 @@ __device__ __forceinline__ void mq_softmax(const f32x4 &d, int nrows, float scal
   *(uint2 *)(pline + lane * 8) = w;
 }
 
-// acc += P . V for the tile whose value rows are in the slab and probabilities in pline.
-__device__ __forceinline__ void mq_values(const char *slab, const char *pline, int nrows, MqState &st, int lane) {
+// acc += P . V for the tile whose value rows are in the slab; the probabilities of head group g
+// are in the 512 bytes at pline + 512 g.  The value operand is read once for all groups.
+template <int NH>
+__device__ __forceinline__ void mq_values(const char *slab, const char *pline, int nrows, MqState (&st)[NH],
+                                          int lane) {
   const int x = lane & 3, grp = lane >> 4, j = lane & 15, r = j >> 2, seg = j & 3;
   const int cc = 2 * grp + (seg >> 1), swz = (r & 1) << 3;
   const char *vb0 = slab + r * 256 + ((cc ^ swz) << 4) + (seg & 1) * 8;        // channels 0 .. 63
@@ -165,44 +179,68 @@ __device__ __forceinline__ void mq_values(const char *slab, const char *pline, i
 #pragma unroll
   for (int ks = 0; ks < kMqRows / 4; ++ks) {
     if (ks < nks) {
-      const s16x4 a_hi = *(const s16x4 *)(pa + ks * 32), a_lo = *(const s16x4 *)(pa + 256 + ks * 32);
       const s16x4 b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
           (__attribute__((address_space(3))) s16x4 *)(vb0 + ks * 1024));
       const s16x4 b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
           (__attribute__((address_space(3))) s16x4 *)(vb1 + ks * 1024));
-      st.acc[0] = mfma4(a_hi, b0, st.acc[0]);
-      st.acc[1] = mfma4(a_hi, b1, st.acc[1]);
-      st.acc[0] = mfma4(a_lo, b0, st.acc[0]);
-      st.acc[1] = mfma4(a_lo, b1, st.acc[1]);
+      s16x4 a_hi[NH], a_lo[NH];
+#pragma unroll
+      for (int g = 0; g < NH; ++g) {
+        a_hi[g] = *(const s16x4 *)(pa + g * 512 + ks * 32);
+        a_lo[g] = *(const s16x4 *)(pa + g * 512 + 256 + ks * 32);
+      }
+#pragma unroll
+      for (int g = 0; g < NH; ++g) {
+        st[g].acc[0] = mfma4(a_hi[g], b0, st[g].acc[0]);
+        st[g].acc[1] = mfma4(a_hi[g], b1, st[g].acc[1]);
+      }
+#pragma unroll
+      for (int g = 0; g < NH; ++g) {
+        st[g].acc[0] = mfma4(a_lo[g], b0, st[g].acc[0]);
+        st[g].acc[1] = mfma4(a_lo[g], b1, st[g].acc[1]);
+      }
     }
   }
 }
 
 // accp += P . V_pruned for the tile whose value bytes sit in the slab as staged (first row at
 // byte `shift`, rows pitch_bytes apart).  A read past a row's T_v channels lands in the next row,
-// or within the 512 bytes that follow every slab, and only feeds kept-channel numbers >= T_v,
+// or within the bytes that follow every slab, and only feeds kept-channel numbers >= T_v,
 // which nobody collects; a row past a ragged tile's end is read as the tile's last row, with
 // probability 0.
+template <int NH>
 __device__ __forceinline__ void mq_values_pruned(const char *slab, int shift, int pitch_bytes, int T_v,
-                                                 const char *pline, int nrows, MqState &st, int lane) {
+                                                 const char *pline, int nrows, MqState (&st)[NH], int lane) {
   const int x = lane & 3, grp = lane >> 4, j = lane & 15, r = j >> 2, seg = j & 3;
   const char *vb = slab + shift + (16 * grp + 4 * seg) * 2;
   const char *pa = pline + x * 8;
   const int nks = (nrows + 3) >> 2;
   const bool wide = T_v > 64;
-  for (int ks = 0; ks < nks; ++ks) {
+#pragma unroll
+  for (int ks = 0; ks < kMqRows / 4; ++ks) {
+    if (ks >= nks) break;
     const char *vrow = vb + min(4 * ks + r, nrows - 1) * pitch_bytes;
-    const s16x4 a_hi = *(const s16x4 *)(pa + ks * 32), a_lo = *(const s16x4 *)(pa + 256 + ks * 32);
     const s16x4 b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vrow));
-    st.accp[0] = mfma4(a_hi, b0, st.accp[0]);
+    s16x4 a_hi[NH], a_lo[NH];
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+      a_hi[g] = *(const s16x4 *)(pa + g * 512 + ks * 32);
+      a_lo[g] = *(const s16x4 *)(pa + g * 512 + 256 + ks * 32);
+      st[g].accp[0] = mfma4(a_hi[g], b0, st[g].accp[0]);
+    }
     if (wide) {
       const s16x4 b1 =
           __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vrow + 128));
-      st.accp[1] = mfma4(a_hi, b1, st.accp[1]);
-      st.accp[0] = mfma4(a_lo, b0, st.accp[0]);
-      st.accp[1] = mfma4(a_lo, b1, st.accp[1]);
+#pragma unroll
+      for (int g = 0; g < NH; ++g) st[g].accp[1] = mfma4(a_hi[g], b1, st[g].accp[1]);
+#pragma unroll
+      for (int g = 0; g < NH; ++g) {
+        st[g].accp[0] = mfma4(a_lo[g], b0, st[g].accp[0]);
+        st[g].accp[1] = mfma4(a_lo[g], b1, st[g].accp[1]);
+      }
     } else {
-      st.accp[0] = mfma4(a_lo, b0, st.accp[0]);
+#pragma unroll
+      for (int g = 0; g < NH; ++g) st[g].accp[0] = mfma4(a_lo[g], b0, st[g].accp[0]);
     }
   }
 }
@@ -210,17 +248,19 @@ __device__ __forceinline__ void mq_values_pruned(const char *slab, int shift, in
 // KB: 16-byte key chunks a lane may have to stage for one tile.  slab_bytes: the wave's LDS slab,
 // which holds a tile's key bytes and, once the logits are done, its value rows.
 // VP = 1: the value rows of the pruned segment are channel-pruned (a.v = V_pruned, a.ld_v, a.idx_v).
-template <int KB, int WPE, int VP>
+// NH: groups of four query heads served by one block (1, or 2 when N_q / N_kv is a multiple of 8:
+// the key and value operands are then read from LDS once for eight heads).
+template <int KB, int WPE, int VP, int NH>
 __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups, int slab_bytes) {
-  constexpr int DT = THK_BF16, GT = 4, EB = 2, TR = kMqRows, LPR = 16;
+  constexpr int DT = THK_BF16, GT = 4 * NH, EB = 2, TR = kMqRows, LPR = 16;
   constexpr int KBT = kTailRows * kD * EB / 16 / kWave;   // chunks per lane of a tail tile
   extern __shared__ uint4 smem[];
   uint32_t *qkp = (uint32_t *)smem;                 // [GT][kQS/2] kept query channels, packed bf16, 0 beyond T
   uint32_t *qfp = qkp + GT * (kQS / 2);             // [GT][kQS/2] full query
   char *wbase = (char *)(qfp + GT * (kQS / 2));
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-  char *slab = wbase + (size_t)wave * (slab_bytes + 512);
-  char *pline = slab + slab_bytes;
+  char *slab = wbase + (size_t)wave * (slab_bytes + 512 * NH);
+  char *pline = slab + slab_bytes;               // 512 bytes of probabilities per head group
 
   const int sp = (int)(blockIdx.x % a.n_split);
   const int64_t ug = blockIdx.x / a.n_split;
@@ -267,13 +307,16 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
   }
   __syncthreads();
 
-  MqState st;
-  st.m = -INFINITY;
-  st.l = 0.f;
+  MqState st[NH];
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    st.acc[h] = f32x4{0.f, 0.f, 0.f, 0.f};
-    st.accp[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int g = 0; g < NH; ++g) {
+    st[g].m = -INFINITY;
+    st[g].l = 0.f;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      st[g].acc[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+      st[g].accp[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
   }
   const int x = lane & 3;
   const int pitch_bytes = a.ldk * EB, nch = a.T >> 2;
@@ -289,8 +332,10 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
     if (more)
       shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)(ti + 4) * TR) * a.ldk * EB, nr4, a.T, a.ldk, lane);
     wave_sync_lds();
-    const f32x4 d = mq_logits(slab, shift, nrows, nch, pitch_bytes, qkp + x * (kQS / 2), lane);
-    mq_softmax<VP>(d, nrows, a.scale_log2, st, pline, lane);
+    f32x4 d[NH];
+    mq_logits<NH>(slab, shift, nrows, nch, pitch_bytes, qkp + x * (kQS / 2), lane, d);
+#pragma unroll
+    for (int g = 0; g < NH; ++g) mq_softmax<VP>(d[g], nrows, a.scale_log2, st[g], pline + 512 * g, lane);
     wave_sync_lds();   // the key bytes are consumed: the slab takes the value rows
     if constexpr (VP) {
       const int vs = vshift;
@@ -299,12 +344,12 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
         vshift = k_issue<DT, KB>(vrp, (const char *)a.v, (krow0 + (size_t)(ti + 4) * TR) * a.ld_v * EB, nr4, a.T_v,
                                  a.ld_v, lane);
       wave_sync_lds();
-      mq_values_pruned(slab, vs, a.ld_v * EB, a.T_v, pline, nrows, st, lane);
+      mq_values_pruned<NH>(slab, vs, a.ld_v * EB, a.T_v, pline, nrows, st, lane);
     } else {
       mq_v_commit(vr, slab, lane);
       if (more) mq_v_issue(vr, vbase + (size_t)(ti + 4) * TR * LPR, nr4, lane);
       wave_sync_lds();
-      mq_values(slab, pline, nrows, st, lane);
+      mq_values<NH>(slab, pline, nrows, st, lane);
     }
     wave_sync_lds();   // slab and pline are rewritten by the next tile
   }
@@ -322,29 +367,34 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
     mq_v_issue(vr, vg, nrows, lane);
     k_commit<KBT>(kt, slab, lane);
     wave_sync_lds();
-    const f32x4 d = mq_logits(slab, 0, nrows, kD / 4, kD * EB, qfp + x * (kQS / 2), lane);
-    mq_softmax<VP>(d, nrows, a.scale_log2, st, pline, lane);
+    f32x4 d[NH];
+    mq_logits<NH>(slab, 0, nrows, kD / 4, kD * EB, qfp + x * (kQS / 2), lane, d);
+#pragma unroll
+    for (int g = 0; g < NH; ++g) mq_softmax<VP>(d[g], nrows, a.scale_log2, st[g], pline + 512 * g, lane);
     wave_sync_lds();
     mq_v_commit(vr, slab, lane);
     wave_sync_lds();
-    mq_values(slab, pline, nrows, st, lane);
+    mq_values<NH>(slab, pline, nrows, st, lane);
     wave_sync_lds();
   }
 
   // ---- wave state -> LDS: [GT][130] floats at the start of the wave's own slab -------------
   {
     float *mrg = (float *)slab;
-    const float lt = quad_column_reduce<false>(st.l);   // both halves of the wave saw every row
-    if (lane < GT) {
-      float *rec = mrg + lane * (kD + 2);
-      rec[0] = st.m;
-      rec[1] = lt;
-    }
 #pragma unroll
-    for (int i = 0; i < GT; ++i) {
-      float *rec = mrg + i * (kD + 2) + 2;
-      rec[lane] = st.acc[0][i];
-      rec[64 + lane] = st.acc[1][i];
+    for (int g = 0; g < NH; ++g) {
+      const float lt = quad_column_reduce<false>(st[g].l);   // both halves of the wave saw every row
+      if (lane < 4) {
+        float *rec = mrg + (4 * g + lane) * (kD + 2);
+        rec[0] = st[g].m;
+        rec[1] = lt;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float *rec = mrg + (4 * g + i) * (kD + 2) + 2;
+        rec[lane] = st[g].acc[0][i];
+        rec[64 + lane] = st[g].acc[1][i];
+      }
     }
     if constexpr (VP) {
       // the sums over the pruned rows go to their channels (distinct for distinct kept numbers)
@@ -356,29 +406,32 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
         if (t < a.T_v) {
           const int c = uidv[t];
 #pragma unroll
-          for (int i = 0; i < GT; ++i) mrg[i * (kD + 2) + 2 + c] += st.accp[h][i];
+          for (int g = 0; g < NH; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mrg[(4 * g + i) * (kD + 2) + 2 + c] += st[g].accp[h][i];
         }
       }
     }
   }
   __syncthreads();
-  block_merge_store<DT, GT>((const float *)wbase, (slab_bytes + 512) / 4, a, bn0, sp);
+  block_merge_store<DT, GT>((const float *)wbase, (slab_bytes + 512 * NH) / 4, a, bn0, sp);
 }
 
-// Four blocks per compute unit with the narrow staging class (37 KB of LDS and at most 128
-// registers per lane each), three with the wide one.
-template <int KB, int VP>
+// Four blocks per compute unit with the narrow staging class and four heads per block (37 KB of
+// LDS and at most 128 registers per lane each), two with the wide class and eight heads, three
+// otherwise.
+template <int KB, int VP, int NH>
 static hipError_t mq_launch(const DecodeArgs &a, int groups, hipStream_t st) {
-  constexpr int WPE = KB <= 5 ? 4 : 3;
+  constexpr int WPE = (KB <= 5 && NH == 1) ? 4 : (KB > 5 && NH == 2) ? 2 : 3;
   const int slab = KB * kWave * 16 > kMqVBytes ? KB * kWave * 16 : kMqVBytes;
-  const size_t lds = (size_t)(2 * 4 * (kQS / 2)) * 4 + 4 * ((size_t)slab + 512);
+  const size_t lds = (size_t)(2 * 4 * NH * (kQS / 2)) * 4 + 4 * ((size_t)slab + 512 * NH);
   const dim3 grid((unsigned)(a.units * groups * a.n_split)), block(256);
   if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void *)k_decode_mq<KB, WPE, VP>,
+    hipError_t e = hipFuncSetAttribute((const void *)k_decode_mq<KB, WPE, VP, NH>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((k_decode_mq<KB, WPE, VP>), grid, block, lds, st, a, groups, slab);
+  hipLaunchKernelGGL((k_decode_mq<KB, WPE, VP, NH>), grid, block, lds, st, a, groups, slab);
   return hipGetLastError();
 }
 
@@ -407,10 +460,20 @@ bool decode_mq_serves(const DecodeArgs &a) {
   return !(env && env[0] == '0');
 }
 
-hipError_t decode_mq_launch(const DecodeArgs &a, int groups, hipStream_t st) {
+// Query heads per block: eight when the KV heads serve a multiple of eight, else four.
+int decode_mq_heads(const DecodeArgs &a) { return (a.N_q / a.N_kv) % 8 == 0 ? 8 : 4; }
+
+hipError_t decode_mq_launch(const DecodeArgs &a, hipStream_t st) {
   const bool narrow = mq_chunks(a) <= 5;
-  if (a.T_v > 0) return narrow ? mq_launch<5, 1>(a, groups, st) : mq_launch<9, 1>(a, groups, st);
-  return narrow ? mq_launch<5, 0>(a, groups, st) : mq_launch<9, 0>(a, groups, st);
+  const int G = a.N_q / a.N_kv;
+  if (decode_mq_heads(a) == 8) {
+    const int groups = G / 8;
+    if (a.T_v > 0) return narrow ? mq_launch<5, 1, 2>(a, groups, st) : mq_launch<9, 1, 2>(a, groups, st);
+    return narrow ? mq_launch<5, 0, 2>(a, groups, st) : mq_launch<9, 0, 2>(a, groups, st);
+  }
+  const int groups = G / 4;
+  if (a.T_v > 0) return narrow ? mq_launch<5, 1, 1>(a, groups, st) : mq_launch<9, 1, 1>(a, groups, st);
+  return narrow ? mq_launch<5, 0, 1>(a, groups, st) : mq_launch<9, 0, 1>(a, groups, st);
 }
 
 }  // namespace thk

@@ -122,6 +122,7 @@ struct DecodeArgs {
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t st);
 // the shape runs on the matrix-core kernel (needs dtype, T, ldk, N_q, N_kv, T_v, ld_v of a)
 bool decode_mq_serves(const DecodeArgs &a);
+int decode_mq_heads(const DecodeArgs &a);   // query heads per block of that kernel: 4 or 8
 
 hipError_t launch_tail_append(int dtype, const void *k_new, const void *v_new, void *k_dst, void *v_dst,
                               int64_t U, int64_t k_unit_rows, int64_t k_row, int64_t v_unit_rows,

@@ -212,8 +212,15 @@ def test_decode_kernel_choice_by_shape(monkeypatch):
     assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16), 51, 52) == 1  # channel-pruned values
     assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16), 51, 51) == 0  # invalid pitch (below the ABI's multiple of 4)
     assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16), 200, 200) == 0
+    # eight heads per block when the KV heads serve a multiple of eight: one block per unit and
+    # split, three resident blocks per compute unit
+    s8 = thk.make_shape(1, 8, 64, 8, 128, 32768, 1, 76, 0, thk.THK_BF16, 0)
+    s4 = thk.make_shape(1, 8, 32, 8, 128, 32768, 1, 76, 0, thk.THK_BF16, 0)
+    assert thk.thk_default_split(s8, thk.THK_OP_DECODE) == 8      # 64 units x 8 = 512 blocks <= 768
+    assert thk.thk_default_split(s4, thk.THK_OP_DECODE) == 16     # 64 units x 16 = 1024 blocks
     monkeypatch.setenv("THK_DECODE_MFMA", "0")
     assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16)) == 0
+    assert thk.thk_default_split(s8, thk.THK_OP_DECODE) == 8      # two blocks of four heads per unit and split
 
 
 def test_plain_c_program_uses_the_boundary(tmp_path):

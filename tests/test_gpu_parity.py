@@ -145,6 +145,11 @@ DECODE_CASES = [
     (1, 1, 4, 200, 124, 0, 0, 2, 4, 1.0),      # 248-byte rows: 8-byte aligned only
     (1, 1, 4, 200, 128, 132, 2, 0, 0, 1.0),    # the widest tile the staging holds
     (1, 2, 4, 555, 64, 128, 0, 5, 8, 0.0),     # kept channels at the front of full-width rows
+    # eight query heads per KV head share one block (and every key / value byte)
+    (1, 1, 16, 700, 76, 0, 0, 3, 8, 1.0),      # two blocks of eight heads
+    (1, 2, 12, 400, 64, 0, 0, 0, 0, 1.0),      # 12 heads: three blocks of four
+    (1, 1, 8, 333, 128, 132, 2, 5, 16, 1.0),   # the widest staging class
+    (2, 2, 8, 4133, 76, 0, 0, 40, 64, 0.0),
 ]
 
 

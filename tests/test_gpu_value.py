@@ -175,6 +175,8 @@ DECODE_CASES = [
     ("bf16", 4, 500, 76, 100, 104, 0, 0, 0),
     ("bf16", 4, 31, 64, 64, 64, 0, 0, 1),       # one ragged tile
     ("bf16", 8, 1300, 64, 76, 76, 33, 64, 2),
+    ("bf16", 8, 300, 128, 100, 128, 2, 4, 0),   # eight heads per block, the widest staging class
+    ("bf16", 16, 900, 76, 51, 52, 0, 0, 3),
     ("f32", 1, 1037, 64, 64, 64, 0, 0, 0),
     ("f32", 4, 900, 76, 51, 52, 9, 16, 4),
     ("f32", 2, 333, 51, 128, 128, 0, 0, 1),
