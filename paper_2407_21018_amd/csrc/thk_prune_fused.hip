@@ -9,6 +9,9 @@
 //      runs the Top_T selection and publishes the index list; the other blocks
 //      of the unit wait for the list (bounded spin);
 //   C. every block compacts ITS OWN rows with the published index list.
+// Units of more than 64 blocks do B differently: the last block of each GROUP of blocks merges
+// the group's partials and publishes the group vector (words with their own validity mark);
+// every block then reads the unit's group vectors and makes scores and index list for itself.
 // Two forms: k_prune_onepass keeps the block's rows on chip (registers and the
 // LDS tiles) from A to C, so K is read from memory once; k_prune_fused streams
 // the rows in A and reads them again in C (any block size; the second read comes
