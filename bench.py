@@ -299,7 +299,8 @@ def main():
     kernels = {
         prune_kernel: {"launches_per_step": 1, "avg_us": prune_k_us, "bytes_per_launch": prune_kernel_bytes,
                        "GBps": prune_kernel_bytes / prune_k_us / 1e3},
-        decode_kernel: {"launches_per_step": n_dec, "avg_us": dec_k_us, "bytes_per_launch": decode_bytes,
+        decode_kernel: {"launches_per_step": n_dec, "avg_us": dec_k_us, "max_us": max(dec_kernel_us),
+                        "timed_launches": len(dec_kernel_us), "bytes_per_launch": decode_bytes,
                         "GBps": decode_bytes / dec_k_us / 1e3},
     }
     # the dominant kernel = most time inside a step
