@@ -195,15 +195,21 @@ PRUNE_CASES = [("bf16", 1, 2048, 76, 1.5), ("bf16", 4, 4096 + 64, 64, 1.0), ("f3
                ("bf16", 1, 1024, 51, 2.0), ("f32", 2, 2048, 64, 1.0), ("bf16", 1, 40, 64, 1.0)]
 
 
-def test_prune_fused_repeated_calls_on_one_workspace(monkeypatch):
-    """The one-launch form hands the index list from the block that selects to the blocks
-    that wait through the workspace.  Calls that alternate between two inputs on the SAME
-    workspace leave the other input's list behind each time: a block that picked up a stale
-    list (or a list that had not fully arrived) would compact the wrong channels.  Checked
+@pytest.mark.parametrize("levels", [1, 2])
+def test_prune_fused_repeated_calls_on_one_workspace(levels, monkeypatch):
+    """The one-launch form hands sums and index lists from block to block through the
+    workspace (one level: the last block's list to the blocks that wait; two levels: the group
+    vectors to every block of the unit).  Calls that alternate between two inputs on the SAME
+    workspace leave the other input's words behind each time: a block that picked up stale
+    words (or words that had not fully arrived) would compact the wrong channels.  Checked
     on the GPU against a plain gather with the index list the call returned, and against the
     oracle's list for the first call of each input."""
     monkeypatch.setenv("THK_PRUNE_PATH", "fused")
-    L, B, N, S, S_obs, T = 4, 4, 16, 4096, 32, 76
+    if levels == 1:
+        L, B, N, S, S_obs, T = 4, 4, 16, 4096, 32, 76
+    else:                                          # 102 blocks of 128 rows per unit
+        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", "128")
+        L, B, N, S, S_obs, T = 1, 3, 4, 13008, 32, 64
     U = L * B * N
     shape = thk.make_shape(L, B, N, N, D, S, S_obs, T, 0, thk.THK_BF16, 0)
     assert thk.thk_prune_is_fused(shape) == 2      # the form that keeps the rows on chip
