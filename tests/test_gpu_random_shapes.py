@@ -127,3 +127,27 @@ def test_prune_random_shapes(case, monkeypatch):
     # compaction is judged with the list the call returned: bit-exact gather
     want = O.compact_keys(as_numpy(k).reshape(U, S, D), idx.cpu().numpy(), dtype)
     np.testing.assert_array_equal(as_numpy(kp), want)
+
+
+def _value_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        dtype = "bf16" if rng.random() < 0.75 else "f32"
+        G = int(rng.choice([1, 1, 2, 3, 4, 8]))
+        # at least 8 query rows per channel norm: with one or two rows the score is a bare signed sum
+        # and the median criterion of the bf16 check (made for norms over many rows) does not apply
+        S = int(rng.choice([int(rng.integers(8, 200)), int(rng.integers(200, 3000))]))
+        S_obs = int(min(S, rng.choice([8, 16, 32, 64])))
+        n_split = int(rng.choice([0, 0, 1, 2, 4]))
+        causal = int(rng.integers(0, 2))
+        sigma = float(rng.choice([0.0, 0.5, 1.0]))
+        out.append((dtype, G, S_obs, S, n_split, causal, sigma))
+    return out
+
+
+@pytest.mark.parametrize("case", _value_shapes(20, 20240724), ids=lambda c: "-".join(map(str, c)))
+def test_value_score_random_shapes(case):
+    from test_gpu_value import test_value_score_matches_oracle
+    dtype, G, S_obs, S, n_split, causal, sigma = case
+    test_value_score_matches_oracle(G, S_obs, S, n_split, causal, sigma, dtype)
