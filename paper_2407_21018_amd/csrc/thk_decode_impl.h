@@ -457,7 +457,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   const int64_t s0 = min(a.S, (int64_t)sp * a.rows_per_split);
   const int64_t s1 = min(a.S, s0 + a.rows_per_split);
   const int nt_p = (int)((s1 - s0 + TR - 1) / TR);
-  const int nt_t = (sp == a.n_split - 1) ? (a.s_tail + kTailRows - 1) / kTailRows : 0;
+  const int nt_t = (a.s_tail + kTailRows - 1) / kTailRows;   // tail tiles of the unit: tile j goes to split j % n_split
   const char *kpg = (const char *)a.kp;
 
   constexpr int NV = VS::NV;
@@ -537,7 +537,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   }
 
   // ---- unpruned tail segment (full-width keys, full query) ------------------
-  for (int ti = wave; ti < nt_t; ti += 4) {
+  for (int ti = sp + wave * a.n_split; ti < nt_t; ti += 4 * a.n_split) {
     const int j0 = ti * kTailRows;
     const int nrows = min(kTailRows, a.s_tail - j0);
     const size_t row0 = (size_t)u * a.s_tail_cap + j0;
