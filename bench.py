@@ -148,6 +148,14 @@ def measured_traffic(kernel):
     return None
 
 
+def device_facts(torch):
+    """What the runtime reports about the card the numbers were taken on."""
+    p = torch.cuda.get_device_properties(0)
+    return {"arch": p.gcnArchName, "compute_units": p.multi_processor_count, "wavefront": p.warp_size,
+            "lds_bytes_per_block_max": p.shared_memory_per_block, "l2_bytes_per_xcd": p.L2_cache_size,
+            "memory_bytes": p.total_memory}
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -333,6 +341,7 @@ def main():
         "host_wall_s": wall, "graph_ms_per_step": graph_ms,
         "kernels": kernels,
         "roofline": roof,
+        "device": device_facts(torch),
     }
     if not args.no_value_cache:
         res["value_cache"] = value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k, v, kp, idx, dec, kt, vt, out,

@@ -330,3 +330,12 @@ def test_tail_append():
         assert torch.equal(kt[:, j], kn) and torch.equal(vt[:, j], vn)
     with pytest.raises(thk.ThkError):
         thk.thk_tail_append(shape, news[0][0], news[0][1], kt, vt, cap, cap)
+
+
+def test_device_is_the_one_the_kernels_are_written_for():
+    """gfx950: 256 compute units, 64-wide wavefronts, 160 KB of LDS per workgroup at most."""
+    p = torch.cuda.get_device_properties(0)
+    assert p.gcnArchName.startswith("gfx950")
+    assert p.multi_processor_count == 256 and p.warp_size == 64
+    assert p.shared_memory_per_block == 160 * 1024
+    assert p.total_memory >= 256 * 2**30
