@@ -28,6 +28,10 @@ int main(void) {
   CHECK(thk_workspace_bytes(&s, THK_OP_SCORE_VALUE) > 0);
   CHECK(thk_default_split(&s, THK_OP_DECODE) >= 1);
   CHECK(thk_prune_is_fused(&s) == 2);
+  CHECK(thk_decode_on_matrix_cores(&s, 0, 0) == 0);   /* one query head per KV head: the general kernel */
+  s.N_kv = 8;
+  CHECK(thk_decode_on_matrix_cores(&s, 0, 0) == 1 && thk_decode_on_matrix_cores(&s, 51, 52) == 1);
+  s.N_kv = 32;
   /* argument errors come back synchronously, before anything touches a device */
   char fake[64] __attribute__((aligned(16)));
   CHECK(thk_score(NULL, fake, fake, (float *)fake, fake, 64, NULL) == THK_ERR_NULL);
