@@ -196,8 +196,8 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
  * multiple of 16, a single kernel does all three steps: a block takes 512 rows of
  * a unit (fewer for small calls), keeps them on chip while the unit's index list
  * is being decided, and compacts them from there, so K is read from memory once;
- * otherwise (and for units of more than 256 such blocks) the three kernels run one
- * after the other.  Scores agree with thk_score to fp64 summation order (the
+ * otherwise (and for units of more blocks than are resident on the chip at once:
+ * 768 blocks of 512 rows, S > 393216) the three kernels run one after the other.  Scores agree with thk_score to fp64 summation order (the
  * last float bit can differ).  `score` may be NULL (then it lives in ws).
  * Environment (read per call, for experiments and tests): THK_PRUNE_PATH =
  * staged | fused | reread (the one-kernel form with the rows read twice),

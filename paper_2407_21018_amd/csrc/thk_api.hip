@@ -3,6 +3,8 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "thk_internal.h"
 
 using namespace thk;
@@ -137,8 +139,9 @@ struct FusedPlan { bool ok; int NB; int64_t RB; int hold; };
 
 // The one-launch forms need the flat K_pruned layout (dense rows, 16-byte aligned units).
 // Their blocks take 512 rows each (measured best on MI355X; fewer for small calls) and the
-// blocks of a unit wait for each other; a unit may have up to 256 of them (above 64 they
-// arrive in two levels), longer sequences go through the staged path instead.
+// blocks of a unit wait for each other; a unit may have as many as are resident at once (768
+// of 512 rows; above 64 their sums travel in two levels), longer sequences go through the
+// staged path instead.
 FusedPlan fused_plan(const thk_shape *s) {
   FusedPlan p{false, 0, 0, 0};
   const char *path = getenv("THK_PRUNE_PATH");
@@ -162,8 +165,12 @@ FusedPlan fused_plan(const thk_shape *s) {
   const bool reread = path != nullptr && path[0] == 'r';
   if (!reread && (rb == 128 || rb == 256 || (rb == 512 && s->dtype == THK_BF16))) p.hold = (int)(rb / 128);
   const int64_t nb = ceil_div(s->S, rb);
-  const bool forced = path != nullptr && (path[0] == 'f' || path[0] == 'r');   // regardless of block count
-  if (nb > (forced ? 256 : env_long("THK_PRUNE_MAX_BLOCKS", 256))) return p;
+  // the blocks of a unit wait for each other, so all of them must be resident at once: three
+  // blocks of 512 held rows per compute unit, four of the smaller ones; 256 where the rows are
+  // read twice (the second read wants the unit's rows still in the memory-side cache)
+  const long fit = p.hold == 4 ? 3L * kCUs : p.hold != 0 ? 4L * kCUs : 256L;
+  const bool forced = path != nullptr && (path[0] == 'f' || path[0] == 'r');   // regardless of the env limit
+  if (nb > (forced ? fit : std::min(fit, env_long("THK_PRUNE_MAX_BLOCKS", fit)))) return p;
   p.RB = rb;
   p.NB = (int)nb;
   p.ok = units_of(s) * p.NB <= kMaxGrid;

@@ -187,7 +187,12 @@ def test_prune_plan_by_shape(monkeypatch):
     cfg2 = thk.make_shape(32, 4, 32, 32, 128, 4096, 32, 76, 0, thk.THK_BF16, 0)
     assert thk.thk_prune_is_fused(cfg2) == 2
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 131072, 64, 64, 0, thk.THK_BF16, 0)) == 2  # 256 blocks per unit
-    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 262144, 64, 64, 0, thk.THK_BF16, 0)) == 0  # 512 blocks per unit
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 262144, 64, 64, 0, thk.THK_BF16, 0)) == 2  # 512 blocks per unit
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 393216, 64, 64, 0, thk.THK_BF16, 0)) == 2  # 768: all that fit at once
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 393217, 64, 64, 0, thk.THK_BF16, 0)) == 0  # one block more: staged
+    monkeypatch.setenv("THK_PRUNE_MAX_BLOCKS", "256")
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 262144, 64, 64, 0, thk.THK_BF16, 0)) == 0
+    monkeypatch.delenv("THK_PRUNE_MAX_BLOCKS")
     assert thk.thk_prune_is_fused(thk.make_shape(1, 8, 32, 8, 128, 32768, 32, 64, 0, thk.THK_BF16, 0)) == 2
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 0, thk.THK_F32, 0)) == 1     # tiny: 64-row blocks
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 72, thk.THK_F32, 0)) == 0    # padded rows: not flat

@@ -238,8 +238,8 @@ def test_prune_fused_repeated_calls_on_one_workspace(levels, monkeypatch):
 
 
 @pytest.mark.parametrize("spin_limit", [None, 0])
-@pytest.mark.parametrize("block_rows", [128, 64])
-def test_prune_two_level_arrival(block_rows, spin_limit, monkeypatch):
+@pytest.mark.parametrize("block_rows,S", [(128, 13008), (64, 13008), (128, 40016)])
+def test_prune_two_level_arrival(block_rows, S, spin_limit, monkeypatch):
     """Units of more than 64 row blocks: the blocks arrive group by group, the last block of a
     group publishes the group's sums, and every block makes the index list from the group sums
     (102 blocks of 128 rows held on chip; 204 blocks of 64 rows read twice).  With the wait
@@ -249,7 +249,7 @@ def test_prune_two_level_arrival(block_rows, spin_limit, monkeypatch):
     monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", str(block_rows))
     if spin_limit is not None:
         monkeypatch.setenv("THK_PRUNE_SPIN_LIMIT", str(spin_limit))
-    L, B, N_kv, G, S, S_obs, T = 1, 2, 2, 2, 13008, 32, 64
+    L, B, N_kv, G, S_obs, T = 1, 2, 2, 2, 32, 64       # S = 40016: 313 blocks per unit, groups of 20
     q_obs = _randn((L, B, N_kv * G, S_obs, D), "bf16", 41, 1.0)
     k = _randn((L, B, N_kv, S, D), "bf16", 42, 1.0)
     shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T, 0, thk.THK_BF16, 0)
