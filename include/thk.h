@@ -192,8 +192,8 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
 
 /*
  * End-of-prefill prune = thk_score + thk_select_topk + thk_compact_keys in one
- * call.  When K_pruned is dense (ld_keep == T) and S * T * sizeof(element) is a
- * multiple of 16, a single kernel does all three steps: a block takes 512 rows of
+ * call.  When K_pruned is dense (ld_keep == T; any S, any unit pitch), a single
+ * kernel does all three steps: a block takes 512 rows of
  * a unit (fewer for small calls), keeps them on chip while the unit's index list
  * is being decided, and compacts them from there, so K is read from memory once;
  * otherwise (and for units of more blocks than are resident on the chip at once:

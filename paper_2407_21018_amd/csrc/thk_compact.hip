@@ -7,26 +7,25 @@
 
 namespace thk {
 
-// Flat path: K_pruned rows dense (ld_keep == T) and the destination slab of every
-// unit starting on a 16-byte boundary, so that a run of whole rows is a run of
-// whole 16-byte chunks (see compact_rows).
+// Flat path: K_pruned rows dense (ld_keep == T), so that a run of whole rows is a run of
+// bytes; the unit may start and end anywhere (see compact_rows).
 template <int DT>
 __global__ __launch_bounds__(256) void k_compact_flat(CompactArgs a) {
   using E = Elem<DT>;
   extern __shared__ u32x4 smem[];
-  uint16_t *tab = (uint16_t *)smem;                       // [8 * T], padded to 2 KiB
+  int16_t *tab = (int16_t *)smem;                         // [8 * T], padded to 2 KiB
   const int64_t u = blockIdx.x / a.blocks_per_unit;
   const int blk = (int)(blockIdx.x % a.blocks_per_unit);
   const int64_t s0 = (int64_t)blk * a.rows_per_block;
   const int64_t s1 = min(a.n_rows, s0 + a.rows_per_block);
-  compact_build_tab<DT>(tab, a.idx + (size_t)u * a.T, a.T);
+  const FlatOut<DT> out((char *)a.dst + ((size_t)u * a.dst_unit_rows + a.dst_row0) * a.T * E::EB);
+  compact_build_tab<DT>(tab, a.idx + (size_t)u * a.T, a.T, out.sh);
   __syncthreads();
   compact_rows<DT>((const u32x4 *)((const char *)a.src + ((size_t)u * a.src_unit_rows + a.src_row0) * kD * E::EB),
-                   (u32x4 *)((char *)a.dst + ((size_t)u * a.dst_unit_rows + a.dst_row0) * a.T * E::EB),
-                   s0, s1, a.T, tab, smem + 128);
+                   out, s0, s1, a.T, tab, smem + 128);
 }
 
-// Element-wise path for padded or unaligned K_pruned layouts.
+// Element-wise path for padded K_pruned rows.
 template <int DT>
 __global__ __launch_bounds__(256) void k_compact_generic(CompactArgs a) {
   using ET = typename std::conditional<DT == THK_BF16, uint16_t, uint32_t>::type;
@@ -95,11 +94,7 @@ __global__ __launch_bounds__(256) void k_tail_append(const void *__restrict__ k_
   ((u32x4 *)v_dst)[((size_t)u * v_unit_rows + v_row) * CPR + c] = ((const u32x4 *)v_new)[i];
 }
 
-bool compact_is_flat(int dtype, int T, int ld_keep, int64_t dst_unit_rows, int64_t dst_row0, int64_t n_rows) {
-  const size_t rowb = (size_t)T * (dtype == THK_BF16 ? 2 : 4);
-  return ld_keep == T && (dst_unit_rows * rowb) % 16 == 0 && (dst_row0 * rowb) % 16 == 0 &&
-         (n_rows * rowb) % 16 == 0;
-}
+bool compact_is_flat(int T, int ld_keep) { return ld_keep == T; }
 
 hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0,
                           const int16_t *idx, void *dst, int64_t dst_unit_rows, int64_t dst_row0,
@@ -115,7 +110,7 @@ hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int
   a.rows_per_block = 512;   // 4 waves x 4 tiles; fewer blocks per unit when the run is short
   a.blocks_per_unit = (int)((n_rows + a.rows_per_block - 1) / a.rows_per_block);
   const dim3 grid((unsigned)(U * a.blocks_per_unit)), block(256);
-  if (compact_is_flat(dtype, T, ld_keep, dst_unit_rows, dst_row0, n_rows)) {
+  if (compact_is_flat(T, ld_keep)) {
     const size_t lds = 2048 + 4 * compact_tile_bytes(eb);
     if (dtype == THK_BF16) hipLaunchKernelGGL((k_compact_flat<THK_BF16>), grid, block, lds, st, a);
     else                   hipLaunchKernelGGL((k_compact_flat<THK_F32>), grid, block, lds, st, a);

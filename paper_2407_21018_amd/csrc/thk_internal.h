@@ -28,6 +28,7 @@ __device__ __forceinline__ void st_stream(u32x4 *p, u32x4 v) { __builtin_nontemp
 template <int DT> struct Elem;
 template <> struct Elem<THK_F32> {
   static constexpr int EB = 4, VEC = 4;
+  using Bits = uint32_t;
   template <class V4> __device__ static inline void unpack(const V4 &r, float (&f)[4]) {
     f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
     f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
@@ -37,6 +38,7 @@ template <> struct Elem<THK_F32> {
 };
 template <> struct Elem<THK_BF16> {
   static constexpr int EB = 2, VEC = 8;
+  using Bits = uint16_t;
   template <class V4> __device__ static inline void unpack(const V4 &r, float (&f)[8]) {
     f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
     f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
@@ -86,7 +88,7 @@ struct CompactArgs {
   int64_t src_unit_rows, src_row0, dst_unit_rows, dst_row0, n_rows, rows_per_block;
   int32_t T, ld, blocks_per_unit;
 };
-bool compact_is_flat(int dtype, int T, int ld_keep, int64_t dst_unit_rows, int64_t dst_row0, int64_t n_rows);
+bool compact_is_flat(int T, int ld_keep);   // dense K_pruned rows: the chunked compaction applies
 hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0,
                           const int16_t *idx, void *dst, int64_t dst_unit_rows, int64_t dst_row0,
                           int64_t U, int64_t n_rows, int T, int ld_keep, hipStream_t st);

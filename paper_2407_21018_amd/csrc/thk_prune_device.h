@@ -312,17 +312,21 @@ __device__ __forceinline__ void select_block(const float *sc, int T, int16_t *ou
 }
 
 // ---------------------------------------------------------------------------
-// Compaction of rows [s0, s1) of one unit (K_pruned rows dense, unit start
-// 16-byte aligned) by a 256-thread block.  Each wavefront works alone on tiles
-// of 32 rows:
+// Compaction of rows [s0, s1) of one unit whose K_pruned rows are dense (row pitch T), by a
+// 256-thread block.  Each wavefront works alone on tiles of 32 rows:
 //   1. 16-byte coalesced loads of the full-width rows into its LDS tile;
-//   2. for every 16-byte chunk of the OUTPUT slab, a table lookup gives the LDS
-//      element offsets of its VEC source elements (the pattern of
-//      row * 128 + idx[t] repeats every 8 output rows because 8 * T elements is
-//      a whole number of chunks), the elements are gathered from LDS, packed
-//      and stored with one 16-byte store.
-// s0 must be a multiple of 32 and (s1 - s0) * T a multiple of VEC.
-// tab: LDS, 8 * T uint16 (<= 2 KiB); tiles: LDS, 4 x [32][128] elements.
+//   2. for every 16-byte chunk of the OUTPUT, a table lookup gives the LDS element offsets of
+//      its VEC source elements (the pattern of row * pitch + idx[t] repeats every 8 output rows
+//      because 8 * T elements is a whole number of chunks), the elements are gathered from LDS,
+//      packed and stored with one 16-byte store.
+// The unit's first output element may sit anywhere: chunks are aligned in MEMORY.  With
+// sh = elements between the 16-byte boundary below the unit's start and that start, position
+// q = e + sh counts from the boundary, chunk k holds positions [VEC k, VEC k + VEC), and the
+// table is built with the shift inside (entry i belongs to element i - sh of an 8-row block;
+// the first sh entries point into the block before, with negative offsets).  A tile's rows end
+// where they end: the chunks it does not own completely (at most one at each end, shared with
+// the neighbouring tile or lying partly outside the unit) are written element by element.
+// s0 must be a multiple of 32.  tab: LDS, 8 * T int16 (<= 2 KiB); tiles: LDS, 4 tiles.
 // ---------------------------------------------------------------------------
 constexpr int kCompactTileRows = 32;
 
@@ -340,52 +344,82 @@ struct Tile {
 };
 constexpr size_t compact_tile_bytes(int eb) { return (size_t)kCompactTileRows * (kD * eb + 16); }
 
+// Where a unit's dense output starts: the 16-byte boundary at or below it and the distance in
+// elements.
 template <int DT>
-__device__ __forceinline__ void compact_build_tab(uint16_t *tab, const int16_t *uidx, int T) {
+struct FlatOut {
+  u32x4 *o;
+  int sh;
+  __device__ explicit FlatOut(void *unit_start) {
+    const uintptr_t a = (uintptr_t)unit_start;
+    sh = (int)(a & 15) / Elem<DT>::EB;
+    o = (u32x4 *)(a & ~(uintptr_t)15);
+  }
+};
+
+template <int DT>
+__device__ __forceinline__ void compact_build_tab(int16_t *tab, const int16_t *uidx, int T, int sh) {
   const int period = 8 * T;
-  for (int e = threadIdx.x; e < period; e += 256) {
+  for (int i = threadIdx.x; i < period; i += 256) {
+    int e = i - sh, back = 0;
+    if (e < 0) { e += period; back = 8 * Tile<DT>::ROW_ELEMS; }   // an element of the 8-row block before
     const int row = e / T, t = e - row * T;
-    tab[e] = (uint16_t)(row * Tile<DT>::ROW_ELEMS + (int)uidx[t]);
+    tab[i] = (int16_t)(row * Tile<DT>::ROW_ELEMS + (int)uidx[t] - back);
   }
 }
 
-// Step 2 of compact_rows for one tile that is already in LDS: rows r0 .. r0 + nr of the unit.
+// Step 2 for one tile that is already in LDS: rows r0 .. r0 + nr of the unit (r0 a multiple of 32).
 template <int DT>
-__device__ __forceinline__ void compact_emit_tile(const u32x4 *tile, u32x4 *__restrict__ dst, int64_t r0, int nr,
-                                                  int T, const uint16_t *tab, int lane) {
+__device__ __forceinline__ void compact_emit_tile(const u32x4 *tile, const FlatOut<DT> &out, int64_t r0, int nr,
+                                                  int T, const int16_t *tab, int lane) {
   using E = Elem<DT>;
+  using ET = typename E::Bits;
   constexpr int VEC = E::VEC;
   const int period = 8 * T;
-  const int nchunks = nr * T / VEC;
-  u32x4 *o = dst + (size_t)r0 * T / VEC;
-  for (int c = lane; c < nchunks; c += kWave) {
-    const int e0 = c * VEC;
-    const int pb = e0 / period;
-    const int pe = e0 - pb * period;
-    const int rowbase = pb * 8 * Tile<DT>::ROW_ELEMS;
+  const int64_t base = r0 * T;                       // first element of the tile; a multiple of VEC
+  const int nq = nr * T;                             // positions base + sh .. base + sh + nq of the unit
+  // tile-relative positions p = q - base in [sh, sh + nq); chunks [VEC c, VEC c + VEC)
+  const int c_lo = (out.sh + VEC - 1) / VEC, c_hi = (out.sh + nq) / VEC;   // whole chunks: c_lo <= c < c_hi
+  u32x4 *o = out.o + base / VEC;
+  const ET *tl0 = (const ET *)tile;
+  for (int c = c_lo + lane; c < c_hi; c += kWave) {
+    const int p0 = c * VEC;
+    const int pb = p0 / period;
+    const int pe = p0 - pb * period;
+    const ET *tl = tl0 + pb * 8 * Tile<DT>::ROW_ELEMS;
     u32x4 w;
     if constexpr (DT == THK_BF16) {
-      const uint16_t *tl = (const uint16_t *)tile + rowbase;
-      const u32x4 offs = *(const u32x4 *)(tab + pe);   // 8 offsets
-      const uint32_t o0 = offs.x & 0xffffu, o1 = offs.x >> 16, o2 = offs.y & 0xffffu, o3 = offs.y >> 16;
-      const uint32_t o4 = offs.z & 0xffffu, o5 = offs.z >> 16, o6 = offs.w & 0xffffu, o7 = offs.w >> 16;
+      const u32x4 offs = *(const u32x4 *)(tab + pe);   // 8 signed offsets
+      const int o0 = (int16_t)(offs.x & 0xffffu), o1 = (int)offs.x >> 16, o2 = (int16_t)(offs.y & 0xffffu);
+      const int o3 = (int)offs.y >> 16, o4 = (int16_t)(offs.z & 0xffffu), o5 = (int)offs.z >> 16;
+      const int o6 = (int16_t)(offs.w & 0xffffu), o7 = (int)offs.w >> 16;
       w.x = (uint32_t)tl[o0] | ((uint32_t)tl[o1] << 16);
       w.y = (uint32_t)tl[o2] | ((uint32_t)tl[o3] << 16);
       w.z = (uint32_t)tl[o4] | ((uint32_t)tl[o5] << 16);
       w.w = (uint32_t)tl[o6] | ((uint32_t)tl[o7] << 16);
     } else {
-      const uint32_t *tl = (const uint32_t *)tile + rowbase;
-      const uint2 offs = *(const uint2 *)(tab + pe);   // 4 offsets
-      w.x = tl[offs.x & 0xffffu]; w.y = tl[offs.x >> 16];
-      w.z = tl[offs.y & 0xffffu]; w.w = tl[offs.y >> 16];
+      const uint2 offs = *(const uint2 *)(tab + pe);   // 4 signed offsets
+      w.x = tl[(int16_t)(offs.x & 0xffffu)]; w.y = tl[(int)offs.x >> 16];
+      w.z = tl[(int16_t)(offs.y & 0xffffu)]; w.w = tl[(int)offs.y >> 16];
     }
     st_stream(o + c, w);
+  }
+  // positions outside the whole chunks: [sh, min(VEC c_lo, sh + nq)) and [max(VEC c_hi, VEC c_lo), sh + nq)
+  const int head_end = min(c_lo * VEC, out.sh + nq);
+  const int n_head = head_end - out.sh;
+  const int tail_beg = max(c_hi * VEC, head_end);
+  const int n_tail = out.sh + nq - tail_beg;
+  if (lane < n_head + n_tail) {                       // at most 2 (VEC - 1) lanes
+    const int p = lane < n_head ? out.sh + lane : tail_beg + (lane - n_head);
+    const int pb = p / period;
+    const int pe = p - pb * period;
+    ((ET *)o)[p] = tl0[pb * 8 * Tile<DT>::ROW_ELEMS + tab[pe]];
   }
 }
 
 template <int DT>
-__device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
-                                             int64_t s0, int64_t s1, int T, const uint16_t *tab,
+__device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, const FlatOut<DT> &out,
+                                             int64_t s0, int64_t s1, int T, const int16_t *tab,
                                              u32x4 *tiles) {
   using E = Elem<DT>;
   constexpr int VEC = E::VEC, CPR = kD / VEC, TR = kCompactTileRows;
@@ -406,7 +440,7 @@ __device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, u32x
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    compact_emit_tile<DT>(tile, dst, r0, nr, T, tab, lane);
+    compact_emit_tile<DT>(tile, out, r0, nr, T, tab, lane);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }

@@ -264,7 +264,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   using E = Elem<DT>;
   extern __shared__ u32x4 smem[];
-  uint16_t *tab = (uint16_t *)smem;          // 2 KiB
+  int16_t *tab = (int16_t *)smem;            // 2 KiB
   u32x4 *tiles = smem + 128;                 // 4 x [32][128] elements
   __shared__ double red[4][kD];
   __shared__ double s_part[kD];
@@ -284,11 +284,11 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   __syncthreads();
   if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
 
-  compact_build_tab<DT>(tab, s_idx, a.T);
+  const FlatOut<DT> out((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
+  compact_build_tab<DT>(tab, s_idx, a.T, out.sh);
   __syncthreads();
   const int64_t s1c = min(s1, a.S_keep);   // rows past S_keep stay at full width with the caller
-  if (s0 < s1c)
-    compact_rows<DT>(src, (u32x4 *)((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB), s0, s1c, a.T, tab, tiles);
+  if (s0 < s1c) compact_rows<DT>(src, out, s0, s1c, a.T, tab, tiles);
   if (tid == 0) a.done[item] = 1;
 }
 
@@ -307,7 +307,7 @@ void k_prune_onepass(PruneFusedArgs a) {
   constexpr int VEC = E::VEC, CPR = kD / VEC, TR = kCompactTileRows, NLD = TR * CPR / kWave;
   constexpr int NRT = NTW - NLT;             // tiles per wave held in registers
   extern __shared__ u32x4 smem[];
-  uint16_t *tab = (uint16_t *)smem;          // 2 KiB
+  int16_t *tab = (int16_t *)smem;            // 2 KiB
   u32x4 *tiles = smem + 128;                 // [4 waves][NLT] x [32][128] elements
   __shared__ double red[4][kD];
   __shared__ double s_part[kD];
@@ -390,10 +390,10 @@ void k_prune_onepass(PruneFusedArgs a) {
   if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
 
   // ---- compaction: the LDS tiles first, then the register tiles through slot 0 ---------------
-  compact_build_tab<DT>(tab, s_idx, a.T);
+  const FlatOut<DT> dst((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
+  compact_build_tab<DT>(tab, s_idx, a.T, dst.sh);
   __syncthreads();
   const int64_t s1c = min(s1, a.S_keep);
-  u32x4 *dst = (u32x4 *)((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
 #pragma unroll
   for (int n = NRT; n < NTW; ++n) {
     const int nr = tile_rows(n, s1c);
@@ -421,7 +421,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
   using E = Elem<DT>;
   extern __shared__ u32x4 smem[];
-  uint16_t *tab = (uint16_t *)smem;
+  int16_t *tab = (int16_t *)smem;
   u32x4 *tiles = smem + 128;
   __shared__ int s_any;
   const int64_t u = blockIdx.x;
@@ -433,6 +433,7 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
   if (undone) s_any = 1;
   __syncthreads();
   if (s_any == 0) return;
+  const FlatOut<DT> dst((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
   if (a.GS > 0) {
     // The blocks of a two-level unit make the list for themselves and block 0 stores the
     // caller's copy, so the copy may be missing.  All group vectors are there by now: the same
@@ -451,13 +452,12 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
       kss = half[0] + half[1];
     }
     score_and_select(a, u, tid < kD ? a.qn[(size_t)u * kD + tid] : 0.0, kss, s_sc, s_idx, s_scratch, true);
-    compact_build_tab<DT>(tab, s_idx, a.T);
+    compact_build_tab<DT>(tab, s_idx, a.T, dst.sh);
   } else {
-    compact_build_tab<DT>(tab, a.idx + (size_t)u * a.T, a.T);
+    compact_build_tab<DT>(tab, a.idx + (size_t)u * a.T, a.T, dst.sh);
   }
   __syncthreads();
   const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
-  u32x4 *dst = (u32x4 *)((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
   for (int blk = 0; blk < a.NB; ++blk) {
     if (done[blk]) continue;   // block-uniform: every thread reads the same byte
     const int64_t s0 = (int64_t)blk * a.RB;
