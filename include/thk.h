@@ -185,7 +185,7 @@ thk_status thk_select_topk(const thk_shape *shape, const float *score,
 /*
  * K_pruned[s][t] = K[s][idx[t]] -- a bit copy of the kept channels (Fig. 1;
  * Sec. 3.3 "pruned keys with a reduced channel size") for rows s < S - S_recent.
- * Columns [T, ld_keep) of K_pruned are not written.  idx entries must lie in [0, D).
+ * Columns [T, ld_keep) of the rows written are set to zero.  idx entries must lie in [0, D).
  */
 thk_status thk_compact_keys(const thk_shape *shape, const void *k,
                             const int16_t *idx, void *k_pruned, void *stream);

@@ -137,7 +137,7 @@ long env_long(const char *name, long dflt) {
 
 struct FusedPlan { bool ok; int NB; int64_t RB; int hold; };
 
-// The one-launch forms need dense K_pruned rows (ld_keep == T).
+// The one-launch forms need dense K_pruned rows (ld_keep == T) or a row pitch of whole 16-byte chunks.
 // Their blocks take 512 rows each (measured best on MI355X; fewer for small calls) and the
 // blocks of a unit wait for each other; a unit may have as many as are resident at once (768
 // of 512 rows; above 64 their sums travel in two levels), longer sequences go through the
@@ -148,7 +148,7 @@ FusedPlan fused_plan(const thk_shape *s) {
   if (path != nullptr && path[0] == 's') return p;   // "staged": the three-kernel path
   const int eb = elem_bytes(s->dtype);
   if (s->S_cap != 0 && s->S_cap < keep_rows(s)) return p;
-  if (!compact_is_flat(s->T, ld_of(s))) return p;
+  if (!compact_is_flat(s->dtype, s->T, ld_of(s))) return p;
   (void)eb;
   int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 0);
   if (rb <= 0) {
@@ -443,7 +443,7 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
   if (fp.ok) {
     const int spin = (int)env_long("THK_PRUNE_SPIN_LIMIT", 4096);
     if (failed(launch_prune_fused(s->dtype, q_obs, k, sc, idx, k_pruned, ws, U, s->S, keep_rows(s),
-                                  cache_rows(s, keep_rows(s)), G, s->S_obs, s->T, fp.NB, fp.RB, fp.hold,
+                                  cache_rows(s, keep_rows(s)), G, s->S_obs, s->T, ld_of(s), fp.NB, fp.RB, fp.hold,
                                   spin < 0 ? 0 : spin, hs)))
       return THK_ERR_HIP;
     return THK_OK;

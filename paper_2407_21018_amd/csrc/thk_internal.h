@@ -88,7 +88,8 @@ struct CompactArgs {
   int64_t src_unit_rows, src_row0, dst_unit_rows, dst_row0, n_rows, rows_per_block;
   int32_t T, ld, blocks_per_unit;
 };
-bool compact_is_flat(int T, int ld_keep);   // dense K_pruned rows: the chunked compaction applies
+// dense K_pruned rows, or rows padded to a multiple of 16 bytes: the chunked compaction applies
+bool compact_is_flat(int dtype, int T, int ld_keep);
 hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0,
                           const int16_t *idx, void *dst, int64_t dst_unit_rows, int64_t dst_row0,
                           int64_t U, int64_t n_rows, int T, int ld_keep, hipStream_t st);
@@ -103,7 +104,7 @@ size_t prune_fused_ws_bytes(int64_t U, int NB);
 // hold = 1, 2, 4 (fp32: 1, 2): RB = 128 * hold and the rows stay on chip in between.
 hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float *score, int16_t *idx,
                               void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
-                              int64_t kp_unit_rows, int G, int S_obs, int T, int NB, int64_t RB,
+                              int64_t kp_unit_rows, int G, int S_obs, int T, int ld, int NB, int64_t RB,
                               int hold, int spin_limit, hipStream_t st);
 
 struct DecodeArgs {

@@ -326,6 +326,11 @@ __device__ __forceinline__ void select_block(const float *sc, int T, int16_t *ou
 // the first sh entries point into the block before, with negative offsets).  A tile's rows end
 // where they end: the chunks it does not own completely (at most one at each end, shared with
 // the neighbouring tile or lying partly outside the unit) are written element by element.
+// Rows with padding behind them (pitch ld > T elements) take the same route row by row when
+// the pitch is a multiple of 16 bytes: every row then starts on a boundary, the table holds one
+// row's offsets, and all ld / VEC chunks of a row are gathered and stored whole -- the padding
+// columns as zeros, which the gather finds in the padding chunk of the LDS row (cleared once):
+// leaving them out would make the last 32 bytes of every row a partial write.
 // s0 must be a multiple of 32.  tab: LDS, 8 * T int16 (<= 2 KiB); tiles: LDS, 4 tiles.
 // ---------------------------------------------------------------------------
 constexpr int kCompactTileRows = 32;
@@ -358,7 +363,11 @@ struct FlatOut {
 };
 
 template <int DT>
-__device__ __forceinline__ void compact_build_tab(int16_t *tab, const int16_t *uidx, int T, int sh) {
+__device__ __forceinline__ void compact_build_tab(int16_t *tab, const int16_t *uidx, int T, int ld, int sh) {
+  if (ld != T) {   // padded rows: entry t = element of the LDS row; the padding columns read its zero chunk
+    for (int i = threadIdx.x; i < ld; i += 256) tab[i] = i < T ? uidx[i] : (int16_t)kD;
+    return;
+  }
   const int period = 8 * T;
   for (int i = threadIdx.x; i < period; i += 256) {
     int e = i - sh, back = 0;
@@ -368,41 +377,55 @@ __device__ __forceinline__ void compact_build_tab(int16_t *tab, const int16_t *u
   }
 }
 
+// VEC elements of the LDS row (or block of rows) at tl through the VEC table entries at te.
+template <int DT>
+__device__ __forceinline__ u32x4 gather_chunk(const typename Elem<DT>::Bits *tl, const int16_t *te) {
+  u32x4 w;
+  if constexpr (DT == THK_BF16) {
+    const u32x4 offs = *(const u32x4 *)te;   // 8 signed offsets
+    const int o0 = (int16_t)(offs.x & 0xffffu), o1 = (int)offs.x >> 16, o2 = (int16_t)(offs.y & 0xffffu);
+    const int o3 = (int)offs.y >> 16, o4 = (int16_t)(offs.z & 0xffffu), o5 = (int)offs.z >> 16;
+    const int o6 = (int16_t)(offs.w & 0xffffu), o7 = (int)offs.w >> 16;
+    w.x = (uint32_t)tl[o0] | ((uint32_t)tl[o1] << 16);
+    w.y = (uint32_t)tl[o2] | ((uint32_t)tl[o3] << 16);
+    w.z = (uint32_t)tl[o4] | ((uint32_t)tl[o5] << 16);
+    w.w = (uint32_t)tl[o6] | ((uint32_t)tl[o7] << 16);
+  } else {
+    const uint2 offs = *(const uint2 *)te;   // 4 signed offsets
+    w.x = tl[(int16_t)(offs.x & 0xffffu)]; w.y = tl[(int)offs.x >> 16];
+    w.z = tl[(int16_t)(offs.y & 0xffffu)]; w.w = tl[(int)offs.y >> 16];
+  }
+  return w;
+}
+
 // Step 2 for one tile that is already in LDS: rows r0 .. r0 + nr of the unit (r0 a multiple of 32).
 template <int DT>
 __device__ __forceinline__ void compact_emit_tile(const u32x4 *tile, const FlatOut<DT> &out, int64_t r0, int nr,
-                                                  int T, const int16_t *tab, int lane) {
+                                                  int T, int ld, const int16_t *tab, int lane) {
   using E = Elem<DT>;
   using ET = typename E::Bits;
   constexpr int VEC = E::VEC;
+  const ET *tl0 = (const ET *)tile;
+  if (ld != T) {
+    // padded rows, pitch a multiple of 16 bytes (so out.sh == 0): every chunk of every row
+    const int cpr = ld / VEC;
+    u32x4 *o = out.o + (size_t)r0 * cpr;
+    for (int i = lane; i < nr * cpr; i += kWave) {
+      const int row = i / cpr, c = i - row * cpr;
+      st_stream(o + i, gather_chunk<DT>(tl0 + row * Tile<DT>::ROW_ELEMS, tab + c * VEC));
+    }
+    return;
+  }
   const int period = 8 * T;
   const int64_t base = r0 * T;                       // first element of the tile; a multiple of VEC
   const int nq = nr * T;                             // positions base + sh .. base + sh + nq of the unit
   // tile-relative positions p = q - base in [sh, sh + nq); chunks [VEC c, VEC c + VEC)
   const int c_lo = (out.sh + VEC - 1) / VEC, c_hi = (out.sh + nq) / VEC;   // whole chunks: c_lo <= c < c_hi
   u32x4 *o = out.o + base / VEC;
-  const ET *tl0 = (const ET *)tile;
   for (int c = c_lo + lane; c < c_hi; c += kWave) {
     const int p0 = c * VEC;
     const int pb = p0 / period;
-    const int pe = p0 - pb * period;
-    const ET *tl = tl0 + pb * 8 * Tile<DT>::ROW_ELEMS;
-    u32x4 w;
-    if constexpr (DT == THK_BF16) {
-      const u32x4 offs = *(const u32x4 *)(tab + pe);   // 8 signed offsets
-      const int o0 = (int16_t)(offs.x & 0xffffu), o1 = (int)offs.x >> 16, o2 = (int16_t)(offs.y & 0xffffu);
-      const int o3 = (int)offs.y >> 16, o4 = (int16_t)(offs.z & 0xffffu), o5 = (int)offs.z >> 16;
-      const int o6 = (int16_t)(offs.w & 0xffffu), o7 = (int)offs.w >> 16;
-      w.x = (uint32_t)tl[o0] | ((uint32_t)tl[o1] << 16);
-      w.y = (uint32_t)tl[o2] | ((uint32_t)tl[o3] << 16);
-      w.z = (uint32_t)tl[o4] | ((uint32_t)tl[o5] << 16);
-      w.w = (uint32_t)tl[o6] | ((uint32_t)tl[o7] << 16);
-    } else {
-      const uint2 offs = *(const uint2 *)(tab + pe);   // 4 signed offsets
-      w.x = tl[(int16_t)(offs.x & 0xffffu)]; w.y = tl[(int)offs.x >> 16];
-      w.z = tl[(int16_t)(offs.y & 0xffffu)]; w.w = tl[(int)offs.y >> 16];
-    }
-    st_stream(o + c, w);
+    st_stream(o + c, gather_chunk<DT>(tl0 + pb * 8 * Tile<DT>::ROW_ELEMS, tab + (p0 - pb * period)));
   }
   // positions outside the whole chunks: [sh, min(VEC c_lo, sh + nq)) and [max(VEC c_hi, VEC c_lo), sh + nq)
   const int head_end = min(c_lo * VEC, out.sh + nq);
@@ -417,15 +440,22 @@ __device__ __forceinline__ void compact_emit_tile(const u32x4 *tile, const FlatO
   }
 }
 
+// The padding chunk of every LDS row of a wave's tile, cleared (the source of the zeros above).
+template <int DT>
+__device__ __forceinline__ void tile_clear_padding(u32x4 *tile, int lane) {
+  if (lane < kCompactTileRows) tile[lane * Tile<DT>::PITCH + Tile<DT>::CPR] = u32x4{0u, 0u, 0u, 0u};
+}
+
 template <int DT>
 __device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, const FlatOut<DT> &out,
-                                             int64_t s0, int64_t s1, int T, const int16_t *tab,
+                                             int64_t s0, int64_t s1, int T, int ld, const int16_t *tab,
                                              u32x4 *tiles) {
   using E = Elem<DT>;
   constexpr int VEC = E::VEC, CPR = kD / VEC, TR = kCompactTileRows;
   constexpr int NLD = TR * CPR / kWave;   // 16-byte loads per lane per tile
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   u32x4 *tile = tiles + wave * Tile<DT>::CHUNKS;
+  if (ld != T) tile_clear_padding<DT>(tile, lane);
   for (int64_t r0 = s0 + (int64_t)wave * TR; r0 < s1; r0 += 4 * TR) {
     const int nr = (int)min((int64_t)TR, s1 - r0);
     // rows past the end of a ragged last tile re-read its last row (kept in bounds, never gathered)
@@ -440,7 +470,7 @@ __device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, cons
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    compact_emit_tile<DT>(tile, out, r0, nr, T, tab, lane);
+    compact_emit_tile<DT>(tile, out, r0, nr, T, ld, tab, lane);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }

@@ -63,7 +63,7 @@ struct PruneFusedArgs {
   int64_t S, RB;          // rows per unit, rows per block
   int64_t S_keep;         // rows [0, S_keep) of every unit are compacted
   int64_t kp_unit_rows;   // rows between units of K_pruned
-  int32_t T, G, S_obs, NB, spin_limit;
+  int32_t T, ld, G, S_obs, NB, spin_limit;   // ld: elements from row to row of K_pruned
 };
 
 __device__ inline void pub_store_f64(double *p, double v) {
@@ -284,11 +284,11 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   __syncthreads();
   if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
 
-  const FlatOut<DT> out((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
-  compact_build_tab<DT>(tab, s_idx, a.T, out.sh);
+  const FlatOut<DT> out((char *)a.kp + (size_t)u * a.kp_unit_rows * a.ld * E::EB);
+  compact_build_tab<DT>(tab, s_idx, a.T, a.ld, out.sh);
   __syncthreads();
   const int64_t s1c = min(s1, a.S_keep);   // rows past S_keep stay at full width with the caller
-  if (s0 < s1c) compact_rows<DT>(src, out, s0, s1c, a.T, tab, tiles);
+  if (s0 < s1c) compact_rows<DT>(src, out, s0, s1c, a.T, a.ld, tab, tiles);
   if (tid == 0) a.done[item] = 1;
 }
 
@@ -323,6 +323,9 @@ void k_prune_onepass(PruneFusedArgs a) {
   const int64_t s1 = min(a.S, s0 + a.RB);
   const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
   u32x4 *wtile = tiles + (size_t)wave * NLT * Tile<DT>::CHUNKS;   // this wave's NLT tiles
+  if (a.ld != a.T)
+#pragma unroll
+    for (int n = 0; n < NLT; ++n) tile_clear_padding<DT>(wtile + (size_t)n * Tile<DT>::CHUNKS, lane);
 
   // tile n of this wave = rows s0 + (4 n + wave) * 32 .. + 32, nr of them inside [s0, hi)
   auto tile_row0 = [&](int n) { return s0 + (int64_t)(4 * n + wave) * TR; };
@@ -390,14 +393,14 @@ void k_prune_onepass(PruneFusedArgs a) {
   if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
 
   // ---- compaction: the LDS tiles first, then the register tiles through slot 0 ---------------
-  const FlatOut<DT> dst((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
-  compact_build_tab<DT>(tab, s_idx, a.T, dst.sh);
+  const FlatOut<DT> dst((char *)a.kp + (size_t)u * a.kp_unit_rows * a.ld * E::EB);
+  compact_build_tab<DT>(tab, s_idx, a.T, a.ld, dst.sh);
   __syncthreads();
   const int64_t s1c = min(s1, a.S_keep);
 #pragma unroll
   for (int n = NRT; n < NTW; ++n) {
     const int nr = tile_rows(n, s1c);
-    if (nr > 0) compact_emit_tile<DT>(wtile + (size_t)(n - NRT) * Tile<DT>::CHUNKS, dst, tile_row0(n), nr, a.T, tab, lane);
+    if (nr > 0) compact_emit_tile<DT>(wtile + (size_t)(n - NRT) * Tile<DT>::CHUNKS, dst, tile_row0(n), nr, a.T, a.ld, tab, lane);
   }
 #pragma unroll
   for (int n = 0; n < NRT; ++n) {
@@ -410,7 +413,7 @@ void k_prune_onepass(PruneFusedArgs a) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      compact_emit_tile<DT>(wtile, dst, tile_row0(n), nr, a.T, tab, lane);
+      compact_emit_tile<DT>(wtile, dst, tile_row0(n), nr, a.T, a.ld, tab, lane);
     }
   }
   if (tid == 0) a.done[item] = 1;
@@ -433,7 +436,7 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
   if (undone) s_any = 1;
   __syncthreads();
   if (s_any == 0) return;
-  const FlatOut<DT> dst((char *)a.kp + (size_t)u * a.kp_unit_rows * a.T * E::EB);
+  const FlatOut<DT> dst((char *)a.kp + (size_t)u * a.kp_unit_rows * a.ld * E::EB);
   if (a.GS > 0) {
     // The blocks of a two-level unit make the list for themselves and block 0 stores the
     // caller's copy, so the copy may be missing.  All group vectors are there by now: the same
@@ -452,9 +455,9 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
       kss = half[0] + half[1];
     }
     score_and_select(a, u, tid < kD ? a.qn[(size_t)u * kD + tid] : 0.0, kss, s_sc, s_idx, s_scratch, true);
-    compact_build_tab<DT>(tab, s_idx, a.T, dst.sh);
+    compact_build_tab<DT>(tab, s_idx, a.T, a.ld, dst.sh);
   } else {
-    compact_build_tab<DT>(tab, a.idx + (size_t)u * a.T, a.T, dst.sh);
+    compact_build_tab<DT>(tab, a.idx + (size_t)u * a.T, a.T, a.ld, dst.sh);
   }
   __syncthreads();
   const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
@@ -462,7 +465,7 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
     if (done[blk]) continue;   // block-uniform: every thread reads the same byte
     const int64_t s0 = (int64_t)blk * a.RB;
     const int64_t s1c = min(a.S_keep, s0 + a.RB);
-    if (s0 < s1c) compact_rows<DT>(src, dst, s0, s1c, a.T, tab, tiles);
+    if (s0 < s1c) compact_rows<DT>(src, dst, s0, s1c, a.T, a.ld, tab, tiles);
   }
 }
 
@@ -485,7 +488,7 @@ size_t prune_fused_ws_bytes(int64_t U, int NB) {
 
 hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float *score, int16_t *idx,
                               void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
-                              int64_t kp_unit_rows, int G, int S_obs, int T, int NB, int64_t RB,
+                              int64_t kp_unit_rows, int G, int S_obs, int T, int ld, int NB, int64_t RB,
                               int hold, int spin_limit, hipStream_t st) {
   clear_stale_hip_error();
   PruneFusedArgs a;
@@ -520,7 +523,7 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
   w = (char *)(((uintptr_t)w + 15) & ~(uintptr_t)15);
   a.idx_pub = (uint32_t *)w; w += (size_t)U * kWave * sizeof(uint32_t);
   a.done = (unsigned char *)w;
-  a.S = S; a.S_keep = S_keep; a.kp_unit_rows = kp_unit_rows; a.RB = RB; a.T = T; a.G = G; a.S_obs = S_obs; a.NB = NB; a.spin_limit = spin_limit;
+  a.S = S; a.S_keep = S_keep; a.kp_unit_rows = kp_unit_rows; a.RB = RB; a.T = T; a.ld = ld; a.G = G; a.S_obs = S_obs; a.NB = NB; a.spin_limit = spin_limit;
   const size_t lds = 2048 + 4 * compact_tile_bytes(eb);
   const dim3 gu((unsigned)U), gi((unsigned)(U * NB));
   // hold == 0: the re-reading form; otherwise RB == 128 * hold and the rows are held on chip

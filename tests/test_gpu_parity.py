@@ -76,7 +76,9 @@ def test_select_bit_exact_on_same_scores(T):
 # --------------------------------------------------------------- compact ----
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("S,T,ld", [(1024, 64, 0), (1056, 76, 0), (2048 + 32, 51, 0), (1037, 51, 0), (1037, 76, 80),
-                                     (520, 128, 0), (16, 1, 0), (3, 7, 0), (4096, 89, 0), (8, 51, 0)])
+                                     (520, 128, 0), (16, 1, 0), (3, 7, 0), (4096, 89, 0), (8, 51, 0),
+                                     # padded rows: pitch a multiple of 16 bytes (chunked, row by row) or not (element-wise)
+                                     (300, 51, 56), (300, 51, 53), (64, 7, 8), (555, 100, 128), (33, 3, 8), (700, 89, 92)])
 def test_compact_bit_exact(dtype, S, T, ld):
     L, B, N_kv = 1, 2, 3
     k = _randn((L, B, N_kv, S, D), dtype, 21)
@@ -85,9 +87,9 @@ def test_compact_bit_exact(dtype, S, T, ld):
     idx_np = O.select_topk(score, T)
     idx = torch.from_numpy(idx_np).cuda()
     shape = thk.make_shape(L, B, N_kv, N_kv, D, S, 1, T, ld, DT[dtype], 0)
-    kp = gpu_compact(shape, k, idx)
+    kp = gpu_compact(shape, k, idx, fill=7)            # every element of every row is written:
     want = O.compact_keys(as_numpy(k).reshape(L * B * N_kv, S, D), idx_np, dtype, ld)
-    np.testing.assert_array_equal(as_numpy(kp), want)   # padding columns stay zero on both sides
+    np.testing.assert_array_equal(as_numpy(kp), want)   # the padding columns as zeros
 
 
 # ---------------------------------------------------------------- decode ----
@@ -235,6 +237,33 @@ def test_prune_fused_repeated_calls_on_one_workspace(levels, monkeypatch):
         else:
             assert torch.equal(idx, first_idx[rep % 2]), f"call {rep}"
     assert not torch.equal(first_idx[0], first_idx[1])
+
+
+@pytest.mark.parametrize("dtype,G,S,T,ld,block_rows", [("bf16", 1, 4096, 76, 80, ""), ("bf16", 4, 3001, 51, 56, "128"),
+                                                       ("f32", 1, 1037, 51, 52, ""), ("bf16", 1, 2048, 76, 88, "64"),
+                                                       ("bf16", 2, 777, 100, 104, "32"), ("bf16", 1, 1500, 76, 77, "")])
+def test_prune_into_padded_rows(dtype, G, S, T, ld, block_rows, monkeypatch):
+    """K_pruned rows with padding behind them: the one-launch prune serves them when the pitch is a
+    multiple of 16 bytes (the last case is not and takes the staged, element-wise way); the
+    padding columns are written as zeros."""
+    if block_rows:
+        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", block_rows)
+    L, B, N_kv, S_obs = 1, 2, 3, 32
+    U = L * B * N_kv
+    q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, 61, 1.0)
+    k = _randn((L, B, N_kv, S, D), dtype, 62, 1.0)
+    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T, ld, DT[dtype], 0)
+    eb = 2 if dtype == "bf16" else 4
+    assert (thk.thk_prune_is_fused(shape) != 0) == ((ld * eb) % 16 == 0)
+    score = torch.empty(U, D, dtype=torch.float32, device="cuda")
+    idx = torch.empty(U, T, dtype=torch.int16, device="cuda")
+    kp = torch.full((U, S, ld), 7, dtype=k.dtype, device="cuda")
+    thk.thk_prune(shape, q_obs, k, score, idx, kp, ws_tensor(thk.thk_workspace_bytes(shape, thk.THK_OP_PRUNE)))
+    torch.cuda.synchronize()
+    o_sc, o_idx, _ = oracle_prune(q_obs, k, dtype, T, ld)
+    check_idx_with_tie_rule(idx.cpu().numpy(), o_idx, o_sc.reshape(U, D), T)
+    want = O.compact_keys(as_numpy(k).reshape(U, S, D), idx.cpu().numpy(), dtype, ld)   # zeros in the padding
+    np.testing.assert_array_equal(as_numpy(kp), want)
 
 
 @pytest.mark.parametrize("spin_limit", [None, 0])

@@ -103,13 +103,14 @@ def _prune_shapes(n, seed):
         S_obs = int(min(S, rng.choice([1, 8, 32, 64])))
         T = int(rng.choice([int(rng.integers(1, 129)), 51, 64, 76]))
         block_rows = rng.choice(["", "32", "64", "128", "256", "512"])
-        out.append((dtype, G, S, S_obs, T, str(block_rows), 9800 + i))
+        ld = 0 if rng.random() < 0.6 else min(128, T + int(rng.choice([1, 2, 4, 8, 12])))
+        out.append((dtype, G, S, S_obs, T, ld, str(block_rows), 9800 + i))
     return out
 
 
-@pytest.mark.parametrize("case", _prune_shapes(24, 20240723), ids=lambda c: "-".join(map(str, c[:6])))
+@pytest.mark.parametrize("case", _prune_shapes(32, 20240723), ids=lambda c: "-".join(map(str, c[:7])))
 def test_prune_random_shapes(case, monkeypatch):
-    dtype, G, S, S_obs, T, block_rows, seed = case
+    dtype, G, S, S_obs, T, ld, block_rows, seed = case
     print(f"prune case {case}", flush=True)
     if block_rows:
         monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", block_rows)
@@ -117,16 +118,16 @@ def test_prune_random_shapes(case, monkeypatch):
     U = L * B * N_kv
     q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, seed, 1.0)
     k = _randn((L, B, N_kv, S, D), dtype, seed + 1, 1.0)
-    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T, 0, DT[dtype], 0)
+    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T, ld, DT[dtype], 0)
     score, idx, kp = gpu_prune(shape, q_obs, k)
-    o_sc, o_idx, _ = oracle_prune(q_obs, k, dtype, T)
+    o_sc, o_idx, _ = oracle_prune(q_obs, k, dtype, T, ld)
     o_sc = o_sc.reshape(U, D)
     rel = np.abs(score.cpu().numpy().astype(np.float64) - o_sc) / o_sc
     assert rel.max() <= SCORE_TOL, case
     check_idx_with_tie_rule(idx.cpu().numpy(), o_idx, o_sc, T)
     # compaction is judged with the list the call returned: bit-exact gather
-    want = O.compact_keys(as_numpy(k).reshape(U, S, D), idx.cpu().numpy(), dtype)
-    np.testing.assert_array_equal(as_numpy(kp), want)
+    want = O.compact_keys(as_numpy(k).reshape(U, S, D), idx.cpu().numpy(), dtype, ld)
+    np.testing.assert_array_equal(as_numpy(kp), want)   # padding columns stay zero on both sides
 
 
 def _value_shapes(n, seed):
