@@ -79,7 +79,7 @@ Split score_split(const thk_shape *s, int64_t units) {
   return {n, rows};
 }
 
-int group_width(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
+int group_width(int G) { return G <= 2 ? G : 4; }   // head slots per block of the general decode kernel
 
 // Query heads that share a block of the decode kernel the shape takes.
 int decode_heads_per_block(const thk_shape *s) {
@@ -91,7 +91,7 @@ int decode_heads_per_block(const thk_shape *s) {
 Split decode_split(const thk_shape *s) {
   int n = s->n_split;
   const int G = s->N_q / s->N_kv;
-  const int64_t wgs = units_of(s) * (G / decode_heads_per_block(s));
+  const int64_t wgs = units_of(s) * ceil_div(G, decode_heads_per_block(s));
   if (n == 0) {
     // about one resident set of blocks (4 per compute unit) over the call, a power of two
     // pieces per unit, each at least 256 rows; big calls still get two pieces per unit so
@@ -540,7 +540,7 @@ static thk_status decode_common(const thk_shape *s, const void *q, const void *k
     return THK_ERR_ALIGN;
   const Split sp = decode_split(s);
   const int G = s->N_q / s->N_kv;
-  if (units_of(s) * (G / group_width(G)) * sp.n > kMaxGrid) return THK_ERR_SHAPE;
+  if (units_of(s) * ceil_div(G, decode_heads_per_block(s)) * sp.n > kMaxGrid) return THK_ERR_SHAPE;
   if (sp.n > 1 && (ws == nullptr || !aligned16(ws) || ws_bytes < thk_workspace_bytes(s, THK_OP_DECODE)))
     return THK_ERR_WORKSPACE;
   DecodeArgs a;

@@ -94,8 +94,10 @@ __global__ __launch_bounds__(128 * PG) void k_decode_merge(const float *__restri
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t st) {
   clear_stale_hip_error();
   const int G = a.N_q / a.N_kv;
-  const int gt = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-  const int groups = G / gt;
+  // query heads per block of the general kernel: 1, 2, or 4 with the unit's last block partly
+  // filled when G is not a multiple of 4 (every block of a unit streams the unit's K and V)
+  const int gt = G <= 2 ? G : 4;
+  const int groups = (G + gt - 1) / gt;
   hipError_t e;
   profile_mark(true, st);
   if (decode_mq_serves(a))

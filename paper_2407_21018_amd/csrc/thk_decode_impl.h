@@ -380,13 +380,13 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
 }
 
 // Merge of the four waves' softmax states (mrg: [GT][130] floats per wave, wstride floats from
-// wave to wave, in LDS, complete and visible to the block): the output row of every query head,
-// or this split's state record.
+// wave to wave, in LDS, complete and visible to the block): the output row of every query head
+// the block serves, or this split's state record.
 template <int DT, int GT>
 __device__ __forceinline__ void block_merge_store(const float *mrg, int wstride, const DecodeArgs &a,
-                                                  int64_t bn0, int sp) {
+                                                  int64_t bn0, int sp, int heads) {
   using E = Elem<DT>;
-  for (int o = threadIdx.x; o < GT * kD; o += 256) {
+  for (int o = threadIdx.x; o < heads * kD; o += 256) {   // heads <= GT of the block's slots are in use
     const int g = o / kD, c = o % kD;
     float M = -INFINITY;
 #pragma unroll
@@ -453,6 +453,9 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   const int64_t u = ug / groups;             // (layer, batch, KV head)
   const int G = a.N_q / a.N_kv;
   const int64_t bn0 = u * G + (int64_t)gi * GT;   // first query head served (heads of unit u: u*G ..)
+  // the unit's last block may have fewer than GT heads left: the other slots carry a zero query
+  // (their logits are 0, their output is never stored)
+  const int hb = min(GT, G - gi * GT);
 
   const int64_t s0 = min(a.S, (int64_t)sp * a.rows_per_split);
   const int64_t s1 = min(a.S, s0 + a.rows_per_split);
@@ -484,16 +487,18 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   for (int o = tid; o < GT * kQS; o += 256) {
     const int g = o / kQS, c = o % kQS;
     const size_t qb = (size_t)(bn0 + g) * kD;
-    qf[o] = c < kD ? E::load1(a.q, qb + c) : 0.f;
-    qk[o] = c < a.T ? E::load1(a.q, qb + uidx[c]) : 0.f;
+    qf[o] = (g < hb && c < kD) ? E::load1(a.q, qb + c) : 0.f;
+    qk[o] = (g < hb && c < a.T) ? E::load1(a.q, qb + uidx[c]) : 0.f;
   }
   if constexpr (DT == THK_BF16) {
     const uint16_t *q16 = (const uint16_t *)a.q;
     for (int o = tid; o < GT * (kQS / 2); o += 256) {
       const int g = o / (kQS / 2), c = 2 * (o % (kQS / 2));
       const size_t qb = (size_t)(bn0 + g) * kD;
-      const uint32_t f0 = c < kD ? q16[qb + c] : 0u, f1 = c + 1 < kD ? q16[qb + c + 1] : 0u;
-      const uint32_t k0 = c < a.T ? q16[qb + uidx[c]] : 0u, k1 = c + 1 < a.T ? q16[qb + uidx[c + 1]] : 0u;
+      const bool used = g < hb;
+      const uint32_t f0 = used && c < kD ? q16[qb + c] : 0u, f1 = used && c + 1 < kD ? q16[qb + c + 1] : 0u;
+      const uint32_t k0 = used && c < a.T ? q16[qb + uidx[c]] : 0u;
+      const uint32_t k1 = used && c + 1 < a.T ? q16[qb + uidx[c + 1]] : 0u;
       qfp[o] = f0 | (f1 << 16);
       qkp[o] = k0 | (k1 << 16);
     }
@@ -587,7 +592,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   }
   __syncthreads();
 
-  block_merge_store<DT, GT>(mrg, GT * (kD + 2), a, bn0, sp);
+  block_merge_store<DT, GT>(mrg, GT * (kD + 2), a, bn0, sp, hb);
 }
 
 // ---- host side: pick the instantiation for a shape --------------------------

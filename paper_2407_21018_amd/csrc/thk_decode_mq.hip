@@ -1,5 +1,5 @@
-// Decode attention over the pruned key cache for bf16 caches whose KV heads serve a multiple of
-// four query heads each (Sec. 3.3, Fig. 2; attention formula of Sec. 3.2) -- gfx950, wave64.
+// Decode attention over the pruned key cache for bf16 caches whose KV heads serve three or more
+// query heads each (Sec. 3.3, Fig. 2; attention formula of Sec. 3.2) -- gfx950, wave64.
 //
 // With four query heads per key row the two products of a tile are skinny matrix products
 // (4 x T by T x 32, then 4 x 32 by 32 x 128) and go to the matrix cores as batches of 4 x 4
@@ -268,6 +268,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
   const int64_t u = ug / groups;             // (layer, batch, KV head)
   const int G = a.N_q / a.N_kv;
   const int64_t bn0 = u * G + (int64_t)gi * GT;
+  const int hb = min(GT, G - gi * GT);   // head slots in use; the others carry a zero query
 
   const int64_t s0 = min(a.S, (int64_t)sp * a.rows_per_split);
   const int64_t s1 = min(a.S, s0 + a.rows_per_split);
@@ -299,8 +300,10 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
     for (int o = tid; o < GT * (kQS / 2); o += 256) {
       const int g = o / (kQS / 2), c = 2 * (o % (kQS / 2));
       const size_t qb = (size_t)(bn0 + g) * kD;
-      const uint32_t f0 = c < kD ? q16[qb + c] : 0u, f1 = c + 1 < kD ? q16[qb + c + 1] : 0u;
-      const uint32_t k0 = c < a.T ? q16[qb + uidx[c]] : 0u, k1 = c + 1 < a.T ? q16[qb + uidx[c + 1]] : 0u;
+      const bool used = g < hb;
+      const uint32_t f0 = used && c < kD ? q16[qb + c] : 0u, f1 = used && c + 1 < kD ? q16[qb + c + 1] : 0u;
+      const uint32_t k0 = used && c < a.T ? q16[qb + uidx[c]] : 0u;
+      const uint32_t k1 = used && c + 1 < a.T ? q16[qb + uidx[c + 1]] : 0u;
       qfp[o] = f0 | (f1 << 16);
       qkp[o] = k0 | (k1 << 16);
     }
@@ -414,7 +417,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
     }
   }
   __syncthreads();
-  block_merge_store<DT, GT>((const float *)wbase, (slab_bytes + 512 * NH) / 4, a, bn0, sp);
+  block_merge_store<DT, GT>((const float *)wbase, (slab_bytes + 512 * NH) / 4, a, bn0, sp, hb);
 }
 
 // Four blocks per compute unit with the narrow staging class and four heads per block (37 KB of
@@ -446,32 +449,33 @@ static int mq_chunks(const DecodeArgs &a) {
   return kb;
 }
 
-// True when the shape is one this kernel serves: bf16, query heads in groups of four, and rows
-// (keys, and values when they are channel-pruned) whose length and pitch are multiples of four
-// elements, so that every operand is 8 bytes.  THK_DECODE_MFMA=0 in the environment keeps such
-// shapes on k_decode.
+// True when the shape is one this kernel serves: bf16, at least three query heads per KV head
+// (one or two share a key row cheaply enough on the vector units), and rows (keys, and values
+// when they are channel-pruned) whose length and pitch are multiples of four elements, so that
+// every operand is 8 bytes.  THK_DECODE_MFMA=0 in the environment keeps such shapes on k_decode.
 bool decode_mq_serves(const DecodeArgs &a) {
   if (a.dtype != THK_BF16 || a.N_kv <= 0) return false;
   const int G = a.N_q / a.N_kv;
-  if (G % 4 != 0 || a.T % 4 != 0 || a.T < 4 || a.ldk % 4 != 0) return false;
+  if (G < 3 || a.T % 4 != 0 || a.T < 4 || a.ldk % 4 != 0) return false;
   if (a.T_v > 0 && a.ld_v % 4 != 0) return false;
   if (mq_chunks(a) > 9) return false;
   const char *env = getenv("THK_DECODE_MFMA");
   return !(env && env[0] == '0');
 }
 
-// Query heads per block: eight when the KV heads serve a multiple of eight, else four.
-int decode_mq_heads(const DecodeArgs &a) { return (a.N_q / a.N_kv) % 8 == 0 ? 8 : 4; }
+// Head slots per block: four for three or four query heads per KV head, else eight; a unit
+// takes ceil(G / slots) blocks per split and the last one may leave slots empty.
+int decode_mq_heads(const DecodeArgs &a) { return (a.N_q / a.N_kv) <= 4 ? 4 : 8; }
 
 hipError_t decode_mq_launch(const DecodeArgs &a, hipStream_t st) {
   const bool narrow = mq_chunks(a) <= 5;
   const int G = a.N_q / a.N_kv;
   if (decode_mq_heads(a) == 8) {
-    const int groups = G / 8;
+    const int groups = (G + 7) / 8;
     if (a.T_v > 0) return narrow ? mq_launch<5, 1, 2>(a, groups, st) : mq_launch<9, 1, 2>(a, groups, st);
     return narrow ? mq_launch<5, 0, 2>(a, groups, st) : mq_launch<9, 0, 2>(a, groups, st);
   }
-  const int groups = G / 4;
+  const int groups = (G + 3) / 4;
   if (a.T_v > 0) return narrow ? mq_launch<5, 1, 1>(a, groups, st) : mq_launch<9, 1, 1>(a, groups, st);
   return narrow ? mq_launch<5, 0, 1>(a, groups, st) : mq_launch<9, 0, 1>(a, groups, st);
 }

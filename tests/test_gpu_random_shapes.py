@@ -21,7 +21,7 @@ def _decode_shapes(n, seed):
     out = []
     for i in range(n):
         dtype = "bf16" if rng.random() < 0.75 else "f32"
-        G = int(rng.choice([1, 2, 3, 4, 4, 8, 8, 12, 16]))
+        G = int(rng.choice([1, 2, 3, 4, 4, 5, 6, 7, 8, 8, 9, 12, 16]))
         T = int(rng.choice([int(rng.integers(1, 129)), 4 * int(rng.integers(1, 33))]))
         ld = 0 if rng.random() < 0.6 else min(128, T + int(rng.choice([1, 2, 4, 6, 8])))
         S = int(rng.choice([int(rng.integers(1, 70)), int(rng.integers(70, 1200)), int(rng.integers(1200, 3000))]))
@@ -52,7 +52,7 @@ def _decode_kv_shapes(n, seed):
     out = []
     for i in range(n):
         dtype = "bf16" if rng.random() < 0.8 else "f32"
-        G = int(rng.choice([1, 2, 4, 4, 8, 8, 16]))
+        G = int(rng.choice([1, 2, 3, 4, 4, 5, 7, 8, 8, 12, 16]))
         T = int(rng.choice([int(rng.integers(1, 129)), 4 * int(rng.integers(1, 33))]))
         T_v = int(rng.integers(1, 129))
         ld_v = min(128, 4 * ((T_v + 3) // 4) + 4 * int(rng.integers(0, 3)))

@@ -177,6 +177,10 @@ DECODE_CASES = [
     ("bf16", 8, 1300, 64, 76, 76, 33, 64, 2),
     ("bf16", 8, 300, 128, 100, 128, 2, 4, 0),   # eight heads per block, the widest staging class
     ("bf16", 16, 900, 76, 51, 52, 0, 0, 3),
+    ("bf16", 3, 700, 64, 40, 40, 4, 8, 0),      # partly filled head groups
+    ("bf16", 7, 500, 76, 90, 92, 0, 0, 2),
+    ("bf16", 5, 400, 51, 64, 64, 3, 4, 0),      # ... on the general kernel (T not a multiple of 4)
+    ("f32", 3, 300, 64, 32, 32, 0, 0, 1),
     ("f32", 1, 1037, 64, 64, 64, 0, 0, 0),
     ("f32", 4, 900, 76, 51, 52, 9, 16, 4),
     ("f32", 2, 333, 51, 128, 128, 0, 0, 1),
@@ -221,7 +225,7 @@ def test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n
 
 
 @pytest.mark.parametrize("dtype,G,S,T,T_v,ld_v,s_tail,cap,n_split",
-                         [c for c in DECODE_CASES if c[0] == "bf16" and c[1] % 4 == 0 and c[3] % 4 == 0])
+                         [c for c in DECODE_CASES if c[0] == "bf16" and c[1] >= 3 and c[3] % 4 == 0])
 def test_decode_attn_kv_general_kernel_on_grouped_heads(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split, monkeypatch):
     """THK_DECODE_MFMA=0: the shapes the matrix-core kernel serves, on the general kernel."""
     monkeypatch.setenv("THK_DECODE_MFMA", "0")
