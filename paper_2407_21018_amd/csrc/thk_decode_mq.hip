@@ -82,14 +82,19 @@ __device__ __forceinline__ void mq_v_commit(const u32x4 (&vr)[kMqVChunks], char 
   for (int j = 0; j < kMqVChunks; ++j) *(u32x4 *)(slab + (4 * j + rsub) * 256 + col * 16) = vr[j];
 }
 
-// Logits of a tile whose key bytes are in the slab, for NH groups of four heads.  nch:
-// 4-channel chunks per row; qrow: this lane's head of the first group as packed bf16, zero from
+// Logits of a tile whose key bytes are in the slab, for NH groups of four heads.  nch =
+// ceil(W / 4) 4-channel chunks per row; qrow: this lane's head of the first group as packed bf16, zero from
 // chunk nch on (the same head of the next group follows 4 * kQS / 2 words later).  d[g] receives,
 // in both halves of the wave, the dot products of rows 4 ((lane / 4) % 8) + r, r = 0 .. 3, with
 // head 4 g + lane % 4: the key operand is read once for all groups.
+// W: elements per key row; the elements the last chunk holds past W (row padding, or whatever
+// follows the tile) are masked off, so their bytes never matter.
 template <int NH>
-__device__ __forceinline__ void mq_logits(const char *slab, int shift, int nrows, int nch, int pitch_bytes,
+__device__ __forceinline__ void mq_logits(const char *slab, int shift, int nrows, int W, int pitch_bytes,
                                           const uint32_t *qrow, int lane, f32x4 (&d)[NH]) {
+  const int nch = (W + 3) >> 2;
+  const uint32_t m0 = (W & 3) == 1 ? 0x0000ffffu : 0xffffffffu;
+  const uint32_t m1 = (W & 3) == 0 ? 0xffffffffu : (W & 3) == 3 ? 0x0000ffffu : 0u;
   const int b = lane >> 2, x = lane & 3, half = b >> 3, bb = b & 7;
   const char *rowp = slab + shift + min(4 * bb + x, nrows - 1) * pitch_bytes;
   const int nst = (nch + 1) >> 1;          // chunks per half = matrix instructions per group
@@ -104,7 +109,12 @@ __device__ __forceinline__ void mq_logits(const char *slab, int shift, int nrows
     const int c = half * nst + rel;
     // a chunk past the row's end: the row's first chunk against the zero chunk of the query
     const bool valid = c < nch;
-    const s16x4 ka = *(const s16x4 *)(rowp + (valid ? c : 0) * 8);
+    const int ck = valid ? c : 0;
+    uint2 kw = *(const uint2 *)(rowp + ck * 8);
+    const bool last = ck == nch - 1;
+    kw.x &= last ? m0 : 0xffffffffu;
+    kw.y &= last ? m1 : 0xffffffffu;
+    const s16x4 ka = __builtin_bit_cast(s16x4, kw);
     const char *qp = (const char *)qrow + (valid ? c : nch) * 8;
 #pragma unroll
     for (int g = 0; g < NH; ++g) acc[g] = mfma4(ka, *(const s16x4 *)(qp + g * 4 * (kQS / 2) * 4), acc[g]);
@@ -322,7 +332,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
     }
   }
   const int x = lane & 3;
-  const int pitch_bytes = a.ldk * EB, nch = a.T >> 2;
+  const int pitch_bytes = a.ldk * EB;
 
   // ---- pruned segment: the bytes of this wave's next tile are in flight while the current
   // one is computed
@@ -336,7 +346,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
       shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)(ti + 4) * TR) * a.ldk * EB, nr4, a.T, a.ldk, lane);
     wave_sync_lds();
     f32x4 d[NH];
-    mq_logits<NH>(slab, shift, nrows, nch, pitch_bytes, qkp + x * (kQS / 2), lane, d);
+    mq_logits<NH>(slab, shift, nrows, a.T, pitch_bytes, qkp + x * (kQS / 2), lane, d);
 #pragma unroll
     for (int g = 0; g < NH; ++g) mq_softmax<VP>(d[g], nrows, a.scale_log2, st[g], pline + 512 * g, lane);
     wave_sync_lds();   // the key bytes are consumed: the slab takes the value rows
@@ -371,7 +381,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
     k_commit<KBT>(kt, slab, lane);
     wave_sync_lds();
     f32x4 d[NH];
-    mq_logits<NH>(slab, 0, nrows, kD / 4, kD * EB, qfp + x * (kQS / 2), lane, d);
+    mq_logits<NH>(slab, 0, nrows, kD, kD * EB, qfp + x * (kQS / 2), lane, d);
 #pragma unroll
     for (int g = 0; g < NH; ++g) mq_softmax<VP>(d[g], nrows, a.scale_log2, st[g], pline + 512 * g, lane);
     wave_sync_lds();
@@ -451,12 +461,13 @@ static int mq_chunks(const DecodeArgs &a) {
 
 // True when the shape is one this kernel serves: bf16, at least three query heads per KV head
 // (one or two share a key row cheaply enough on the vector units), and rows (keys, and values
-// when they are channel-pruned) whose length and pitch are multiples of four elements, so that
-// every operand is 8 bytes.  THK_DECODE_MFMA=0 in the environment keeps such shapes on k_decode.
+// when they are channel-pruned) whose pitch is a multiple of four elements, so that every operand
+// is an aligned 8 bytes (T itself is free: dense rows qualify when T is a multiple of 4, other T
+// with a padded pitch).  THK_DECODE_MFMA=0 in the environment keeps such shapes on k_decode.
 bool decode_mq_serves(const DecodeArgs &a) {
   if (a.dtype != THK_BF16 || a.N_kv <= 0) return false;
   const int G = a.N_q / a.N_kv;
-  if (G < 3 || a.T % 4 != 0 || a.T < 4 || a.ldk % 4 != 0) return false;
+  if (G < 3 || a.ldk % 4 != 0) return false;
   if (a.T_v > 0 && a.ld_v % 4 != 0) return false;
   if (mq_chunks(a) > 9) return false;
   const char *env = getenv("THK_DECODE_MFMA");

@@ -215,7 +215,8 @@ def test_decode_kernel_choice_by_shape(monkeypatch):
     assert thk.thk_decode_on_matrix_cores(mk(16, 8, 64, 0, thk.THK_BF16)) == 0        # two heads per KV head
     assert thk.thk_decode_on_matrix_cores(mk(24, 8, 64, 0, thk.THK_BF16)) == 1        # three: 3 of 4 slots
     assert thk.thk_decode_on_matrix_cores(mk(28, 4, 64, 0, thk.THK_BF16)) == 1        # seven: 7 of 8 slots
-    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 51, 0, thk.THK_BF16)) == 0        # T not a multiple of 4
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 51, 0, thk.THK_BF16)) == 0        # dense rows of 51: pitch not a multiple of 4
+    assert thk.thk_decode_on_matrix_cores(mk(32, 8, 51, 52, thk.THK_BF16)) == 1       # the same rows padded to 52
     assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 66, thk.THK_BF16)) == 0       # pitch not a multiple of 4
     assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_F32)) == 0
     assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16), 51, 52) == 1  # channel-pruned values

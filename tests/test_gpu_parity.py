@@ -184,6 +184,32 @@ def test_decode_general_kernel_on_grouped_heads(case, monkeypatch):
     assert err1.max() <= ATTN_TOL["bf16"]
 
 
+@pytest.mark.parametrize("G,T,ld", [(4, 51, 52), (8, 89, 92), (3, 1, 4), (5, 38, 40), (8, 127, 128)])
+def test_decode_ignores_whatever_sits_in_the_row_padding(G, T, ld):
+    """Rows of T kept channels padded to a multiple of 4 elements run on the matrix-core kernel, which
+    reads whole 4-element chunks: what the padding holds (here NaN) must not reach the logits."""
+    B, N_kv, S, s_tail, cap = 1, 2, 1234, 7, 16
+    N_q = N_kv * G
+    q = _randn((1, B, N_q, D), "bf16", 31, 1.0)
+    k = _randn((1, B, N_kv, S, D), "bf16", 32, 1.0)
+    v = _randn((1, B, N_kv, S, D), "bf16", 33, 0)
+    kt = _randn((1, B, N_kv, cap, D), "bf16", 34, 1.0)
+    vt = _randn((1, B, N_kv, cap, D), "bf16", 35, 0)
+    g = torch.Generator(device="cpu"); g.manual_seed(36)
+    idx_np = O.select_topk(torch.rand(B * N_kv, D, generator=g).numpy().astype(np.float64), T)
+    idx = torch.from_numpy(idx_np).cuda()
+    shape = thk.make_shape(1, B, N_q, N_kv, D, S, 1, T, ld, thk.THK_BF16, 0)
+    assert thk.thk_decode_on_matrix_cores(shape) == 1
+    kp = gpu_compact(shape, k, idx)
+    kp[:, :, T:] = float("nan")
+    out = gpu_decode(shape, q, kp, idx, v, kt, vt, s_tail, cap)
+    ref = O.decode_attn(as_numpy(q)[0], as_numpy(kp).reshape(B, N_kv, S, -1), idx_np.reshape(B, N_kv, T),
+                        as_numpy(v)[0], "bf16", as_numpy(kt)[0], as_numpy(vt)[0], s_tail)
+    err = attn_rel_err(out, ref.reshape(B * N_q, D))
+    assert np.isfinite(out.float().cpu().numpy()).all()
+    assert err.max() <= ATTN_TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_decode_split_invariance_and_determinism(dtype):
     outs = {}
