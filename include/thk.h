@@ -67,7 +67,8 @@ typedef struct {
   int64_t S;       /* keys in the prunable segment, >= 1                         */
   int32_t S_obs;   /* observation-window queries, 1..S (score / prune only)      */
   int32_t T;       /* channels kept, 1..D                                        */
-  int32_t ld_keep; /* row stride of K_pruned in elements, >= T; 0 means T        */
+  int32_t ld_keep; /* row stride of K_pruned in elements, >= T; 0 means T (the
+                      columns past T are written as zeros and never read)      */
   int32_t dtype;   /* thk_dtype of Q, K, V, K_pruned, out                        */
   int32_t n_split; /* pieces the S axis is cut into per unit; 0 = library choice */
   int32_t S_recent;/* prune: the last S_recent of the S scored keys are NOT compacted    */
@@ -192,8 +193,8 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
 
 /*
  * End-of-prefill prune = thk_score + thk_select_topk + thk_compact_keys in one
- * call.  When K_pruned is dense (ld_keep == T; any S, any unit pitch), a single
- * kernel does all three steps: a block takes 512 rows of
+ * call.  A single kernel does all three steps (dense or padded rows, any S, any
+ * unit pitch): a block takes 512 rows of
  * a unit (fewer for small calls), keeps them on chip while the unit's index list
  * is being decided, and compacts them from there, so K is read from memory once;
  * otherwise (and for units of more blocks than are resident on the chip at once:
@@ -223,9 +224,13 @@ thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,
  * S_obs in the shape is ignored.  With n_split > 1 partial (max, sum, acc[D])
  * states go through ws and a second kernel merges them in split order without
  * atomics, so repeated calls give identical bits.
- * bf16 caches with N_q / N_kv a multiple of 4 and T, ld_keep multiples of 4 (here
- * and in thk_decode_attn_kv) run the two products on the matrix cores (probabilities as two bf16 terms, exact to
- * 2^-16; accumulation in fp32); THK_DECODE_MFMA=0 in the environment (read per
+ * bf16 caches with N_q / N_kv >= 3 and a key row pitch (ld_keep, or T when rows are
+ * dense) that is a multiple of 4 elements run the two products on the matrix cores,
+ * here and in thk_decode_attn_kv: four or eight query heads share every key and
+ * value byte a block reads (probabilities as two bf16 terms, exact to 2^-16;
+ * accumulation in fp32; elements of a padded row past T are masked, whatever they
+ * hold).  For T that is not a multiple of 4 (51, 89, ...) a pitch rounded up to one
+ * therefore pays with several query heads per KV head. THK_DECODE_MFMA=0 in the environment (read per
  * call, for experiments and tests) keeps them on the general kernel.
  *   ws : THK_OP_DECODE bytes.
  */

@@ -137,7 +137,6 @@ long env_long(const char *name, long dflt) {
 
 struct FusedPlan { bool ok; int NB; int64_t RB; int hold; };
 
-// The one-launch forms need dense K_pruned rows (ld_keep == T) or a row pitch of whole 16-byte chunks.
 // Their blocks take 512 rows each (measured best on MI355X; fewer for small calls) and the
 // blocks of a unit wait for each other; a unit may have as many as are resident at once (768
 // of 512 rows; above 64 their sums travel in two levels), longer sequences go through the
@@ -148,7 +147,6 @@ FusedPlan fused_plan(const thk_shape *s) {
   if (path != nullptr && path[0] == 's') return p;   // "staged": the three-kernel path
   const int eb = elem_bytes(s->dtype);
   if (s->S_cap != 0 && s->S_cap < keep_rows(s)) return p;
-  if (!compact_is_flat(s->dtype, s->T, ld_of(s))) return p;
   (void)eb;
   int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 0);
   if (rb <= 0) {

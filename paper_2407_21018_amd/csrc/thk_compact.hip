@@ -1,15 +1,12 @@
 // Key compaction K_pruned[s][t] = K[s][idx[t]] (Fig. 1; Sec. 3.3), full-width row
 // copies and the tail append (gfx950, wave64).  Pure byte movement: no arithmetic
 // on values.
-#include <type_traits>
-
 #include "thk_prune_device.h"
 
 namespace thk {
 
-// Chunked path: K_pruned rows dense (ld_keep == T), so that a run of whole rows is a run of
-// bytes and the unit may start and end anywhere, or padded to a multiple of 16 bytes (see
-// compact_rows).
+// A run of rows of K_pruned is a run of bytes (dense rows, or rows with padding behind them,
+// which is written as zeros); the unit may start and end anywhere (see compact_rows).
 template <int DT>
 __global__ __launch_bounds__(256) void k_compact_flat(CompactArgs a) {
   using E = Elem<DT>;
@@ -24,25 +21,6 @@ __global__ __launch_bounds__(256) void k_compact_flat(CompactArgs a) {
   __syncthreads();
   compact_rows<DT>((const u32x4 *)((const char *)a.src + ((size_t)u * a.src_unit_rows + a.src_row0) * kD * E::EB),
                    out, s0, s1, a.T, a.ld, tab, smem + 128);
-}
-
-// Element-wise path for padded K_pruned rows whose pitch is not a multiple of 16 bytes.
-template <int DT>
-__global__ __launch_bounds__(256) void k_compact_generic(CompactArgs a) {
-  using ET = typename std::conditional<DT == THK_BF16, uint16_t, uint32_t>::type;
-  const int64_t u = blockIdx.x / a.blocks_per_unit;
-  const int blk = (int)(blockIdx.x % a.blocks_per_unit);
-  const int64_t s0 = (int64_t)blk * a.rows_per_block;
-  const int64_t s1 = min(a.n_rows, s0 + a.rows_per_block);
-  const ET *src = (const ET *)a.src + ((size_t)u * a.src_unit_rows + a.src_row0) * kD;
-  ET *dst = (ET *)a.dst + ((size_t)u * a.dst_unit_rows + a.dst_row0) * a.ld;
-  const int16_t *uidx = a.idx + (size_t)u * a.T;
-  const int64_t n = (s1 - s0) * a.ld;   // the padding columns are written too, as zeros
-  for (int64_t e = threadIdx.x; e < n; e += 256) {
-    const int64_t s = s0 + e / a.ld;
-    const int t = (int)(e % a.ld);
-    dst[(size_t)s * a.ld + t] = t < a.T ? src[(size_t)s * kD + uidx[t]] : (ET)0;
-  }
 }
 
 // Full-width row copy dst[u][dst_row0 + r][:] = src[u][src_row0 + r][:], r < n_rows.
@@ -95,10 +73,6 @@ __global__ __launch_bounds__(256) void k_tail_append(const void *__restrict__ k_
   ((u32x4 *)v_dst)[((size_t)u * v_unit_rows + v_row) * CPR + c] = ((const u32x4 *)v_new)[i];
 }
 
-bool compact_is_flat(int dtype, int T, int ld_keep) {
-  return ld_keep == T || (ld_keep * (dtype == THK_BF16 ? 2 : 4)) % 16 == 0;
-}
-
 hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0,
                           const int16_t *idx, void *dst, int64_t dst_unit_rows, int64_t dst_row0,
                           int64_t U, int64_t n_rows, int T, int ld_keep, hipStream_t st) {
@@ -113,14 +87,9 @@ hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int
   a.rows_per_block = 512;   // 4 waves x 4 tiles; fewer blocks per unit when the run is short
   a.blocks_per_unit = (int)((n_rows + a.rows_per_block - 1) / a.rows_per_block);
   const dim3 grid((unsigned)(U * a.blocks_per_unit)), block(256);
-  if (compact_is_flat(dtype, T, ld_keep)) {
-    const size_t lds = 2048 + 4 * compact_tile_bytes(eb);
-    if (dtype == THK_BF16) hipLaunchKernelGGL((k_compact_flat<THK_BF16>), grid, block, lds, st, a);
-    else                   hipLaunchKernelGGL((k_compact_flat<THK_F32>), grid, block, lds, st, a);
-  } else {
-    if (dtype == THK_BF16) hipLaunchKernelGGL((k_compact_generic<THK_BF16>), grid, block, 0, st, a);
-    else                   hipLaunchKernelGGL((k_compact_generic<THK_F32>), grid, block, 0, st, a);
-  }
+  const size_t lds = 2048 + 4 * compact_tile_bytes(eb);
+  if (dtype == THK_BF16) hipLaunchKernelGGL((k_compact_flat<THK_BF16>), grid, block, lds, st, a);
+  else                   hipLaunchKernelGGL((k_compact_flat<THK_F32>), grid, block, lds, st, a);
   return hipGetLastError();
 }
 

@@ -88,8 +88,6 @@ struct CompactArgs {
   int64_t src_unit_rows, src_row0, dst_unit_rows, dst_row0, n_rows, rows_per_block;
   int32_t T, ld, blocks_per_unit;
 };
-// dense K_pruned rows, or rows padded to a multiple of 16 bytes: the chunked compaction applies
-bool compact_is_flat(int dtype, int T, int ld_keep);
 hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0,
                           const int16_t *idx, void *dst, int64_t dst_unit_rows, int64_t dst_row0,
                           int64_t U, int64_t n_rows, int T, int ld_keep, hipStream_t st);

@@ -326,12 +326,11 @@ __device__ __forceinline__ void select_block(const float *sc, int T, int16_t *ou
 // the first sh entries point into the block before, with negative offsets).  A tile's rows end
 // where they end: the chunks it does not own completely (at most one at each end, shared with
 // the neighbouring tile or lying partly outside the unit) are written element by element.
-// Rows with padding behind them (pitch ld > T elements) take the same route row by row when
-// the pitch is a multiple of 16 bytes: every row then starts on a boundary, the table holds one
-// row's offsets, and all ld / VEC chunks of a row are gathered and stored whole -- the padding
-// columns as zeros, which the gather finds in the padding chunk of the LDS row (cleared once):
-// leaving them out would make the last 32 bytes of every row a partial write.
-// s0 must be a multiple of 32.  tab: LDS, 8 * T int16 (<= 2 KiB); tiles: LDS, 4 tiles.
+// Rows with padding behind them (pitch ld > T elements) are rows of ld elements whose last
+// ld - T come from nowhere: the table points them at the padding chunk of the LDS row, which is
+// cleared once, so they are written as zeros along with the rest (leaving them out would make
+// the end of every row a partial write, which costs more than the bytes).
+// s0 must be a multiple of 32.  tab: LDS, 8 * ld int16 (<= 2 KiB); tiles: LDS, 4 tiles.
 // ---------------------------------------------------------------------------
 constexpr int kCompactTileRows = 32;
 
@@ -364,16 +363,12 @@ struct FlatOut {
 
 template <int DT>
 __device__ __forceinline__ void compact_build_tab(int16_t *tab, const int16_t *uidx, int T, int ld, int sh) {
-  if (ld != T) {   // padded rows: entry t = element of the LDS row; the padding columns read its zero chunk
-    for (int i = threadIdx.x; i < ld; i += 256) tab[i] = i < T ? uidx[i] : (int16_t)kD;
-    return;
-  }
-  const int period = 8 * T;
+  const int period = 8 * ld;
   for (int i = threadIdx.x; i < period; i += 256) {
     int e = i - sh, back = 0;
     if (e < 0) { e += period; back = 8 * Tile<DT>::ROW_ELEMS; }   // an element of the 8-row block before
-    const int row = e / T, t = e - row * T;
-    tab[i] = (int16_t)(row * Tile<DT>::ROW_ELEMS + (int)uidx[t] - back);
+    const int row = e / ld, t = e - row * ld;
+    tab[i] = (int16_t)(row * Tile<DT>::ROW_ELEMS + (t < T ? (int)uidx[t] : kD) - back);   // kD: the zero chunk
   }
 }
 
@@ -398,27 +393,18 @@ __device__ __forceinline__ u32x4 gather_chunk(const typename Elem<DT>::Bits *tl,
   return w;
 }
 
-// Step 2 for one tile that is already in LDS: rows r0 .. r0 + nr of the unit (r0 a multiple of 32).
+// Step 2 for one tile that is already in LDS: rows r0 .. r0 + nr of the unit (r0 a multiple of
+// 32), ld elements each in the output.
 template <int DT>
 __device__ __forceinline__ void compact_emit_tile(const u32x4 *tile, const FlatOut<DT> &out, int64_t r0, int nr,
-                                                  int T, int ld, const int16_t *tab, int lane) {
+                                                  int ld, const int16_t *tab, int lane) {
   using E = Elem<DT>;
   using ET = typename E::Bits;
   constexpr int VEC = E::VEC;
   const ET *tl0 = (const ET *)tile;
-  if (ld != T) {
-    // padded rows, pitch a multiple of 16 bytes (so out.sh == 0): every chunk of every row
-    const int cpr = ld / VEC;
-    u32x4 *o = out.o + (size_t)r0 * cpr;
-    for (int i = lane; i < nr * cpr; i += kWave) {
-      const int row = i / cpr, c = i - row * cpr;
-      st_stream(o + i, gather_chunk<DT>(tl0 + row * Tile<DT>::ROW_ELEMS, tab + c * VEC));
-    }
-    return;
-  }
-  const int period = 8 * T;
-  const int64_t base = r0 * T;                       // first element of the tile; a multiple of VEC
-  const int nq = nr * T;                             // positions base + sh .. base + sh + nq of the unit
+  const int period = 8 * ld;
+  const int64_t base = r0 * ld;                      // first element of the tile; a multiple of VEC
+  const int nq = nr * ld;                            // positions base + sh .. base + sh + nq of the unit
   // tile-relative positions p = q - base in [sh, sh + nq); chunks [VEC c, VEC c + VEC)
   const int c_lo = (out.sh + VEC - 1) / VEC, c_hi = (out.sh + nq) / VEC;   // whole chunks: c_lo <= c < c_hi
   u32x4 *o = out.o + base / VEC;
@@ -470,7 +456,7 @@ __device__ __forceinline__ void compact_rows(const u32x4 *__restrict__ src, cons
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    compact_emit_tile<DT>(tile, out, r0, nr, T, ld, tab, lane);
+    compact_emit_tile<DT>(tile, out, r0, nr, ld, tab, lane);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }

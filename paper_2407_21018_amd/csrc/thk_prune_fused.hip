@@ -400,7 +400,7 @@ void k_prune_onepass(PruneFusedArgs a) {
 #pragma unroll
   for (int n = NRT; n < NTW; ++n) {
     const int nr = tile_rows(n, s1c);
-    if (nr > 0) compact_emit_tile<DT>(wtile + (size_t)(n - NRT) * Tile<DT>::CHUNKS, dst, tile_row0(n), nr, a.T, a.ld, tab, lane);
+    if (nr > 0) compact_emit_tile<DT>(wtile + (size_t)(n - NRT) * Tile<DT>::CHUNKS, dst, tile_row0(n), nr, a.ld, tab, lane);
   }
 #pragma unroll
   for (int n = 0; n < NRT; ++n) {
@@ -413,7 +413,7 @@ void k_prune_onepass(PruneFusedArgs a) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      compact_emit_tile<DT>(wtile, dst, tile_row0(n), nr, a.T, a.ld, tab, lane);
+      compact_emit_tile<DT>(wtile, dst, tile_row0(n), nr, a.ld, tab, lane);
     }
   }
   if (tid == 0) a.done[item] = 1;

@@ -196,7 +196,7 @@ def test_prune_plan_by_shape(monkeypatch):
     assert thk.thk_prune_is_fused(thk.make_shape(1, 8, 32, 8, 128, 32768, 32, 64, 0, thk.THK_BF16, 0)) == 2
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 0, thk.THK_F32, 0)) == 1     # tiny: 64-row blocks
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 72, thk.THK_F32, 0)) == 1    # padded rows, pitch 288 bytes
-    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 73, thk.THK_F32, 0)) == 0    # pitch 292 bytes: not whole chunks
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 73, thk.THK_F32, 0)) == 1    # any pitch
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2047, 32, 51, 0, thk.THK_BF16, 0)) == 1    # dense rows: any length
     monkeypatch.setenv("THK_PRUNE_PATH", "reread")
     assert thk.thk_prune_is_fused(cfg2) == 1

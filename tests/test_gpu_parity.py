@@ -77,7 +77,7 @@ def test_select_bit_exact_on_same_scores(T):
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("S,T,ld", [(1024, 64, 0), (1056, 76, 0), (2048 + 32, 51, 0), (1037, 51, 0), (1037, 76, 80),
                                      (520, 128, 0), (16, 1, 0), (3, 7, 0), (4096, 89, 0), (8, 51, 0),
-                                     # padded rows: pitch a multiple of 16 bytes (chunked, row by row) or not (element-wise)
+                                     # padded rows, pitches that are and are not multiples of 16 bytes
                                      (300, 51, 56), (300, 51, 53), (64, 7, 8), (555, 100, 128), (33, 3, 8), (700, 89, 92)])
 def test_compact_bit_exact(dtype, S, T, ld):
     L, B, N_kv = 1, 2, 3
@@ -276,9 +276,8 @@ def test_prune_fused_repeated_calls_on_one_workspace(levels, monkeypatch):
                                                        ("f32", 1, 1037, 51, 52, ""), ("bf16", 1, 2048, 76, 88, "64"),
                                                        ("bf16", 2, 777, 100, 104, "32"), ("bf16", 1, 1500, 76, 77, "")])
 def test_prune_into_padded_rows(dtype, G, S, T, ld, block_rows, monkeypatch):
-    """K_pruned rows with padding behind them: the one-launch prune serves them when the pitch is a
-    multiple of 16 bytes (the last case is not and takes the staged, element-wise way); the
-    padding columns are written as zeros."""
+    """K_pruned rows with padding behind them, whatever the pitch: the one-launch prune serves them
+    and the padding columns are written as zeros."""
     if block_rows:
         monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", block_rows)
     L, B, N_kv, S_obs = 1, 2, 3, 32
@@ -286,8 +285,7 @@ def test_prune_into_padded_rows(dtype, G, S, T, ld, block_rows, monkeypatch):
     q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, 61, 1.0)
     k = _randn((L, B, N_kv, S, D), dtype, 62, 1.0)
     shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T, ld, DT[dtype], 0)
-    eb = 2 if dtype == "bf16" else 4
-    assert (thk.thk_prune_is_fused(shape) != 0) == ((ld * eb) % 16 == 0)
+    assert thk.thk_prune_is_fused(shape) != 0
     score = torch.empty(U, D, dtype=torch.float32, device="cuda")
     idx = torch.empty(U, T, dtype=torch.int16, device="cuda")
     kp = torch.full((U, S, ld), 7, dtype=k.dtype, device="cuda")
