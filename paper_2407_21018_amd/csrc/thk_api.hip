@@ -150,11 +150,13 @@ FusedPlan fused_plan(const thk_shape *s) {
   (void)eb;
   int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 0);
   if (rb <= 0) {
-    // the default block size, halved for small calls until the launch has ~4 blocks per CU
-    rb = env_long("THK_PRUNE_HOLD_ROWS", 512);
+    // the default block size: 128 KB of rows, the most a block can hold on chip (512 bf16 rows,
+    // 256 fp32 rows), halved for small calls until the launch has ~4 blocks per CU
+    const int64_t rb_max = env_long("THK_PRUNE_HOLD_ROWS", s->dtype == THK_BF16 ? 512 : 256);
+    rb = rb_max;
     while (rb > 64 && units_of(s) * ceil_div(s->S, rb) < (int64_t)kCUs * 4) rb /= 2;
-    // a unit may have at most 64 blocks: long sequences take larger blocks
-    while (rb < 512 && ceil_div(s->S, rb) > 64) rb *= 2;
+    // long sequences take the largest blocks (beyond 64 of them a unit's sums travel in two levels)
+    while (rb < rb_max && ceil_div(s->S, rb) > 64) rb *= 2;
   }
   if (rb < 32) rb = 32;
   rb = ceil_div(rb, 32) * 32;
@@ -163,10 +165,11 @@ FusedPlan fused_plan(const thk_shape *s) {
   const bool reread = path != nullptr && path[0] == 'r';
   if (!reread && (rb == 128 || rb == 256 || (rb == 512 && s->dtype == THK_BF16))) p.hold = (int)(rb / 128);
   const int64_t nb = ceil_div(s->S, rb);
-  // the blocks of a unit wait for each other, so all of them must be resident at once: three
-  // blocks of 512 held rows per compute unit, four of the smaller ones; 256 where the rows are
-  // read twice (the second read wants the unit's rows still in the memory-side cache)
-  const long fit = p.hold == 4 ? 3L * kCUs : p.hold != 0 ? 4L * kCUs : 256L;
+  // the blocks of a unit wait for each other, so all of them must be resident at once; 256 where
+  // the rows are read twice (the second read wants the unit's rows still in the memory-side cache)
+  // (LDS decides: 2 KB + four tiles + 7 KB per block, i.e. three bf16 blocks or two fp32 blocks
+  // per compute unit)
+  const long fit = p.hold == 0 ? 256L : (s->dtype == THK_BF16 ? 3L : 2L) * kCUs;
   const bool forced = path != nullptr && (path[0] == 'f' || path[0] == 'r');   // regardless of the env limit
   if (nb > (forced ? fit : std::min(fit, env_long("THK_PRUNE_MAX_BLOCKS", fit)))) return p;
   p.RB = rb;

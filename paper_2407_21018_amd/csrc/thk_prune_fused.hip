@@ -499,8 +499,8 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
   a.GS = group_size(NB);
   a.stagger_blocks = 0; a.stagger_units = 1; a.stagger_ticks = 0;
   if (hold != 0) {
-    // resident blocks: 3 per compute unit for 512-row blocks, 4 otherwise
-    const int64_t resident = (int64_t)kCUs * (hold == 4 ? 3 : 4);
+    // resident blocks per compute unit (LDS decides): 3 with bf16 tiles, 2 with fp32 tiles
+    const int64_t resident = (int64_t)kCUs * (dtype == THK_BF16 ? 3 : 2);
     const int64_t total = U * NB;
     const int64_t res_units = resident / NB;
     double ns = -1.0;
