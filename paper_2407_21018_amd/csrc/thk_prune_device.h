@@ -355,9 +355,9 @@ struct FlatOut {
   u32x4 *o;
   int sh;
   __device__ explicit FlatOut(void *unit_start) {
-    const uintptr_t a = (uintptr_t)unit_start;
-    sh = (int)(a & 15) / Elem<DT>::EB;
-    o = (u32x4 *)(a & ~(uintptr_t)15);
+    const int back = (int)((uintptr_t)unit_start & 15);
+    sh = back / Elem<DT>::EB;
+    o = (u32x4 *)((char *)unit_start - back);   // pointer arithmetic, so that it stays a global pointer
   }
 };
 
