@@ -657,7 +657,7 @@ hipError_t decode_launch_gt(const DecodeArgs &a, int groups, hipStream_t st) {
   constexpr int KBW = (DT == THK_BF16) ? 9 : 17;   // up to ld_keep = 128
   // fp32 stages twice as many registers per tile: one wave per SIMD fewer than bf16 (at four
   // the fp32 kernels spilled 27-63 registers and ran at 3.7 TB/s instead of 5.3)
-  constexpr int WN = DT == THK_F32 ? (VP ? 2 : 3) : (GT <= 2 ? 4 : 3);
+  constexpr int WN = DT == THK_F32 ? ((VP || GT == 4) ? 2 : 3) : (GT <= 2 ? 4 : 3);
   constexpr int WW = DT == THK_F32 ? 2 : (VP ? 2 : 3);
   if (p.kb <= KBN) return decode_launch_ra<DT, GT, KBN, TR, WN, VP>(a, p.ra, groups, st);
   if (p.kb <= KBW) return decode_launch_ra<DT, GT, KBW, TR, WW, VP>(a, p.ra, groups, st);
