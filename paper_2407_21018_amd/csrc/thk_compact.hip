@@ -56,6 +56,37 @@ __global__ __launch_bounds__(256) void k_copy_rows(const void *__restrict__ src,
   }
 }
 
+// The same copy when source and destination ranges cannot touch each other: many blocks per
+// unit, each streaming its own run of rows (eight 16-byte chunks in flight per thread).
+template <int DT>
+__global__ __launch_bounds__(256) void k_copy_rows_wide(const void *__restrict__ src, void *__restrict__ dst,
+                                                        int64_t src_unit_rows, int64_t src_row0,
+                                                        int64_t dst_unit_rows, int64_t dst_row0,
+                                                        int64_t n_rows, int64_t rows_per_block, int blocks_per_unit) {
+  using E = Elem<DT>;
+  constexpr int CPR = kD / E::VEC;
+  constexpr int PER = 8;
+  const int64_t u = blockIdx.x / blocks_per_unit;
+  const int64_t r0 = (int64_t)(blockIdx.x % blocks_per_unit) * rows_per_block;
+  const int64_t r1 = min(n_rows, r0 + rows_per_block);
+  const u32x4 *s = (const u32x4 *)src + ((size_t)u * src_unit_rows + src_row0 + r0) * CPR;
+  u32x4 *d = (u32x4 *)dst + ((size_t)u * dst_unit_rows + dst_row0 + r0) * CPR;
+  const int64_t total = (r1 - r0) * CPR;
+  for (int64_t c0 = 0; c0 < total; c0 += 256 * PER) {
+    u32x4 r[PER];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int64_t c = c0 + (int64_t)j * 256 + threadIdx.x;
+      if (c < total) r[j] = ld_stream(s + c);
+    }
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int64_t c = c0 + (int64_t)j * 256 + threadIdx.x;
+      if (c < total) st_stream(d + c, r[j]);
+    }
+  }
+}
+
 // One new token per unit: K_tail[u][k_row] = k_new[u], Vdst[u][v_row] = v_new[u].
 template <int DT>
 __global__ __launch_bounds__(256) void k_tail_append(const void *__restrict__ k_new,
@@ -98,7 +129,34 @@ hipError_t launch_copy_rows(int dtype, const void *src, int64_t src_unit_rows, i
                             hipStream_t st) {
   clear_stale_hip_error();
   if (n_rows <= 0) return hipSuccess;
-  const dim3 grid((unsigned)U), block(256);
+  // byte ranges the call touches, over all units: disjoint ranges may be copied in any order
+  auto ceil_div = [](int64_t a, int64_t b) { return (a + b - 1) / b; };
+  constexpr int64_t kMaxBlocks = 0x7fffffff;
+  const size_t rowb = (size_t)kD * (dtype == THK_BF16 ? 2 : 4);
+  const char *s_lo = (const char *)src + (size_t)src_row0 * rowb;
+  const char *s_hi = (const char *)src + ((size_t)(U - 1) * src_unit_rows + src_row0 + n_rows) * rowb;
+  const char *d_lo = (const char *)dst + (size_t)dst_row0 * rowb;
+  const char *d_hi = (const char *)dst + ((size_t)(U - 1) * dst_unit_rows + dst_row0 + n_rows) * rowb;
+  const bool disjoint = s_hi <= d_lo || d_hi <= s_lo;
+  const dim3 block(256);
+  if (disjoint && n_rows > 64) {
+    // ~8 blocks per compute unit, at least 64 rows each
+    int64_t bpu = ceil_div((int64_t)kCUs * 8, U);
+    const int64_t cap = ceil_div(n_rows, 64);
+    if (bpu > cap) bpu = cap;
+    if (bpu < 1) bpu = 1;
+    const int64_t rpb = ceil_div(n_rows, bpu);
+    bpu = ceil_div(n_rows, rpb);
+    if (U * bpu <= kMaxBlocks) {
+      const dim3 grid((unsigned)(U * bpu));
+      if (dtype == THK_BF16)
+        hipLaunchKernelGGL((k_copy_rows_wide<THK_BF16>), grid, block, 0, st, src, dst, src_unit_rows, src_row0, dst_unit_rows, dst_row0, n_rows, rpb, (int)bpu);
+      else
+        hipLaunchKernelGGL((k_copy_rows_wide<THK_F32>), grid, block, 0, st, src, dst, src_unit_rows, src_row0, dst_unit_rows, dst_row0, n_rows, rpb, (int)bpu);
+      return hipGetLastError();
+    }
+  }
+  const dim3 grid((unsigned)U);
   if (dtype == THK_BF16)
     hipLaunchKernelGGL((k_copy_rows<THK_BF16>), grid, block, 0, st, src, dst, src_unit_rows, src_row0, dst_unit_rows, dst_row0, n_rows);
   else
