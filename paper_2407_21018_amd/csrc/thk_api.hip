@@ -151,12 +151,14 @@ FusedPlan fused_plan(const thk_shape *s) {
   int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 0);
   if (rb <= 0) {
     // the default block size: 128 KB of rows, the most a block can hold on chip (512 bf16 rows,
-    // 256 fp32 rows), halved for small calls until the launch has ~4 blocks per CU
+    // 256 fp32 rows); small calls take the smallest held size (down to 128 rows) that keeps the
+    // launch within two blocks per compute unit, i.e. within one round of resident blocks:
+    // a launch that spills into a second round pays the whole load -> list -> store chain twice
+    // (32 units of 4096 bf16 rows: 23 us with 512 blocks of 256 rows, 36 us with 1024 of 128)
     const int64_t rb_max = env_long("THK_PRUNE_HOLD_ROWS", s->dtype == THK_BF16 ? 512 : 256);
+    auto blocks = [&](int64_t r) { return units_of(s) * ceil_div(s->S, r); };
     rb = rb_max;
-    while (rb > 64 && units_of(s) * ceil_div(s->S, rb) < (int64_t)kCUs * 4) rb /= 2;
-    // long sequences take the largest blocks (beyond 64 of them a unit's sums travel in two levels)
-    while (rb < rb_max && ceil_div(s->S, rb) > 64) rb *= 2;
+    while (rb > 128 && (blocks(rb / 2) <= (int64_t)kCUs * 2 || blocks(rb / 2) == blocks(rb))) rb /= 2;
   }
   if (rb < 32) rb = 32;
   rb = ceil_div(rb, 32) * 32;

@@ -194,10 +194,14 @@ def test_prune_plan_by_shape(monkeypatch):
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 262144, 64, 64, 0, thk.THK_BF16, 0)) == 0
     monkeypatch.delenv("THK_PRUNE_MAX_BLOCKS")
     assert thk.thk_prune_is_fused(thk.make_shape(1, 8, 32, 8, 128, 32768, 32, 64, 0, thk.THK_BF16, 0)) == 2
-    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 0, thk.THK_F32, 0)) == 1     # tiny: 64-row blocks
-    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 72, thk.THK_F32, 0)) == 1    # padded rows, pitch 288 bytes
-    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 73, thk.THK_F32, 0)) == 1    # any pitch
-    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2047, 32, 51, 0, thk.THK_BF16, 0)) == 1    # dense rows: any length
+    tiny = thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 0, thk.THK_F32, 0)
+    assert thk.thk_prune_is_fused(tiny) == 2     # small calls: 128-row blocks, still held on chip
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 72, thk.THK_F32, 0)) == 2    # padded rows, pitch 288 bytes
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 73, thk.THK_F32, 0)) == 2    # any pitch
+    assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2047, 32, 51, 0, thk.THK_BF16, 0)) == 2    # dense rows: any length
+    monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", "64")
+    assert thk.thk_prune_is_fused(tiny) == 1     # a block size that is not held: rows read twice
+    monkeypatch.delenv("THK_PRUNE_BLOCK_ROWS")
     monkeypatch.setenv("THK_PRUNE_PATH", "reread")
     assert thk.thk_prune_is_fused(cfg2) == 1
     monkeypatch.setenv("THK_PRUNE_PATH", "staged")
