@@ -93,18 +93,24 @@ Split decode_split(const thk_shape *s) {
   const int G = s->N_q / s->N_kv;
   const int64_t wgs = units_of(s) * ceil_div(G, decode_heads_per_block(s));
   if (n == 0) {
-    // about one resident set of blocks (4 per compute unit) over the call, a power of two
-    // pieces per unit, each at least 256 rows; big calls still get two pieces per unit so
-    // that the last blocks to finish are short
+    // About one resident set of blocks over the call (4 per compute unit, 3 where a block
+    // serves eight heads), a power of two pieces per unit.  A piece has at least 256 rows, or
+    // 128 while the launch stays within one block per compute unit; more than 64 pieces (the
+    // merge grows with n) only where even that leaves compute units idle.  Short sequences
+    // take one block per unit: below these lengths the second launch (the merge) costs more
+    // than the split saves.  Big calls still get two pieces per unit so that the last blocks
+    // to finish are short.
+    const int hpb = decode_heads_per_block(s);
+    const int per_cu = hpb == 8 ? 3 : 4;
+    const int64_t one_block_rows = (hpb >= 4 ? 320 : 768) * 2 / elem_bytes(s->dtype);   // bf16 rows; half as many fp32 rows
     n = 1;
-    // (3 per compute unit where a block serves eight heads)
-    const int per_cu = decode_heads_per_block(s) == 8 ? 3 : 4;
-    while ((int64_t)n * 2 * wgs <= (int64_t)kCUs * per_cu && n < 64) n *= 2;   // the merge grows with n
+    while (s->S > one_block_rows && n < 128) {
+      const int64_t blocks = (int64_t)n * 2 * wgs;
+      if (blocks > (int64_t)kCUs * per_cu || (n >= 64 && blocks > kCUs)) break;
+      if (ceil_div(s->S, (int64_t)n * 2) < (blocks <= kCUs ? 128 : 256)) break;
+      n *= 2;
+    }
     if (n == 1 && s->S >= 2048) n = 2;
-    const int64_t cap = ceil_div(s->S, 256);
-    if (n > cap) n = (int)cap;
-    if (n > kMaxSplit) n = kMaxSplit;
-    if (n < 1) n = 1;
   }
   int64_t rows = ceil_div(s->S, n);
   rows = ceil_div(rows, 64) * 64;
