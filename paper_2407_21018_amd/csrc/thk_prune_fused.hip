@@ -55,7 +55,7 @@ struct PruneFusedArgs {
   int *arrived_g;         // [U][kMaxGroups] blocks of a group that have published (two-level form)
   double *gpartial;       // [U][kMaxGroups][128] group sums (two-level form)
   int32_t GS;             // blocks per group; 0 = one level
-  // graded start of a short launch's first round: block `item` < stagger_blocks of unit u first
+  // graded start of a launch's first round: block `item` < stagger_blocks of unit u first
   // sleeps (u % stagger_units) * stagger_ticks times 64 cycles
   int32_t stagger_blocks, stagger_units, stagger_ticks;
   uint32_t *idx_pub;      // [U][64]  the index list, two entries per word, for the waiting blocks
@@ -331,7 +331,7 @@ void k_prune_onepass(PruneFusedArgs a) {
   auto tile_row0 = [&](int n) { return s0 + (int64_t)(4 * n + wave) * TR; };
   auto tile_rows = [&](int n, int64_t hi) { return (int)max((int64_t)0, min((int64_t)TR, hi - tile_row0(n))); };
 
-  // A launch of only a few rounds of resident blocks would run in lock-step (everybody loads,
+  // A launch of two or more rounds of resident blocks would run in lock-step (everybody loads,
   // everybody waits for the index lists, everybody stores).  The first round's units therefore
   // start one after the other, a unit's transfer time apart; the later rounds inherit the
   // spacing because a unit's blocks leave, and their successors start, together.
@@ -505,8 +505,11 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
     const int64_t res_units = resident / NB;
     double ns = -1.0;
     if (const char *e = getenv("THK_PRUNE_STAGGER_NS")) ns = atof(e);
-    else if (res_units >= 2 && total >= 2 * resident && total <= 12 * resident)
-      ns = (double)S * kD * eb * 1.5 / 5.7e3;     // a unit's rows in and compacted rows out at 5.7 TB/s
+    else if (res_units >= 2 && total >= 2 * resident)
+      // 0.6 of the time a unit's rows in and compacted rows out take at 5.7 TB/s: the full time
+      // would be the spacing of the steady state, but the first round loads against no stores
+      // and a wider spread only delays it (swept 0..1.5: 0.5-0.7 is best from 2 to 50 rounds)
+      ns = 0.6 * (double)S * kD * eb * 1.5 / 5.7e3;
     if (ns > 0.0 && res_units >= 2) {
       a.stagger_blocks = (int32_t)(res_units * NB);
       a.stagger_units = (int32_t)res_units;
