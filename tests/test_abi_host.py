@@ -237,6 +237,30 @@ def test_decode_kernel_choice_by_shape(monkeypatch):
     assert thk.thk_default_split(s8, thk.THK_OP_DECODE) == 8      # two blocks of four heads per unit and split
 
 
+def test_default_decode_split_follows_the_size_of_the_call(monkeypatch):
+    """Short sequences are not split (no merge launch), few units get small pieces, one unit may
+    get up to 128 pieces; the workspace size follows the same choice."""
+    monkeypatch.delenv("THK_DECODE_MFMA", raising=False)
+    def split(B, N_q, N_kv, S, dtype=thk.THK_BF16):
+        s = thk.make_shape(1, B, N_q, N_kv, 128, S, 1, 64, 0, dtype, 0)
+        n = thk.thk_default_split(s, thk.THK_OP_DECODE)
+        explicit = thk.make_shape(1, B, N_q, N_kv, 128, S, 1, 64, 0, dtype, n)
+        assert thk.thk_workspace_bytes(s, thk.THK_OP_DECODE) == thk.thk_workspace_bytes(explicit, thk.THK_OP_DECODE)
+        return n
+    assert split(1, 8, 8, 512) == 1            # one head per block: no split up to 768 rows
+    assert split(1, 8, 8, 768) == 1
+    assert split(1, 8, 8, 1024) == 8           # 64 blocks of 128 rows
+    assert split(1, 32, 8, 256) == 1           # four heads per block: no split up to 320 rows
+    assert split(1, 32, 8, 512) == 4           # 128-row pieces while the launch is small
+    assert split(1, 8, 8, 384, thk.THK_F32) == 1   # fp32 rows are twice the bytes: half the limits
+    assert split(1, 8, 8, 512, thk.THK_F32) == 4
+    assert split(4, 32, 32, 1024) == 4         # 128 units: 512 blocks of 256 rows, not 1024 of 128
+    assert split(4, 32, 32, 4096) == 8         # the benchmark's shape
+    assert split(1, 1, 1, 32768) == 128        # one unit: beyond 64 pieces
+    assert split(1, 4, 4, 32768) == 64         # four units: 256 blocks already
+    assert split(32, 40, 40, 16384) == 2       # big calls: two pieces per unit
+
+
 def test_plain_c_program_uses_the_boundary(tmp_path):
     """thk.h is a C header and libthk.so a C library: a gcc-built program with no C++ and no
     Python in it includes the one and links the other."""
