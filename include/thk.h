@@ -194,16 +194,22 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
 /*
  * End-of-prefill prune = thk_score + thk_select_topk + thk_compact_keys in one
  * call.  A single kernel does all three steps (dense or padded rows, any S, any
- * unit pitch): a block takes 512 rows of
- * a unit (fewer for small calls), keeps them on chip while the unit's index list
- * is being decided, and compacts them from there, so K is read from memory once;
- * otherwise (and for units of more blocks than are resident on the chip at once:
- * 768 blocks of 512 rows, S > 393216) the three kernels run one after the other.  Scores agree with thk_score to fp64 summation order (the
- * last float bit can differ).  `score` may be NULL (then it lives in ws).
+ * unit pitch): a block takes 512 bf16 or 256 fp32 rows of a unit (256 or 128
+ * for calls small enough to stay within two blocks per compute unit), keeps
+ * them on chip while the unit's index list is being decided, and compacts them
+ * from there, so K is read from memory once.  Units of more blocks than are
+ * resident on the chip at once (768 blocks of 512 bf16 rows: S > 393216) take
+ * the three kernels one after the other.  Scores agree with thk_score to fp64
+ * summation order (the last float bit can differ).  `score` may be NULL (then
+ * it lives in ws).
  * Environment (read per call, for experiments and tests): THK_PRUNE_PATH =
- * staged | fused | reread (the one-kernel form with the rows read twice),
- * THK_PRUNE_BLOCK_ROWS, THK_PRUNE_HOLD_ROWS, THK_PRUNE_MAX_BLOCKS,
- * THK_PRUNE_SPIN_LIMIT, THK_PRUNE_GROUP_MIB.
+ * staged | fused | reread (the one-kernel form with the rows read twice);
+ * THK_PRUNE_BLOCK_ROWS (rows per block; 128, 256 and 512 are held on chip),
+ * THK_PRUNE_HOLD_ROWS (largest default block), THK_PRUNE_MAX_BLOCKS (blocks
+ * per unit beyond which the staged form is taken), THK_PRUNE_SPIN_LIMIT (polls
+ * before a waiting block leaves its rows to the repair kernel; 0 forces that
+ * path), THK_PRUNE_STAGGER_NS (spacing of the first round's unit starts; 0 =
+ * none), THK_PRUNE_GROUP_MIB (bytes of K per group of units in the staged form).
  *   ws : THK_OP_PRUNE bytes.
  */
 thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,
