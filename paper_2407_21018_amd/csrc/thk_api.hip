@@ -187,8 +187,10 @@ FusedPlan fused_plan(const thk_shape *s) {
 }
 
 // Split of the S axis for the value score: pieces are whole 128-row chunks of at least 512
-// rows, enough of them for ~4 blocks per compute unit, and few enough that the merge kernel's
-// weight table (at most 256 pieces) fits.
+// rows, enough of them for one resident set of blocks (two per compute unit: 74 KB of LDS
+// each; more pieces only add merge work -- one layer of config 2: 65 us with 8 pieces per
+// unit, 54-55 us with 2-4), and few enough that the merge kernel's weight table (at most 256
+// pieces) fits.
 Split value_split(const thk_shape *s) {
   const int G = s->N_q / s->N_kv;
   const int QT = value_attn_qt(G, s->S_obs);
@@ -196,7 +198,7 @@ Split value_split(const thk_shape *s) {
   const int64_t blocks1 = units_of(s) * ceil_div(nqt, QT);
   int n = s->n_split;
   if (n == 0) {
-    n = (int)ceil_div((int64_t)kCUs * 4, blocks1);
+    n = (int)ceil_div((int64_t)kCUs * 2, blocks1);
     const int64_t cap = ceil_div(s->S, 512);
     if (n > cap) n = (int)cap;
     if (n < 1) n = 1;
