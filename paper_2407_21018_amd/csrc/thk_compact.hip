@@ -115,7 +115,11 @@ hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int
   a.src_unit_rows = src_unit_rows; a.src_row0 = src_row0;
   a.dst_unit_rows = dst_unit_rows; a.dst_row0 = dst_row0; a.n_rows = n_rows;
   a.T = T; a.ld = ld_keep;
-  a.rows_per_block = 512;   // 4 waves x 4 tiles; fewer blocks per unit when the run is short
+  // 4 waves x 4 tiles of 32 rows; smaller blocks (down to one tile per wave) while the call has
+  // fewer than four blocks per compute unit: a wave's tiles go load -> LDS -> gather -> store one
+  // after the other, so a small call is as long as its longest block
+  a.rows_per_block = 512;
+  while (a.rows_per_block > 128 && U * ((n_rows + a.rows_per_block - 1) / a.rows_per_block) < 4 * kCUs) a.rows_per_block /= 2;
   a.blocks_per_unit = (int)((n_rows + a.rows_per_block - 1) / a.rows_per_block);
   const dim3 grid((unsigned)(U * a.blocks_per_unit)), block(256);
   const size_t lds = 2048 + 4 * compact_tile_bytes(eb);
