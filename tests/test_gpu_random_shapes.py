@@ -130,6 +130,38 @@ def test_prune_random_shapes(case, monkeypatch):
     np.testing.assert_array_equal(as_numpy(kp), want)   # padding columns stay zero on both sides
 
 
+def _long_shapes(n, seed):
+    """Longer sequences: units of 6 to 550 blocks (one and two levels of sums, launches of several
+    rounds of resident blocks with the graded start), decode pieces of thousands of rows."""
+    rng = np.random.default_rng(seed)
+    prune, decode = [], []
+    for i in range(n):
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        S = int(rng.integers(3000, 70000))
+        T = int(rng.choice([int(rng.integers(1, 129)), 51, 64, 76]))
+        ld = 0 if rng.random() < 0.7 else min(128, T + int(rng.choice([1, 4, 8])))
+        br = str(rng.choice(["", "", "", "128", "256", "512"]))
+        if dtype == "f32" and br == "512":
+            br = ""
+        prune.append((dtype, int(rng.choice([1, 2, 4])), S, int(rng.choice([1, 32, 64])), T, ld, br, 12000 + i))
+        G = int(rng.choice([1, 2, 3, 4, 5, 8, 16]))
+        cap = int(rng.choice([0, 16, 64]))
+        s_tail = int(rng.integers(0, cap + 1)) if cap else 0
+        decode.append((dtype, 1, int(rng.integers(1, 4)), G, int(rng.integers(3000, 60000)), T, ld,
+                       int(rng.choice([0, 0, 0, 1, 3, 7, 100])), s_tail, cap, float(rng.choice([0.0, 1.0, 2.0])), 13000 + i))
+    return prune, decode
+
+
+@pytest.mark.parametrize("case", _long_shapes(10, 20240725)[0], ids=lambda c: "-".join(map(str, c[:7])))
+def test_prune_random_long_sequences(case, monkeypatch):
+    test_prune_random_shapes(case, monkeypatch)
+
+
+@pytest.mark.parametrize("case", _long_shapes(10, 20240725)[1], ids=lambda c: "-".join(map(str, c[:10])))
+def test_decode_random_long_sequences(case):
+    test_decode_random_shapes(case)
+
+
 def _value_shapes(n, seed):
     rng = np.random.default_rng(seed)
     out = []
