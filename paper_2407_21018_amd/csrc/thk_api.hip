@@ -143,17 +143,15 @@ long env_long(const char *name, long dflt) {
 
 struct FusedPlan { bool ok; int NB; int64_t RB; int hold; };
 
-// Their blocks take 512 rows each (measured best on MI355X; fewer for small calls) and the
-// blocks of a unit wait for each other; a unit may have as many as are resident at once (768
-// of 512 rows; above 64 their sums travel in two levels), longer sequences go through the
-// staged path instead.
+// The one-launch forms of thk_prune.  Blocks take 512 bf16 / 256 fp32 rows each (measured best on
+// MI355X; fewer for small calls) and the blocks of a unit wait for each other; a unit may have
+// as many as are resident at once (768 bf16 / 512 fp32; above 64 their sums travel in two
+// levels), longer sequences go through the staged path instead.
 FusedPlan fused_plan(const thk_shape *s) {
   FusedPlan p{false, 0, 0, 0};
   const char *path = getenv("THK_PRUNE_PATH");
   if (path != nullptr && path[0] == 's') return p;   // "staged": the three-kernel path
-  const int eb = elem_bytes(s->dtype);
   if (s->S_cap != 0 && s->S_cap < keep_rows(s)) return p;
-  (void)eb;
   int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 0);
   if (rb <= 0) {
     // the default block size: 128 KB of rows, the most a block can hold on chip (512 bf16 rows,
