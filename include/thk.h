@@ -313,13 +313,15 @@ thk_status thk_tail_flush(const thk_shape *shape, const int16_t *idx, void *k_pr
                           int32_t s_tail_cap, int32_t n_flush, void *stream);
 
 /*
- * Timing hook for benchmarks: the NEXT thk_prune or thk_decode_attn call made by
- * this host thread records `ev_start` immediately before and `ev_stop`
- * immediately after its main kernel (the one-launch prune kernel, or the
- * compaction kernel of the staged form; the attention kernel, not the split
- * merge) on that call's stream.  Both are hipEvent_t handles passed as void*,
- * created by the caller with timing enabled; the pair is used once.  Passing
- * NULL for either cancels a pending pair.
+ * Timing hook for benchmarks: the main kernel of the NEXT call made by this host
+ * thread (the one-launch prune kernel, or the compaction kernel of the staged
+ * form; the attention kernel, not the split merge; the value-score attention
+ * kernel) is launched with `ev_start` and `ev_stop` attached to it, so that the
+ * interval between the two events is that kernel's own duration -- begin to end
+ * of its execution, as a profiler reports it; nothing extra enters the stream.
+ * Both are hipEvent_t handles passed as void*, created by the caller with
+ * timing enabled; the pair is used once.  Passing NULL for either cancels a
+ * pending pair.
  */
 void thk_profile_next(void *ev_start, void *ev_stop);
 

@@ -13,14 +13,11 @@ namespace thk {
 namespace {
 thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
 }
-void profile_mark(bool start, hipStream_t st) {
-  if (g_prof_start == nullptr || g_prof_stop == nullptr) return;
-  if (start) {
-    (void)hipEventRecord(g_prof_start, st);
-  } else {
-    (void)hipEventRecord(g_prof_stop, st);
-    g_prof_start = g_prof_stop = nullptr;
-  }
+hipError_t launch_main_kernel(const void *fn, dim3 grid, dim3 block, void **args, size_t lds, hipStream_t st) {
+  if (g_prof_start == nullptr || g_prof_stop == nullptr) return hipLaunchKernel(fn, grid, block, args, lds, st);
+  const hipEvent_t e0 = g_prof_start, e1 = g_prof_stop;
+  g_prof_start = g_prof_stop = nullptr;
+  return hipExtLaunchKernel(fn, grid, block, args, lds, st, e0, e1, 0);
 }
 }  // namespace thk
 
@@ -475,11 +472,9 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
     if (failed(launch_finalize(s->dtype, 0, partial, qg, sc + (size_t)u0 * kD, idx + (size_t)u0 * s->T, nu, G,
                         s->S_obs, sp.n, s->T, hs)))
       return THK_ERR_HIP;
-    profile_mark(true, hs);
     const hipError_t ce = launch_compact(s->dtype, kg, s->S, 0, idx + (size_t)u0 * s->T,
                                          (char *)k_pruned + (size_t)u0 * kp_rows * ld * eb, kp_rows, 0, nu,
                                          keep_rows(s), s->T, ld, hs);
-    profile_mark(false, hs);
     if (failed(ce)) return THK_ERR_HIP;
   }
   return THK_OK;

@@ -123,9 +123,10 @@ hipError_t launch_compact(int dtype, const void *src, int64_t src_unit_rows, int
   a.blocks_per_unit = (int)((n_rows + a.rows_per_block - 1) / a.rows_per_block);
   const dim3 grid((unsigned)(U * a.blocks_per_unit)), block(256);
   const size_t lds = 2048 + 4 * compact_tile_bytes(eb);
-  if (dtype == THK_BF16) hipLaunchKernelGGL((k_compact_flat<THK_BF16>), grid, block, lds, st, a);
-  else                   hipLaunchKernelGGL((k_compact_flat<THK_F32>), grid, block, lds, st, a);
-  return hipGetLastError();
+  void *kargs[] = {(void *)&a};
+  const void *fn = dtype == THK_BF16 ? (const void *)k_compact_flat<THK_BF16> : (const void *)k_compact_flat<THK_F32>;
+  const hipError_t e = launch_main_kernel(fn, grid, block, kargs, lds, st);
+  return e != hipSuccess ? e : hipGetLastError();
 }
 
 hipError_t launch_copy_rows(int dtype, const void *src, int64_t src_unit_rows, int64_t src_row0, void *dst,

@@ -99,7 +99,6 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st) {
   const int gt = G <= 2 ? G : 4;
   const int groups = (G + gt - 1) / gt;
   hipError_t e;
-  profile_mark(true, st);
   if (decode_mq_serves(a))
     e = decode_mq_launch(a, st);
   else if (a.T_v > 0 && a.dtype == THK_BF16)
@@ -114,7 +113,6 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st) {
   else
     e = gt == 4 ? decode_launch_f32_g4(a, groups, st)
                 : gt == 2 ? decode_launch_f32_g2(a, groups, st) : decode_launch_f32_g1(a, groups, st);
-  profile_mark(false, st);
   if (e != hipSuccess) return e;
   if (a.n_split > 1) {
     const int64_t heads = a.units / a.N_kv * a.N_q;

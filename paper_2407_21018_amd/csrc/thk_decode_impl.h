@@ -627,8 +627,9 @@ inline hipError_t decode_launch_one(const DecodeArgs &a, int groups, hipStream_t
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((k_decode<DT, GT, RA, KB, TR, WPE, VP>), grid, block, lds, st, a, groups, kbuf);
-  return hipGetLastError();
+  void *kargs[] = {(void *)&a, (void *)&groups, (void *)&kbuf};
+  const hipError_t e = launch_main_kernel((const void *)k_decode<DT, GT, RA, KB, TR, WPE, VP>, grid, block, kargs, lds, st);
+  return e != hipSuccess ? e : hipGetLastError();
 }
 
 template <int DT, int GT, int KB, int TR, int WPE, int VP>

@@ -444,8 +444,9 @@ static hipError_t mq_launch(const DecodeArgs &a, int groups, hipStream_t st) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((k_decode_mq<KB, WPE, VP, NH>), grid, block, lds, st, a, groups, slab);
-  return hipGetLastError();
+  void *kargs[] = {(void *)&a, (void *)&groups, (void *)&slab};
+  const hipError_t e = launch_main_kernel((const void *)k_decode_mq<KB, WPE, VP, NH>, grid, block, kargs, lds, st);
+  return e != hipSuccess ? e : hipGetLastError();
 }
 
 // Staged 16-byte chunks per lane for one tile: the wider of the key rows and, when they are

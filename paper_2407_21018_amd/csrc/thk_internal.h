@@ -1,6 +1,7 @@
 // Internal declarations shared by the libthk translation units (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "thk.h"
@@ -57,8 +58,12 @@ template <> struct Elem<THK_BF16> {
   __device__ static inline void store1(void *p, size_t i, float x) { ((uint16_t *)p)[i] = round_bf16(x); }
 };
 
-// ---- one-shot timing hook (thk_profile_next): record around a call's main kernel ----
-void profile_mark(bool start, hipStream_t st);   // no-op unless a pair is pending; stop consumes it
+// ---- one-shot timing hook (thk_profile_next) ----
+// The launch of a call's main kernel.  With an event pair pending the kernel goes out through
+// hipExtLaunchKernel, which stamps the two events with the kernel's own begin and end (nothing
+// extra enters the queue, so the interval is the kernel's duration as a profiler reports it),
+// and the pair is consumed; otherwise a plain launch.  `args` as for hipLaunchKernel.
+hipError_t launch_main_kernel(const void *fn, dim3 grid, dim3 block, void **args, size_t lds, hipStream_t st);
 
 // hipGetLastError() reports the calling thread's most recent unconsumed error, whoever caused
 // it; a launcher consumes whatever is pending first so that what it returns is about its own

@@ -563,9 +563,7 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
     hipLaunchKernelGGL((k_prune_prep<THK_BF16>), dim3(prep_blocks), dim3(256), 0, st, a, U);
   else
     hipLaunchKernelGGL((k_prune_prep<THK_F32>), dim3(prep_blocks), dim3(256), 0, st, a, U);
-  profile_mark(true, st);
-  hipError_t le = hipLaunchKernel(main_fn, gi, dim3(256), kargs, lds_main, st);
-  profile_mark(false, st);
+  hipError_t le = launch_main_kernel(main_fn, gi, dim3(256), kargs, lds_main, st);
   if (le != hipSuccess) return le;
   if (dtype == THK_BF16)
     hipLaunchKernelGGL((k_prune_repair<THK_BF16>), gu, dim3(256), lds, st, a);

@@ -505,18 +505,17 @@ hipError_t launch_value_score(int dtype, const void *q_obs, const void *k, const
   a.n_qblk = (nqt_real + QT - 1) / QT;
   a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)kD));
   const unsigned grid = (unsigned)(U * n_split * a.n_qblk);
-  profile_mark(true, st);
+  const void *fn;
+  int threads = 256;
   if (dtype == THK_BF16) {
-    if (QT == 4) hipLaunchKernelGGL(k_value_attn_bf16<4>, dim3(grid), dim3(256), 0, st, a);
-    else if (QT == 2) hipLaunchKernelGGL(k_value_attn_bf16<2>, dim3(grid), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(k_value_attn_bf16<1>, dim3(grid), dim3(256), 0, st, a);
+    fn = QT == 4 ? (const void *)k_value_attn_bf16<4> : QT == 2 ? (const void *)k_value_attn_bf16<2> : (const void *)k_value_attn_bf16<1>;
   } else {
-    if (QT == 4) hipLaunchKernelGGL(k_value_attn_f32<4>, dim3(grid), dim3(256), 0, st, a);
-    else if (QT == 2) hipLaunchKernelGGL(k_value_attn_f32<2>, dim3(grid), dim3(128), 0, st, a);
-    else hipLaunchKernelGGL(k_value_attn_f32<1>, dim3(grid), dim3(64), 0, st, a);
+    fn = QT == 4 ? (const void *)k_value_attn_f32<4> : QT == 2 ? (const void *)k_value_attn_f32<2> : (const void *)k_value_attn_f32<1>;
+    threads = QT == 4 ? 256 : QT == 2 ? 128 : 64;
   }
-  profile_mark(false, st);
-  hipError_t e = hipGetLastError();
+  void *kargs[] = {(void *)&a};
+  hipError_t e = launch_main_kernel(fn, dim3(grid), dim3(threads), kargs, 0, st);
+  if (e == hipSuccess) e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int n_part = n_split;
   const int nqt = a.n_qblk * QT;
