@@ -38,6 +38,8 @@
 // themselves, and k_prune_prep clears them before every call.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "thk_prune_device.h"
 
 namespace thk {
@@ -513,7 +515,7 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
     if (ns > 0.0 && res_units >= 2) {
       a.stagger_blocks = (int32_t)(res_units * NB);
       a.stagger_units = (int32_t)res_units;
-      a.stagger_ticks = (int32_t)(ns * 2.4 / 64.0) + 1;   // 2.4 GHz, s_sleep counts 64-cycle ticks
+      a.stagger_ticks = std::max((int32_t)(ns * 2.4 / 64.0), 1);   // 2.4 GHz, s_sleep counts 64-cycle ticks
     }
   }
   a.gpartial = nullptr; a.arrived_g = nullptr;
