@@ -45,12 +45,13 @@ def test_timed_launch_gives_the_kernel_duration_and_the_same_result():
     assert kernel_ms * 1e3 > U * S * (T + D) * 2 / 8e6   # not faster than the HBM peak allows (bytes / 8 TB/s, in us)
     assert torch.equal(timed, plain) and torch.equal(after, plain)
 
-    # a cancelled pair is not used
+    # a cancelled pair is not used: its two events keep the records they had
     c0, c1 = _recorded_event(), _recorded_event()
     torch.cuda.synchronize()
+    before = c0.elapsed_time(c1)
     thk.thk_profile_next(c0, c1)
     thk.thk_profile_next(None, None)
     thk.thk_decode_attn(shape, q, kp, idx, v, None, None, 0, 0, after, ws)
     torch.cuda.synchronize()
     assert torch.equal(after, plain)
-    assert c0.elapsed_time(c1) * 1e3 < 0.5 * kernel_ms * 1e3   # still the two back-to-back records, not a kernel
+    assert c0.elapsed_time(c1) == before
