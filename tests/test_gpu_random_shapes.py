@@ -29,6 +29,12 @@ def _decode_shapes(n, seed):
         cap = int(rng.choice([0, 1, 4, 16, 64]))
         s_tail = int(rng.integers(0, cap + 1)) if cap else 0
         sigma = float(rng.choice([0.0, 1.0, 1.0, 2.0]))
+        if dtype == "f32" and sigma > 1.0:
+            # channel scales of sigma = 2 on both the query and the keys put logits in the thousands,
+            # where ONE fp32 rounding of a logit is already of the order of the 1e-4 bar (a sweep
+            # with other seeds met 1.2e-4 on a head with two contending keys); the fp32 bar is for
+            # logits of ordinary size, the bf16 cases keep sigma = 2
+            sigma = 1.0
         out.append((dtype, 1, int(rng.integers(1, 3)), G, S, T, ld, n_split, s_tail, cap, sigma, 9000 + i))
     return out
 
@@ -147,8 +153,10 @@ def _long_shapes(n, seed):
         G = int(rng.choice([1, 2, 3, 4, 5, 8, 16]))
         cap = int(rng.choice([0, 16, 64]))
         s_tail = int(rng.integers(0, cap + 1)) if cap else 0
+        sigma = float(rng.choice([0.0, 1.0, 2.0]))
         decode.append((dtype, 1, int(rng.integers(1, 4)), G, int(rng.integers(3000, 60000)), T, ld,
-                       int(rng.choice([0, 0, 0, 1, 3, 7, 100])), s_tail, cap, float(rng.choice([0.0, 1.0, 2.0])), 13000 + i))
+                       int(rng.choice([0, 0, 0, 1, 3, 7, 100])), s_tail, cap, min(sigma, 1.0) if dtype == "f32" else sigma,
+                       13000 + i))
     return prune, decode
 
 
