@@ -44,7 +44,9 @@ typedef enum {
   THK_ERR_UNSUPPORTED = 3, /* valid in principle, not built (D != 128, dtype)  */
   THK_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                 */
   THK_ERR_WORKSPACE = 5,   /* ws is NULL or smaller than thk_workspace_bytes   */
-  THK_ERR_HIP = 6          /* the HIP runtime refused a launch                 */
+  THK_ERR_HIP = 6,         /* the HIP runtime refused a launch                 */
+  THK_ERR_SCRATCH = 7      /* thk_decode_attn_static: the shape needs more than
+                              THK_STATIC_SCRATCH_BYTES of scratch                */
 } thk_status;
 
 typedef enum { THK_F32 = 0, THK_BF16 = 1 } thk_dtype;
@@ -266,6 +268,30 @@ thk_status thk_decode_attn_kv(const thk_shape *shape, const void *q, const void 
                               const void *k_tail, const void *v_tail, int32_t s_tail,
                               int32_t s_tail_cap, void *out, void *ws, size_t ws_bytes,
                               void *stream);
+
+/*
+ * thk_decode_attn for callers that cannot allocate or carry a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels, same split and therefore the same bits as thk_decode_attn with
+ * n_split as given in the shape (0 = library choice), but the split partials go to a
+ * buffer of THK_STATIC_SCRATCH_BYTES that is part of the library's device image (a
+ * file-scope device array; each GPU the library runs on holds its own copy until the
+ * process ends).  The call allocates nothing and frees nothing.  The array's address on a
+ * device is looked up on the first call made with that device current (one runtime query,
+ * no allocation; make that first call outside graph capture).
+ *   - A shape whose thk_workspace_bytes(shape, THK_OP_DECODE) exceeds
+ *     THK_STATIC_SCRATCH_BYTES is rejected with THK_ERR_SCRATCH and nothing is enqueued
+ *     (the five workloads of the benchmark need 0.07 - 2.1 MiB).
+ *   - All calls on one GPU share that GPU's buffer: calls whose execution may overlap
+ *     (different streams, concurrent graphs) race on it and must be ordered by the caller.
+ *     Nothing in it needs to start at zero; a call overwrites every record it later reads.
+ */
+#define THK_STATIC_SCRATCH_BYTES (8u << 20)
+thk_status thk_decode_attn_static(const thk_shape *shape, const void *q,
+                                  const void *k_pruned, const int16_t *idx,
+                                  const void *v, const void *k_tail,
+                                  const void *v_tail, int32_t s_tail,
+                                  int32_t s_tail_cap, void *out, void *stream);
 
 /*
  * Append one newly decoded token per (layer, batch, KV head) to the unpruned

@@ -80,6 +80,8 @@ def load():
     L.thk_prune.argtypes = [sp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.thk_decode_attn.restype = ctypes.c_int
     L.thk_decode_attn.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    L.thk_decode_attn_static.restype = ctypes.c_int
+    L.thk_decode_attn_static.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
     i64 = ctypes.c_int64
     L.thk_decode_attn_kv.restype = ctypes.c_int
     L.thk_decode_attn_kv.argtypes = [sp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, i32, vp, vp,
@@ -280,6 +282,23 @@ def thk_decode_attn(shape, q, k_pruned, idx, v, k_tail, v_tail, s_tail, s_tail_c
     _check(load().thk_decode_attn(ctypes.byref(shape), _ptr(q), _ptr(k_pruned), _ptr(idx), _ptr(v),
                                   _ptr(k_tail), _ptr(v_tail), s_tail, s_tail_cap, _ptr(out),
                                   _ws(ws), _nbytes(ws), _stream(stream)), "thk_decode_attn")
+
+
+def thk_decode_attn_static(shape, q, k_pruned, idx, v, k_tail, v_tail, s_tail, s_tail_cap, out, stream=None):
+    U, H, ld = _dims(shape)
+    w = "thk_decode_attn_static"
+    _need(q, H * shape.D, "q", w)
+    _need(out, H * shape.D, "out", w)
+    rows = _cache_rows(shape, shape.S)
+    _need(k_pruned, U * rows * ld, "k_pruned", w)
+    _need(idx, U * shape.T, "idx", w)
+    _need(v, U * rows * shape.D, "v", w)
+    if s_tail > 0:
+        _need(k_tail, U * s_tail_cap * shape.D, "k_tail", w)
+        _need(v_tail, U * s_tail_cap * shape.D, "v_tail", w)
+    _check(load().thk_decode_attn_static(ctypes.byref(shape), _ptr(q), _ptr(k_pruned), _ptr(idx), _ptr(v),
+                                         _ptr(k_tail), _ptr(v_tail), s_tail, s_tail_cap, _ptr(out),
+                                         _stream(stream)), w)
 
 
 def thk_decode_attn_kv(shape, q, k_pruned, idx, v_pruned, idx_v, T_v, ld_v, k_tail, v_tail, s_tail,

@@ -4,6 +4,8 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <atomic>
+#include <mutex>
 
 #include "thk_internal.h"
 
@@ -231,6 +233,7 @@ const char *thk_status_string(thk_status st) {
     case THK_ERR_ALIGN: return "pointer not 16-byte aligned";
     case THK_ERR_WORKSPACE: return "workspace missing or too small";
     case THK_ERR_HIP: return "HIP launch failed";
+    case THK_ERR_SCRATCH: return "the call needs more scratch than the library's static buffer holds";
   }
   return "unknown status";
 }
@@ -578,6 +581,54 @@ thk_status thk_decode_attn_kv(const thk_shape *s, const void *q, const void *k_p
   if (T_v < 1) return s == nullptr ? THK_ERR_NULL : THK_ERR_SHAPE;
   return decode_common(s, q, k_pruned, idx, v_pruned, idx_v, T_v, ld_v, k_tail, v_tail, s_tail, s_tail_cap, out,
                        ws, ws_bytes, stream);
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------
+// Split partials of thk_decode_attn_static live in this file-scope device array instead of a
+// caller workspace.  Every GPU the library runs on holds its own copy, at its own address,
+// until the process ends.  In host code the array's NAME is only a stand-in for the symbol:
+// the memory is reached through the per-device address hipGetSymbolAddress returns, looked up
+// once per device on the entry point's first call there, and nowhere through the name.
+static __device__ __align__(256) unsigned char scratch[THK_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mu;
+
+// Device address of `scratch` on the current device (set-up on first use, no allocation).
+thk_status static_scratch(void **out) {
+  int dev = -1;
+  if (failed(hipGetDevice(&dev))) return THK_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return THK_ERR_UNSUPPORTED;
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (p == nullptr) {
+      if (failed(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) || p == nullptr) return THK_ERR_HIP;
+      g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+  }
+  *out = p;
+  return THK_OK;
+}
+}  // namespace
+
+thk_status thk_decode_attn_static(const thk_shape *s, const void *q, const void *k_pruned,
+                                  const int16_t *idx, const void *v, const void *k_tail,
+                                  const void *v_tail, int32_t s_tail, int32_t s_tail_cap, void *out,
+                                  void *stream) {
+  thk_status st = check_shape(s, false);
+  if (st != THK_OK) return st;
+  // the size check comes before anything touches the device
+  const size_t need = thk_workspace_bytes(s, THK_OP_DECODE);
+  if (need > (size_t)THK_STATIC_SCRATCH_BYTES) return THK_ERR_SCRATCH;
+  void *ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != THK_OK) return st;
+  return decode_common(s, q, k_pruned, idx, v, nullptr, 0, 0, k_tail, v_tail, s_tail, s_tail_cap, out, ws,
+                       (size_t)THK_STATIC_SCRATCH_BYTES, stream);
 }
 
 thk_status thk_tail_append(const thk_shape *s, const void *k_new, const void *v_new, void *k_tail,
