@@ -1,13 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the ThinK hot path on one MI355X.
 
-One step = one pass of the whole path over one batch of synthetic input of the
-LLaMA-2-7B-shaped workload: prune the key caches of all 32 layers (score ->
-Top_T -> compaction), then one decode-attention step per layer over the pruned
-cache.  Inputs are resident in HBM before the timed region.  Prints ONE JSON
-line; `value` is the algorithmic bytes of a step divided by its time.
+One step = one pass of the whole path over one batch of synthetic input: prune the key caches
+of all layers of the workload in one thk_prune call (score -> Top_T -> compaction), then the
+workload's decode-attention steps over the pruned cache (one thk_decode_attn call per layer
+and step, with thk_tail_append before it where the workload grows a tail).  Inputs are resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+The headline (`value`, `ms_per_step`, `roofline`, `cpu_baseline`, `value_cache`) is the
+LLaMA-2-7B-shaped workload (configs[1]), the one the metric is quoted on; with no --config the
+other four workloads are run as well and every workload gets an entry in `per_config`.
+
+Bytes.  `value` and every fraction are computed from the bytes the path has to move:
+  prune  per layer  U * S * e * (D + T) + |Q_obs|   when thk_prune keeps the rows on chip (K read
+                    once, T kept channels written once); the metric's own definition counts
+                    D + 2T per row (kept channels read a second time) and is reported beside it as
+                    `*_metric_def`, as a rate only -- the one-pass kernel moves fewer bytes than
+                    that, so a fraction of the HBM peak computed from it could exceed 1;
+  decode per step   U * e * [S * (T + D) + s_tail * 2 D].
 """
 import argparse
+import gc
+import glob
 import json
 import os
 import sys
@@ -18,6 +32,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+HEADLINE = 2            # the workload the metric is quoted on
 
 
 def parse():
@@ -25,12 +40,13 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload id (synth.CONFIGS); 2 = the metric's")
+    ap.add_argument("--config", type=int, default=0,
+                    help="workload id 1..5 (synth.CONFIGS) to run alone; 0 = headline workload + all five in per_config")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-value-cache", action="store_true",
                     help="skip the value-cache extension leg (value score, value prune, decode over both caches)")
-    ap.add_argument("--graph", action="store_true",
-                    help="additionally time the step replayed from a HIP graph (reported as graph_ms_per_step)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the replay of the step from a HIP graph (graph_ms_per_step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference dispatches of known size "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -63,13 +79,14 @@ def cpu_baseline(cfg_id, cfg, T, device, budget_s=20.0):
         t2 = time.perf_counter()
         t_prune += t1 - t0
         t_dec += t2 - t1
-        nbytes += U * cfg["S"] * eb * (cfg["D"] + 2 * T) + qn.nbytes + U * cfg["S"] * eb * (T + cfg["D"])
+        # the same byte accounting as the GPU figure: K once, kept channels written once, decode stream
+        nbytes += U * cfg["S"] * eb * (cfg["D"] + T) + qn.nbytes + U * cfg["S"] * eb * (T + cfg["D"])
         layers += 1
         if t_prune + t_dec > budget_s:
             break
     return {"value": nbytes / (t_prune + t_dec) / 1e9, "unit": "GB/s", "cores": O.max_threads(), "kind": "oracle",
-            "sample": f"{layers} of {cfg['L']} layers, all {U} units each: prune + 1 decode step per layer "
-                      f"({t_prune + t_dec:.1f} s of oracle time)",
+            "sample": f"{layers} of {cfg['L']} layers of configs[{cfg_id - 1}], all {U} units each: prune + 1 decode "
+                      f"step per layer ({t_prune + t_dec:.1f} s of oracle time)",
             "prune_ms_per_layer": t_prune / layers * 1e3, "decode_us_per_step": t_dec / layers * 1e6}
 
 
@@ -80,7 +97,7 @@ def value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k, v, kp, idx, dec, 
     HBM roofline (it streams K and V once) with its matrix-core rate beside it."""
     L, B, N_q, N_kv, D, S, S_obs = (cfg[n] for n in ("L", "B", "N_q", "N_kv", "D", "S", "S_obs"))
     U, G, dev = B * N_kv, N_q // N_kv, q_obs.device
-    cap, spl = cfg["tail_cap"], cfg["steps"]
+    cap = cfg["tail_cap"]
     T_v = T
     ld_v = (T_v + 3) // 4 * 4
     shape_v = thk.make_shape(L, B, N_q, N_kv, D, S, S_obs, T_v, ld_v, tdt, 0)
@@ -132,20 +149,22 @@ def value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k, v, kp, idx, dec, 
             "score_GBps": score_bytes / score_us / 1e3, "score_frac_of_hbm_peak": score_bytes / score_us / 1e3 / HBM_PEAK_GBS,
             "score_TFLOPs": score_flops / score_us / 1e6,
             "prune_value_ms_per_layer": prune_ms_layer, "prune_value_GBps": prune_v_bytes / L / prune_ms_layer / 1e6,
+            "prune_value_frac_of_hbm_peak": prune_v_bytes / L / prune_ms_layer / 1e6 / HBM_PEAK_GBS,
             "decode_kv_us_per_step": dec_us, "decode_kv_GBps": dec_bytes / dec_us / 1e3,
+            "decode_kv_frac_of_hbm_peak": dec_bytes / dec_us / 1e3 / HBM_PEAK_GBS,
             "decode_kv_bytes_vs_k_only": (T + T_v) / (T + D)}
 
 
-def measured_traffic(kernel):
-    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 counter summaries
-    (profiles/*.txt, lines 'traffic_bytes_per_launch <kernel> <bytes>'); None when absent."""
-    import glob
+def measured_traffic(cfg_id, kernel):
+    """HBM-side bytes per launch of `kernel` at workload cfg_id from the committed rocprofv3
+    counter summaries (profiles/*.txt, lines 'traffic_bytes_per_launch cfg<N> <kernel> <bytes>').
+    Returns (bytes, file name) or (None, None): the counters are not collected in this run."""
     for f in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
         for line in open(f):
             w = line.split()
-            if len(w) == 3 and w[0] == "traffic_bytes_per_launch" and w[1] == kernel:
-                return float(w[2])
-    return None
+            if len(w) == 4 and w[0] == "traffic_bytes_per_launch" and w[1] == f"cfg{cfg_id}" and w[2] == kernel:
+                return float(w[3]), "profiles/" + os.path.basename(f)
+    return None, None
 
 
 def device_facts(torch):
@@ -156,19 +175,9 @@ def device_facts(torch):
             "memory_bytes": p.total_memory}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (units are independent; no collective "
-              "exists in the path) -- run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    import torch
-    import paper_2407_21018_amd as thk
-    from paper_2407_21018_amd import synth
-
+def run_config(cfg_id, args, torch, thk, synth, full):
+    """Time workload cfg_id.  full: also the value-cache leg and the oracle leg (headline only)."""
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    cfg_id = args.config
     cfg = synth.CONFIGS[cfg_id]
     L, B, N_q, N_kv, D, S, S_obs = (cfg[k] for k in ("L", "B", "N_q", "N_kv", "D", "S", "S_obs"))
     T = thk.thk_keep_count(D, cfg["lam"])
@@ -178,6 +187,7 @@ def main():
     U = B * N_kv                      # units per layer
     steps_per_layer = cfg["steps"]
     cap = cfg["tail_cap"]
+    steps = args.steps
 
     # ---- inputs, resident in HBM ------------------------------------------
     q_obs = torch.empty(L, B, N_q, S_obs, D, dtype=dt, device=dev)
@@ -208,7 +218,7 @@ def main():
     # interval is the kernel's own begin-to-end time): the prune call of every step, and every
     # eighth decode call (offset rotating with the step)
     n_prof = max(1, n_dec // 8)
-    pairs = [[(ev(), ev()) for _ in range(1 + n_prof)] for _ in range(args.steps)]
+    pairs = [[(ev(), ev()) for _ in range(1 + n_prof)] for _ in range(steps)]
     torch.cuda.synchronize()
 
     def step(evs=None, ph=None, rot=0):
@@ -253,25 +263,25 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
-    phases = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    phases = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     e0.record()
     used_pairs = []
     # A workload with only a few calls per step would carry an event pair on every call, and a
     # launch with events attached costs the host ~12 us more than a plain one, which a step of
     # a few short calls does not hide; there the kernels are timed on every fourth step only and
     # the phases are read off the other steps.
-    sparse = n_dec < 8 and args.steps >= 2
-    kernel_steps = [i for i in range(args.steps) if not sparse or i % 4 == 0]
-    phase_steps = [i for i in range(args.steps) if not sparse or i % 4 != 0]
-    for i in range(args.steps):
+    sparse = n_dec < 8 and steps >= 2
+    kernel_steps = [i for i in range(steps) if not sparse or i % 4 == 0]
+    phase_steps = [i for i in range(steps) if not sparse or i % 4 != 0]
+    for i in range(steps):
         used_pairs += step(pairs[i] if i in kernel_steps else None, phases[i], i)
     e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    ms_per_step = e0.elapsed_time(e1) / steps
 
     graph_ms = None
-    if args.graph:
+    if not args.no_graph:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -284,11 +294,12 @@ def main():
         torch.cuda.synchronize()
         g0 = torch.cuda.Event(enable_timing=True); g1 = torch.cuda.Event(enable_timing=True)
         g0.record()
-        for _ in range(args.steps):
+        for _ in range(steps):
             gr.replay()
         g1.record()
         torch.cuda.synchronize()
-        graph_ms = g0.elapsed_time(g1) / args.steps
+        graph_ms = g0.elapsed_time(g1) / steps
+        del gr
 
     # main-kernel durations measured inside the timed region
     prune_kernel_us = [pairs[i][0][0].elapsed_time(pairs[i][0][1]) * 1e3 for i in kernel_steps]
@@ -299,18 +310,20 @@ def main():
     prune_ms_layer = sum(phases[i][0].elapsed_time(phases[i][1]) for i in phase_steps) / len(phase_steps) / L
     dec_us_step = sum(phases[i][1].elapsed_time(phases[i][2]) for i in phase_steps) / len(phase_steps) / n_dec * 1e3
 
-    # ---- algorithmic bytes (per layer), K and V counted once per KV head -----
+    # ---- bytes the path has to move (per layer), K and V counted once per KV head -----
+    form = thk.thk_prune_is_fused(shape_all)     # 2: rows held on chip, K read once
     qobs_bytes = B * N_q * S_obs * D * eb
-    prune_bytes = U * S * eb * (D + 2 * T) + qobs_bytes
+    prune_bytes_def = U * S * eb * (D + 2 * T) + qobs_bytes          # the metric's definition
+    prune_bytes = U * S * eb * (D + T) + qobs_bytes if form == 2 else prune_bytes_def
     mean_tail = (steps_per_layer + 1) / 2 if cap else 0
     decode_bytes = U * eb * (S * (T + D) + mean_tail * 2 * D)
     step_bytes = L * (prune_bytes + steps_per_layer * decode_bytes)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    form = thk.thk_prune_is_fused(shape_all)
-    fused = form != 0
     prune_kernel = {2: "k_prune_onepass", 1: "k_prune_fused", 0: "k_compact_flat"}[form]
-    prune_kernel_bytes = L * prune_bytes if fused else L * U * S * eb * (D + T)
+    # what the timed kernel itself has to move per launch (the staged form's compaction kernel
+    # is only the last of three: rows in, kept channels out)
+    prune_kernel_bytes = L * prune_bytes if form else L * U * S * eb * (D + T)
     decode_kernel = "k_decode_mq" if thk.thk_decode_on_matrix_cores(shape_1) else "k_decode"
     kernels = {
         prune_kernel: {"launches_per_step": 1, "avg_us": prune_k_us, "bytes_per_launch": prune_kernel_bytes,
@@ -319,42 +332,87 @@ def main():
                         "timed_launches": len(dec_kernel_us), "bytes_per_launch": decode_bytes,
                         "GBps": decode_bytes / dec_k_us / 1e3},
     }
-    # the dominant kernel = most time inside a step (at config 2 the two are within a few per cent
-    # of each other, so the other one's figures are reported beside it)
+
     def roof_of(name):
+        traffic, src = measured_traffic(cfg_id, name)
         return {"bound": "hbm", "kernel": name, "achieved": kernels[name]["GBps"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": kernels[name]["GBps"] / HBM_PEAK_GBS,
-                "traffic": measured_traffic(name) if cfg_id == 2 else None,
+                "traffic": traffic, "traffic_source": src,
                 "launch_us": kernels[name]["avg_us"], "bytes_per_launch": kernels[name]["bytes_per_launch"]}
+    # the dominant kernel = most time inside a step
     dom = max(kernels, key=lambda n: kernels[n]["avg_us"] * kernels[n]["launches_per_step"])
     roof = roof_of(dom)
     roof_other = roof_of(next(n for n in kernels if n != dom))
 
     res = {
-        "metric": "pruned-K decode attention us/step + achieved HBM GB/s; prune ms per layer",
-        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": f"configs[{cfg_id - 1}]: L={L} B={B} N_q={N_q} N_kv={N_kv} D={D} S={S} "
-                               f"S_obs={S_obs} lambda={cfg['lam']} T={T} {cfg['dtype']}; prune all layers, "
-                               f"then {steps_per_layer} decode step(s) per layer",
-                   "step_bytes": step_bytes},
-        "frac_of_hbm_peak": value / HBM_PEAK_GBS,
-        "prune_ms_per_layer": prune_ms_layer, "prune_GBps": prune_bytes / prune_ms_layer / 1e6,
+        "workload": f"configs[{cfg_id - 1}]: L={L} B={B} N_q={N_q} N_kv={N_kv} D={D} S={S} "
+                    f"S_obs={S_obs} lambda={cfg['lam']} T={T} {cfg['dtype']}; prune all layers, "
+                    f"then {steps_per_layer} decode step(s) per layer",
+        "dtype": cfg["dtype"], "steps": steps, "ms_per_step": ms_per_step, "graph_ms_per_step": graph_ms,
+        "step_bytes": step_bytes, "GBps": value, "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+        "prune_form": {2: "one launch, K read once", 1: "one launch, K read twice", 0: "three kernels"}[form],
+        "prune_ms_per_layer": prune_ms_layer, "prune_bytes_per_layer": prune_bytes,
+        "prune_GBps": prune_bytes / prune_ms_layer / 1e6,
         "prune_frac": prune_bytes / prune_ms_layer / 1e6 / HBM_PEAK_GBS,
-        "decode_us_per_step": dec_us_step, "decode_GBps": decode_bytes / dec_us_step / 1e3,
+        "prune_bytes_per_layer_metric_def": prune_bytes_def,
+        "prune_GBps_metric_def": prune_bytes_def / prune_ms_layer / 1e6,
+        "decode_us_per_step": dec_us_step, "decode_bytes_per_step": decode_bytes,
+        "decode_GBps": decode_bytes / dec_us_step / 1e3,
         "decode_frac": decode_bytes / dec_us_step / 1e3 / HBM_PEAK_GBS,
-        "host_wall_s": wall, "graph_ms_per_step": graph_ms,
-        "kernels": kernels,
-        "roofline": roof,
-        "roofline_other": roof_other,
+        "host_wall_s": wall,
+        "kernels": kernels, "roofline": roof, "roofline_other": roof_other,
+    }
+    if full and not args.no_value_cache:
+        res["value_cache"] = value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k, v, kp, idx, dec, kt, vt, out,
+                                             steps)
+    del q_obs, k, v, dec, score, idx, kp, out, kt, vt, ws, pairs, phases, used_pairs
+    gc.collect()
+    torch.cuda.empty_cache()
+    if full and not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg_id, cfg, T, dev)
+    return res
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (units are independent; no collective "
+              "exists in the path) -- run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2407_21018_amd as thk
+    from paper_2407_21018_amd import synth
+
+    torch.cuda.set_device(0)
+    head_id = args.config if args.config else HEADLINE
+    head = run_config(head_id, args, torch, thk, synth, full=True)
+    per_config = []
+    for cid in ([args.config] if args.config else sorted(synth.CONFIGS)):
+        r = head if cid == head_id else run_config(cid, args, torch, thk, synth, full=False)
+        per_config.append({k: v for k, v in r.items() if k not in ("value_cache", "cpu_baseline", "host_wall_s")}
+                          | {"config": cid})
+
+    res = {
+        "metric": "pruned-K decode attention us/step + achieved HBM GB/s; prune ms per layer",
+        "value": head["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"], "step_bytes": head["step_bytes"]},
+        "frac_of_hbm_peak": head["frac_of_hbm_peak"],
+        "prune_ms_per_layer": head["prune_ms_per_layer"], "prune_GBps": head["prune_GBps"],
+        "prune_frac": head["prune_frac"], "prune_GBps_metric_def": head["prune_GBps_metric_def"],
+        "decode_us_per_step": head["decode_us_per_step"], "decode_GBps": head["decode_GBps"],
+        "decode_frac": head["decode_frac"],
+        "host_wall_s": head["host_wall_s"], "graph_ms_per_step": head["graph_ms_per_step"],
+        "kernels": head["kernels"],
+        "roofline": head["roofline"],
+        "roofline_other": head["roofline_other"],
+        "per_config": per_config,
         "device": device_facts(torch),
     }
-    if not args.no_value_cache:
-        res["value_cache"] = value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k, v, kp, idx, dec, kt, vt, out,
-                                             args.steps)
-    if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cfg_id, cfg, T, dev)
+    for key in ("value_cache", "cpu_baseline"):
+        if key in head:
+            res[key] = head[key]
     print(json.dumps(res))
 
 
