@@ -559,7 +559,8 @@ static thk_status decode_common(const thk_shape *s, const void *q, const void *k
   a.units = units_of(s);
   a.unit_rows = unit_rows;
   a.unified_v = unified_v ? 1 : 0;
-  a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)s->D));
+  a.scale_log2_d = 1.4426950408889634 / sqrt((double)s->D);
+  a.scale_log2 = (float)a.scale_log2_d;
   a.idx_v = idx_v; a.T_v = pruned_v ? T_v : 0; a.ld_v = pruned_v ? ld_v : 0;
   if (failed(launch_decode(a, (hipStream_t)stream))) return THK_ERR_HIP;
   return THK_OK;

@@ -77,6 +77,12 @@ __device__ inline float wave_sum(float x) {
 }
 // value of the neighbouring lane (lane ^ 1): quad_perm [1,0,3,2]
 __device__ inline float lane_swap1(float x) { return dpp_move<0xB1, 0xf>(0.f, x); }
+__device__ inline double lane_swap1(double x) {
+  const long long b = __double_as_longlong(x);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), 0xB1, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), 0xB1, 0xf, 0xf, false);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
 
 // RA bytes of an LDS row at element offset t, widened to floats.
 template <int DT, int RA>
@@ -126,6 +132,11 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ inline float dot2_bf16(uint32_t a, uint32_t b, float c) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
 }
+
+template <int DT> struct LogitType { using type = float; };
+template <> struct LogitType<THK_F32> { using type = double; };
+__device__ inline float fma_z(float a, float b, float c) { return fmaf(a, b, c); }
+__device__ inline double fma_z(double a, double b, double c) { return fma(a, b, c); }
 
 template <int DT, int GT>
 struct TileState {
@@ -211,15 +222,22 @@ __device__ __forceinline__ void v_issue(u32x4 (&vr)[NV], const u32x4 *__restrict
 // bytes are in vrp (KBV staged chunks per lane) and are walked out of LDS as described by vp.
 // PV = 2: a full-width tile (the tail) of a kernel that also carries pruned-value sums, which
 // follow every change of the running maximum.
+// Precision of a logit.  bf16 inputs: products are exact in fp32 and the sum runs in fp32.  fp32
+// inputs: the dot product and the scaling run in fp64 and the running maximum is subtracted
+// before the result is rounded to fp32, so the error of exp2(z - m) does not grow with |z| (an
+// fp32 logit of a few thousand -- channel scales of sigma = 2 on query and keys -- is only
+// accurate to 1e-4 in absolute terms, which is the whole error budget of fp32 outputs).
 template <int DT, int GT, int RA, int TR, int NV, int PV = 0, int KBV = 1>
 __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld,
                                              const float *__restrict__ qs,
                                              const uint32_t *__restrict__ qp,
                                              const u32x4 *__restrict__ vg,
                                              u32x4 (&vr)[NV], const char *kbuf,
-                                             float *ps, TileState<DT, GT> &st, float scale, int lane,
+                                             float *ps, TileState<DT, GT> &st, double scale_d, int lane,
                                              const u32x4 (*vrp)[KBV] = nullptr, const VPruned *vp = nullptr) {
   using E = Elem<DT>;
+  using ZT = typename LogitType<DT>::type;   // accumulator of a logit: float (bf16 inputs), double (fp32 inputs)
+  const ZT scale = (ZT)scale_d;
   using VS = VShape<DT, TR>;
   constexpr int VEC = E::VEC, EB = E::EB;
   constexpr int LPK = kWave / TR;            // lanes that share one K row (1 or 2)
@@ -234,9 +252,9 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
   const int gran0 = (n_gran + LPK - 1) / LPK;              // granules of lane share 0 = trip count
   const int my_first = h * gran0;
   const int my_cnt = (LPK == 1 || h == 0) ? gran0 : n_gran - gran0;
-  float z[GT];
+  ZT z[GT];
 #pragma unroll
-  for (int g = 0; g < GT; ++g) z[g] = 0.f;
+  for (int g = 0; g < GT; ++g) z[g] = (ZT)0;
   if constexpr (DT == THK_BF16 && RA >= 4) {
     // bf16 pairs straight from LDS into v_dot2c_f32_bf16: products are exact, sums in fp32
     constexpr int DW = RA / 4;   // words per granule
@@ -268,14 +286,14 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
 #pragma unroll
       for (int g = 0; g < GT; ++g)
 #pragma unroll
-        for (int e = 0; e < EPR; ++e) z[g] = fmaf(f[e], qs[g * kQS + tq + e], z[g]);
+        for (int e = 0; e < EPR; ++e) z[g] = fma_z((ZT)f[e], (ZT)qs[g * kQS + tq + e], z[g]);
     }
   }
   for (int t = n_gran * EPR; t < W; ++t) {   // elements past the last whole granule: share 0
     const float f = E::load1(rowp, t);
     const int tq = (LPK == 1 || h == 0) ? t : kD;
 #pragma unroll
-    for (int g = 0; g < GT; ++g) z[g] = fmaf(f, qs[g * kQS + tq], z[g]);
+    for (int g = 0; g < GT; ++g) z[g] = fma_z((ZT)f, (ZT)qs[g * kQS + tq], z[g]);
   }
   if constexpr (LPK == 2) {
 #pragma unroll
@@ -287,7 +305,8 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
   float pr[GT];
 #pragma unroll
   for (int g = 0; g < GT; ++g) {
-    const float zz = r < nrows ? z[g] * scale : -INFINITY;
+    const ZT zs = z[g] * scale;
+    const float zz = r < nrows ? (float)zs : -INFINITY;
     const float m_new = max_nn(st.m[g], wave_max(zz));   // finite: the tile has >= 1 row
     if (m_new != st.m[g]) {                             // wave-uniform; rare after the first tiles
       const float corr = __builtin_amdgcn_exp2f(st.m[g] - m_new);
@@ -300,7 +319,12 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
       }
       st.m[g] = m_new;
     }
-    pr[g] = __builtin_amdgcn_exp2f(zz - m_new);
+    // fp32 inputs: z - m in fp64, then one rounding (m_new is the maximum of the ROUNDED logits, so
+    // the difference may exceed 0 by half an fp32 ulp of a logit: a factor 1 + 1e-4 at most)
+    if constexpr (DT == THK_F32)
+      pr[g] = r < nrows ? __builtin_amdgcn_exp2f((float)(zs - (ZT)m_new)) : 0.f;
+    else
+      pr[g] = __builtin_amdgcn_exp2f(zz - m_new);
     st.l[g] += pr[g];
   }
   // probabilities to LDS as [row][GT]
@@ -536,9 +560,9 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     wave_sync_lds();
     if constexpr (VP)
       tile_compute<DT, GT, RA, TR, NV, 1, KB>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st,
-                                              a.scale_log2, lane, &vrp, &vpd);
+                                              a.scale_log2_d, lane, &vrp, &vpd);
     else
-      tile_compute<DT, GT, RA, TR, NV>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st, a.scale_log2, lane);
+      tile_compute<DT, GT, RA, TR, NV>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st, a.scale_log2_d, lane);
   }
 
   // ---- unpruned tail segment (full-width keys, full query) ------------------
@@ -554,7 +578,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
     k_commit<KBT>(kt, kbuf, lane);
     wave_sync_lds();
-    tile_compute<DT, GT, 16, TR, NV, (VP ? 2 : 0)>(0, nrows, kD, kD, qf, qfp, vg, vr, kbuf, ps, st, a.scale_log2,
+    tile_compute<DT, GT, 16, TR, NV, (VP ? 2 : 0)>(0, nrows, kD, kD, qf, qfp, vg, vr, kbuf, ps, st, a.scale_log2_d,
                                                     lane);
   }
 

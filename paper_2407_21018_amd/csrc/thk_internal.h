@@ -121,6 +121,7 @@ struct DecodeArgs {
   int32_t T, ldk, N_q, N_kv, s_tail, s_tail_cap, n_split, dtype;
   int64_t units;              // L * B * N_kv
   float scale_log2;           // log2(e) / sqrt(D)
+  double scale_log2_d;        // the same, not rounded to float (logits of fp32 inputs)
   // channel-pruned values (T_v > 0): v is V_pruned, rows ld_v elements apart, channels idx_v
   const int16_t *idx_v;
   int32_t T_v, ld_v;
