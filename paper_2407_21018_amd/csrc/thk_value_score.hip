@@ -12,8 +12,8 @@
 // number w / QT of every chunk.  Per 32-key sub-tile a wave computes
 //   S^T = K_sub Q^T        8 x v_mfma_f32_32x32x16_bf16 (A = keys from LDS, B = queries in VGPRs)
 //   P^T = exp2(S^T - m)    in the accumulator layout, which already is the B-operand layout
-//   O^T += V_sub^T P^T     8 x MFMA; the A operand (values transposed) comes from row-major LDS
-//                          through ds_read_b64_tr_b16
+//   O^T += V_sub^T P^T     16 x MFMA (P^T as two bf16 terms, hi + lo); the A operand (values
+//                          transposed) comes from row-major LDS through ds_read_b64_tr_b16
 // so neither the softmax maximum (a query is a lane column: 16 registers and one cross-half
 // exchange) nor the probabilities ever move between lanes.
 #include "thk_internal.h"
@@ -192,18 +192,18 @@ __global__ __launch_bounds__(256, 2) void k_value_attn_bf16(ValueAttnArgs a) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[ks], s, 0, 0, 0);
       }
       softmax_step(s, kb, h, lim, lim_min, a.scale_log2, m_run, l_run, o);
-      // probabilities, rounded to bf16 once; the same rounded values feed the row sum
-      // (v_dot2_f32_bf16 against a pair of ones adds two of them per instruction)
-      bf16x8 pb[2];
+      // The probabilities enter the second product as TWO bf16 terms, p = hi + lo with hi the
+      // nearest bf16 to p and lo the nearest bf16 to p - hi (that difference is exact in fp32):
+      // |p - hi - lo| <= 2^-18 p, so the matrix product loses nothing that fp32 arithmetic keeps.
+      // The row sum takes the fp32 values.
+      bf16x8 ph[2], pl[2];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) pb[r >> 3][r & 7] = (__bf16)s[r];
-#pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const bf16x2 pr = {pb[k2][2 * i], pb[k2][2 * i + 1]};
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l_run, false);
-        }
+      for (int r = 0; r < 16; ++r) {
+        const __bf16 hi = (__bf16)s[r];
+        ph[r >> 3][r & 7] = hi;
+        pl[r >> 3][r & 7] = (__bf16)(s[r] - (float)hi);
+        l_run += s[r];
+      }
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) {
 #pragma unroll
@@ -215,7 +215,8 @@ __global__ __launch_bounds__(256, 2) void k_value_attn_bf16(ValueAttnArgs a) {
               (__attribute__((address_space(3))) s16x4 *)(vp + 8 * kVst));
           const bf16x8 va = __builtin_bit_cast(
               bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[k2], o[dt], 0, 0, 0);
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, ph[k2], o[dt], 0, 0, 0);
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pl[k2], o[dt], 0, 0, 0);
         }
       }
     }

@@ -139,9 +139,11 @@ def test_config_value_prune_and_decode(cfg_id):
     """The value-cache path at full size, in the launch configuration the benchmark uses: one
     thk_prune_value call over all layers (causal window), then thk_decode_attn_kv per layer.
     The fp64 oracle recomputes the value score on a fixed sample of units spread over the call
-    (an S_obs x S attention per unit and head); the selection is checked on EVERY unit in the
-    kernel's precision, the compacted values bit for bit on the sampled units, and the decode
-    output on the sampled units' heads."""
+    (an S_obs x S attention per unit and head): there the score is held to 1e-5 relative per
+    channel and the index list is compared with the ORACLE's own ranking (differences only in
+    channels that tie with the threshold score within 1e-5).  On EVERY unit the list must equal
+    the selection from the scores the GPU produced; the compacted values are checked bit for bit
+    on the sampled units, and the decode output on the sampled units' heads."""
     _value_cfg_body(cfg_id)
 
 
@@ -177,28 +179,20 @@ def _value_cfg_body(cfg_id):
     units = sorted({int(round(i * (L * U - 1) / max(1, n_s - 1))) for i in range(n_s)})
     qf = q_obs.reshape(L * U, G, S_obs, D)
     kf, vf = k.reshape(L * U, S, D), v.reshape(L * U, S, D)
-    worst_med, worst_hard = 0.0, 0.0
+    from test_gpu_value import SCORE_V_TOL, check_idx_against_oracle_ranking
     ui = torch.tensor(units, device=DEV)
     # one oracle call for all sampled units (its OpenMP loop runs over units)
     want_all = O.score_value(as_numpy(qf[ui])[:, None], as_numpy(kf[ui])[:, None, None],
                              as_numpy(vf[ui])[:, None, None], dtn, causal=True)[:, 0, 0]
-    for j, u in enumerate(units):
-        want = want_all[j]
-        err = np.abs(g_sc[u] - want)
-        v64 = vf[u].cpu().to(torch.float64).numpy()
-        if dtn == "bf16":
-            hard = G * np.sqrt(S_obs) * 2.0 ** -8 * np.abs(v64).max(axis=0) + 1e-6 * want
-            assert np.all(err <= hard), f"unit {u}"
-            worst_hard = max(worst_hard, float((err / hard).max()))
-            worst_med = max(worst_med, float(np.median(err / want)))
-        else:
-            scale = np.maximum(want, G * np.sqrt(S_obs) * np.abs(v64).mean(axis=0))
-            assert np.all(err <= 1e-5 * scale), f"unit {u}"
+    rel = np.abs(g_sc[units] - want_all) / want_all
+    g_idx = idx_v.cpu().numpy()
+    n_diff = check_idx_against_oracle_ranking(g_idx[units], want_all, T_v)
+    print(f"config {cfg_id} value score on units {units}: max rel err {rel.max():.2e}, median {np.median(rel):.2e}; "
+          f"{n_diff} channels differ from the oracle's ranking (ties)", flush=True)
+    assert rel.max() <= SCORE_V_TOL
+    for u in units:
         got_vp = as_numpy(vp.reshape(L * U, S, ld_v)[u][:, :T_v].contiguous())
         np.testing.assert_array_equal(got_vp, O.compact_keys(as_numpy(vf[u])[None], want_idx[u][None], dtn)[0])
-    assert worst_med <= 1e-3
-    print(f"config {cfg_id} value score on units {units}: worst median rel err {worst_med:.2e}, "
-          f"worst err / hard bound {worst_hard:.2e}", flush=True)
 
     # decode over both pruned caches: prune the keys as the benchmark does, then one step per
     # sampled layer, checked on the batch rows that hold sampled units

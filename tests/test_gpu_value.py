@@ -1,13 +1,13 @@
 """GPU parity of the value-cache path (Appendix "Value Cache Pruning"): value-channel score
 on the matrix cores, selection and compaction of value channels, against the CPU fp64 oracle.
 
-Tolerance of the score.  The kernel rounds each softmax probability to bf16 once (relative
-error <= 2^-9) and normalises by the sum of the rounded values, so every row of A stays a
-convex combination: |o_ij - o_ij(exact)| <= 2^-9 * sum_s p_s |v_sj - o_ij| / sum_s p_s
-<= 2^-8 max_s |V[s, j]|, hence |Score_v[j] - exact| <= G sqrt(S_obs) 2^-8 max_s |V[s, j]| in the
-worst case (HARD_TOL, checked on every channel).  The errors of different keys are independent
-and mostly cancel; the typical deviation is a few 1e-4 of the score, and the test also bounds the
-median relative error by MEDIAN_TOL.
+Tolerance of the score: 1e-5 relative, per channel, for both element types.  Logits and
+softmax run in fp32; with bf16 tensors each probability enters the product with V as two bf16
+terms (hi + lo, |p - hi - lo| <= 2^-18 p), so nothing is lost against fp32 arithmetic, and the
+row sum takes the fp32 probabilities.  What is left is the fp32 accumulation over the keys
+(measured: 1e-7 typical, up to 5e-6 on short windows where a channel's few outputs nearly
+cancel).  The index set is compared with the ORACLE's own ranking: the two may differ only in
+channels whose oracle score lies within TIE_V_TOL (relative) of the oracle's T-th largest.
 """
 import numpy as np
 import pytest
@@ -20,8 +20,8 @@ from helpers import DT, TDT, gpu_compact, gpu_select, ws_tensor
 
 pytestmark = pytest.mark.gpu
 D = 128
-MEDIAN_TOL = 1e-3
-F32_TOL = 1e-5      # fp32 products and sums throughout: relative, per channel
+SCORE_V_TOL = 1e-5   # relative, per channel, fp32 and bf16 tensors alike
+TIE_V_TOL = 1e-5     # oracle scores closer than this (relative) to the T-th largest may swap
 
 
 def _randn(shape, dtype, seed, sigma=0.0):
@@ -42,21 +42,26 @@ def gpu_score_value(shape, q_obs, k, v, causal):
 
 
 def check_score(got, want, v_np_f64, G, S_obs, tag, dtype="bf16"):
-    """got, want [U, D]; v_np_f64 [U, S, D]."""
-    err = np.abs(got - want)
-    if dtype == "f32":
-        # relative to the channel's scale: a column whose outputs cancel keeps absolute accuracy
-        scale = np.maximum(want, G * np.sqrt(S_obs) * np.abs(v_np_f64).mean(axis=1))
-        print(f"{tag} f32: max err/scale {(err / scale).max():.3e}", flush=True)
-        assert np.all(err <= F32_TOL * scale)
-        return
-    hard = G * np.sqrt(S_obs) * 2.0 ** -8 * np.abs(v_np_f64).max(axis=1) + 1e-6 * want
-    rel = err / np.maximum(want, 1e-30)
-    print(f"{tag}: max rel {rel.max():.3e} median rel {np.median(rel):.3e} "
-          f"max err/hard bound {(err / hard).max():.3e}", flush=True)
+    """got, want [U, D] (want > 0 for any non-zero value column)."""
     assert np.all(np.isfinite(got))
-    assert np.all(err <= hard)
-    assert np.median(rel) <= MEDIAN_TOL
+    rel = np.abs(got - want) / np.maximum(want, 1e-300)
+    print(f"{tag} {dtype}: max rel {rel.max():.3e} median rel {np.median(rel):.3e}", flush=True)
+    assert rel.max() <= SCORE_V_TOL
+
+
+def check_idx_against_oracle_ranking(gpu_idx, ora_score, T_v):
+    """gpu_idx [U, T_v] against Top_T of the oracle's own scores [U, D]: ascending, valid, and
+    different only in channels that tie with the threshold score within TIE_V_TOL."""
+    ora_idx = O.select_topk(ora_score, T_v)
+    n_diff = 0
+    for u in range(ora_score.shape[0]):
+        g = gpu_idx[u].tolist()
+        assert g == sorted(set(g)) and len(g) == T_v and 0 <= g[0] and g[-1] < D, f"unit {u}: invalid list"
+        thr = np.sort(ora_score[u])[::-1][T_v - 1]
+        for c in set(g) ^ set(ora_idx[u].tolist()):
+            n_diff += 1
+            assert abs(ora_score[u, c] - thr) <= TIE_V_TOL * thr, (u, c, ora_score[u, c], thr)
+    return n_diff
 
 
 CASES = [
@@ -104,9 +109,8 @@ def test_value_score_split_count_changes_only_rounding():
         got = gpu_score_value(shape, q_obs, k, v, 1).cpu().numpy().astype(np.float64)
         if ref is None:
             ref = got
-        # the probabilities are rounded relative to the running maximum of their own piece, so
-        # a different cut rounds differently: same tolerance class as against the oracle
-        assert np.median(np.abs(got - ref) / ref) <= MEDIAN_TOL
+        # a different cut changes the order of the fp32 sums: same tolerance class as against the oracle
+        assert (np.abs(got - ref) / ref).max() <= 2 * SCORE_V_TOL
 
 
 def test_value_prune_select_and_compact():
@@ -126,14 +130,9 @@ def test_value_prune_select_and_compact():
     vp = gpu_compact(shape, v, idx)
     want_vp = O.compact_keys(as_numpy(v).reshape(-1, S, D), want_idx, "bf16")
     np.testing.assert_array_equal(as_numpy(vp), want_vp)
-    # the oracle's own ranking differs only where its scores are within the score tolerance
+    # ... and the list agrees with the ORACLE's own ranking up to exact-tolerance ties
     ora = O.score_value(as_numpy(q_obs), as_numpy(k), as_numpy(v), "bf16", causal=True).reshape(-1, D)
-    ora_idx = O.select_topk(ora, T_v)
-    for u in range(ora.shape[0]):
-        diff = set(ora_idx[u].tolist()) ^ set(want_idx[u].tolist())
-        thr = np.sort(ora[u])[::-1][T_v - 1]
-        for c in diff:
-            assert abs(ora[u, c] - thr) <= 4e-3 * thr, (u, c, ora[u, c], thr)
+    check_idx_against_oracle_ranking(idx.cpu().numpy(), ora, T_v)
 
 
 def test_value_score_argument_errors():
