@@ -26,6 +26,13 @@
  *     thk_workspace_bytes(shape, op) bytes, 16-byte aligned (THK_ERR_WORKSPACE).
  *   - Inputs must be finite; results for NaN/Inf inputs are unspecified.
  *   - Element types: fp32 and bf16.  D must be 128.
+ *   - Built for one card: gfx950 code only, and the launch heuristics (default splits,
+ *     block sizes of the prune, its graded start) assume an MI355X in SPX mode -- 256
+ *     compute units at about 2.4 GHz behind one device, 8 TB/s of HBM.  On another
+ *     partitioning the results are the same and the launch shapes are merely not tuned.
+ *   - The THK_* environment switches named below are for experiments and tests.  They
+ *     are read once per process, on the first call that needs them; thk_reload_env()
+ *     reads them again.
  */
 #ifndef THK_H
 #define THK_H
@@ -81,6 +88,12 @@ typedef struct {
 
 /* Library version, major*10000 + minor*100 + patch. */
 int32_t thk_version(void);
+
+/* Reads the THK_* environment switches again (they are otherwise read once per process).
+ * A hook for tests and experiments; not meant to be called while other threads are inside
+ * the library's entry points with a call half planned (each entry point takes one
+ * consistent snapshot, so the worst case is a call planned with the previous values). */
+void thk_reload_env(void);
 
 /* Static string for a status code. */
 const char *thk_status_string(thk_status st);
@@ -205,7 +218,7 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
  * the three kernels one after the other.  Scores agree with thk_score to fp64
  * summation order (the last float bit can differ).  `score` may be NULL (then
  * it lives in ws).
- * Environment (read per call, for experiments and tests): THK_PRUNE_PATH =
+ * Environment (for experiments and tests): THK_PRUNE_PATH =
  * staged | fused | reread (the one-kernel form with the rows read twice);
  * THK_PRUNE_BLOCK_ROWS (rows per block; 128, 256 and 512 are held on chip),
  * THK_PRUNE_HOLD_ROWS (largest default block), THK_PRUNE_MAX_BLOCKS (blocks
@@ -239,8 +252,8 @@ thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,
  * value byte a block reads (probabilities as two bf16 terms, exact to 2^-16;
  * accumulation in fp32; elements of a padded row past T are masked, whatever they
  * hold).  For T that is not a multiple of 4 (51, 89, ...) a pitch rounded up to one
- * therefore pays with several query heads per KV head. THK_DECODE_MFMA=0 in the environment (read per
- * call, for experiments and tests) keeps them on the general kernel.
+ * therefore pays with several query heads per KV head. THK_DECODE_MFMA=0 in the environment
+ * (for experiments and tests) keeps them on the general kernel.
  *   ws : THK_OP_DECODE bytes.
  */
 thk_status thk_decode_attn(const thk_shape *shape, const void *q,

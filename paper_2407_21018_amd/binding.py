@@ -50,6 +50,8 @@ def load():
     sp, vp, i32 = ctypes.POINTER(thk_shape), ctypes.c_void_p, ctypes.c_int32
     L.thk_version.restype = i32
     L.thk_version.argtypes = []
+    L.thk_reload_env.restype = None
+    L.thk_reload_env.argtypes = []
     L.thk_status_string.restype = ctypes.c_char_p
     L.thk_status_string.argtypes = [ctypes.c_int]
     L.thk_last_hip_error.restype = ctypes.c_char_p
@@ -170,6 +172,11 @@ def _check(st, where):
 
 def thk_version():
     return int(load().thk_version())
+
+
+def thk_reload_env():
+    """Make the library read its THK_* environment switches again (it reads them once per process)."""
+    load().thk_reload_env()
 
 
 def thk_status_string(st):

@@ -14,7 +14,48 @@ using namespace thk;
 namespace thk {
 namespace {
 thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+
+std::atomic<const EnvSwitches *> g_env{nullptr};
+std::mutex g_env_mu;
+
+long env_long_raw(const char *name, long unset) {
+  const char *e = getenv(name);
+  return (e == nullptr || *e == 0) ? unset : atol(e);
 }
+
+// A fresh, immutable snapshot of the switches; earlier snapshots stay valid for threads that
+// still hold them (reloading is a test hook: the few bytes per reload are never freed).
+const EnvSwitches *read_env() {
+  EnvSwitches *s = new EnvSwitches();
+  const char *path = getenv("THK_PRUNE_PATH");
+  s->prune_path = (path != nullptr) ? path[0] : 0;
+  s->group_mib = env_long_raw("THK_PRUNE_GROUP_MIB", 0);
+  s->block_rows = env_long_raw("THK_PRUNE_BLOCK_ROWS", 0);
+  s->hold_rows = env_long_raw("THK_PRUNE_HOLD_ROWS", 0);
+  s->max_blocks = env_long_raw("THK_PRUNE_MAX_BLOCKS", -1);
+  s->spin_limit = env_long_raw("THK_PRUNE_SPIN_LIMIT", -1);
+  const char *ns = getenv("THK_PRUNE_STAGGER_NS");
+  s->stagger_set = ns != nullptr;
+  s->stagger_ns = ns != nullptr ? atof(ns) : -1.0;
+  const char *mf = getenv("THK_DECODE_MFMA");
+  s->decode_mfma_off = mf != nullptr && mf[0] == '0';
+  return s;
+}
+}  // namespace
+
+const EnvSwitches &env_switches() {
+  const EnvSwitches *s = g_env.load(std::memory_order_acquire);
+  if (s == nullptr) {
+    std::lock_guard<std::mutex> lock(g_env_mu);
+    s = g_env.load(std::memory_order_relaxed);
+    if (s == nullptr) {
+      s = read_env();
+      g_env.store(s, std::memory_order_release);
+    }
+  }
+  return *s;
+}
+
 hipError_t launch_main_kernel(const void *fn, dim3 grid, dim3 block, void **args, size_t lds, hipStream_t st) {
   if (g_prof_start == nullptr || g_prof_stop == nullptr) return hipLaunchKernel(fn, grid, block, args, lds, st);
   const hipEvent_t e0 = g_prof_start, e1 = g_prof_stop;
@@ -122,10 +163,7 @@ Split decode_split(const thk_shape *s) {
 // but measured launch overheads outweigh that; the default keeps groups large.
 int64_t prune_group_units(const thk_shape *s) {
   size_t budget = (size_t)1024 << 20;
-  if (const char *e = getenv("THK_PRUNE_GROUP_MIB")) {
-    const long v = atol(e);
-    if (v > 0) budget = (size_t)v << 20;
-  }
+  if (env_switches().group_mib > 0) budget = (size_t)env_switches().group_mib << 20;
   const size_t per_unit = (size_t)s->S * kD * elem_bytes(s->dtype);
   int64_t g = (int64_t)(budget / per_unit);
   if (g < 1) g = 1;
@@ -134,12 +172,6 @@ int64_t prune_group_units(const thk_shape *s) {
 }
 
 // ---- one-launch prune: eligibility and blocking -------------------------------
-long env_long(const char *name, long dflt) {
-  const char *e = getenv(name);
-  if (e == nullptr || *e == 0) return dflt;
-  return atol(e);
-}
-
 struct FusedPlan { bool ok; int NB; int64_t RB; int hold; };
 
 // The one-launch forms of thk_prune.  Blocks take 512 bf16 / 256 fp32 rows each (measured best on
@@ -148,17 +180,18 @@ struct FusedPlan { bool ok; int NB; int64_t RB; int hold; };
 // levels), longer sequences go through the staged path instead.
 FusedPlan fused_plan(const thk_shape *s) {
   FusedPlan p{false, 0, 0, 0};
-  const char *path = getenv("THK_PRUNE_PATH");
-  if (path != nullptr && path[0] == 's') return p;   // "staged": the three-kernel path
+  const EnvSwitches &env = env_switches();
+  const char path = env.prune_path;
+  if (path == 's') return p;   // "staged": the three-kernel path
   if (s->S_cap != 0 && s->S_cap < keep_rows(s)) return p;
-  int64_t rb = env_long("THK_PRUNE_BLOCK_ROWS", 0);
+  int64_t rb = env.block_rows;
   if (rb <= 0) {
     // the default block size: 128 KB of rows, the most a block can hold on chip (512 bf16 rows,
     // 256 fp32 rows); small calls take the smallest held size (down to 128 rows) that keeps the
     // launch within two blocks per compute unit, i.e. within one round of resident blocks:
     // a launch that spills into a second round pays the whole load -> list -> store chain twice
     // (32 units of 4096 bf16 rows: 23 us with 512 blocks of 256 rows, 36 us with 1024 of 128)
-    const int64_t rb_max = env_long("THK_PRUNE_HOLD_ROWS", s->dtype == THK_BF16 ? 512 : 256);
+    const int64_t rb_max = env.hold_rows > 0 ? env.hold_rows : (s->dtype == THK_BF16 ? 512 : 256);
     auto blocks = [&](int64_t r) { return units_of(s) * ceil_div(s->S, r); };
     rb = rb_max;
     while (rb > 128 && (blocks(rb / 2) <= (int64_t)kCUs * 2 || blocks(rb / 2) == blocks(rb))) rb /= 2;
@@ -167,7 +200,7 @@ FusedPlan fused_plan(const thk_shape *s) {
   rb = ceil_div(rb, 32) * 32;
   // blocks of 128, 256 or 512 rows (fp32: 128 or 256) keep their rows on chip between the
   // column sums and the compaction; other sizes, or THK_PRUNE_PATH=reread, read them twice
-  const bool reread = path != nullptr && path[0] == 'r';
+  const bool reread = path == 'r';
   if (!reread && (rb == 128 || rb == 256 || (rb == 512 && s->dtype == THK_BF16))) p.hold = (int)(rb / 128);
   const int64_t nb = ceil_div(s->S, rb);
   // the blocks of a unit wait for each other, so all of them must be resident at once; 256 where
@@ -175,8 +208,8 @@ FusedPlan fused_plan(const thk_shape *s) {
   // (LDS decides: 2 KB + four tiles + 7 KB per block, i.e. three bf16 blocks or two fp32 blocks
   // per compute unit)
   const long fit = p.hold == 0 ? 256L : (s->dtype == THK_BF16 ? 3L : 2L) * kCUs;
-  const bool forced = path != nullptr && (path[0] == 'f' || path[0] == 'r');   // regardless of the env limit
-  if (nb > (forced ? fit : std::min(fit, env_long("THK_PRUNE_MAX_BLOCKS", fit)))) return p;
+  const bool forced = path == 'f' || path == 'r';   // regardless of the env limit
+  if (nb > (forced || env.max_blocks < 0 ? fit : std::min(fit, env.max_blocks))) return p;
   p.RB = rb;
   p.NB = (int)nb;
   p.ok = units_of(s) * p.NB <= kMaxGrid;
@@ -215,7 +248,12 @@ size_t score_ws_bytes(const thk_shape *s, int64_t units) {
 
 extern "C" {
 
-int32_t thk_version(void) { return 100; }
+int32_t thk_version(void) { return 200; }
+
+void thk_reload_env(void) {
+  std::lock_guard<std::mutex> lock(g_env_mu);
+  g_env.store(read_env(), std::memory_order_release);
+}
 
 void thk_profile_next(void *ev_start, void *ev_stop) {
   g_prof_start = (ev_start != nullptr && ev_stop != nullptr) ? (hipEvent_t)ev_start : nullptr;
@@ -450,7 +488,7 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
   float *sc = score != nullptr ? score : (float *)((char *)ws + score_off);
   const FusedPlan fp = fused_plan(s);
   if (fp.ok) {
-    const int spin = (int)env_long("THK_PRUNE_SPIN_LIMIT", 4096);
+    const int spin = env_switches().spin_limit >= 0 ? (int)env_switches().spin_limit : 4096;
     if (failed(launch_prune_fused(s->dtype, q_obs, k, sc, idx, k_pruned, ws, U, s->S, keep_rows(s),
                                   cache_rows(s, keep_rows(s)), G, s->S_obs, s->T, ld_of(s), fp.NB, fp.RB, fp.hold,
                                   spin < 0 ? 0 : spin, hs)))

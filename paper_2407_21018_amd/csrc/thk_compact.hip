@@ -26,9 +26,9 @@ __global__ __launch_bounds__(256) void k_compact_flat(CompactArgs a) {
 // Full-width row copy dst[u][dst_row0 + r][:] = src[u][src_row0 + r][:], r < n_rows.
 // One block per unit; rows move in ascending chunks, each chunk loaded completely
 // before any of it is stored, so a downward shift inside one buffer
-// (dst_row0 <= src_row0) is safe.
+// (dst_row0 <= src_row0) is safe.  src and dst may alias: neither is declared restrict.
 template <int DT>
-__global__ __launch_bounds__(256) void k_copy_rows(const void *__restrict__ src, void *dst,
+__global__ __launch_bounds__(256) void k_copy_rows(const void *src, void *dst,
                                                    int64_t src_unit_rows, int64_t src_row0,
                                                    int64_t dst_unit_rows, int64_t dst_row0,
                                                    int64_t n_rows) {

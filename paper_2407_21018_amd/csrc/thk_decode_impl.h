@@ -646,9 +646,9 @@ inline hipError_t decode_launch_one(const DecodeArgs &a, int groups, hipStream_t
   if (kbuf < tailbuf) kbuf = tailbuf;
   const size_t lds = (size_t)(3 * GT * kQS + 4 * GT * (kD + 2)) * 4 + 4 * ((size_t)kbuf + GT * TR * 4);
   const dim3 grid((unsigned)(a.units * groups * a.n_split)), block(256);
-  if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void *)k_decode<DT, GT, RA, KB, TR, WPE, VP>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  {
+    static DynLds set;   // one per instantiation
+    const hipError_t e = ensure_dyn_lds((const void *)k_decode<DT, GT, RA, KB, TR, WPE, VP>, lds, set);
     if (e != hipSuccess) return e;
   }
   void *kargs[] = {(void *)&a, (void *)&groups, (void *)&kbuf};

@@ -439,9 +439,9 @@ static hipError_t mq_launch(const DecodeArgs &a, int groups, hipStream_t st) {
   const int slab = KB * kWave * 16 > kMqVBytes ? KB * kWave * 16 : kMqVBytes;
   const size_t lds = (size_t)(2 * 4 * NH * (kQS / 2)) * 4 + 4 * ((size_t)slab + 512 * NH);
   const dim3 grid((unsigned)(a.units * groups * a.n_split)), block(256);
-  if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void *)k_decode_mq<KB, WPE, VP, NH>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  {
+    static DynLds set;   // one per instantiation
+    const hipError_t e = ensure_dyn_lds((const void *)k_decode_mq<KB, WPE, VP, NH>, lds, set);
     if (e != hipSuccess) return e;
   }
   void *kargs[] = {(void *)&a, (void *)&groups, (void *)&slab};
@@ -471,8 +471,7 @@ bool decode_mq_serves(const DecodeArgs &a) {
   if (G < 3 || a.ldk % 4 != 0) return false;
   if (a.T_v > 0 && a.ld_v % 4 != 0) return false;
   if (mq_chunks(a) > 9) return false;
-  const char *env = getenv("THK_DECODE_MFMA");
-  return !(env && env[0] == '0');
+  return !env_switches().decode_mfma_off;
 }
 
 // Head slots per block: four for three or four query heads per KV head, else eight; a unit

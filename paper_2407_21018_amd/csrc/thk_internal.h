@@ -4,6 +4,8 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "thk.h"
 
 namespace thk {
@@ -69,6 +71,39 @@ hipError_t launch_main_kernel(const void *fn, dim3 grid, dim3 block, void **args
 // it; a launcher consumes whatever is pending first so that what it returns is about its own
 // launches only.
 inline void clear_stale_hip_error() { (void)hipGetLastError(); }
+
+// ---- environment switches (experiments and tests) ----
+// Read from the environment ONCE per process, on first use; thk_reload_env() reads them again.
+struct EnvSwitches {
+  char prune_path;        // first letter of THK_PRUNE_PATH ('s'taged, 'f'used, 'r'eread), 0 = unset
+  long group_mib;         // THK_PRUNE_GROUP_MIB, <= 0 = unset
+  long block_rows;        // THK_PRUNE_BLOCK_ROWS, <= 0 = unset
+  long hold_rows;         // THK_PRUNE_HOLD_ROWS, <= 0 = unset
+  long max_blocks;        // THK_PRUNE_MAX_BLOCKS, < 0 = unset
+  long spin_limit;        // THK_PRUNE_SPIN_LIMIT, < 0 = unset
+  bool stagger_set;       // THK_PRUNE_STAGGER_NS present
+  double stagger_ns;
+  bool decode_mfma_off;   // THK_DECODE_MFMA=0
+};
+const EnvSwitches &env_switches();
+
+// hipFuncAttributeMaxDynamicSharedMemorySize is set once per kernel and device, not per launch.
+// One DynLds object per kernel (a function-local static of the launcher's instantiation).
+struct DynLds {
+  static constexpr int kDevs = 64;
+  std::atomic<int> bytes[kDevs];
+};
+inline hipError_t ensure_dyn_lds(const void *fn, size_t lds, DynLds &st) {
+  if (lds <= 48 * 1024) return hipSuccess;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < DynLds::kDevs;
+  if (tracked && st.bytes[dev].load(std::memory_order_acquire) >= (int)lds) return hipSuccess;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e == hipSuccess && tracked) st.bytes[dev].store((int)lds, std::memory_order_release);
+  return e;
+}
 
 // ---- launchers (one per kernel family; each returns hipGetLastError()) ----
 // Column sums of squares (p == 2) or of absolute values (p == 1) of K per

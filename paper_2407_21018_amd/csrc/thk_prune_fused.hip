@@ -506,7 +506,7 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
     const int64_t total = U * NB;
     const int64_t res_units = resident / NB;
     double ns = -1.0;
-    if (const char *e = getenv("THK_PRUNE_STAGGER_NS")) ns = atof(e);
+    if (env_switches().stagger_set) ns = env_switches().stagger_ns;
     else if (res_units >= 2 && total >= 2 * resident)
       // 0.6 of the time a unit's rows in and compacted rows out take at 5.7 TB/s: the full time
       // would be the spacing of the steady state, but the first round loads against no stores
@@ -550,13 +550,12 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
   }
   if (main_fn == nullptr || (hold != 0 && RB != 128 * hold)) return hipErrorInvalidValue;
   const size_t lds_main = 2048 + 4 * (size_t)nlt * compact_tile_bytes(eb);
-  if (lds_main > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(main_fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_main);
+  {
+    // one record per main kernel: [dtype][hold]
+    static DynLds main_set[2][5], repair_set;
+    hipError_t e = ensure_dyn_lds(main_fn, lds_main, main_set[dtype == THK_BF16 ? 1 : 0][hold]);
     if (e != hipSuccess) return e;
-  }
-  if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void *)k_prune_repair<THK_F32>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (dtype == THK_F32) e = ensure_dyn_lds((const void *)k_prune_repair<THK_F32>, lds, repair_set);
     if (e != hipSuccess) return e;
   }
   void *kargs[] = {(void *)&a};

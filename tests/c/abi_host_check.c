@@ -43,6 +43,36 @@ int main(void) {
   s.T = 32; s.D = 64;
   CHECK(thk_decode_attn(&s, fake, fake, (const int16_t *)fake, fake, NULL, NULL, 0, 0, fake, fake, 64, NULL) ==
         THK_ERR_UNSUPPORTED);
+  /* every other entry point: a valid shape, then one bad argument each; nothing reaches a device */
+  s.T = 76; s.D = 128; s.ld_keep = 0;
+  size_t big = (size_t)1 << 40;
+  int16_t *i16 = (int16_t *)fake;
+  CHECK(thk_prune(&s, fake, fake, NULL, i16, fake, fake, 16, NULL) == THK_ERR_WORKSPACE);
+  CHECK(thk_prune(&s, fake, NULL, NULL, i16, fake, fake, big, NULL) == THK_ERR_NULL);
+  CHECK(thk_score_magnitude(&s, fake, 3, (float *)fake, fake, big, NULL) == THK_ERR_SHAPE);
+  CHECK(thk_score_value(&s, fake, fake, fake, 2, (float *)fake, fake, big, NULL) == THK_ERR_SHAPE);
+  CHECK(thk_prune_value(&s, fake, fake, fake, 1, NULL, NULL, fake, fake, big, NULL) == THK_ERR_NULL);
+  CHECK(thk_compact_keys(&s, fake, i16, fake + 2, NULL) == THK_ERR_ALIGN);
+  CHECK(thk_compact_rows(&s, fake, 64, 60, i16, fake, 0, 8, NULL) == THK_ERR_SHAPE);
+  CHECK(thk_copy_rows(&s, fake, 64, 0, fake, 64, 4, 8, NULL) == THK_ERR_SHAPE);   /* upward shift in place */
+  CHECK(thk_cache_append(&s, fake, fake, fake, fake, 0, 4, NULL) == THK_ERR_SHAPE); /* value cache full: S_cap == S */
+  CHECK(thk_tail_flush(&s, i16, fake, fake, NULL, NULL, 4, 8, 5, NULL) == THK_ERR_SHAPE);
+  CHECK(thk_tail_append(&s, fake, fake, fake, fake, 4, 4, NULL) == THK_ERR_SHAPE);
+  CHECK(thk_decode_attn(&s, fake, fake, i16, fake, NULL, NULL, 1, 4, fake, fake, big, NULL) == THK_ERR_NULL);
+  CHECK(thk_decode_attn_kv(&s, fake, fake, i16, fake, i16, 51, 51, NULL, NULL, 0, 0, fake, fake, big, NULL) ==
+        THK_ERR_UNSUPPORTED);
+  CHECK(thk_decode_attn_kv(&s, fake, fake, i16, fake, i16, 0, 0, NULL, NULL, 0, 0, fake, fake, big, NULL) ==
+        THK_ERR_SHAPE);
+  {
+    thk_shape huge = s;   /* split partials beyond the static buffer: refused before any device call */
+    huge.L = 1; huge.B = 64; huge.N_q = 64; huge.N_kv = 64; huge.S = 1 << 20; huge.n_split = 64;
+    CHECK(thk_workspace_bytes(&huge, THK_OP_DECODE) > THK_STATIC_SCRATCH_BYTES);
+    CHECK(thk_decode_attn_static(&huge, fake, fake, i16, fake, NULL, NULL, 0, 0, fake, NULL) == THK_ERR_SCRATCH);
+  }
+  thk_reload_env();
+  thk_profile_next(NULL, NULL);
+  for (int st = 0; st <= 7; ++st) CHECK(thk_status_string((thk_status)st) != NULL);
+  CHECK(thk_last_hip_error() != NULL);
   printf("abi host check ok\n");
   return 0;
 }

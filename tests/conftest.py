@@ -27,3 +27,38 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+class _ThkEnv:
+    """Sets or removes THK_* environment switches for one test and makes the library read them
+    (it reads them once per process, so a change needs thk_reload_env)."""
+
+    def __init__(self, monkeypatch):
+        self._mp = monkeypatch
+
+    def setenv(self, name, value):
+        import paper_2407_21018_amd as thk
+        self._mp.setenv(name, value)
+        thk.thk_reload_env()
+
+    def delenv(self, name, raising=True):
+        import paper_2407_21018_amd as thk
+        self._mp.delenv(name, raising=raising)
+        thk.thk_reload_env()
+
+
+@pytest.fixture(autouse=True)
+def _thk_env_restored():
+    """Set up before any other fixture of a test, hence torn down last: after monkeypatch has put
+    the environment back, the library re-reads its switches, so no test leaks its settings."""
+    yield
+    try:
+        import paper_2407_21018_amd as thk
+        thk.thk_reload_env()
+    except ImportError:
+        pass
+
+
+@pytest.fixture
+def thk_env(monkeypatch):
+    return _ThkEnv(monkeypatch)

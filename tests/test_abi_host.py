@@ -180,37 +180,37 @@ def test_value_workspace_and_split_sizes():
     assert thk.thk_workspace_bytes(_shape(S_obs=0), thk.THK_OP_SCORE_VALUE) == 0
 
 
-def test_prune_plan_by_shape(monkeypatch):
+def test_prune_plan_by_shape(thk_env):
     """Which form thk_prune takes (2 = rows held on chip, 1 = rows read twice, 0 = staged)."""
     for v in ("THK_PRUNE_PATH", "THK_PRUNE_BLOCK_ROWS", "THK_PRUNE_HOLD_ROWS"):
-        monkeypatch.delenv(v, raising=False)
+        thk_env.delenv(v, raising=False)
     cfg2 = thk.make_shape(32, 4, 32, 32, 128, 4096, 32, 76, 0, thk.THK_BF16, 0)
     assert thk.thk_prune_is_fused(cfg2) == 2
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 131072, 64, 64, 0, thk.THK_BF16, 0)) == 2  # 256 blocks per unit
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 262144, 64, 64, 0, thk.THK_BF16, 0)) == 2  # 512 blocks per unit
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 393216, 64, 64, 0, thk.THK_BF16, 0)) == 2  # 768: all that fit at once
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 393217, 64, 64, 0, thk.THK_BF16, 0)) == 0  # one block more: staged
-    monkeypatch.setenv("THK_PRUNE_MAX_BLOCKS", "256")
+    thk_env.setenv("THK_PRUNE_MAX_BLOCKS", "256")
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 32, 8, 128, 262144, 64, 64, 0, thk.THK_BF16, 0)) == 0
-    monkeypatch.delenv("THK_PRUNE_MAX_BLOCKS")
+    thk_env.delenv("THK_PRUNE_MAX_BLOCKS")
     assert thk.thk_prune_is_fused(thk.make_shape(1, 8, 32, 8, 128, 32768, 32, 64, 0, thk.THK_BF16, 0)) == 2
     tiny = thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 0, thk.THK_F32, 0)
     assert thk.thk_prune_is_fused(tiny) == 2     # small calls: 128-row blocks, still held on chip
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 72, thk.THK_F32, 0)) == 2    # padded rows, pitch 288 bytes
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2048, 32, 64, 73, thk.THK_F32, 0)) == 2    # any pitch
     assert thk.thk_prune_is_fused(thk.make_shape(1, 1, 8, 8, 128, 2047, 32, 51, 0, thk.THK_BF16, 0)) == 2    # dense rows: any length
-    monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", "64")
+    thk_env.setenv("THK_PRUNE_BLOCK_ROWS", "64")
     assert thk.thk_prune_is_fused(tiny) == 1     # a block size that is not held: rows read twice
-    monkeypatch.delenv("THK_PRUNE_BLOCK_ROWS")
-    monkeypatch.setenv("THK_PRUNE_PATH", "reread")
+    thk_env.delenv("THK_PRUNE_BLOCK_ROWS")
+    thk_env.setenv("THK_PRUNE_PATH", "reread")
     assert thk.thk_prune_is_fused(cfg2) == 1
-    monkeypatch.setenv("THK_PRUNE_PATH", "staged")
+    thk_env.setenv("THK_PRUNE_PATH", "staged")
     assert thk.thk_prune_is_fused(cfg2) == 0
 
 
-def test_decode_kernel_choice_by_shape(monkeypatch):
+def test_decode_kernel_choice_by_shape(thk_env):
     """bf16, query heads in groups of four, T and the row pitches multiples of 4: the matrix-core kernel."""
-    monkeypatch.delenv("THK_DECODE_MFMA", raising=False)
+    thk_env.delenv("THK_DECODE_MFMA", raising=False)
     mk = lambda N_q, N_kv, T, ld, dt: thk.make_shape(1, 1, N_q, N_kv, 128, 4096, 1, T, ld, dt, 0)
     assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16)) == 1
     assert thk.thk_decode_on_matrix_cores(mk(32, 8, 76, 80, thk.THK_BF16)) == 1
@@ -232,15 +232,15 @@ def test_decode_kernel_choice_by_shape(monkeypatch):
     s4 = thk.make_shape(1, 8, 32, 8, 128, 32768, 1, 76, 0, thk.THK_BF16, 0)
     assert thk.thk_default_split(s8, thk.THK_OP_DECODE) == 8      # 64 units x 8 = 512 blocks <= 768
     assert thk.thk_default_split(s4, thk.THK_OP_DECODE) == 16     # 64 units x 16 = 1024 blocks
-    monkeypatch.setenv("THK_DECODE_MFMA", "0")
+    thk_env.setenv("THK_DECODE_MFMA", "0")
     assert thk.thk_decode_on_matrix_cores(mk(32, 8, 64, 0, thk.THK_BF16)) == 0
     assert thk.thk_default_split(s8, thk.THK_OP_DECODE) == 8      # two blocks of four heads per unit and split
 
 
-def test_default_decode_split_follows_the_size_of_the_call(monkeypatch):
+def test_default_decode_split_follows_the_size_of_the_call(thk_env):
     """Short sequences are not split (no merge launch), few units get small pieces, one unit may
     get up to 128 pieces; the workspace size follows the same choice."""
-    monkeypatch.delenv("THK_DECODE_MFMA", raising=False)
+    thk_env.delenv("THK_DECODE_MFMA", raising=False)
     def split(B, N_q, N_kv, S, dtype=thk.THK_BF16):
         s = thk.make_shape(1, B, N_q, N_kv, 128, S, 1, 64, 0, dtype, 0)
         n = thk.thk_default_split(s, thk.THK_OP_DECODE)
@@ -275,9 +275,62 @@ def test_plain_c_program_uses_the_boundary(tmp_path):
     assert "abi host check ok" in out.stdout
 
 
+def test_host_code_of_the_boundary_under_sanitizers(tmp_path):
+    """The translation unit that holds every argument check (csrc/thk_api.hip) rebuilt with
+    AddressSanitizer and UndefinedBehaviorSanitizer on the HOST side, linked with the other
+    objects of the in-tree build, and driven by the plain-C program above: no report, exit 0."""
+    import glob
+    import shutil
+    import subprocess
+    objs = [o for o in glob.glob(os.path.join(ROOT, "paper_2407_21018_amd", "_build", "*.o"))
+            if os.path.basename(o) != "thk_api.o"]
+    clang = "/opt/rocm/lib/llvm/bin/clang"
+    if not objs or shutil.which("hipcc") is None or not os.path.exists(clang):
+        pytest.skip("needs the in-tree object files and the ROCm compilers")
+    csrc = os.path.join(ROOT, "paper_2407_21018_amd", "csrc")
+    san = ["-fsanitize=address", "-fsanitize=undefined"]
+    host_san = [x for f in san for x in ("-Xarch_host", f)]
+    api_o, lib, exe = tmp_path / "thk_api.o", tmp_path / "libthk.so", tmp_path / "abi_host_check"
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fPIC", "-Xclang",
+                           "-target-feature", "-Xclang", "-packed-fp32-ops", *host_san, "-I",
+                           os.path.join(ROOT, "include"), "-I", csrc, "-c", os.path.join(csrc, "thk_api.hip"),
+                           "-o", str(api_o)], stderr=subprocess.DEVNULL)
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *san, "-shared-libsan", str(api_o),
+                           *objs, "-o", str(lib)], stderr=subprocess.DEVNULL)
+    rt = os.path.dirname(subprocess.check_output([clang, "-print-file-name=libclang_rt.asan-x86_64.so"], text=True).strip())
+    subprocess.check_call([clang, "-std=c11", "-g", *san, "-shared-libsan", "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "c", "abi_host_check.c"), "-o", str(exe), "-L", str(tmp_path),
+                           "-lthk", f"-Wl,-rpath,{tmp_path}", "-Wl,-rpath,/opt/rocm/lib", f"-Wl,-rpath,{rt}"])
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:halt_on_error=1", UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120, env=env)
+    assert out.returncode == 0 and "abi host check ok" in out.stdout, out.stdout + out.stderr
+    assert "runtime error" not in out.stderr and "AddressSanitizer" not in out.stderr, out.stderr
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
     out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
                          text=True, timeout=120)
     assert out.returncode == 2 and "ONE GPU" in out.stderr
+
+
+def test_environment_switches_are_read_once_and_on_reload(monkeypatch):
+    """The library takes its THK_* switches from the environment once per process: a change made
+    afterwards shows only after thk_reload_env()."""
+    cfg2 = thk.make_shape(32, 4, 32, 32, 128, 4096, 32, 76, 0, thk.THK_BF16, 0)
+    gqa = thk.make_shape(1, 1, 32, 8, 128, 4096, 1, 64, 0, thk.THK_BF16, 0)
+    for v in ("THK_PRUNE_PATH", "THK_PRUNE_BLOCK_ROWS", "THK_PRUNE_HOLD_ROWS", "THK_DECODE_MFMA"):
+        monkeypatch.delenv(v, raising=False)
+    thk.thk_reload_env()
+    assert thk.thk_prune_is_fused(cfg2) == 2 and thk.thk_decode_on_matrix_cores(gqa) == 1
+    monkeypatch.setenv("THK_PRUNE_PATH", "staged")
+    monkeypatch.setenv("THK_DECODE_MFMA", "0")
+    assert thk.thk_prune_is_fused(cfg2) == 2 and thk.thk_decode_on_matrix_cores(gqa) == 1   # cached
+    thk.thk_reload_env()
+    assert thk.thk_prune_is_fused(cfg2) == 0 and thk.thk_decode_on_matrix_cores(gqa) == 0   # re-read
+    monkeypatch.delenv("THK_PRUNE_PATH")
+    monkeypatch.delenv("THK_DECODE_MFMA")
+    assert thk.thk_prune_is_fused(cfg2) == 0
+    thk.thk_reload_env()
+    assert thk.thk_prune_is_fused(cfg2) == 2 and thk.thk_decode_on_matrix_cores(gqa) == 1

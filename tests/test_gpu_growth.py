@@ -56,12 +56,12 @@ def test_copy_rows_and_compact_rows(dtype):
 
 @pytest.mark.parametrize("path", ["fused", "hold-128", "hold-256", "hold-512", "staged"])
 @pytest.mark.parametrize("dtype,G,S,R,T", [("bf16", 1, 2048, 32, 76), ("bf16", 4, 1056, 128, 64), ("f32", 1, 1037, 13, 51)])
-def test_prune_leaves_recent_keys_unpruned(dtype, G, S, R, T, path, monkeypatch):
+def test_prune_leaves_recent_keys_unpruned(dtype, G, S, R, T, path, thk_env):
     if path.startswith("hold"):     # row blocks kept on chip: the cut S - S_recent falls inside a block
-        monkeypatch.setenv("THK_PRUNE_PATH", "fused")
-        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", path.split("-")[1])
+        thk_env.setenv("THK_PRUNE_PATH", "fused")
+        thk_env.setenv("THK_PRUNE_BLOCK_ROWS", path.split("-")[1])
     else:
-        monkeypatch.setenv("THK_PRUNE_PATH", path)
+        thk_env.setenv("THK_PRUNE_PATH", path)
     L, B, N_kv, S_obs, S_cap = 1, 2, 3, 32, S + 96
     U = L * B * N_kv
     q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, 5)

@@ -40,19 +40,34 @@ def test_score_matches_oracle(dtype, G, n_split, S):
     assert rel.max() <= SCORE_TOL
 
 
+MAGNITUDE_CASES = [
+    # dtype, L, B, N_kv, S, n_split, sigma
+    ("bf16", 1, 2, 3, 777, 0, 1.0),
+    ("f32", 1, 2, 3, 777, 0, 1.0),
+    ("bf16", 4, 2, 8, 4100, 0, 1.5),     # a layer stack in one call, several splits, ragged pieces
+    ("f32", 3, 1, 5, 2049, 7, 2.0),
+    ("bf16", 1, 1, 1, 5, 1, 0.0),        # shorter than one row group
+    ("f32", 2, 1, 2, 33000, 0, 1.0),     # long units: fp32 chains folded into fp64 many times
+]
+
+
 @pytest.mark.parametrize("p", [1, 2])
-def test_magnitude_score_matches_oracle(p):
-    L, B, N_kv, S = 1, 2, 3, 777
-    k = _randn((L, B, N_kv, S, D), "bf16", 13)
-    shape = thk.make_shape(L, B, N_kv, N_kv, D, S, 1, 64, 0, thk.THK_BF16, 0)
+@pytest.mark.parametrize("dtype,L,B,N_kv,S,n_split,sigma", MAGNITUDE_CASES)
+def test_magnitude_score_matches_oracle(dtype, L, B, N_kv, S, n_split, sigma, p):
+    """Eq. 1: M[n, d] = ||K[n, :, d]||_p, p = 1, 2, and the Top_T taken from it."""
+    k = _randn((L, B, N_kv, S, D), dtype, 13 + S, sigma)
+    shape = thk.make_shape(L, B, N_kv, N_kv, D, S, 1, 64, 0, DT[dtype], n_split)
     U = L * B * N_kv
     score = torch.empty(U, D, dtype=torch.float32, device="cuda")
     ws = ws_tensor(thk.thk_workspace_bytes(shape, thk.THK_OP_SCORE))
     thk.thk_score_magnitude(shape, k, p, score, ws)
     torch.cuda.synchronize()
-    want = O.score_magnitude(as_numpy(k), "bf16", p).reshape(U, D)
+    want = O.score_magnitude(as_numpy(k), dtype, p).reshape(U, D)
     rel = np.abs(score.cpu().numpy().astype(np.float64) - want) / want
     assert rel.max() <= SCORE_TOL
+    # I = Top_T(M, T): the list from the GPU's scores against the oracle's, up to exact-tolerance ties
+    idx = gpu_select(shape, score).cpu().numpy()
+    check_idx_with_tie_rule(idx, O.select_topk(want, 64), want, 64)
 
 
 # ---------------------------------------------------------------- select ----
@@ -172,13 +187,13 @@ def test_decode_matches_oracle(dtype, case):
 
 
 @pytest.mark.parametrize("case", [c for c in DECODE_CASES if c[2] >= 3], ids=lambda c: "-".join(map(str, c)))
-def test_decode_general_kernel_on_grouped_heads(case, monkeypatch):
+def test_decode_general_kernel_on_grouped_heads(case, thk_env):
     """THK_DECODE_MFMA=0 keeps bf16 shapes with three or more query heads per KV head on the general kernel."""
-    monkeypatch.setenv("THK_DECODE_MFMA", "0")
+    thk_env.setenv("THK_DECODE_MFMA", "0")
     B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma = case
     err, out0 = _decode_case("bf16", B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma, 1000 + S + T)
     assert err.max() <= ATTN_TOL["bf16"]
-    monkeypatch.setenv("THK_DECODE_MFMA", "1")
+    thk_env.setenv("THK_DECODE_MFMA", "1")
     err1, out1 = _decode_case("bf16", B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma, 1000 + S + T)
     print(f"decode bf16 {case}: max rel err general {err.max():.3e}, matrix cores {err1.max():.3e}")
     assert err1.max() <= ATTN_TOL["bf16"]
@@ -231,7 +246,7 @@ PRUNE_CASES = [("bf16", 1, 2048, 76, 1.5), ("bf16", 4, 4096 + 64, 64, 1.0), ("f3
 
 
 @pytest.mark.parametrize("levels", [1, 2])
-def test_prune_fused_repeated_calls_on_one_workspace(levels, monkeypatch):
+def test_prune_fused_repeated_calls_on_one_workspace(levels, thk_env):
     """The one-launch form hands sums and index lists from block to block through the
     workspace (one level: the last block's list to the blocks that wait; two levels: the group
     vectors to every block of the unit).  Calls that alternate between two inputs on the SAME
@@ -239,11 +254,11 @@ def test_prune_fused_repeated_calls_on_one_workspace(levels, monkeypatch):
     words (or words that had not fully arrived) would compact the wrong channels.  Checked
     on the GPU against a plain gather with the index list the call returned, and against the
     oracle's list for the first call of each input."""
-    monkeypatch.setenv("THK_PRUNE_PATH", "fused")
+    thk_env.setenv("THK_PRUNE_PATH", "fused")
     if levels == 1:
         L, B, N, S, S_obs, T = 4, 4, 16, 4096, 32, 76
     else:                                          # 102 blocks of 128 rows per unit
-        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", "128")
+        thk_env.setenv("THK_PRUNE_BLOCK_ROWS", "128")
         L, B, N, S, S_obs, T = 1, 3, 4, 13008, 32, 64
     U = L * B * N
     shape = thk.make_shape(L, B, N, N, D, S, S_obs, T, 0, thk.THK_BF16, 0)
@@ -275,11 +290,11 @@ def test_prune_fused_repeated_calls_on_one_workspace(levels, monkeypatch):
 @pytest.mark.parametrize("dtype,G,S,T,ld,block_rows", [("bf16", 1, 4096, 76, 80, ""), ("bf16", 4, 3001, 51, 56, "128"),
                                                        ("f32", 1, 1037, 51, 52, ""), ("bf16", 1, 2048, 76, 88, "64"),
                                                        ("bf16", 2, 777, 100, 104, "32"), ("bf16", 1, 1500, 76, 77, "")])
-def test_prune_into_padded_rows(dtype, G, S, T, ld, block_rows, monkeypatch):
+def test_prune_into_padded_rows(dtype, G, S, T, ld, block_rows, thk_env):
     """K_pruned rows with padding behind them, whatever the pitch: the one-launch prune serves them
     and the padding columns are written as zeros."""
     if block_rows:
-        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", block_rows)
+        thk_env.setenv("THK_PRUNE_BLOCK_ROWS", block_rows)
     L, B, N_kv, S_obs = 1, 2, 3, 32
     U = L * B * N_kv
     q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, 61, 1.0)
@@ -299,16 +314,16 @@ def test_prune_into_padded_rows(dtype, G, S, T, ld, block_rows, monkeypatch):
 
 @pytest.mark.parametrize("spin_limit", [None, 0])
 @pytest.mark.parametrize("block_rows,S", [(128, 13008), (64, 13008), (128, 40016)])
-def test_prune_two_level_arrival(block_rows, S, spin_limit, monkeypatch):
+def test_prune_two_level_arrival(block_rows, S, spin_limit, thk_env):
     """Units of more than 64 row blocks: the blocks arrive group by group, the last block of a
     group publishes the group's sums, and every block makes the index list from the group sums
     (102 blocks of 128 rows held on chip; 204 blocks of 64 rows read twice).  With the wait
     switched off from the host, blocks that find a group vector missing leave their rows, and
     possibly the caller's copy of the list, to the repair kernel."""
-    monkeypatch.setenv("THK_PRUNE_PATH", "fused")
-    monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", str(block_rows))
+    thk_env.setenv("THK_PRUNE_PATH", "fused")
+    thk_env.setenv("THK_PRUNE_BLOCK_ROWS", str(block_rows))
     if spin_limit is not None:
-        monkeypatch.setenv("THK_PRUNE_SPIN_LIMIT", str(spin_limit))
+        thk_env.setenv("THK_PRUNE_SPIN_LIMIT", str(spin_limit))
     L, B, N_kv, G, S_obs, T = 1, 2, 2, 2, 32, 64       # S = 40016: 313 blocks per unit, groups of 20
     q_obs = _randn((L, B, N_kv * G, S_obs, D), "bf16", 41, 1.0)
     k = _randn((L, B, N_kv, S, D), "bf16", 42, 1.0)
@@ -326,27 +341,27 @@ def test_prune_two_level_arrival(block_rows, S, spin_limit, monkeypatch):
 @pytest.mark.parametrize("path", ["fused", "fused-small-blocks", "fused-no-wait", "hold-128", "hold-256", "hold-512",
                                   "hold-256-no-wait", "reread-256", "staged", "staged-groups"])
 @pytest.mark.parametrize("dtype,G,S,T,sigma", PRUNE_CASES)
-def test_prune_pipeline_matches_oracle(dtype, G, S, T, sigma, path, monkeypatch):
+def test_prune_pipeline_matches_oracle(dtype, G, S, T, sigma, path, thk_env):
     """thk_prune in its one-launch form (default row blocks, 32-row blocks, and with
     the wait for the index list switched off from the host so that the repair
     kernel does every compaction) and in its staged form (one group, many groups)."""
     if path.startswith("fused") or path.startswith("hold"):
-        monkeypatch.setenv("THK_PRUNE_PATH", "fused")
+        thk_env.setenv("THK_PRUNE_PATH", "fused")
     if path.startswith("hold"):      # row blocks that stay in registers between score and compaction
-        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", path.split("-")[1])
+        thk_env.setenv("THK_PRUNE_BLOCK_ROWS", path.split("-")[1])
     if path == "hold-256-no-wait":
-        monkeypatch.setenv("THK_PRUNE_SPIN_LIMIT", "0")
+        thk_env.setenv("THK_PRUNE_SPIN_LIMIT", "0")
     if path == "reread-256":         # the same blocking with the rows read twice
-        monkeypatch.setenv("THK_PRUNE_PATH", "reread")
-        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", "256")
+        thk_env.setenv("THK_PRUNE_PATH", "reread")
+        thk_env.setenv("THK_PRUNE_BLOCK_ROWS", "256")
     if path == "fused-small-blocks":
-        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", "32")
+        thk_env.setenv("THK_PRUNE_BLOCK_ROWS", "32")
     if path == "fused-no-wait":
-        monkeypatch.setenv("THK_PRUNE_SPIN_LIMIT", "0")
+        thk_env.setenv("THK_PRUNE_SPIN_LIMIT", "0")
     if path.startswith("staged"):
-        monkeypatch.setenv("THK_PRUNE_PATH", "staged")
+        thk_env.setenv("THK_PRUNE_PATH", "staged")
     if path == "staged-groups":
-        monkeypatch.setenv("THK_PRUNE_GROUP_MIB", "1")     # several groups, some starting mid-batch
+        thk_env.setenv("THK_PRUNE_GROUP_MIB", "1")     # several groups, some starting mid-batch
     L, B, N_kv, S_obs = 2, 2, 3, min(32, S)
     q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, 31, sigma)
     k = _randn((L, B, N_kv, S, D), dtype, 32, sigma)

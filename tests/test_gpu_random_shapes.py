@@ -136,11 +136,11 @@ def _prune_shapes(n, seed):
 
 
 @pytest.mark.parametrize("case", _prune_shapes(32, 20240723), ids=lambda c: "-".join(map(str, c[:7])))
-def test_prune_random_shapes(case, monkeypatch):
+def test_prune_random_shapes(case, thk_env):
     dtype, G, S, S_obs, T, ld, block_rows, seed = case
     print(f"prune case {case}", flush=True)
     if block_rows:
-        monkeypatch.setenv("THK_PRUNE_BLOCK_ROWS", block_rows)
+        thk_env.setenv("THK_PRUNE_BLOCK_ROWS", block_rows)
     L, B, N_kv = 1, 2, 3
     U = L * B * N_kv
     q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, seed, 1.0)
@@ -182,8 +182,8 @@ def _long_shapes(n, seed):
 
 
 @pytest.mark.parametrize("case", _long_shapes(10, 20240725)[0], ids=lambda c: "-".join(map(str, c[:7])))
-def test_prune_random_long_sequences(case, monkeypatch):
-    test_prune_random_shapes(case, monkeypatch)
+def test_prune_random_long_sequences(case, thk_env):
+    test_prune_random_shapes(case, thk_env)
 
 
 @pytest.mark.parametrize("case", _long_shapes(10, 20240725)[1], ids=lambda c: "-".join(map(str, c[:10])))

@@ -225,9 +225,9 @@ def test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n
 
 @pytest.mark.parametrize("dtype,G,S,T,T_v,ld_v,s_tail,cap,n_split",
                          [c for c in DECODE_CASES if c[0] == "bf16" and c[1] >= 3 and c[3] % 4 == 0])
-def test_decode_attn_kv_general_kernel_on_grouped_heads(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split, monkeypatch):
+def test_decode_attn_kv_general_kernel_on_grouped_heads(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split, thk_env):
     """THK_DECODE_MFMA=0: the shapes the matrix-core kernel serves, on the general kernel."""
-    monkeypatch.setenv("THK_DECODE_MFMA", "0")
+    thk_env.setenv("THK_DECODE_MFMA", "0")
     test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split)
 
 

@@ -311,3 +311,18 @@ def test_table7_memory_column():
         assert vkv * per_token_kv == pytest.approx(vanilla_m, abs=0.05)
         k_tokens_equiv = (kv - 32) * (1 - 0.4) + 32
         assert (k_tokens_equiv + kv) * per_token_kv / 2 == pytest.approx(think_m, abs=0.05)
+
+
+def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """Every oracle routine on buffers of exactly the stated sizes (three element types, edge
+    shapes), built with gcc -fsanitize=address,undefined: any out-of-bounds access or undefined
+    arithmetic aborts the program (tests/c/oracle_sanitize_check.c)."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = tmp_path / "oracle_sanitize_check"
+    subprocess.check_call(["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-ffp-contract=off",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+                           "-o", str(exe), os.path.join(root, "tests", "c", "oracle_sanitize_check.c"),
+                           os.path.join(root, "oracle", "thk_oracle.c"), "-lm"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0 and "oracle sanitize check ok" in out.stdout, out.stdout + out.stderr
