@@ -320,7 +320,9 @@ def run_config(cfg_id, args, torch, thk, synth, full):
     step_bytes = L * (prune_bytes + steps_per_layer * decode_bytes)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    prune_kernel = {2: "k_prune_onepass", 1: "k_prune_fused", 0: "k_compact_flat"}[form]
+    prune_launches = thk.thk_prune_launches(shape_all)
+    prune_kernel = {2: "k_prune_solo" if prune_launches == 1 else "k_prune_onepass", 1: "k_prune_fused",
+                    0: "k_compact_flat"}[form]
     # what the timed kernel itself has to move per launch (the staged form's compaction kernel
     # is only the last of three: rows in, kept channels out)
     prune_kernel_bytes = L * prune_bytes if form else L * U * S * eb * (D + T)
@@ -350,7 +352,8 @@ def run_config(cfg_id, args, torch, thk, synth, full):
                     f"then {steps_per_layer} decode step(s) per layer",
         "dtype": cfg["dtype"], "steps": steps, "ms_per_step": ms_per_step, "graph_ms_per_step": graph_ms,
         "step_bytes": step_bytes, "GBps": value, "frac_of_hbm_peak": value / HBM_PEAK_GBS,
-        "prune_form": {2: "one launch, K read once", 1: "one launch, K read twice", 0: "three kernels"}[form],
+        "prune_form": {2: "rows held on chip, K read once", 1: "K read twice", 0: "staged: three kernels per group"}[form],
+        "prune_launches": prune_launches,
         "prune_ms_per_layer": prune_ms_layer, "prune_bytes_per_layer": prune_bytes,
         "prune_GBps": prune_bytes / prune_ms_layer / 1e6,
         "prune_frac": prune_bytes / prune_ms_layer / 1e6 / HBM_PEAK_GBS,

@@ -127,6 +127,13 @@ int32_t thk_default_split(const thk_shape *shape, int32_t op);
  * staged three-kernel form (or an invalid shape).  Host-only. */
 int32_t thk_prune_is_fused(const thk_shape *shape);
 
+/* Kernels a thk_prune call on `shape` enqueues: 1 when the rows are held on chip (the kernel
+ * initialises its own hand-off state and serves blocks whose wait ran out by itself), 3 with
+ * THK_PRUNE_LAUNCH=classic or for blocks that re-read their rows (a kernel in front that
+ * clears the state and computes the query norms, one behind that compacts what was left
+ * undone), 3 per group of units in the staged form; 0 for an invalid shape.  Host-only. */
+int32_t thk_prune_launches(const thk_shape *shape);
+
 /* 1 if thk_decode_attn (T_v == 0) or thk_decode_attn_kv (value rows of T_v kept channels,
  * ld_v elements apart) would run `shape` on the matrix-core kernel k_decode_mq, 0 if on the
  * general kernel k_decode (or the shape is invalid).  Host-only; honours THK_DECODE_MFMA. */
@@ -218,7 +225,9 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
  * the three kernels one after the other.  Scores agree with thk_score to fp64
  * summation order (the last float bit can differ).  `score` may be NULL (then
  * it lives in ws).
- * Environment (for experiments and tests): THK_PRUNE_PATH =
+ * Environment (for experiments and tests): THK_PRUNE_LAUNCH = classic (three launches:
+ * state and query norms, the main kernel, repair) | solo (one launch; the default wherever
+ * the rows are held on chip); THK_PRUNE_PATH =
  * staged | fused | reread (the one-kernel form with the rows read twice);
  * THK_PRUNE_BLOCK_ROWS (rows per block; 128, 256 and 512 are held on chip),
  * THK_PRUNE_HOLD_ROWS (largest default block), THK_PRUNE_MAX_BLOCKS (blocks

@@ -64,6 +64,8 @@ def load():
     L.thk_default_split.argtypes = [sp, i32]
     L.thk_prune_is_fused.restype = i32
     L.thk_prune_is_fused.argtypes = [sp]
+    L.thk_prune_launches.restype = i32
+    L.thk_prune_launches.argtypes = [sp]
     L.thk_decode_on_matrix_cores.restype = i32
     L.thk_decode_on_matrix_cores.argtypes = [sp, i32, i32]
     L.thk_score.restype = ctypes.c_int
@@ -197,6 +199,10 @@ def thk_default_split(shape, op):
 
 def thk_prune_is_fused(shape):
     return int(load().thk_prune_is_fused(ctypes.byref(shape)))
+
+
+def thk_prune_launches(shape):
+    return int(load().thk_prune_launches(ctypes.byref(shape)))
 
 
 def thk_decode_on_matrix_cores(shape, T_v=0, ld_v=0):

@@ -39,6 +39,8 @@ const EnvSwitches *read_env() {
   s->stagger_ns = ns != nullptr ? atof(ns) : -1.0;
   const char *mf = getenv("THK_DECODE_MFMA");
   s->decode_mfma_off = mf != nullptr && mf[0] == '0';
+  const char *pl = getenv("THK_PRUNE_LAUNCH");
+  s->prune_launch = pl != nullptr ? pl[0] : 0;
   return s;
 }
 }  // namespace
@@ -216,6 +218,24 @@ FusedPlan fused_plan(const thk_shape *s) {
   return p;
 }
 
+// Calls whose rows are held on chip and whose blocks make at most two rounds of resident blocks
+// (three for units of more than 64 blocks) run as ONE launch (thk_prune_solo.hip): the two extra
+// launches of the other form and the gaps around them are 4-30 % of such a call (fp32, 8 units
+// x 2048 rows: 17.8 -> 12.7 us; 128 units x 4096 bf16 rows: 58.5 -> 56.2 us; 8 units x 131072
+// rows: 97 -> 93 us).  Longer launches keep the three-launch form: a unit's extra prologue
+// block breaks the alignment of units with the resident set, and the main kernel runs 6-12 %
+// slower (32 layers of 128 units x 4096 rows: 1141 -> 1251 us); between two and four rounds
+// the two forms are within 2 % of each other.  THK_PRUNE_LAUNCH = solo | classic overrides.
+bool prune_single_launch(const thk_shape *s, const FusedPlan &fp) {
+  if (!fp.ok || fp.hold == 0) return false;
+  if (units_of(s) * ((int64_t)fp.NB + 1) > kMaxGrid) return false;
+  const char sw = env_switches().prune_launch;
+  if (sw == 'c') return false;
+  if (sw == 's') return true;
+  const int64_t resident = (int64_t)kCUs * (s->dtype == THK_BF16 ? 3 : 2);
+  return units_of(s) * fp.NB <= (fp.NB > 64 ? 3 : 2) * resident;
+}
+
 // Split of the S axis for the value score: pieces are whole 128-row chunks of at least 512
 // rows, enough of them for one resident set of blocks (two per compute unit: 74 KB of LDS
 // each; more pieces only add merge work -- one layer of config 2: 65 us with 8 pieces per
@@ -298,6 +318,13 @@ int32_t thk_prune_is_fused(const thk_shape *s) {
   return !fp.ok ? 0 : fp.hold != 0 ? 2 : 1;
 }
 
+int32_t thk_prune_launches(const thk_shape *s) {
+  if (check_shape(s, true) != THK_OK) return 0;
+  const FusedPlan fp = fused_plan(s);
+  if (!fp.ok) return 3 * (int32_t)ceil_div(units_of(s), prune_group_units(s));
+  return prune_single_launch(s, fp) ? 1 : 3;
+}
+
 int32_t thk_decode_on_matrix_cores(const thk_shape *s, int32_t T_v, int32_t ld_v) {
   if (check_shape(s, false) != THK_OK) return 0;
   if (T_v < 0 || T_v > kD || (T_v > 0 && (ld_v < T_v || ld_v > kD))) return 0;
@@ -330,7 +357,7 @@ size_t thk_workspace_bytes(const thk_shape *s, int32_t op) {
       const FusedPlan fp = fused_plan(s);
       size_t a = score_ws_bytes(s, prune_group_units(s));
       if (fp.ok) {
-        const size_t b = prune_fused_ws_bytes(units_of(s), fp.NB);
+        const size_t b = std::max(prune_fused_ws_bytes(units_of(s), fp.NB), prune_solo_ws_bytes(units_of(s), fp.NB));
         if (b > a) a = b;
       }
       return ((a + 15) & ~(size_t)15) + (size_t)units_of(s) * kD * sizeof(float);
@@ -489,6 +516,13 @@ thk_status thk_prune(const thk_shape *s, const void *q_obs, const void *k, float
   const FusedPlan fp = fused_plan(s);
   if (fp.ok) {
     const int spin = env_switches().spin_limit >= 0 ? (int)env_switches().spin_limit : 4096;
+    if (prune_single_launch(s, fp)) {
+      if (failed(launch_prune_solo(s->dtype, q_obs, k, sc, idx, k_pruned, ws, U, s->S, keep_rows(s),
+                                   cache_rows(s, keep_rows(s)), G, s->S_obs, s->T, ld_of(s), fp.NB, fp.RB, fp.hold,
+                                   spin, hs)))
+        return THK_ERR_HIP;
+      return THK_OK;
+    }
     if (failed(launch_prune_fused(s->dtype, q_obs, k, sc, idx, k_pruned, ws, U, s->S, keep_rows(s),
                                   cache_rows(s, keep_rows(s)), G, s->S_obs, s->T, ld_of(s), fp.NB, fp.RB, fp.hold,
                                   spin < 0 ? 0 : spin, hs)))

@@ -84,6 +84,7 @@ struct EnvSwitches {
   bool stagger_set;       // THK_PRUNE_STAGGER_NS present
   double stagger_ns;
   bool decode_mfma_off;   // THK_DECODE_MFMA=0
+  char prune_launch;      // first letter of THK_PRUNE_LAUNCH ('c'lassic: three launches, 's'olo: one), 0 = unset
 };
 const EnvSwitches &env_switches();
 
@@ -144,6 +145,15 @@ hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float
                               void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
                               int64_t kp_unit_rows, int G, int S_obs, int T, int ld, int NB, int64_t RB,
                               int hold, int spin_limit, hipStream_t st);
+
+// The same work in ONE launch (rows held on chip only: hold = 1, 2, 4; fp32: 1, 2): the state is
+// initialised and the query norms are computed by a prologue block per unit, and blocks whose
+// wait ran out are served by the unit's finisher.  ws: prune_solo_ws_bytes(U, NB) bytes.
+size_t prune_solo_ws_bytes(int64_t U, int NB);
+hipError_t launch_prune_solo(int dtype, const void *q_obs, const void *k, float *score, int16_t *idx,
+                             void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
+                             int64_t kp_unit_rows, int G, int S_obs, int T, int ld, int NB, int64_t RB,
+                             int hold, int spin_limit, hipStream_t st);
 
 struct DecodeArgs {
   const void *q, *kp, *v, *kt, *vt;

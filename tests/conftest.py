@@ -62,3 +62,11 @@ def _thk_env_restored():
 @pytest.fixture
 def thk_env(monkeypatch):
     return _ThkEnv(monkeypatch)
+
+
+@pytest.fixture(params=["solo", "classic"])
+def prune_launch(request, thk_env):
+    """Both launch forms of thk_prune where the rows are held on chip: everything in one kernel
+    (prologue block per unit, finisher), or state / main / repair kernels."""
+    thk_env.setenv("THK_PRUNE_LAUNCH", request.param)
+    return request.param

@@ -208,6 +208,27 @@ def test_prune_plan_by_shape(thk_env):
     assert thk.thk_prune_is_fused(cfg2) == 0
 
 
+def test_prune_launch_count_by_shape(thk_env):
+    """One launch for calls of at most two rounds of resident blocks (three for units of more than
+    64 blocks), three launches beyond, three per group of units in the staged form."""
+    for v in ("THK_PRUNE_PATH", "THK_PRUNE_BLOCK_ROWS", "THK_PRUNE_HOLD_ROWS", "THK_PRUNE_LAUNCH"):
+        thk_env.delenv(v, raising=False)
+    mk = lambda L, B, N_q, N_kv, S, T, dt=thk.THK_BF16: thk.make_shape(L, B, N_q, N_kv, 128, S, 32, T, 0, dt, 0)
+    cfg1, cfg2, cfg2_1 = mk(1, 1, 8, 8, 2048, 64, thk.THK_F32), mk(32, 4, 32, 32, 4096, 76), mk(1, 4, 32, 32, 4096, 76)
+    cfg3, cfg4, cfg5 = mk(1, 8, 32, 8, 32768, 64), mk(1, 1, 32, 8, 131072, 64), mk(1, 32, 40, 40, 16384, 51)
+    assert [thk.thk_prune_launches(s) for s in (cfg1, cfg2_1, cfg4)] == [1, 1, 1]
+    assert [thk.thk_prune_launches(s) for s in (cfg2, cfg3, cfg5)] == [3, 3, 3]
+    thk_env.setenv("THK_PRUNE_LAUNCH", "classic")
+    assert thk.thk_prune_launches(cfg1) == 3
+    thk_env.setenv("THK_PRUNE_LAUNCH", "solo")
+    assert thk.thk_prune_launches(cfg2) == 1
+    thk_env.setenv("THK_PRUNE_PATH", "reread")      # rows read twice: only the three-launch form exists
+    assert thk.thk_prune_launches(cfg1) == 3
+    thk_env.setenv("THK_PRUNE_PATH", "staged")
+    assert thk.thk_prune_launches(cfg2) == 3 * 4    # groups of at most 1 GiB of K: 4 groups of 8 layers
+    assert thk.thk_prune_launches(mk(1, 1, 8, 8, 2048, 200)) == 0
+
+
 def test_decode_kernel_choice_by_shape(thk_env):
     """bf16, query heads in groups of four, T and the row pitches multiples of 4: the matrix-core kernel."""
     thk_env.delenv("THK_DECODE_MFMA", raising=False)

@@ -56,7 +56,7 @@ def test_copy_rows_and_compact_rows(dtype):
 
 @pytest.mark.parametrize("path", ["fused", "hold-128", "hold-256", "hold-512", "staged"])
 @pytest.mark.parametrize("dtype,G,S,R,T", [("bf16", 1, 2048, 32, 76), ("bf16", 4, 1056, 128, 64), ("f32", 1, 1037, 13, 51)])
-def test_prune_leaves_recent_keys_unpruned(dtype, G, S, R, T, path, thk_env):
+def test_prune_leaves_recent_keys_unpruned(dtype, G, S, R, T, path, thk_env, prune_launch):
     if path.startswith("hold"):     # row blocks kept on chip: the cut S - S_recent falls inside a block
         thk_env.setenv("THK_PRUNE_PATH", "fused")
         thk_env.setenv("THK_PRUNE_BLOCK_ROWS", path.split("-")[1])

@@ -246,7 +246,7 @@ PRUNE_CASES = [("bf16", 1, 2048, 76, 1.5), ("bf16", 4, 4096 + 64, 64, 1.0), ("f3
 
 
 @pytest.mark.parametrize("levels", [1, 2])
-def test_prune_fused_repeated_calls_on_one_workspace(levels, thk_env):
+def test_prune_fused_repeated_calls_on_one_workspace(levels, thk_env, prune_launch):
     """The one-launch form hands sums and index lists from block to block through the
     workspace (one level: the last block's list to the blocks that wait; two levels: the group
     vectors to every block of the unit).  Calls that alternate between two inputs on the SAME
@@ -290,7 +290,7 @@ def test_prune_fused_repeated_calls_on_one_workspace(levels, thk_env):
 @pytest.mark.parametrize("dtype,G,S,T,ld,block_rows", [("bf16", 1, 4096, 76, 80, ""), ("bf16", 4, 3001, 51, 56, "128"),
                                                        ("f32", 1, 1037, 51, 52, ""), ("bf16", 1, 2048, 76, 88, "64"),
                                                        ("bf16", 2, 777, 100, 104, "32"), ("bf16", 1, 1500, 76, 77, "")])
-def test_prune_into_padded_rows(dtype, G, S, T, ld, block_rows, thk_env):
+def test_prune_into_padded_rows(dtype, G, S, T, ld, block_rows, thk_env, prune_launch):
     """K_pruned rows with padding behind them, whatever the pitch: the one-launch prune serves them
     and the padding columns are written as zeros."""
     if block_rows:
@@ -314,7 +314,7 @@ def test_prune_into_padded_rows(dtype, G, S, T, ld, block_rows, thk_env):
 
 @pytest.mark.parametrize("spin_limit", [None, 0])
 @pytest.mark.parametrize("block_rows,S", [(128, 13008), (64, 13008), (128, 40016)])
-def test_prune_two_level_arrival(block_rows, S, spin_limit, thk_env):
+def test_prune_two_level_arrival(block_rows, S, spin_limit, thk_env, prune_launch):
     """Units of more than 64 row blocks: the blocks arrive group by group, the last block of a
     group publishes the group's sums, and every block makes the index list from the group sums
     (102 blocks of 128 rows held on chip; 204 blocks of 64 rows read twice).  With the wait
@@ -341,10 +341,12 @@ def test_prune_two_level_arrival(block_rows, S, spin_limit, thk_env):
 @pytest.mark.parametrize("path", ["fused", "fused-small-blocks", "fused-no-wait", "hold-128", "hold-256", "hold-512",
                                   "hold-256-no-wait", "reread-256", "staged", "staged-groups"])
 @pytest.mark.parametrize("dtype,G,S,T,sigma", PRUNE_CASES)
-def test_prune_pipeline_matches_oracle(dtype, G, S, T, sigma, path, thk_env):
+def test_prune_pipeline_matches_oracle(dtype, G, S, T, sigma, path, thk_env, prune_launch):
     """thk_prune in its one-launch form (default row blocks, 32-row blocks, and with
     the wait for the index list switched off from the host so that the repair
     kernel does every compaction) and in its staged form (one group, many groups)."""
+    if prune_launch == "solo" and not (path.startswith("hold") or path in ("fused", "fused-no-wait")):
+        pytest.skip("the single-launch form exists only where the rows are held on chip")
     if path.startswith("fused") or path.startswith("hold"):
         thk_env.setenv("THK_PRUNE_PATH", "fused")
     if path.startswith("hold"):      # row blocks that stay in registers between score and compaction

@@ -136,7 +136,7 @@ def _prune_shapes(n, seed):
 
 
 @pytest.mark.parametrize("case", _prune_shapes(32, 20240723), ids=lambda c: "-".join(map(str, c[:7])))
-def test_prune_random_shapes(case, thk_env):
+def test_prune_random_shapes(case, thk_env, prune_launch):
     dtype, G, S, S_obs, T, ld, block_rows, seed = case
     print(f"prune case {case}", flush=True)
     if block_rows:
@@ -182,8 +182,8 @@ def _long_shapes(n, seed):
 
 
 @pytest.mark.parametrize("case", _long_shapes(10, 20240725)[0], ids=lambda c: "-".join(map(str, c[:7])))
-def test_prune_random_long_sequences(case, thk_env):
-    test_prune_random_shapes(case, thk_env)
+def test_prune_random_long_sequences(case, thk_env, prune_launch):
+    test_prune_random_shapes(case, thk_env, prune_launch)
 
 
 @pytest.mark.parametrize("case", _long_shapes(10, 20240725)[1], ids=lambda c: "-".join(map(str, c[:10])))
