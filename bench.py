@@ -176,7 +176,16 @@ def device_facts(torch):
 
 
 def run_config(cfg_id, args, torch, thk, synth, full):
-    """Time workload cfg_id.  full: also the value-cache leg and the oracle leg (headline only)."""
+    """Time workload cfg_id.  full: also the value-cache leg and the oracle leg (headline only).
+
+    Four timed regions, all with inputs resident and warmed up:
+      A  `steps` whole steps back to back, two events around all of them -> ms_per_step, value;
+      B  the step's prune call alone, back to back                        -> prune_ms_per_layer;
+      C  the step's decode calls alone (all layers and steps), back to back -> decode_us_per_step;
+      D  a few steps whose main kernels carry event pairs (thk_profile_next) -> kernel durations.
+    Small workloads rotate over several input sets so that no region re-reads a cache-resident
+    tensor: a set is used again only after more than 1.5 GiB of other sets' tensors (the
+    memory-side cache holds 256 MB)."""
     dev = "cuda:0"
     cfg = synth.CONFIGS[cfg_id]
     L, B, N_q, N_kv, D, S, S_obs = (cfg[k] for k in ("L", "B", "N_q", "N_kv", "D", "S", "S_obs"))
@@ -188,17 +197,23 @@ def run_config(cfg_id, args, torch, thk, synth, full):
     steps_per_layer = cfg["steps"]
     cap = cfg["tail_cap"]
     steps = args.steps
+    n_dec = steps_per_layer * L
 
     # ---- inputs, resident in HBM ------------------------------------------
+    set_bytes = L * U * S * eb * (2 * D + T)
+    nrot = max(1, min(16, -(-(3 << 29) // set_bytes)))
     q_obs = torch.empty(L, B, N_q, S_obs, D, dtype=dt, device=dev)
-    k = torch.empty(L, B, N_kv, S, D, dtype=dt, device=dev)
-    v = torch.empty(L, B, N_kv, S, D, dtype=dt, device=dev)
+    k0 = torch.empty(L, B, N_kv, S, D, dtype=dt, device=dev)
+    v0 = torch.empty(L, B, N_kv, S, D, dtype=dt, device=dev)
     for l in range(L):
-        q_obs[l], k[l], v[l] = (t[0] for t in synth.gen_prefill(cfg_id, l, dev, **cfg))
+        q_obs[l], k0[l], v0[l] = (t[0] for t in synth.gen_prefill(cfg_id, l, dev, **cfg))
+    # further sets hold the same values (the timing does not depend on them, parity is checked elsewhere)
+    ks = [k0] + [k0.clone() for _ in range(nrot - 1)]
+    vs = [v0] + [v0.clone() for _ in range(nrot - 1)]
+    kps = [torch.empty(L, U, S, T, dtype=dt, device=dev) for _ in range(nrot)]
     dec = [[synth.gen_decode(cfg_id, l, s, dev, **cfg) for s in range(steps_per_layer)] for l in range(L)]
     score = torch.empty(L * U, D, dtype=torch.float32, device=dev)
     idx = torch.empty(L * U, T, dtype=torch.int16, device=dev)
-    kp = torch.empty(L, U, S, T, dtype=dt, device=dev)
     out = torch.empty(L, B * N_q, D, dtype=dt, device=dev)
     kt = torch.zeros(L, U, max(cap, 1), D, dtype=dt, device=dev)
     vt = torch.zeros_like(kt)
@@ -210,45 +225,43 @@ def run_config(cfg_id, args, torch, thk, synth, full):
 
     def ev():
         e = torch.cuda.Event(enable_timing=True)
-        e.record()          # torch creates the HIP event on first record; done outside the timed region
+        e.record()          # torch creates the HIP event on first record; done outside the timed regions
         return e
 
-    n_dec = steps_per_layer * L
-    # event pairs the library attaches to the main kernel of a call (thk_profile_next: the
-    # interval is the kernel's own begin-to-end time): the prune call of every step, and every
-    # eighth decode call (offset rotating with the step)
-    n_prof = max(1, n_dec // 8)
-    pairs = [[(ev(), ev()) for _ in range(1 + n_prof)] for _ in range(steps)]
-    torch.cuda.synchronize()
+    # per-(set, layer) views made once: slicing a tensor costs the host several microseconds, which
+    # the smallest workload's calls (about 10 us each) would not hide
+    kp_l = [[kps[r][l] for l in range(L)] for r in range(nrot)]
+    v_l = [[vs[r][l] for l in range(L)] for r in range(nrot)]
+    idx_l = [idx[l * U:(l + 1) * U] for l in range(L)]
+    kt_l = [kt[l] if cap else None for l in range(L)]
+    vt_l = [vt[l] if cap else None for l in range(L)]
+    out_l = [out[l] for l in range(L)]
 
-    def step(evs=None, ph=None, rot=0):
-        """Whole hot path once.  evs: this step's event pairs (prune first, then one per decode call);
-        ph: three events recorded before the prune, after it, and after the last decode call."""
-        if evs is not None:
-            thk.thk_profile_next(*evs[0])
-        if ph is not None:
-            ph[0].record()
-        thk.thk_prune(shape_all, q_obs, k, score, idx, kp, ws)
-        if ph is not None:
-            ph[1].record()
-        i, call = 1, 0
-        used = []
+    def prune(r, pair=None):
+        if pair is not None:
+            thk.thk_profile_next(*pair)
+        thk.thk_prune(shape_all, q_obs, ks[r], score, idx, kps[r], ws)
+
+    def decode(r, pairs=None, rot=0):
+        """The decode calls of one step; pairs: event pairs for every eighth call (offset rot)."""
+        i, call, used = 0, 0, []
         for s in range(steps_per_layer):
             for l in range(L):
                 q, k_new, v_new = dec[l][s]
                 if cap:
-                    thk.thk_tail_append(shape_1, k_new, v_new, kt[l], vt[l], s, cap)
-                if evs is not None and call % 8 == rot % min(8, n_dec) and i < len(evs):
-                    thk.thk_profile_next(*evs[i])
-                    used.append(evs[i])
+                    thk.thk_tail_append(shape_1, k_new, v_new, kt_l[l], vt_l[l], s, cap)
+                if pairs is not None and call % 8 == rot % min(8, n_dec) and i < len(pairs):
+                    thk.thk_profile_next(*pairs[i])
+                    used.append(pairs[i])
                     i += 1
                 call += 1
-                thk.thk_decode_attn(shape_1, q, kp[l], idx[l * U:(l + 1) * U], v[l],
-                                    kt[l] if cap else None, vt[l] if cap else None,
-                                    s + 1 if cap else 0, cap, out[l], ws)
-        if ph is not None:
-            ph[2].record()
+                thk.thk_decode_attn(shape_1, q, kp_l[r][l], idx_l[l], v_l[r][l], kt_l[l], vt_l[l],
+                                    s + 1 if cap else 0, cap, out_l[l], ws)
         return used
+
+    def step(r):
+        prune(r)
+        decode(r)
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -258,57 +271,56 @@ def run_config(cfg_id, args, torch, thk, synth, full):
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
+    def timed(fn, reps):
+        """fn(i) for i < reps back to back between two events: milliseconds per repetition."""
+        a, b = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(reps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    for r in range(max(args.warmup, nrot)):
+        step(r % nrot)          # every set gets its pruned cache
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
-    phases = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
-    e0.record()
-    used_pairs = []
-    # A workload with only a few calls per step would carry an event pair on every call, and a
-    # launch with events attached costs the host ~12 us more than a plain one, which a step of
-    # a few short calls does not hide; there the kernels are timed on every fourth step only and
-    # the phases are read off the other steps.
-    sparse = n_dec < 8 and steps >= 2
-    kernel_steps = [i for i in range(steps) if not sparse or i % 4 == 0]
-    phase_steps = [i for i in range(steps) if not sparse or i % 4 != 0]
-    for i in range(steps):
-        used_pairs += step(pairs[i] if i in kernel_steps else None, phases[i], i)
-    e1.record()
-    torch.cuda.synchronize()
+    ms_per_step = timed(lambda i: step(i % nrot), steps)                       # region A
     wall = time.perf_counter() - t0
-    ms_per_step = e0.elapsed_time(e1) / steps
+    # the phase loops of a short step run longer than `steps` repetitions (about 30 ms each)
+    reps_ph = min(300, max(steps, int(30.0 / ms_per_step)))
+    prune_ms_layer = timed(lambda i: prune(i % nrot), reps_ph) / L             # region B
+    dec_us_step = timed(lambda i: decode(i % nrot), reps_ph) / n_dec * 1e3     # region C
+    # region D: kernel durations from events attached to the launches themselves.  Such a launch
+    # costs the host ~12 us more than a plain one, so only every eighth decode call carries a pair.
+    n_prof = max(1, n_dec // 8)
+    ksteps = min(steps, 5)
+    pairs = [[(ev(), ev()) for _ in range(1 + n_prof)] for _ in range(ksteps)]
+    torch.cuda.synchronize()
+    used_pairs = []
+    for i in range(ksteps):
+        prune(i % nrot, pairs[i][0])
+        used_pairs += decode(i % nrot, pairs[i][1:], i)
+    torch.cuda.synchronize()
+    prune_k_us = sum(p[0][0].elapsed_time(p[0][1]) for p in pairs) / ksteps * 1e3
+    dec_kernel_us = [a.elapsed_time(b) * 1e3 for (a, b) in used_pairs]
+    dec_k_us = sum(dec_kernel_us) / len(dec_kernel_us)
 
     graph_ms = None
     if not args.no_graph:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            step()
+            step(0)
         torch.cuda.current_stream().wait_stream(side)
         gr = torch.cuda.CUDAGraph()
         with torch.cuda.graph(gr):
-            step()
+            for r in range(nrot):
+                step(r)
         gr.replay()
-        torch.cuda.synchronize()
-        g0 = torch.cuda.Event(enable_timing=True); g1 = torch.cuda.Event(enable_timing=True)
-        g0.record()
-        for _ in range(steps):
-            gr.replay()
-        g1.record()
-        torch.cuda.synchronize()
-        graph_ms = g0.elapsed_time(g1) / steps
+        graph_ms = timed(lambda i: gr.replay(), max(1, steps // nrot)) / nrot
         del gr
-
-    # main-kernel durations measured inside the timed region
-    prune_kernel_us = [pairs[i][0][0].elapsed_time(pairs[i][0][1]) * 1e3 for i in kernel_steps]
-    dec_kernel_us = [a.elapsed_time(b) * 1e3 for (a, b) in used_pairs]
-    prune_k_us = sum(prune_kernel_us) / len(prune_kernel_us)
-    dec_k_us = sum(dec_kernel_us) / len(dec_kernel_us)
-    # whole calls (all kernels of a call and the gaps between them)
-    prune_ms_layer = sum(phases[i][0].elapsed_time(phases[i][1]) for i in phase_steps) / len(phase_steps) / L
-    dec_us_step = sum(phases[i][1].elapsed_time(phases[i][2]) for i in phase_steps) / len(phase_steps) / n_dec * 1e3
 
     # ---- bytes the path has to move (per layer), K and V counted once per KV head -----
     form = thk.thk_prune_is_fused(shape_all)     # 2: rows held on chip, K read once
@@ -351,6 +363,8 @@ def run_config(cfg_id, args, torch, thk, synth, full):
                     f"S_obs={S_obs} lambda={cfg['lam']} T={T} {cfg['dtype']}; prune all layers, "
                     f"then {steps_per_layer} decode step(s) per layer",
         "dtype": cfg["dtype"], "steps": steps, "ms_per_step": ms_per_step, "graph_ms_per_step": graph_ms,
+        "input_sets_rotated": nrot, "phase_loop_reps": reps_ph,
+        "cache_state": "cold: more than 1.5 GiB of other tensors pass between two uses of a tensor",
         "step_bytes": step_bytes, "GBps": value, "frac_of_hbm_peak": value / HBM_PEAK_GBS,
         "prune_form": {2: "rows held on chip, K read once", 1: "K read twice", 0: "staged: three kernels per group"}[form],
         "prune_launches": prune_launches,
@@ -362,13 +376,14 @@ def run_config(cfg_id, args, torch, thk, synth, full):
         "decode_us_per_step": dec_us_step, "decode_bytes_per_step": decode_bytes,
         "decode_GBps": decode_bytes / dec_us_step / 1e3,
         "decode_frac": decode_bytes / dec_us_step / 1e3 / HBM_PEAK_GBS,
+        "phases_vs_step": (prune_ms_layer * L + dec_us_step * n_dec / 1e3) / ms_per_step,
         "host_wall_s": wall,
         "kernels": kernels, "roofline": roof, "roofline_other": roof_other,
     }
     if full and not args.no_value_cache:
-        res["value_cache"] = value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k, v, kp, idx, dec, kt, vt, out,
-                                             steps)
-    del q_obs, k, v, dec, score, idx, kp, out, kt, vt, ws, pairs, phases, used_pairs
+        res["value_cache"] = value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k0, v0, kps[0], idx, dec, kt, vt,
+                                             out, steps)
+    del q_obs, k0, v0, ks, vs, kps, dec, score, idx, out, kt, vt, ws, pairs, used_pairs, kp_l, v_l, idx_l, kt_l, vt_l, out_l
     gc.collect()
     torch.cuda.empty_cache()
     if full and not args.no_cpu_baseline:
