@@ -76,8 +76,8 @@ typedef struct {
   int64_t S;       /* keys in the prunable segment, >= 1                         */
   int32_t S_obs;   /* observation-window queries, 1..S (score / prune only)      */
   int32_t T;       /* channels kept, 1..D                                        */
-  int32_t ld_keep; /* row stride of K_pruned in elements, >= T; 0 means T (the
-                      columns past T are written as zeros and never read)      */
+  int32_t ld_keep; /* row stride of K_pruned in elements, T <= ld_keep <= D; 0 means
+                      T (the columns past T are written as zeros and never read) */
   int32_t dtype;   /* thk_dtype of Q, K, V, K_pruned, out                        */
   int32_t n_split; /* pieces the S axis is cut into per unit; 0 = library choice */
   int32_t S_recent;/* prune: the last S_recent of the S scored keys are NOT compacted    */

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <mutex>
 
 #include "thk_internal.h"
@@ -41,6 +42,8 @@ const EnvSwitches *read_env() {
   s->decode_mfma_off = mf != nullptr && mf[0] == '0';
   const char *pl = getenv("THK_PRUNE_LAUNCH");
   s->prune_launch = pl != nullptr ? pl[0] : 0;
+  const char *mk = getenv("THK_DECODE_MERGE");
+  s->decode_merge = mk != nullptr ? mk[0] : 0;
   return s;
 }
 }  // namespace
@@ -92,7 +95,9 @@ thk_status check_shape(const thk_shape *s, bool need_obs) {
   if (s->L < 1 || s->B < 1 || s->N_q < 1 || s->N_kv < 1 || s->D < 1 || s->S < 1) return THK_ERR_SHAPE;
   if (s->N_q % s->N_kv != 0) return THK_ERR_SHAPE;
   if (s->T < 1 || s->T > s->D) return THK_ERR_SHAPE;
-  if (s->ld_keep != 0 && s->ld_keep < s->T) return THK_ERR_SHAPE;
+  // rows of K_pruned hold T kept channels and at most D elements in all (the compaction's gather
+  // table and the decode kernels' staging are sized for rows of up to D elements)
+  if (s->ld_keep != 0 && (s->ld_keep < s->T || s->ld_keep > s->D)) return THK_ERR_SHAPE;
   if (need_obs && (s->S_obs < 1 || (int64_t)s->S_obs > s->S)) return THK_ERR_SHAPE;
   if (s->n_split < 0 || s->n_split > kMaxSplit) return THK_ERR_SHAPE;
   if (s->S_recent < 0 || (int64_t)s->S_recent >= s->S) return THK_ERR_SHAPE;
@@ -130,6 +135,32 @@ int decode_heads_per_block(const thk_shape *s) {
   return decode_mq_serves(a) ? decode_mq_heads(a) : group_width(s->N_q / s->N_kv);
 }
 
+// Head groups (blocks per split) of a call, and the bytes of its split records rounded up to
+// the 8-byte boundary where the flag words (one per group and split) start.
+int64_t decode_groups(const thk_shape *s) {
+  return units_of(s) * ceil_div(s->N_q / s->N_kv, decode_heads_per_block(s));
+}
+size_t decode_records_bytes(const thk_shape *s, int n_split) {
+  const size_t b = (size_t)s->L * s->B * s->N_q * n_split * (kD + 2) * sizeof(float);
+  return (b + 7) & ~(size_t)7;
+}
+
+// A 64-bit number, never 0, different for every call of the process and spread over the whole
+// range (what an earlier call or other data left in a workspace will not look like it).
+unsigned long long next_nonce() {
+  static std::atomic<unsigned long long> counter{
+      (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9e3779b97f4a7c15ull};
+  unsigned long long z = counter.fetch_add(0x9e3779b97f4a7c15ull, std::memory_order_relaxed);
+  z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+  z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+  z = z ^ (z >> 31);
+  return z != 0 ? z : 1;
+}
+
+// The split records of a call are merged inside the launch (by the block that finishes last for
+// a head group) where that saves more than it costs -- see decode_merge_in_launch below.
+bool decode_merge_in_launch(const thk_shape *s, int n_split);
+
 Split decode_split(const thk_shape *s) {
   int n = s->n_split;
   const int G = s->N_q / s->N_kv;
@@ -158,6 +189,23 @@ Split decode_split(const thk_shape *s) {
   rows = ceil_div(rows, 64) * 64;
   if (s->n_split == 0) n = (int)ceil_div(s->S, rows);   // drop empty pieces
   return {n, rows};
+}
+
+// Small calls merge their split records inside the launch: the block that finishes last for a
+// head group does it, and the second launch goes away (fp32, 8 heads x 2048 rows: 11.8 -> 9.3 us;
+// one sequence of 32 heads x 1024 bf16 rows: 11.1 -> 9.4 us).  The hand-off costs three memory
+// round trips at the end of the kernel, a second launch about as much, so the gain fades as the
+// launch grows (nothing left at 1024 blocks; a launch that fills the chip four blocks deep --
+// 128 units x 8 pieces of 512 rows -- runs 1 us SLOWER: 38.4 -> 39.5 us) and a block that
+// serves four or eight heads needs two or four rounds of loads for its merge (+1.1 .. 1.6 us).
+// Hence: at most 16 pieces, at most two heads per block, at most two blocks per compute unit.
+// THK_DECODE_MERGE = kernel | fused overrides (fused only within the 16 pieces).
+bool decode_merge_in_launch(const thk_shape *s, int n_split) {
+  if (n_split < 2 || n_split > kDecodeFuseMaxSplit) return false;
+  const char sw = env_switches().decode_merge;
+  if (sw == 'k') return false;
+  if (sw == 'f') return true;
+  return decode_heads_per_block(s) <= 2 && decode_groups(s) * n_split <= 2 * (int64_t)kCUs;
 }
 
 // Units per group in the staged form of thk_prune (three launches per group).
@@ -342,7 +390,7 @@ size_t thk_workspace_bytes(const thk_shape *s, int32_t op) {
     case THK_OP_DECODE: {
       const Split sp = decode_split(s);
       if (sp.n == 1) return 16;
-      return (size_t)s->L * s->B * s->N_q * sp.n * (kD + 2) * sizeof(float);
+      return decode_records_bytes(s, sp.n) + (size_t)decode_groups(s) * sp.n * sizeof(unsigned long long);
     }
     case THK_OP_SCORE_VALUE:
       if (s->S_obs < 1 || (int64_t)s->S_obs > s->S) return 0;
@@ -634,6 +682,14 @@ static thk_status decode_common(const thk_shape *s, const void *q, const void *k
   a.scale_log2_d = 1.4426950408889634 / sqrt((double)s->D);
   a.scale_log2 = (float)a.scale_log2_d;
   a.idx_v = idx_v; a.T_v = pruned_v ? T_v : 0; a.ld_v = pruned_v ? ld_v : 0;
+  // up to kDecodeFuseMaxSplit pieces per unit are merged inside the launch by the block that
+  // finishes last; more pieces go to the merge kernel
+  a.arrive = nullptr;
+  a.nonce = 0;
+  if (decode_merge_in_launch(s, sp.n)) {
+    a.arrive = (unsigned long long *)((char *)ws + decode_records_bytes(s, sp.n));
+    a.nonce = next_nonce();
+  }
   if (failed(launch_decode(a, (hipStream_t)stream))) return THK_ERR_HIP;
   return THK_OK;
 }

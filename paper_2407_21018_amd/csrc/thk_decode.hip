@@ -5,6 +5,7 @@
 namespace thk {
 
 constexpr int kMaxSplitDev = 4096;   // largest n_split the API accepts
+static_assert(kFuseMaxSplit == kDecodeFuseMaxSplit, "the host and the kernels must agree on the fused merge's reach");
 
 hipError_t decode_launch_bf16_g1(const DecodeArgs &, int, hipStream_t);
 hipError_t decode_launch_bf16_g2(const DecodeArgs &, int, hipStream_t);
@@ -114,7 +115,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st) {
     e = gt == 4 ? decode_launch_f32_g4(a, groups, st)
                 : gt == 2 ? decode_launch_f32_g2(a, groups, st) : decode_launch_f32_g1(a, groups, st);
   if (e != hipSuccess) return e;
-  if (a.n_split > 1) {
+  if (a.n_split > 1 && a.arrive == nullptr) {
     const int64_t heads = a.units / a.N_kv * a.N_q;
     const bool wide = a.n_split >= 32;   // many splits: four thread groups share them
     if (a.dtype == THK_BF16) {

@@ -403,13 +403,41 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
   wave_sync_lds();   // ps and kbuf are rewritten by the next tile
 }
 
+// ---- cross-block hand-off of the split records (n_split > 1, at most kFuseMaxSplit pieces) ----
+// The block that finishes LAST for a (unit, head group) merges the group's split records itself,
+// so the call needs no second launch.  No read-modify-write is involved (the blocks of a group
+// finish together, and a contended compare-and-swap loop costs a memory round trip per
+// contender): every block has a FLAG word per (group, split).  A block
+//   1. stores its record with device-scope relaxed atomic stores (they reach the coherence
+//      point themselves: the L2 caches of the XCDs are not coherent with each other, and a
+//      device-scope fence would write back a whole L2) and waits until they are acknowledged,
+//   2. stores the call's nonce into its own flag and waits for that acknowledgement,
+//   3. loads the group's flags: if all of them hold the nonce it merges.
+// The block whose flag store is performed last finds all flags set, and by 1. every record is
+// then visible to it.  Blocks that finish within a round trip of each other may both find all
+// flags set: both merge, in split order, and store the same bits.  A merging block clears the
+// flags afterwards, so that a replay of the same launch from a graph, which carries the same
+// nonce, starts clean; whatever else the flag words held before the call (another call's nonce,
+// other data of the workspace) is not the nonce: 64 bits drawn per call.
+constexpr int kFuseMaxSplit = 16;
+
+__device__ inline void pub_store_f32(float *p, float v) {
+  __hip_atomic_store((unsigned int *)p, __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float pub_load_f32(const float *p) {
+  return __uint_as_float(__hip_atomic_load((const unsigned int *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
 // Merge of the four waves' softmax states (mrg: [GT][130] floats per wave, wstride floats from
 // wave to wave, in LDS, complete and visible to the block): the output row of every query head
-// the block serves, or this split's state record.
+// the block serves, or this split's state record -- and, where the call merges inside the
+// launch, the output rows again, from all records, by the block that arrives last.
+// grp: index of the block's (unit, head group) among all of the call's; s_last: one int of LDS.
 template <int DT, int GT>
 __device__ __forceinline__ void block_merge_store(const float *mrg, int wstride, const DecodeArgs &a,
-                                                  int64_t bn0, int sp, int heads) {
+                                                  int64_t bn0, int sp, int heads, int64_t grp, int *s_last) {
   using E = Elem<DT>;
+  const bool fused = a.arrive != nullptr;
   for (int o = threadIdx.x; o < heads * kD; o += 256) {   // heads <= GT of the block's slots are in use
     const int g = o / kD, c = o % kD;
     float M = -INFINITY;
@@ -428,10 +456,61 @@ __device__ __forceinline__ void block_merge_store(const float *mrg, int wstride,
       E::store1(a.out, bn * kD + c, A / Lsum);
     } else {
       float *rec = a.ws + (bn * a.n_split + sp) * (kD + 2);
-      rec[2 + c] = A;
-      if (c == 0) { rec[0] = M; rec[1] = Lsum; }
+      if (fused) {
+        pub_store_f32(rec + 2 + c, A);
+        if (c == 0) { pub_store_f32(rec, M); pub_store_f32(rec + 1, Lsum); }
+      } else {
+        rec[2 + c] = A;
+        if (c == 0) { rec[0] = M; rec[1] = Lsum; }
+      }
     }
   }
+  if (a.n_split == 1 || !fused) return;
+
+  // ---- the group's last block merges: m = max m_i, l = sum l_i 2^(m_i - m), acc likewise, in
+  // split order (the result does not depend on who arrives last) ---------------------------
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's record stores are acknowledged
+  __syncthreads();                                   // ... and every wave's
+  unsigned long long *flags = a.arrive + (size_t)grp * a.n_split;
+  if (threadIdx.x < kWave) {
+    if (threadIdx.x == 0)
+      __hip_atomic_store(flags + sp, a.nonce, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the flag is out before the flags are read
+    const unsigned long long f =
+        (int)threadIdx.x < a.n_split
+            ? __hip_atomic_load(flags + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+            : a.nonce;
+    const bool all = __all(f == a.nonce);
+    if (threadIdx.x == 0) *s_last = all ? 1 : 0;
+  }
+  __syncthreads();
+  if (*s_last == 0) return;
+  for (int o = threadIdx.x; o < heads * kD; o += 256) {
+    const int g = o / kD, c = o % kD;
+    const size_t bn = (size_t)(bn0 + g);
+    const float *rec0 = a.ws + bn * a.n_split * (kD + 2);
+    float mv[kFuseMaxSplit], lv[kFuseMaxSplit], av[kFuseMaxSplit];
+#pragma unroll
+    for (int i = 0; i < kFuseMaxSplit; ++i) {   // all loads in flight at once; entries past n_split repeat the last
+      const float *rec = rec0 + (size_t)min(i, a.n_split - 1) * (kD + 2);
+      mv[i] = pub_load_f32(rec);
+      lv[i] = pub_load_f32(rec + 1);
+      av[i] = pub_load_f32(rec + 2 + c);
+    }
+    float M = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kFuseMaxSplit; ++i) M = fmaxf(M, mv[i]);
+    float Lsum = 0.f, A = 0.f;
+#pragma unroll
+    for (int i = 0; i < kFuseMaxSplit; ++i) {
+      const float wgt = (i >= a.n_split || mv[i] == -INFINITY) ? 0.f : exp2f(mv[i] - M);
+      Lsum = fmaf(lv[i], wgt, Lsum);
+      A = fmaf(av[i], wgt, A);
+    }
+    E::store1(a.out, bn * kD + c, A / Lsum);
+  }
+  if ((int)threadIdx.x < a.n_split)
+    __hip_atomic_store(flags + threadIdx.x, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // KB: 16-byte K chunks a lane may have to stage for one TR-row pruned tile.
@@ -455,6 +534,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   uint32_t *qfp = qkp + GT * (kQS / 2);          // [GT][kQS/2] qf as packed bf16 pairs
   float *mrg = (float *)(qfp + GT * (kQS / 2));  // [4][GT][130] per-wave states for the final merge
   char *wbase = (char *)(mrg + 4 * GT * (kD + 2));
+  __shared__ int s_last;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int wstride = kbuf_bytes + GT * TR * 4;
   char *kbuf = wbase + (size_t)wave * wstride;
@@ -616,7 +696,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   }
   __syncthreads();
 
-  block_merge_store<DT, GT>(mrg, GT * (kD + 2), a, bn0, sp, hb);
+  block_merge_store<DT, GT>(mrg, GT * (kD + 2), a, bn0, sp, hb, ug, &s_last);
 }
 
 // ---- host side: pick the instantiation for a shape --------------------------

@@ -271,6 +271,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   char *slab = wbase + (size_t)wave * (slab_bytes + 512 * NH);
   char *pline = slab + slab_bytes;               // 512 bytes of probabilities per head group
+  __shared__ int s_last;
 
   const int sp = (int)(blockIdx.x % a.n_split);
   const int64_t ug = blockIdx.x / a.n_split;
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
     }
   }
   __syncthreads();
-  block_merge_store<DT, GT>((const float *)wbase, (slab_bytes + 512 * NH) / 4, a, bn0, sp, hb);
+  block_merge_store<DT, GT>((const float *)wbase, (slab_bytes + 512 * NH) / 4, a, bn0, sp, hb, ug, &s_last);
 }
 
 // Four blocks per compute unit with the narrow staging class and four heads per block (37 KB of

@@ -85,6 +85,8 @@ struct EnvSwitches {
   double stagger_ns;
   bool decode_mfma_off;   // THK_DECODE_MFMA=0
   char prune_launch;      // first letter of THK_PRUNE_LAUNCH ('c'lassic: three launches, 's'olo: one), 0 = unset
+  char decode_merge;      // first letter of THK_DECODE_MERGE ('k'ernel: a second launch merges the split
+                          // records, 'f'used: the last block of a head group merges), 0 = unset
 };
 const EnvSwitches &env_switches();
 
@@ -167,11 +169,16 @@ struct DecodeArgs {
   int64_t units;              // L * B * N_kv
   float scale_log2;           // log2(e) / sqrt(D)
   double scale_log2_d;        // the same, not rounded to float (logits of fp32 inputs)
+  // merge inside the launch: one flag word per (unit, head group, split) behind the split
+  // records (nullptr: a second kernel merges), and the call's nonce (64 bits, never 0)
+  unsigned long long *arrive;
+  unsigned long long nonce;
   // channel-pruned values (T_v > 0): v is V_pruned, rows ld_v elements apart, channels idx_v
   const int16_t *idx_v;
   int32_t T_v, ld_v;
 };
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t st);
+constexpr int kDecodeFuseMaxSplit = 16;   // most pieces per unit the launch merges by itself
 // the shape runs on the matrix-core kernel (needs dtype, T, ldk, N_q, N_kv, T_v, ld_v of a)
 bool decode_mq_serves(const DecodeArgs &a);
 int decode_mq_heads(const DecodeArgs &a);   // query heads per block of that kernel: 4 or 8

@@ -70,3 +70,11 @@ def prune_launch(request, thk_env):
     (prologue block per unit, finisher), or state / main / repair kernels."""
     thk_env.setenv("THK_PRUNE_LAUNCH", request.param)
     return request.param
+
+
+@pytest.fixture(params=["kernel", "fused"])
+def decode_merge(request, thk_env):
+    """Both ways of merging the split records of a decode call with at most 16 pieces: a second
+    launch, or the last block of every head group inside the one launch."""
+    thk_env.setenv("THK_DECODE_MERGE", request.param)
+    return request.param

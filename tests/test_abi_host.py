@@ -57,7 +57,7 @@ def _status(fn, *a, **k):
 
 @pytest.mark.parametrize("kw,want", [
     (dict(N_q=7), 2), (dict(T=0), 2), (dict(T=129), 2), (dict(S=0), 2), (dict(S_obs=0), 2),
-    (dict(S_obs=1001), 2), (dict(ld_keep=63), 2), (dict(n_split=-1), 2), (dict(n_split=5000), 2),
+    (dict(S_obs=1001), 2), (dict(ld_keep=63), 2), (dict(ld_keep=132), 2), (dict(T=128, ld_keep=129), 2), (dict(n_split=-1), 2), (dict(n_split=5000), 2),
     (dict(B=0), 2), (dict(D=64, T=32), 3), (dict(dtype=7), 3),
 ])
 def test_bad_shapes_are_rejected_before_launch(kw, want):
@@ -98,12 +98,14 @@ def test_workspace_sizes_follow_the_split():
     s = _shape(S=4096, B=4, N_q=32, N_kv=32, T=76)
     n_dec = thk.thk_default_split(s, thk.THK_OP_DECODE)
     assert n_dec >= 1
-    want = 16 if n_dec == 1 else 4 * 32 * n_dec * 130 * 4
+    # split records (max, sum, acc[128]) per head and piece, then one 8-byte flag word per
+    # (unit, head group, piece) -- here one head per group
+    want = 16 if n_dec == 1 else 4 * 32 * n_dec * 130 * 4 + 4 * 32 * n_dec * 8
     assert thk.thk_workspace_bytes(s, thk.THK_OP_DECODE) == want
     n_sc = thk.thk_default_split(s, thk.THK_OP_SCORE)
     assert thk.thk_workspace_bytes(s, thk.THK_OP_SCORE) == 4 * 32 * n_sc * 128 * 8
     s2 = _shape(S=4096, B=4, N_q=32, N_kv=32, T=76, n_split=7)
-    assert thk.thk_workspace_bytes(s2, thk.THK_OP_DECODE) == 4 * 32 * 7 * 130 * 4
+    assert thk.thk_workspace_bytes(s2, thk.THK_OP_DECODE) == 4 * 32 * 7 * 130 * 4 + 4 * 32 * 7 * 8
     assert thk.thk_workspace_bytes(s2, thk.THK_OP_SCORE) == 4 * 32 * 7 * 128 * 8
 
 

@@ -21,7 +21,7 @@ def _randn(shape, seed, sigma=1.0):
 
 
 @pytest.mark.parametrize("G,T", [(2, 76), (4, 76), (8, 128)])   # general kernel; matrix-core kernel, 4 and 8 heads per block
-def test_prune_and_decode_replay_from_a_graph(G, T, prune_launch):
+def test_prune_and_decode_replay_from_a_graph(G, T, prune_launch, decode_merge):
     L, B, N_kv, S, S_obs, cap = 2, 2, 4, 2048, 32, 8
     N_q, U = N_kv * G, B * N_kv
     q_obs = _randn((L, B, N_q, S_obs, D), 1); k = _randn((L, B, N_kv, S, D), 2); v = _randn((L, B, N_kv, S, D), 3, 0)

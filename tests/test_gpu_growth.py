@@ -90,7 +90,7 @@ def test_prune_leaves_recent_keys_unpruned(dtype, G, S, R, T, path, thk_env, pru
 
 
 @pytest.mark.parametrize("dtype,G,T,unified", [("bf16", 2, 76, True), ("bf16", 1, 51, False), ("f32", 4, 64, True)])
-def test_decode_over_a_growing_cache(dtype, G, T, unified):
+def test_decode_over_a_growing_cache(dtype, G, T, unified, decode_merge):
     B, N_kv, S0, R, cap, steps = 1, 2, 1024 + 32, 32, 64, 75
     N_q, U = N_kv * G, B * N_kv
     S_cap = S0 + steps + 8

@@ -37,7 +37,7 @@ def _decode_shapes(n, seed):
 
 
 @pytest.mark.parametrize("case", _decode_shapes(40, 20240721), ids=lambda c: "-".join(map(str, c[:10])))
-def test_decode_random_shapes(case):
+def test_decode_random_shapes(case, decode_merge):
     dtype, B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma, seed = case
     print(f"decode case {case}", flush=True)
     err, _ = _decode_case(dtype, B, N_kv, G, S, T, ld, n_split, s_tail, cap, sigma, seed)
@@ -60,12 +60,12 @@ def _f32_heavy_shapes(n, seed):
 
 
 @pytest.mark.parametrize("case", _f32_heavy_shapes(32, 20240726), ids=lambda c: "-".join(map(str, c[:10])))
-def test_decode_f32_heavy_tailed_logits(case):
+def test_decode_f32_heavy_tailed_logits(case, decode_merge):
     """fp32 inputs with channel scales of sigma = 2 on BOTH the query and the keys: logits reach
     the thousands, where a logit held in fp32 is only accurate to ~1e-4 in absolute terms and a
     softmax that hangs between two keys shows it.  The kernel forms these logits in fp64 and
     rounds z - max, so the fp32 bar holds at any logit size."""
-    test_decode_random_shapes(case)
+    test_decode_random_shapes(case, decode_merge)
 
 
 def _rand_idx(U, T, seed):
@@ -92,7 +92,7 @@ def _decode_kv_shapes(n, seed):
 
 
 @pytest.mark.parametrize("case", _decode_kv_shapes(24, 20240722), ids=lambda c: "-".join(map(str, c[:9])))
-def test_decode_kv_random_shapes(case):
+def test_decode_kv_random_shapes(case, decode_merge):
     dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split, seed = case
     print(f"decode kv case {case}", flush=True)
     B, N_kv = 1, 2
@@ -187,8 +187,8 @@ def test_prune_random_long_sequences(case, thk_env, prune_launch):
 
 
 @pytest.mark.parametrize("case", _long_shapes(10, 20240725)[1], ids=lambda c: "-".join(map(str, c[:10])))
-def test_decode_random_long_sequences(case):
-    test_decode_random_shapes(case)
+def test_decode_random_long_sequences(case, decode_merge):
+    test_decode_random_shapes(case, decode_merge)
 
 
 def _value_shapes(n, seed):

@@ -188,7 +188,7 @@ DECODE_CASES = [
 
 
 @pytest.mark.parametrize("dtype,G,S,T,T_v,ld_v,s_tail,cap,n_split", DECODE_CASES)
-def test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split):
+def test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split, decode_merge):
     from helpers import ATTN_TOL, attn_rel_err
     L, B, N_kv = 1, 2, 2
     U = L * B * N_kv
@@ -225,10 +225,11 @@ def test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n
 
 @pytest.mark.parametrize("dtype,G,S,T,T_v,ld_v,s_tail,cap,n_split",
                          [c for c in DECODE_CASES if c[0] == "bf16" and c[1] >= 3 and c[3] % 4 == 0])
-def test_decode_attn_kv_general_kernel_on_grouped_heads(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split, thk_env):
+def test_decode_attn_kv_general_kernel_on_grouped_heads(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split, thk_env,
+                                                        decode_merge):
     """THK_DECODE_MFMA=0: the shapes the matrix-core kernel serves, on the general kernel."""
     thk_env.setenv("THK_DECODE_MFMA", "0")
-    test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split)
+    test_decode_attn_kv_matches_oracle(dtype, G, S, T, T_v, ld_v, s_tail, cap, n_split, decode_merge)
 
 
 def test_decode_attn_kv_with_identity_value_index_equals_key_only_decode():

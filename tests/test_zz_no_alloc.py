@@ -38,7 +38,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("pair", CASES, ids=["bf16-g1", "bf16-g4-mfma", "f32"])
-def test_static_scratch_decode_matches_workspace_decode(pair):
+def test_static_scratch_decode_matches_workspace_decode(pair, decode_merge):
     for n, c in enumerate(pair):
         print(f"static decode case {c}", flush=True)
         shape, q, kp, idx, v, kt, vt, s_tail, cap = _case(*c, seed=4200 + n)
