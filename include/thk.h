@@ -253,8 +253,13 @@ thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,
  * with s_tail > 0 selects the unified value cache: the tail's value rows are rows
  * [S, S + s_tail) of v (needs S_cap >= S + s_tail).
  * S_obs in the shape is ignored.  With n_split > 1 partial (max, sum, acc[D])
- * states go through ws and a second kernel merges them in split order without
- * atomics, so repeated calls give identical bits.
+ * states go through ws and are merged in split order, so repeated calls give
+ * identical bits: by a second kernel, or -- for small calls (at most 16 pieces, at
+ * most two query heads per block, at most two blocks per compute unit) -- inside the
+ * one launch by the block that finishes last for a head group (the blocks signal
+ * through per-piece flag words in ws that carry a nonce drawn per call; no
+ * read-modify-write, nothing in ws has to be cleared beforehand).
+ * THK_DECODE_MERGE = kernel | fused in the environment overrides the choice.
  * bf16 caches with N_q / N_kv >= 3 and a key row pitch (ld_keep, or T when rows are
  * dense) that is a multiple of 4 elements run the two products on the matrix cores,
  * here and in thk_decode_attn_kv: four or eight query heads share every key and
