@@ -234,7 +234,11 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
  * per unit beyond which the staged form is taken), THK_PRUNE_SPIN_LIMIT (polls
  * before a waiting block leaves its rows to the repair kernel; 0 forces that
  * path), THK_PRUNE_STAGGER_NS (spacing of the first round's unit starts; 0 =
- * none), THK_PRUNE_GROUP_MIB (bytes of K per group of units in the staged form).
+ * none), THK_PRUNE_GROUP_MIB (bytes of K per group of units in the staged form),
+ * THK_PRUNE_PROLOGUE_DELAY_US (single-launch form: the unit's prologue block starts
+ * that late, at most 500 us, so that the row blocks find their arrival counters not
+ * yet initialised and have to wait for them -- a path that otherwise needs an
+ * unlucky schedule).
  *   ws : THK_OP_PRUNE bytes.
  */
 thk_status thk_prune(const thk_shape *shape, const void *q_obs, const void *k,

@@ -42,6 +42,7 @@ const EnvSwitches *read_env() {
   s->decode_mfma_off = mf != nullptr && mf[0] == '0';
   const char *pl = getenv("THK_PRUNE_LAUNCH");
   s->prune_launch = pl != nullptr ? pl[0] : 0;
+  s->prologue_delay_us = env_long_raw("THK_PRUNE_PROLOGUE_DELAY_US", 0);
   const char *mk = getenv("THK_DECODE_MERGE");
   s->decode_merge = mk != nullptr ? mk[0] : 0;
   return s;

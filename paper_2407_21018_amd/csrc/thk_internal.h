@@ -85,6 +85,7 @@ struct EnvSwitches {
   double stagger_ns;
   bool decode_mfma_off;   // THK_DECODE_MFMA=0
   char prune_launch;      // first letter of THK_PRUNE_LAUNCH ('c'lassic: three launches, 's'olo: one), 0 = unset
+  long prologue_delay_us; // THK_PRUNE_PROLOGUE_DELAY_US (test hook of the single-launch prune), <= 0 = none
   char decode_merge;      // first letter of THK_DECODE_MERGE ('k'ernel: a second launch merges the split
                           // records, 'f'used: the last block of a head group merges), 0 = unset
 };

@@ -50,6 +50,9 @@ template <int DT>
 __device__ __forceinline__ void solo_prologue(const PruneFusedArgs &a, int64_t u, double *lds) {
   const int tid = threadIdx.x;
   double *hn = lds, *qn_l = lds + 4 * kD;
+  // test hook (THK_PRUNE_PROLOGUE_DELAY_US): a late prologue makes the row blocks arrive on
+  // counters that are not initialised yet, the path that otherwise needs an unlucky schedule
+  for (int t = a.prologue_delay; t > 0; t -= 127) __builtin_amdgcn_s_sleep(127);
   if (tid < kWave) __hip_atomic_store(a.idx_pub + (size_t)u * kWave + tid, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   for (int i = tid; i < a.NB; i += 256)
     __hip_atomic_store(a.undone + (size_t)u * a.NB + i, (unsigned char)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -453,6 +456,8 @@ hipError_t launch_prune_solo(int dtype, const void *q_obs, const void *k, float 
   a.idx_pub = (uint32_t *)w;         w += (size_t)U * kWave * sizeof(uint32_t);
   a.undone = (unsigned char *)w;
   a.nonce = next_nonce48();
+  // at most 500 us, in 64-cycle ticks at about 2.4 GHz
+  a.prologue_delay = (int32_t)(std::min(std::max(env_switches().prologue_delay_us, 0L), 500L) * 2400 / 64);
   a.S = S; a.S_keep = S_keep; a.kp_unit_rows = kp_unit_rows; a.RB = RB; a.T = T; a.ld = ld; a.G = G;
   a.S_obs = S_obs; a.NB = NB; a.spin_limit = spin_limit;
   a.stagger_blocks = 0; a.stagger_units = 1; a.stagger_ticks = 0;

@@ -287,6 +287,48 @@ def test_prune_fused_repeated_calls_on_one_workspace(levels, thk_env, prune_laun
     assert not torch.equal(first_idx[0], first_idx[1])
 
 
+@pytest.mark.parametrize("levels", [1, 2])
+@pytest.mark.parametrize("delay_us", [30, 200])
+def test_prune_single_launch_with_a_late_prologue(levels, delay_us, thk_env):
+    """The single-launch prune initialises its hand-off state inside the launch: a prologue block
+    per unit clears it and then tags the unit's arrival counters with the call's nonce; a row
+    block that arrives earlier finds a foreign tag, waits for the right one and arrives again.
+    Here the prologue is held back from the host (THK_PRUNE_PROLOGUE_DELAY_US) so that EVERY row
+    block arrives first -- on a workspace full of garbage, on the state the previous call left,
+    and with the wait for the index list switched off as well (spin limit 0: the blocks give up
+    and the unit's finisher compacts their rows).  Every kernel exits normally; results as ever."""
+    thk_env.setenv("THK_PRUNE_LAUNCH", "solo")
+    thk_env.setenv("THK_PRUNE_PROLOGUE_DELAY_US", str(delay_us))
+    if levels == 1:
+        L, B, N, G, S, S_obs, T = 2, 2, 4, 2, 3000, 32, 76
+    else:                                          # 102 blocks of 128 rows per unit: two levels of sums
+        thk_env.setenv("THK_PRUNE_BLOCK_ROWS", "128")
+        L, B, N, G, S, S_obs, T = 1, 2, 2, 1, 13008, 32, 64
+    U = L * B * N
+    shape = thk.make_shape(L, B, N * G, N, D, S, S_obs, T, 0, thk.THK_BF16, 0)
+    assert thk.thk_prune_launches(shape) == 1
+    ws = ws_tensor(thk.thk_workspace_bytes(shape, thk.THK_OP_PRUNE))
+    score = torch.empty(U, D, dtype=torch.float32, device="cuda")
+    idx = torch.empty(U, T, dtype=torch.int16, device="cuda")
+    kp = torch.empty(U, S, T, dtype=torch.bfloat16, device="cuda")
+    for rep, (fill, spin) in enumerate([(0xA5, None), (None, None), (0xFF, "0"), (None, "0"), (0x00, None)]):
+        if fill is not None:
+            ws.fill_(fill)
+        if spin is not None:
+            thk_env.setenv("THK_PRUNE_SPIN_LIMIT", spin)
+        q_obs = _randn((L, B, N * G, S_obs, D), "bf16", 171 + rep, 1.0)
+        k = _randn((L, B, N, S, D), "bf16", 181 + rep, 1.0)
+        kp.fill_(-7.0)
+        thk.thk_prune(shape, q_obs, k, score, idx, kp, ws)
+        torch.cuda.synchronize()
+        o_sc, o_idx, _ = oracle_prune(q_obs, k, "bf16", T)
+        rel = np.abs(score.cpu().numpy().astype(np.float64) - o_sc.reshape(U, D)) / o_sc.reshape(U, D)
+        assert rel.max() <= SCORE_TOL, f"call {rep}"
+        check_idx_with_tie_rule(idx.cpu().numpy(), o_idx, o_sc, T)
+        want = O.compact_keys(as_numpy(k).reshape(U, S, D), idx.cpu().numpy(), "bf16")
+        np.testing.assert_array_equal(as_numpy(kp), want, err_msg=f"call {rep}")
+
+
 @pytest.mark.parametrize("dtype,G,S,T,ld,block_rows", [("bf16", 1, 4096, 76, 80, ""), ("bf16", 4, 3001, 51, 56, "128"),
                                                        ("f32", 1, 1037, 51, 52, ""), ("bf16", 1, 2048, 76, 88, "64"),
                                                        ("bf16", 2, 777, 100, 104, "32"), ("bf16", 1, 1500, 76, 77, "")])
