@@ -269,12 +269,12 @@ FusedPlan fused_plan(const thk_shape *s) {
 
 // Calls whose rows are held on chip and whose blocks make at most two rounds of resident blocks
 // (three for units of more than 64 blocks) run as ONE launch (thk_prune_solo.hip): the two extra
-// launches of the other form and the gaps around them are 4-30 % of such a call (fp32, 8 units
-// x 2048 rows: 17.8 -> 12.7 us; 128 units x 4096 bf16 rows: 58.5 -> 56.2 us; 8 units x 131072
-// rows: 97 -> 93 us).  Longer launches keep the three-launch form: a unit's extra prologue
-// block breaks the alignment of units with the resident set, and the main kernel runs 6-12 %
-// slower (32 layers of 128 units x 4096 rows: 1141 -> 1251 us); between two and four rounds
-// the two forms are within 2 % of each other.  THK_PRUNE_LAUNCH = solo | classic overrides.
+// launches of the other form and the gaps around them are 7-30 % of such a call (fp32, 8 units
+// x 2048 rows: 17.8 -> 12.8 us; 128 units x 4096 bf16 rows: 58.1 -> 51.8 us; 8 units x 131072
+// rows: 97 -> 88-90 us).  From about four rounds on the single launch is no better (4 x 128
+// units x 4096 rows: 161 against 161 us) and then worse (32 x 128 units: 1151-1282 against
+// 1141-1154 us; 1280 units x 16384 rows: 1379-1497 against 1287-1306 us), so longer launches keep
+// the three-launch form.  THK_PRUNE_LAUNCH = solo | classic overrides.
 bool prune_single_launch(const thk_shape *s, const FusedPlan &fp) {
   if (!fp.ok || fp.hold == 0) return false;
   if (units_of(s) * ((int64_t)fp.NB + 1) > kMaxGrid) return false;

@@ -39,6 +39,7 @@ struct PruneFusedArgs {
   unsigned char *undone;       // [U * NB] raised by a block that gave up waiting: its rows are the finisher's
   int *gaveup;                 // [U] tickets: +1 per block that gave up, + kFinisherDone by the finisher
   int32_t prologue_delay;      // test hook: 64-cycle ticks the prologue block sleeps before it starts
+  int64_t U;                   // units of the call: blocks 0 .. U-1 are the prologue blocks, the row blocks follow
   int64_t S, RB;          // rows per unit, rows per block
   int64_t S_keep;         // rows [0, S_keep) of every unit are compacted
   int64_t kp_unit_rows;   // rows between units of K_pruned

@@ -6,11 +6,13 @@
 // when its bounded wait ran out.  For calls of a few hundred microseconds and less those two
 // launches and the gaps around them are 10-15 % of the call.  Here both jobs move inside:
 //
-//   * A unit owns NB + 1 consecutive blocks.  The first is the unit's PROLOGUE block: it has no
-//     rows; it clears the unit's hand-off state (index-list words, group vectors, give-up flags
-//     and tickets), computes the query norms, waits until all of that has been acknowledged, and
-//     only then initialises the unit's arrival counters.  The other NB blocks are the row
-//     blocks of k_prune_onepass.
+//   * Blocks 0 .. U-1 of the grid are PROLOGUE blocks, one per unit, the U * NB row blocks of
+//     k_prune_onepass follow.  A prologue block has no rows; it clears its unit's hand-off state
+//     (index-list words, group vectors, give-up flags and tickets), computes the query norms,
+//     waits until all of that has been acknowledged, and only then initialises the unit's
+//     arrival counters.  (A unit's prologue block directly in front of its row blocks, the
+//     first layout, put NB + 1 blocks per unit into a chip that holds a whole number of NB-block
+//     units: units straddled the rounds of resident blocks and long launches ran 6-12 % slower.)
 //   * The arrival counters are the first shared thing a row block touches, and they are TAGGED:
 //     the upper 48 bits hold the call's nonce.  A block whose atomic add returns a word with
 //     another tag has arrived before the prologue's initialisation (which will overwrite what
@@ -21,15 +23,15 @@
 //     the previous replay's count for its own.
 //   * One block of every unit never waits: the FINISHER, whose arrival completes the unit's
 //     sums.  A block that gives up waiting raises a flag for its rows and draws a ticket from
-//     the unit's give-up counter; the finisher, after its own rows, draws the closing ticket,
-//     learns from it how many blocks gave up before, and compacts their rows (re-reading them).
+//     the unit's give-up counter; the finisher draws the closing ticket, learns from it how
+//     many blocks gave up before, and compacts their rows after its own (re-reading them).
 //     A block that gives up later than that finds the closing ticket in the counter: the list is
 //     there by then, so it fetches it and carries on by itself.  Every block exits whatever the
 //     others do.  All sums run in a fixed order: the result does not depend on who arrives last.
 //
 // Waiting is safe for the same reason as in the three-launch form: a block only waits for blocks
 // of its own unit, which have lower or neighbouring block numbers and were dispatched with it
-// (the prologue block has the lowest number of all).
+// (the prologue blocks have the lowest numbers of all).
 #include <algorithm>
 #include <atomic>
 #include <chrono>
@@ -243,17 +245,26 @@ __device__ __forceinline__ bool hand_over_rows(const PruneFusedArgs &a, int64_t 
   return true;
 }
 
-// The finisher, after its own rows: everything it has published (index list or group vector,
-// the caller's scores and list) has landed before it draws the closing ticket; the ticket's
-// value is the number of blocks that gave up before, whose flags are in place, and whose row
-// blocks it compacts now (re-reading them from memory).  tab: the gather table of the unit.
-template <int DT>
-__device__ __forceinline__ void finish_unit(const PruneFusedArgs &a, int64_t u, const u32x4 *src,
-                                            const FlatOut<DT> &dst, const int16_t *tab, u32x4 *tiles, int *s_flag) {
-  block_stores_done();
+// The finisher closes the unit BEFORE it compacts its own rows: it draws the closing ticket from
+// the give-up counter, whose value is the number of blocks that gave up so far (their flags are
+// in place: a block raises its flag, waits for the acknowledgement, and only then draws its
+// ticket).  A block that gives up later finds the closing ticket, fetches the list -- published
+// before the ticket was drawn; the late block polls for it all the same -- and carries on by
+// itself.  (Drawing the ticket after the finisher's own rows instead, behind a wait for the
+// acknowledgement of everything it had published, measured the same on every shape.)
+__device__ __forceinline__ int close_unit(const PruneFusedArgs &a, int64_t u, int *s_flag) {
   if (threadIdx.x == 0) *s_flag = atomicAdd(a.gaveup + u, kFinisherDone);
   __syncthreads();
-  if (*s_flag == 0) return;
+  const int n = *s_flag;
+  __syncthreads();
+  return n;
+}
+
+// ... and after its own rows it compacts the row blocks whose flags are raised (re-reading them
+// from memory).  tab: the gather table of the unit.
+template <int DT>
+__device__ __forceinline__ void serve_gaveup(const PruneFusedArgs &a, int64_t u, const u32x4 *src,
+                                             const FlatOut<DT> &dst, const int16_t *tab, u32x4 *tiles) {
   const unsigned char *flags = a.undone + (size_t)u * a.NB;
   for (int blk = 0; blk < a.NB; ++blk) {
     // block-uniform: every thread reads the same byte
@@ -284,14 +295,13 @@ void k_prune_solo(PruneFusedArgs a) {
   __shared__ int s_flag;
   const int tid = threadIdx.x, lane = tid % kWave;
   const int wave = tid / kWave;
-  const int64_t u = blockIdx.x / (a.NB + 1);
-  const int b = (int)(blockIdx.x % (a.NB + 1));
-  if (b == 0) {
-    solo_prologue<DT>(a, u, (double *)tiles);   // the tiles are free in a block without rows
+  if ((int64_t)blockIdx.x < a.U) {
+    solo_prologue<DT>(a, blockIdx.x, (double *)tiles);   // the tiles are free in a block without rows
     return;
   }
-  const int blk = b - 1;
-  const int64_t item = u * a.NB + blk;
+  const int64_t item = (int64_t)blockIdx.x - a.U;
+  const int64_t u = item / a.NB;
+  const int blk = (int)(item % a.NB);
   const int64_t s0 = (int64_t)blk * a.RB;   // a.RB == 128 * NTW
   const int64_t s1 = min(a.S, s0 + a.RB);
   const u32x4 *src = (const u32x4 *)((const char *)a.k + (size_t)u * a.S * kD * E::EB);
@@ -305,7 +315,7 @@ void k_prune_solo(PruneFusedArgs a) {
   auto tile_rows = [&](int n, int64_t hi) { return (int)max((int64_t)0, min((int64_t)TR, hi - tile_row0(n))); };
 
   // the graded start of the launch's first round (see k_prune_onepass)
-  if ((int64_t)blockIdx.x < a.stagger_blocks) {
+  if (item < a.stagger_blocks) {
     int ticks = (int)(u % a.stagger_units) * a.stagger_ticks;
     for (; ticks >= 127; ticks -= 127) __builtin_amdgcn_s_sleep(127);
     for (; ticks >= 16; ticks -= 16) __builtin_amdgcn_s_sleep(16);
@@ -365,6 +375,7 @@ void k_prune_solo(PruneFusedArgs a) {
     if (!hand_over_rows(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
     st = kHaveList;
   }
+  const int n_gaveup = st == kFinisher ? close_unit(a, u, &s_flag) : 0;
 
   // ---- compaction: the LDS tiles first, then the register tiles through slot 0 ---------------
   // (row numbers are formed again from an opaque copy of the wave index: kept alive from the
@@ -396,9 +407,9 @@ void k_prune_solo(PruneFusedArgs a) {
       compact_emit_tile<DT>(wtile, dst, tile_row0_c(n), nr, a.ld, tab, lane);
     }
   }
-  if (st == kFinisher) {
-    __syncthreads();   // every wave is done with the tiles, which the finisher's re-read uses
-    finish_unit<DT>(a, u, src, dst, tab, tiles, &s_flag);
+  if (n_gaveup > 0) {   // block-uniform
+    __syncthreads();   // every wave is done with the tiles, which the re-read uses
+    serve_gaveup<DT>(a, u, src, dst, tab, tiles);
   }
 }
 
@@ -461,16 +472,17 @@ hipError_t launch_prune_solo(int dtype, const void *q_obs, const void *k, float 
   a.S = S; a.S_keep = S_keep; a.kp_unit_rows = kp_unit_rows; a.RB = RB; a.T = T; a.ld = ld; a.G = G;
   a.S_obs = S_obs; a.NB = NB; a.spin_limit = spin_limit;
   a.stagger_blocks = 0; a.stagger_units = 1; a.stagger_ticks = 0;
+  a.U = U;
   {
-    // the graded start of the first round, as in the three-launch form (a unit has NB + 1 blocks here)
+    // the graded start of the first round, as in the three-launch form
     const int64_t resident = (int64_t)kCUs * (dtype == THK_BF16 ? 3 : 2);
-    const int64_t total = U * (NB + 1);
-    const int64_t res_units = resident / (NB + 1);
+    const int64_t total = U * NB;
+    const int64_t res_units = resident / NB;
     double ns = -1.0;
     if (env_switches().stagger_set) ns = env_switches().stagger_ns;
     else if (res_units >= 2 && total >= 2 * resident) ns = 0.6 * (double)S * kD * eb * 1.5 / 5.7e3;
     if (ns > 0.0 && res_units >= 2) {
-      a.stagger_blocks = (int32_t)(res_units * (NB + 1));
+      a.stagger_blocks = (int32_t)(res_units * NB);
       a.stagger_units = (int32_t)res_units;
       a.stagger_ticks = std::max((int32_t)(ns * 2.4 / 64.0), 1);   // 2.4 GHz, s_sleep counts 64-cycle ticks
     }
@@ -488,7 +500,7 @@ hipError_t launch_prune_solo(int dtype, const void *q_obs, const void *k, float 
       case 2: fn = (const void *)k_prune_solo<THK_F32, 2, 1>; break;
     }
   }
-  if (fn == nullptr || RB != 128 * hold || U * (NB + 1) > 2147483647LL) return hipErrorInvalidValue;
+  if (fn == nullptr || RB != 128 * hold || U * ((int64_t)NB + 1) > 2147483647LL) return hipErrorInvalidValue;
   const size_t lds = 2048 + 4 * compact_tile_bytes(eb);
   static DynLds set[2][5];
   hipError_t e = ensure_dyn_lds(fn, lds, set[dtype == THK_BF16 ? 1 : 0][hold]);
