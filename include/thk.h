@@ -127,11 +127,13 @@ int32_t thk_default_split(const thk_shape *shape, int32_t op);
  * staged three-kernel form (or an invalid shape).  Host-only. */
 int32_t thk_prune_is_fused(const thk_shape *shape);
 
-/* Kernels a thk_prune call on `shape` enqueues: 1 when the rows are held on chip (the kernel
- * initialises its own hand-off state and serves blocks whose wait ran out by itself), 3 with
- * THK_PRUNE_LAUNCH=classic or for blocks that re-read their rows (a kernel in front that
+/* Kernels a thk_prune call on `shape` enqueues: 1 when the rows are held on chip and the call
+ * is short -- at most two rounds of resident blocks, three for units of more than 64 blocks (the
+ * kernel then initialises its own hand-off state, computes the query norms in a prologue block
+ * per unit, and serves blocks whose wait ran out by itself); 3 for longer calls, with
+ * THK_PRUNE_LAUNCH=classic, or for blocks that re-read their rows (a kernel in front that
  * clears the state and computes the query norms, one behind that compacts what was left
- * undone), 3 per group of units in the staged form; 0 for an invalid shape.  Host-only. */
+ * undone); 3 per group of units in the staged form; 0 for an invalid shape.  Host-only. */
 int32_t thk_prune_launches(const thk_shape *shape);
 
 /* 1 if thk_decode_attn (T_v == 0) or thk_decode_attn_kv (value rows of T_v kept channels,
@@ -216,8 +218,9 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
 
 /*
  * End-of-prefill prune = thk_score + thk_select_topk + thk_compact_keys in one
- * call.  A single kernel does all three steps (dense or padded rows, any S, any
- * unit pitch): a block takes 512 bf16 or 256 fp32 rows of a unit (256 or 128
+ * call.  A single kernel does all three steps (alone for short calls, between a
+ * small set-up and a small repair kernel for long ones: see thk_prune_launches),
+ * for dense or padded rows, any S, any unit pitch: a block takes 512 bf16 or 256 fp32 rows of a unit (256 or 128
  * for calls small enough to stay within two blocks per compute unit), keeps
  * them on chip while the unit's index list is being decided, and compacts them
  * from there, so K is read from memory once.  Units of more blocks than are
@@ -226,14 +229,14 @@ thk_status thk_compact_keys(const thk_shape *shape, const void *k,
  * summation order (the last float bit can differ).  `score` may be NULL (then
  * it lives in ws).
  * Environment (for experiments and tests): THK_PRUNE_LAUNCH = classic (three launches:
- * state and query norms, the main kernel, repair) | solo (one launch; the default wherever
- * the rows are held on chip); THK_PRUNE_PATH =
+ * state and query norms, the main kernel, repair) | solo (one launch; the default for
+ * short calls whose rows are held on chip); THK_PRUNE_PATH =
  * staged | fused | reread (the one-kernel form with the rows read twice);
  * THK_PRUNE_BLOCK_ROWS (rows per block; 128, 256 and 512 are held on chip),
  * THK_PRUNE_HOLD_ROWS (largest default block), THK_PRUNE_MAX_BLOCKS (blocks
  * per unit beyond which the staged form is taken), THK_PRUNE_SPIN_LIMIT (polls
- * before a waiting block leaves its rows to the repair kernel; 0 forces that
- * path), THK_PRUNE_STAGGER_NS (spacing of the first round's unit starts; 0 =
+ * before a waiting block leaves its rows to the repair kernel or to the unit's
+ * finisher; 0 forces that path), THK_PRUNE_STAGGER_NS (spacing of the first round's unit starts; 0 =
  * none), THK_PRUNE_GROUP_MIB (bytes of K per group of units in the staged form),
  * THK_PRUNE_PROLOGUE_DELAY_US (single-launch form: the unit's prologue block starts
  * that late, at most 500 us, so that the row blocks find their arrival counters not
