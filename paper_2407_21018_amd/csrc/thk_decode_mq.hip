@@ -30,6 +30,17 @@
 //            are scattered to their output channels at the end.  The tail keeps full-width rows.
 //   NH = 2   eight query heads per KV head in one block: two groups of four share every key
 //            and value operand read from LDS; queries, probabilities and accumulators double.
+//
+// The kernel streams at the rate of a plain read of the same bytes only while its instruction
+// stream stays short (a wave64 instruction holds its SIMD for four cycles, and three or four
+// waves share one): the wave index is made uniform so that tile counts, row counts and their
+// branches live in scalar registers; a whole tile (32 rows, all but a block's last) takes
+// straight-line paths -- value loads at fixed offsets without per-row clamps, the eight 4-row
+// steps of the second product without a test between them so that later reads overlap earlier
+// products; rows of whole 8-channel groups (T a multiple of 8) take a logit loop without masks or
+// range checks; tiles of at most 4 KB of keys get a staging class of their own (no fifth,
+// duplicate chunk).  Together: 805 MB (64 units x 32768 rows, G = 4) 130.4 -> 125.9 us, 403 MB
+// (8 units x 131072 rows) 68.0 -> 65.0 us; with no arithmetic at all the same loads take 123 us.
 #include <stdlib.h>
 
 #include "thk_decode_impl.h"
@@ -54,6 +65,19 @@ __device__ __forceinline__ f32x4 mfma4(s16x4 a, s16x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, c, 0, 0, 0);
 }
 
+// x of the two lanes 16 (or 32) apart, by one register-to-register swap (v_permlane16_swap /
+// v_permlane32_swap with both operands x) instead of a trip through the LDS crossbar: a = x of
+// the pair's lane in the even 16-lane row (in the lower half of the wave), b = x of the other
+// one; both lanes of a pair receive the same (a, b), so a + b has the same bits in both.
+struct LanePair { float a, b; };
+__device__ __forceinline__ LanePair pair16(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return {__uint_as_float(r[0]), __uint_as_float(r[1])};
+}
+__device__ __forceinline__ LanePair pair32(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return {__uint_as_float(r[0]), __uint_as_float(r[1])};
+}
 // x combined over the lanes of equal lane % 4 inside each half of the wave (rotations by 4 and 8
 // inside the 16-lane rows, then the neighbouring row).
 template <bool MAX>
@@ -62,14 +86,19 @@ __device__ __forceinline__ float quad_column_reduce(float x) {
   x = MAX ? max_nn(x, y) : x + y;
   y = dpp_move<0x128, 0xf>(x, x);         // row_ror:8
   x = MAX ? max_nn(x, y) : x + y;
-  y = __shfl_xor(x, 16);
-  return MAX ? max_nn(x, y) : x + y;
+  const LanePair p = pair16(x);
+  return MAX ? max_nn(p.a, p.b) : p.a + p.b;
 }
 
 // Value rows of a tile into registers: chunk j * 64 + lane is 16 bytes of row 4 j + lane / 16.
 // Rows past a ragged tile's end re-read its last row (their probability is 0).
 __device__ __forceinline__ void mq_v_issue(u32x4 (&vr)[kMqVChunks], const u32x4 *__restrict__ vg, int nrows,
                                            int lane) {
+  if (nrows == kMqRows) {   // a whole tile is one contiguous run: chunk j * 64 + lane as it lies in memory
+#pragma unroll
+    for (int j = 0; j < kMqVChunks; ++j) vr[j] = ld_stream(vg + j * kWave + lane);
+    return;
+  }
   const int rsub = lane >> 4, col = lane & 15;
 #pragma unroll
   for (int j = 0; j < kMqVChunks; ++j) vr[j] = ld_stream(vg + (size_t)min(4 * j + rsub, nrows - 1) * 16 + col);
@@ -120,15 +149,34 @@ __device__ __forceinline__ void mq_logits(const char *slab, int shift, int nrows
     for (int g = 0; g < NH; ++g) acc[g] = mfma4(ka, *(const s16x4 *)(qp + g * 4 * (kQS / 2) * 4), acc[g]);
     rel = rel + 1 == nst ? 0 : rel + 1;
   };
-  int ks = 0;
-  for (; ks + 2 <= nst; ks += 2) { step(d0); step(d1); }
-  if (ks < nst) step(d0);
+  if ((W & 7) == 0) {
+    // Rows of whole chunks, an even number of them: every step of both halves is a real chunk
+    // and nothing is masked.  off walks this lane's chunks as a byte offset, wrapping inside
+    // the half's range.
+    const int lo = half * nst * 8, hi = lo + nst * 8;
+    int off = lo + rel * 8;
+    const char *qb = (const char *)qrow;
+    auto pstep = [&](f32x4 (&acc)[NH]) {
+      const s16x4 ka = *(const s16x4 *)(rowp + off);
+#pragma unroll
+      for (int g = 0; g < NH; ++g) acc[g] = mfma4(ka, *(const s16x4 *)(qb + off + g * 4 * (kQS / 2) * 4), acc[g]);
+      off = off + 8 == hi ? lo : off + 8;
+    };
+    int ks = 0;
+    for (; ks + 4 <= nst; ks += 4) { pstep(d0); pstep(d1); pstep(d0); pstep(d1); }
+    for (; ks + 2 <= nst; ks += 2) { pstep(d0); pstep(d1); }
+    if (ks < nst) pstep(d0);
+  } else {
+    int ks = 0;
+    for (; ks + 2 <= nst; ks += 2) { step(d0); step(d1); }
+    if (ks < nst) step(d0);
+  }
 #pragma unroll
   for (int g = 0; g < NH; ++g)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const float t = d0[g][r] + d1[g][r];
-      d[g][r] = t + __shfl_xor(t, 32);
+      const LanePair t = pair32(d0[g][r] + d1[g][r]);
+      d[g][r] = t.a + t.b;
     }
 }
 
@@ -141,7 +189,7 @@ __device__ __forceinline__ void mq_softmax(const f32x4 &d, int nrows, float scal
   const int bb = (lane >> 2) & 7;
   float zz[4];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) zz[r] = 4 * bb + r < nrows ? d[r] * scale : -INFINITY;
+  for (int r = 0; r < 4; ++r) zz[r] = (nrows == kMqRows || 4 * bb + r < nrows) ? d[r] * scale : -INFINITY;
   const float mx = quad_column_reduce<true>(max_nn(max_nn(zz[0], zz[1]), max_nn(zz[2], zz[3])));
   const float m_new = max_nn(st.m, mx);             // finite: the tile has at least one row
   if (__builtin_amdgcn_ballot_w64(m_new != st.m) != 0) {   // rare after the first tiles
@@ -185,32 +233,37 @@ __device__ __forceinline__ void mq_values(const char *slab, const char *pline, i
   const char *vb0 = slab + r * 256 + ((cc ^ swz) << 4) + (seg & 1) * 8;        // channels 0 .. 63
   const char *vb1 = slab + r * 256 + (((8 + cc) ^ swz) << 4) + (seg & 1) * 8;  // channels 64 .. 127
   const char *pa = pline + x * 8;
+  auto rows4 = [&](const int ks) {
+    const s16x4 b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4 *)(vb0 + ks * 1024));
+    const s16x4 b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4 *)(vb1 + ks * 1024));
+    s16x4 a_hi[NH], a_lo[NH];
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+      a_hi[g] = *(const s16x4 *)(pa + g * 512 + ks * 32);
+      a_lo[g] = *(const s16x4 *)(pa + g * 512 + 256 + ks * 32);
+    }
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+      st[g].acc[0] = mfma4(a_hi[g], b0, st[g].acc[0]);
+      st[g].acc[1] = mfma4(a_hi[g], b1, st[g].acc[1]);
+    }
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+      st[g].acc[0] = mfma4(a_lo[g], b0, st[g].acc[0]);
+      st[g].acc[1] = mfma4(a_lo[g], b1, st[g].acc[1]);
+    }
+  };
+  if (nrows == kMqRows) {   // a whole tile: straight-line code, the reads of later rows overlap the products
+#pragma unroll
+    for (int ks = 0; ks < kMqRows / 4; ++ks) rows4(ks);
+    return;
+  }
   const int nks = (nrows + 3) >> 2;
 #pragma unroll
-  for (int ks = 0; ks < kMqRows / 4; ++ks) {
-    if (ks < nks) {
-      const s16x4 b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4 *)(vb0 + ks * 1024));
-      const s16x4 b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4 *)(vb1 + ks * 1024));
-      s16x4 a_hi[NH], a_lo[NH];
-#pragma unroll
-      for (int g = 0; g < NH; ++g) {
-        a_hi[g] = *(const s16x4 *)(pa + g * 512 + ks * 32);
-        a_lo[g] = *(const s16x4 *)(pa + g * 512 + 256 + ks * 32);
-      }
-#pragma unroll
-      for (int g = 0; g < NH; ++g) {
-        st[g].acc[0] = mfma4(a_hi[g], b0, st[g].acc[0]);
-        st[g].acc[1] = mfma4(a_hi[g], b1, st[g].acc[1]);
-      }
-#pragma unroll
-      for (int g = 0; g < NH; ++g) {
-        st[g].acc[0] = mfma4(a_lo[g], b0, st[g].acc[0]);
-        st[g].acc[1] = mfma4(a_lo[g], b1, st[g].acc[1]);
-      }
-    }
-  }
+  for (int ks = 0; ks < kMqRows / 4; ++ks)
+    if (ks < nks) rows4(ks);
 }
 
 // accp += P . V_pruned for the tile whose value bytes sit in the slab as staged (first row at
@@ -268,7 +321,8 @@ __global__ __launch_bounds__(256, WPE) void k_decode_mq(DecodeArgs a, int groups
   uint32_t *qkp = (uint32_t *)smem;                 // [GT][kQS/2] kept query channels, packed bf16, 0 beyond T
   uint32_t *qfp = qkp + GT * (kQS / 2);             // [GT][kQS/2] full query
   char *wbase = (char *)(qfp + GT * (kQS / 2));
-  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // uniform: tile counts and branches stay scalar
   char *slab = wbase + (size_t)wave * (slab_bytes + 512 * NH);
   char *pline = slab + slab_bytes;               // 512 bytes of probabilities per head group
   __shared__ int s_last;
@@ -479,17 +533,24 @@ bool decode_mq_serves(const DecodeArgs &a) {
 // takes ceil(G / slots) blocks per split and the last one may leave slots empty.
 int decode_mq_heads(const DecodeArgs &a) { return (a.N_q / a.N_kv) <= 4 ? 4 : 8; }
 
+// Staging classes: 4 chunks per lane (a 32-row tile of at most 4 KB: T <= 64 with 16-byte rows),
+// 5 (T <= 79) and 9 (up to 128 kept channels).
+template <int VP, int NH>
+static hipError_t mq_launch_class(const DecodeArgs &a, int groups, hipStream_t st) {
+  const int kb = mq_chunks(a);
+  if (kb <= 4) return mq_launch<4, VP, NH>(a, groups, st);
+  if (kb <= 5) return mq_launch<5, VP, NH>(a, groups, st);
+  return mq_launch<9, VP, NH>(a, groups, st);
+}
+
 hipError_t decode_mq_launch(const DecodeArgs &a, hipStream_t st) {
-  const bool narrow = mq_chunks(a) <= 5;
   const int G = a.N_q / a.N_kv;
   if (decode_mq_heads(a) == 8) {
     const int groups = (G + 7) / 8;
-    if (a.T_v > 0) return narrow ? mq_launch<5, 1, 2>(a, groups, st) : mq_launch<9, 1, 2>(a, groups, st);
-    return narrow ? mq_launch<5, 0, 2>(a, groups, st) : mq_launch<9, 0, 2>(a, groups, st);
+    return a.T_v > 0 ? mq_launch_class<1, 2>(a, groups, st) : mq_launch_class<0, 2>(a, groups, st);
   }
   const int groups = (G + 3) / 4;
-  if (a.T_v > 0) return narrow ? mq_launch<5, 1, 1>(a, groups, st) : mq_launch<9, 1, 1>(a, groups, st);
-  return narrow ? mq_launch<5, 0, 1>(a, groups, st) : mq_launch<9, 0, 1>(a, groups, st);
+  return a.T_v > 0 ? mq_launch_class<1, 1>(a, groups, st) : mq_launch_class<0, 1>(a, groups, st);
 }
 
 }  // namespace thk
