@@ -15,8 +15,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-def _prune_all(cfg_id):
-    cfg = synth.CONFIGS[cfg_id]
+def _prune_all(cfg_id, **override):
+    cfg = dict(synth.CONFIGS[cfg_id], **override)
     L, B, N_q, N_kv, D, S, S_obs = (cfg[k] for k in ("L", "B", "N_q", "N_kv", "D", "S", "S_obs"))
     T = thk.thk_keep_count(D, cfg["lam"])
     assert T == O.keep_count(D, cfg["lam"])
@@ -98,6 +98,28 @@ def test_config_prune_and_decode(cfg_id):
     assert n_checked == L * cfg["steps"] * cfg["B"] * cfg["N_q"]
     print(f"config {cfg_id}: attention max rel err {worst:.3e} over {n_checked} output vectors", flush=True)
     assert worst <= ATTN_TOL[cfg["dtype"]]
+
+
+def test_sequence_too_long_to_hold_on_chip():
+    """Config 4's layout with a sequence four times as long and ragged (524365 rows: 1025 row blocks
+    per unit, more than the 768 the chip holds at once), so the prune takes its staged form by
+    itself and a decode call splits every unit into its largest default number of pieces.  Two
+    KV heads keep the oracle's part to seconds; every unit and every head is checked."""
+    cfg_id = 4
+    S = 4 * 131072 + 77
+    cfg, T, q_obs, k, v, score, idx, kp = _prune_all(cfg_id, S=S, N_q=8, N_kv=2)
+    shape = thk.make_shape(1, cfg["B"], cfg["N_q"], cfg["N_kv"], cfg["D"], S, cfg["S_obs"], T, 0, thk.THK_BF16, 0)
+    assert thk.thk_prune_is_fused(shape) != 2, "a unit of 1025 blocks cannot be held: not the one-pass form"
+    _check_prune(cfg, T, q_obs, k, score, idx, kp)
+    U = cfg["B"] * cfg["N_kv"]
+    worst = 0.0
+    for s_ in range(2):
+        q, _, _ = synth.gen_decode(cfg_id, 0, s_, DEV, **cfg)
+        out = _decode_layer(cfg, T, 0, 0, q, kp, idx, v, None, None, 0)
+        ref = _oracle_decode(cfg, T, q, kp[0], idx[:U], v[0])
+        worst = max(worst, attn_rel_err(out, ref.reshape(-1, cfg["D"])).max())
+    print(f"S = {S}: attention max rel err {worst:.3e}", flush=True)
+    assert worst <= ATTN_TOL["bf16"]
 
 
 def test_config5_prune_and_tail_decode():
