@@ -270,43 +270,43 @@ __device__ inline void select_wave(float s_lo, float s_hi, int T, int16_t *out, 
 }
 
 // ---------------------------------------------------------------------------
-// The same selection by a 256-thread block, by counting: channel c is kept iff fewer than T
-// channels rank before it (larger score, or equal score and lower index).  Thread (c, h)
-// counts over one half of the channels, read as LDS broadcasts; the kept channels are emitted
-// in ascending order through ballot + prefix popcount.  A few hundred cycles, against the
-// ~5000 of the one-wave sort, which matters where other blocks wait for the list.
-// sc: 128 scores in LDS (complete and visible); scratch: 257 words of LDS; out: LDS, T entries,
-// visible to the block on return.
+// The same selection inside a 256-thread block whose other blocks wait for the list: one
+// wavefront, no LDS traffic and no barrier inside the search.  The T-th largest key is found by
+// bisection on its 32 bits (count of keys >= candidate = two ballots and two population counts,
+// all in scalar registers); channels with a larger key are kept, and of those that tie with it
+// the lowest-numbered ones, as many as are still missing -- channel c is kept iff fewer than T
+// channels rank before it (larger score, or equal score and lower index).  The kept channels are
+// emitted in ascending order through ballot + prefix popcount.  About 0.5 us wherever it runs.
+// (Its predecessor counted, per channel, the channels ranking before it, 64 LDS broadcast reads
+// per thread and three barriers: a few hundred cycles alone, but 2.0-2.9 us (median 2.4) inside
+// the prune kernels, where the neighbouring blocks' compaction keeps the LDS pipeline busy.)
+// sc: 128 scores in LDS (complete and visible); out: LDS, T entries, visible to the block on
+// return.  scratch is not used.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void select_block(const float *sc, int T, int16_t *out, uint32_t *scratch) {
-  const int tid = threadIdx.x, c = tid & (kD - 1), h = tid >> 7;
-  uint32_t *key = scratch, *part = scratch + kD, *cnt0 = scratch + 2 * kD;
-  if (tid < kD) {
-    const uint32_t b = __float_as_uint(sc[tid]);
-    key[tid] = (b & 0x80000000u) ? ~b : (b | 0x80000000u);   // unsigned order == float order
-  }
-  __syncthreads();
-  const uint32_t mine = key[c];
-  int before = 0;
-#pragma unroll 8
-  for (int j = h * 64; j < h * 64 + 64; ++j) {
-    const uint32_t kj = key[j];
-    before += (kj > mine) || (kj == mine && j < c);
-  }
-  if (h) part[c] = (uint32_t)before;
-  __syncthreads();
-  bool keep = false;
-  unsigned long long m = 0;
-  if (!h) {
-    keep = before + (int)part[c] < T;
-    m = __ballot(keep);
-    if (tid == 0) *cnt0 = (uint32_t)__popcll(m);   // kept among channels 0 .. 63
-  }
-  __syncthreads();
-  if (keep) {
-    const int lane = tid % kWave;
-    const int pos = __popcll(m & ((1ull << lane) - 1ull)) + (tid >= kWave ? (int)*cnt0 : 0);
-    out[pos] = (int16_t)c;
+  (void)scratch;
+  using u64 = unsigned long long;
+  if (threadIdx.x < kWave) {
+    const int lane = threadIdx.x;
+    auto key_of = [](float s) {
+      const uint32_t b = __float_as_uint(s);
+      return (b & 0x80000000u) ? ~b : (b | 0x80000000u);   // unsigned order == float order
+    };
+    const uint32_t k0 = key_of(sc[lane]), k1 = key_of(sc[lane + kWave]);
+    uint32_t thr = 0;   // ends as the largest v with count(key >= v) >= T: the T-th largest key
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = thr | (1u << bit);
+      const int n = __popcll(__ballot(k0 >= cand)) + __popcll(__ballot(k1 >= cand));
+      if (n >= T) thr = cand;   // wave-uniform
+    }
+    const u64 e0 = __ballot(k0 == thr), e1 = __ballot(k1 == thr);
+    const int need = T - __popcll(__ballot(k0 > thr)) - __popcll(__ballot(k1 > thr));   // ties to keep, >= 1
+    const u64 below = (1ull << lane) - 1ull;
+    const bool keep0 = k0 > thr || (k0 == thr && __popcll(e0 & below) < need);
+    const bool keep1 = k1 > thr || (k1 == thr && __popcll(e0) + __popcll(e1 & below) < need);
+    const u64 m0 = __ballot(keep0), m1 = __ballot(keep1);
+    if (keep0) out[__popcll(m0 & below)] = (int16_t)lane;
+    if (keep1) out[__popcll(m0) + __popcll(m1 & below)] = (int16_t)(lane + kWave);
   }
   __syncthreads();
 }
