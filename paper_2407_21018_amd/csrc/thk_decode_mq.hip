@@ -65,19 +65,6 @@ __device__ __forceinline__ f32x4 mfma4(s16x4 a, s16x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, c, 0, 0, 0);
 }
 
-// x of the two lanes 16 (or 32) apart, by one register-to-register swap (v_permlane16_swap /
-// v_permlane32_swap with both operands x) instead of a trip through the LDS crossbar: a = x of
-// the pair's lane in the even 16-lane row (in the lower half of the wave), b = x of the other
-// one; both lanes of a pair receive the same (a, b), so a + b has the same bits in both.
-struct LanePair { float a, b; };
-__device__ __forceinline__ LanePair pair16(float x) {
-  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return {__uint_as_float(r[0]), __uint_as_float(r[1])};
-}
-__device__ __forceinline__ LanePair pair32(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return {__uint_as_float(r[0]), __uint_as_float(r[1])};
-}
 // x combined over the lanes of equal lane % 4 inside each half of the wave (rotations by 4 and 8
 // inside the 16-lane rows, then the neighbouring row).
 template <bool MAX>

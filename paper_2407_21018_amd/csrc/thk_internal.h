@@ -26,6 +26,49 @@ __device__ __forceinline__ u32x4 ld_stream(const u32x4 *p) { return __builtin_no
 // read / write streams).
 __device__ __forceinline__ void st_stream(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
 
+// ---- values of the lane 16 or 32 lanes away, without the LDS crossbar ------
+// v_permlane16_swap / v_permlane32_swap with both operands x: a = x of the pair's lane in the even
+// 16-lane row (in the lower half of the wave), b = x of the other one; both lanes of a pair
+// receive the same (a, b), so a + b has the same bits in both.
+struct LanePair { float a, b; };
+__device__ __forceinline__ LanePair pair16(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return {__uint_as_float(r[0]), __uint_as_float(r[1])};
+}
+__device__ __forceinline__ LanePair pair32(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return {__uint_as_float(r[0]), __uint_as_float(r[1])};
+}
+// x + (x of the lane OFF away) for a double, OFF = 16 or 32: the same bits as x + __shfl_xor(x, OFF)
+// (the sum of two values does not depend on their order), by four register swaps instead of
+// four trips through the LDS crossbar.
+template <int OFF>
+__device__ __forceinline__ double add_across(double x) {
+  static_assert(OFF == 16 || OFF == 32, "one swap instruction exists for each of these distances");
+  const unsigned long long bits = (unsigned long long)__double_as_longlong(x);
+  const unsigned lo = (unsigned)bits, hi = (unsigned)(bits >> 32);
+  unsigned alo, blo, ahi, bhi;
+  if constexpr (OFF == 16) {
+    const auto rl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    const auto rh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    alo = rl[0]; blo = rl[1]; ahi = rh[0]; bhi = rh[1];
+  } else {
+    const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    alo = rl[0]; blo = rl[1]; ahi = rh[0]; bhi = rh[1];
+  }
+  const double a = __longlong_as_double((long long)(((unsigned long long)ahi << 32) | alo));
+  const double b = __longlong_as_double((long long)(((unsigned long long)bhi << 32) | blo));
+  return a + b;
+}
+// A per-lane double summed over the lane groups of LPR lanes each (LPR = 16 or 32) of a wavefront.
+template <int LPR>
+__device__ __forceinline__ double add_lane_groups(double x) {
+  static_assert(LPR == 16 || LPR == 32, "lane groups of a 16-byte-chunk row: 16 (bf16) or 32 (fp32) lanes");
+  if constexpr (LPR == 16) x = add_across<16>(x);
+  return add_across<32>(x);
+}
+
 // ---- element access ------------------------------------------------------
 // A 16-byte chunk holds VEC elements; unpack() widens them to float exactly.
 template <int DT> struct Elem;

@@ -52,9 +52,7 @@ __device__ __forceinline__ void colsum_block(const u32x4 *__restrict__ base, int
 
   // rows held by the other lane groups of this wave
 #pragma unroll
-  for (int off = LPR; off < kWave; off <<= 1)
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) dacc[v] += __shfl_xor(dacc[v], off);
+  for (int v = 0; v < VEC; ++v) dacc[v] = add_lane_groups<LPR>(dacc[v]);
 
   const int wave = tid / kWave, lane = tid % kWave;
   if (lane < LPR)
@@ -163,9 +161,7 @@ __device__ __forceinline__ void wave_head_sumsq(const u32x4 *__restrict__ qhead,
     }
   }
 #pragma unroll
-  for (int off = LPR; off < kWave; off <<= 1)
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) qa[v] += __shfl_xor(qa[v], off);
+  for (int v = 0; v < VEC; ++v) qa[v] = add_lane_groups<LPR>(qa[v]);
 }
 
 template <int DT>

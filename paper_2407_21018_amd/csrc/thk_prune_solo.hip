@@ -360,9 +360,7 @@ void k_prune_solo(PruneFusedArgs a) {
     for (int v = 0; v < VEC; ++v) dacc[v] += (double)facc[v];
   }
 #pragma unroll
-  for (int off = CPR; off < kWave; off <<= 1)
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) dacc[v] += __shfl_xor(dacc[v], off);
+  for (int v = 0; v < VEC; ++v) dacc[v] = add_lane_groups<CPR>(dacc[v]);
   if (lane < CPR)
 #pragma unroll
     for (int v = 0; v < VEC; ++v) red[wave][lane * VEC + v] = dacc[v];
