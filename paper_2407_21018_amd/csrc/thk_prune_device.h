@@ -272,7 +272,8 @@ __device__ inline void select_wave(float s_lo, float s_hi, int T, int16_t *out, 
 // all in scalar registers); channels with a larger key are kept, and of those that tie with it
 // the lowest-numbered ones, as many as are still missing -- channel c is kept iff fewer than T
 // channels rank before it (larger score, or equal score and lower index).  The kept channels are
-// emitted in ascending order through ballot + prefix popcount.  About 0.5 us wherever it runs.
+// emitted in ascending order through ballot + prefix popcount.  1.5 us inside the prune kernels
+// when all 32 rounds run (the wave gets about every third issue slot of its SIMD there).
 // (Its predecessor counted, per channel, the channels ranking before it, 64 LDS broadcast reads
 // per thread and three barriers: a few hundred cycles alone, but 2.0-2.9 us (median 2.4) inside
 // the prune kernels, where the neighbouring blocks' compaction keeps the LDS pipeline busy.)
@@ -289,17 +290,27 @@ __device__ __forceinline__ void select_block(const float *sc, int T, int16_t *ou
       return (b & 0x80000000u) ? ~b : (b | 0x80000000u);   // unsigned order == float order
     };
     const uint32_t k0 = key_of(sc[lane]), k1 = key_of(sc[lane + kWave]);
-    uint32_t thr = 0;   // ends as the largest v with count(key >= v) >= T: the T-th largest key
+    // thr ends as the largest v with count(key >= v) >= T: the T-th largest key.  The search stops
+    // as soon as a candidate has EXACTLY T keys at or above it: those are the list (every one of
+    // them is larger than every other key, so no tie crosses the boundary).  With 128 scores
+    // spread over a few binades that happens after some ten rounds; only a tie across the T-th
+    // place runs all 32 and is then resolved by channel number.
+    uint32_t thr = 0;
+    bool exact = false;
     for (int bit = 31; bit >= 0; --bit) {
       const uint32_t cand = thr | (1u << bit);
       const int n = __popcll(__ballot(k0 >= cand)) + __popcll(__ballot(k1 >= cand));
       if (n >= T) thr = cand;   // wave-uniform
+      if (n == T) { exact = true; break; }
     }
-    const u64 e0 = __ballot(k0 == thr), e1 = __ballot(k1 == thr);
-    const int need = T - __popcll(__ballot(k0 > thr)) - __popcll(__ballot(k1 > thr));   // ties to keep, >= 1
     const u64 below = (1ull << lane) - 1ull;
-    const bool keep0 = k0 > thr || (k0 == thr && __popcll(e0 & below) < need);
-    const bool keep1 = k1 > thr || (k1 == thr && __popcll(e0) + __popcll(e1 & below) < need);
+    bool keep0 = k0 >= thr, keep1 = k1 >= thr;
+    if (!exact) {
+      const u64 e0 = __ballot(k0 == thr), e1 = __ballot(k1 == thr);
+      const int need = T - __popcll(__ballot(k0 > thr)) - __popcll(__ballot(k1 > thr));   // ties to keep, >= 1
+      keep0 = k0 > thr || (k0 == thr && __popcll(e0 & below) < need);
+      keep1 = k1 > thr || (k1 == thr && __popcll(e0) + __popcll(e1 & below) < need);
+    }
     const u64 m0 = __ballot(keep0), m1 = __ballot(keep1);
     if (keep0) out[__popcll(m0 & below)] = (int16_t)lane;
     if (keep1) out[__popcll(m0) + __popcll(m1 & below)] = (int16_t)(lane + kWave);
