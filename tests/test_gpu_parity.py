@@ -435,7 +435,7 @@ def test_prune_pipeline_matches_oracle(dtype, G, S, T, sigma, path, thk_env, pru
     assert torch.equal(score_b, score) and torch.equal(idx_b, idx) and torch.equal(kp_b, kp)
 
 
-@pytest.mark.parametrize("pattern", ["pairs", "all-equal", "blocks-of-16"])
+@pytest.mark.parametrize("pattern", ["pairs", "all-equal", "blocks-of-16", "half-zero"])
 @pytest.mark.parametrize("T", [1, 2, 51, 64, 65, 127, 128])
 def test_prune_breaks_exact_ties_by_channel_number(pattern, T, prune_launch):
     """Channels that are copies of each other score the same to the last bit (on the GPU and in the
@@ -443,12 +443,15 @@ def test_prune_breaks_exact_ties_by_channel_number(pattern, T, prune_launch):
     (Sec. 3.2's Top_T is silent on ties; the stable order is this build's reading).  The whole
     prune call must then give exactly the oracle's list: with pairs of copies, with 16 copies
     of each of 8 columns (the T-th place falls inside a run of equal scores for most T), and with
-    128 equal channels (the list is 0 .. T-1)."""
+    128 equal channels (the list is 0 .. T-1); and with 64 channels that are zero everywhere
+    (scores of exactly 0, the smallest key there is: for T > 64 the list ends with the lowest zeros)."""
     L, B, N_kv, G, S, S_obs = 1, 2, 3, 2, 777, 32
     src = {"pairs": torch.arange(D) // 2 * 2, "all-equal": torch.zeros(D, dtype=torch.long),
-           "blocks-of-16": torch.arange(D) % 8}[pattern].cuda()
+           "blocks-of-16": torch.arange(D) % 8, "half-zero": torch.arange(D)}[pattern].cuda()
     q_obs = _randn((L, B, N_kv * G, S_obs, D), "bf16", 41)[..., src].contiguous()
     k = _randn((L, B, N_kv, S, D), "bf16", 42)[..., src].contiguous()
+    if pattern == "half-zero":      # every third and every fourth channel all zero: 64 scores of exactly +0
+        k[..., (torch.arange(D) % 4 >= 2).cuda()] = 0
     shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T, 0, thk.THK_BF16, 0)
     score, idx, kp = gpu_prune(shape, q_obs, k)
     o_sc, o_idx, o_kp = oracle_prune(q_obs, k, "bf16", T)
