@@ -415,10 +415,23 @@ __device__ __forceinline__ void compact_emit_tile(const u32x4 *tile, const FlatO
   // tile-relative positions p = q - base in [sh, sh + nq); chunks [VEC c, VEC c + VEC)
   const int c_lo = (out.sh + VEC - 1) / VEC, c_hi = (out.sh + nq) / VEC;   // whole chunks: c_lo <= c < c_hi
   u32x4 *o = out.o + base / VEC;
-  for (int c = c_lo + lane; c < c_hi; c += kWave) {
-    const int p0 = c * VEC;
-    const int pb = p0 / period;
-    st_stream(o + c, gather_chunk<DT>(tl0 + pb * 8 * Tile<DT>::ROW_ELEMS, tab + (p0 - pb * period)));
+  {
+    // chunk c lies in 8-row block pb = c / cpp of the tile, at chunk rc = c % cpp of the table's
+    // period.  A tile spans four periods (and the shift), so the first quotient is four
+    // comparisons, and from one step to the next (c += 64) quotient and remainder move by
+    // constants: no division in the loop, which runs in every block between the arrival of
+    // the index list and the block's last store.
+    const int cpp = period / VEC;
+    const int dq = kWave / cpp, dr = kWave - dq * cpp;   // uniform
+    int c = c_lo + lane;
+    int pb = (c >= cpp) + (c >= 2 * cpp) + (c >= 3 * cpp) + (c >= 4 * cpp);
+    int rc = c - pb * cpp;
+    for (; c < c_hi; c += kWave) {
+      st_stream(o + c, gather_chunk<DT>(tl0 + pb * 8 * Tile<DT>::ROW_ELEMS, tab + rc * VEC));
+      rc += dr;
+      pb += dq;
+      if (rc >= cpp) { rc -= cpp; ++pb; }
+    }
   }
   // positions outside the whole chunks: [sh, min(VEC c_lo, sh + nq)) and [max(VEC c_hi, VEC c_lo), sh + nq)
   const int head_end = min(c_lo * VEC, out.sh + nq);
