@@ -375,27 +375,33 @@ __device__ __forceinline__ void compact_build_tab(int16_t *tab, const int16_t *u
     int e = i - sh, back = 0;
     if (e < 0) { e += period; back = 8 * Tile<DT>::ROW_ELEMS; }   // an element of the 8-row block before
     const int row = e / ld, t = e - row * ld;
-    tab[i] = (int16_t)(row * Tile<DT>::ROW_ELEMS + (t < T ? (int)uidx[t] : kD) - back);   // kD: the zero chunk
+    // BYTE offsets (at most 8 rows of 272 or 528 bytes: they fit 16 bits), so that a gather address
+    // is base + entry with no shift in between; kD: the zero chunk
+    tab[i] = (int16_t)((row * Tile<DT>::ROW_ELEMS + (t < T ? (int)uidx[t] : kD) - back) * (int)sizeof(typename Elem<DT>::Bits));
   }
 }
 
-// VEC elements of the LDS row (or block of rows) at tl through the VEC table entries at te.
+// VEC elements of the LDS row (or block of rows) at tl through the VEC table entries (signed byte
+// offsets) at te.
 template <int DT>
 __device__ __forceinline__ u32x4 gather_chunk(const typename Elem<DT>::Bits *tl, const int16_t *te) {
+  using ET = typename Elem<DT>::Bits;
+  const char *b = (const char *)tl;
+  auto at = [&](int off) { return *(const ET *)(b + off); };
   u32x4 w;
   if constexpr (DT == THK_BF16) {
-    const u32x4 offs = *(const u32x4 *)te;   // 8 signed offsets
+    const u32x4 offs = *(const u32x4 *)te;   // 8 entries
     const int o0 = (int16_t)(offs.x & 0xffffu), o1 = (int)offs.x >> 16, o2 = (int16_t)(offs.y & 0xffffu);
     const int o3 = (int)offs.y >> 16, o4 = (int16_t)(offs.z & 0xffffu), o5 = (int)offs.z >> 16;
     const int o6 = (int16_t)(offs.w & 0xffffu), o7 = (int)offs.w >> 16;
-    w.x = (uint32_t)tl[o0] | ((uint32_t)tl[o1] << 16);
-    w.y = (uint32_t)tl[o2] | ((uint32_t)tl[o3] << 16);
-    w.z = (uint32_t)tl[o4] | ((uint32_t)tl[o5] << 16);
-    w.w = (uint32_t)tl[o6] | ((uint32_t)tl[o7] << 16);
+    w.x = (uint32_t)at(o0) | ((uint32_t)at(o1) << 16);
+    w.y = (uint32_t)at(o2) | ((uint32_t)at(o3) << 16);
+    w.z = (uint32_t)at(o4) | ((uint32_t)at(o5) << 16);
+    w.w = (uint32_t)at(o6) | ((uint32_t)at(o7) << 16);
   } else {
-    const uint2 offs = *(const uint2 *)te;   // 4 signed offsets
-    w.x = tl[(int16_t)(offs.x & 0xffffu)]; w.y = tl[(int)offs.x >> 16];
-    w.z = tl[(int16_t)(offs.y & 0xffffu)]; w.w = tl[(int)offs.y >> 16];
+    const uint2 offs = *(const uint2 *)te;   // 4 entries
+    w.x = at((int16_t)(offs.x & 0xffffu)); w.y = at((int)offs.x >> 16);
+    w.z = at((int16_t)(offs.y & 0xffffu)); w.w = at((int)offs.y >> 16);
   }
   return w;
 }
@@ -442,7 +448,7 @@ __device__ __forceinline__ void compact_emit_tile(const u32x4 *tile, const FlatO
     const int p = lane < n_head ? out.sh + lane : tail_beg + (lane - n_head);
     const int pb = p / period;
     const int pe = p - pb * period;
-    ((ET *)o)[p] = tl0[pb * 8 * Tile<DT>::ROW_ELEMS + tab[pe]];
+    ((ET *)o)[p] = *(const ET *)((const char *)(tl0 + pb * 8 * Tile<DT>::ROW_ELEMS) + tab[pe]);
   }
 }
 
