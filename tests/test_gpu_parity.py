@@ -240,6 +240,19 @@ def test_decode_split_invariance_and_determinism(dtype, decode_merge):
         assert rel <= ATTN_TOL[dtype], f"n_split={n_split} deviates by {rel}"
 
 
+@pytest.mark.parametrize("dtype,G,S,tail", [("bf16", 1, 1000, 0), ("bf16", 4, 70000, 9), ("f32", 2, 300, 3)])
+def test_decode_with_the_largest_split_count(dtype, G, S, tail):
+    """n_split = 4096, the most the interface takes: nearly every piece is empty (64 rows per piece
+    at least, so S = 70000 fills 1094 of them and S = 300 five); empty pieces must carry a weight
+    of zero into the merge, and the tail tiles go to pieces that have no pruned rows at all."""
+    err, out = _decode_case(dtype, 1, 2, G, S, 64, 0, 4096, tail, 16, 1.0, 123)
+    assert np.isfinite(out.float().cpu().numpy()).all()
+    assert err.max() <= ATTN_TOL[dtype]
+    _, out1 = _decode_case(dtype, 1, 2, G, S, 64, 0, 1, tail, 16, 1.0, 123)
+    rel = ((out.float() - out1.float()).abs().amax(-1) / out1.float().abs().amax(-1)).max().item()
+    assert rel <= ATTN_TOL[dtype]
+
+
 # ----------------------------------------------------------------- prune ----
 PRUNE_CASES = [("bf16", 1, 2048, 76, 1.5), ("bf16", 4, 4096 + 64, 64, 1.0), ("f32", 1, 1037, 64, 1.0),
                ("bf16", 1, 1024, 51, 2.0), ("f32", 2, 2048, 64, 1.0), ("bf16", 1, 40, 64, 1.0)]
