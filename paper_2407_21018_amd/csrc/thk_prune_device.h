@@ -278,10 +278,9 @@ __device__ inline void select_wave(float s_lo, float s_hi, int T, int16_t *out, 
 // per thread and three barriers: a few hundred cycles alone, but 2.0-2.9 us (median 2.4) inside
 // the prune kernels, where the neighbouring blocks' compaction keeps the LDS pipeline busy.)
 // sc: 128 scores in LDS (complete and visible); out: LDS, T entries, visible to the block on
-// return.  scratch is not used.
+// return.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void select_block(const float *sc, int T, int16_t *out, uint32_t *scratch) {
-  (void)scratch;
+__device__ __forceinline__ void select_block(const float *sc, int T, int16_t *out) {
   using u64 = unsigned long long;
   if (threadIdx.x < kWave) {
     const int lane = threadIdx.x;

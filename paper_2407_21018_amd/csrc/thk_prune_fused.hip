@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void k_prune_prep(PruneFusedArgs a, int64_t U)
 
 __device__ __forceinline__ bool unit_index_list(const PruneFusedArgs &a, int64_t u, int64_t item,
                                                 double *s_part, float *s_sc, int16_t *s_idx,
-                                                int *s_flag, uint32_t *scratch) {
+                                                int *s_flag) {
   const int tid = threadIdx.x;
   // the query norms are needed last; their load travels with the stores below
   const double qn_c = tid < kD ? a.qn[(size_t)u * kD + tid] : 0.0;
@@ -125,13 +125,13 @@ __device__ __forceinline__ bool unit_index_list(const PruneFusedArgs &a, int64_t
     __syncthreads();
     if (*s_flag == 0) return false;
     if (tid < kD) kss += s_part[c];
-    score_and_select(a, u, qn_c, kss, s_sc, s_idx, scratch, blk == 0);
+    score_and_select(a, u, qn_c, kss, s_sc, s_idx, blk == 0);
     return true;
   }
 
   if (arrive(a.arrived + u, a.NB, s_flag)) {
     const double kss = merge_partials(src, a.NB, s_part);   // s_part: its sums are published already
-    score_and_select(a, u, qn_c, kss, s_sc, s_idx, scratch, true);
+    score_and_select(a, u, qn_c, kss, s_sc, s_idx, true);
     if (tid < kWave) {
       const uint32_t lo = 2 * tid < a.T ? (uint16_t)s_idx[2 * tid] : 0u;
       const uint32_t hi = 2 * tid + 1 < a.T ? (uint16_t)s_idx[2 * tid + 1] : 0u;
@@ -171,7 +171,6 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
   __shared__ double s_part[kD];
   __shared__ float s_sc[kD];
   __shared__ int16_t s_idx[kD];
-  __shared__ uint32_t s_scratch[2 * kD + 1];
   __shared__ int s_flag;
   const int tid = threadIdx.x;
   const int64_t item = blockIdx.x;
@@ -183,7 +182,7 @@ __global__ __launch_bounds__(256) void k_prune_fused(PruneFusedArgs a) {
 
   colsum_block<DT, 2, false>(src, s0, s1, s_part, red);
   __syncthreads();
-  if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
+  if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag)) return;
 
   const FlatOut<DT> out((char *)a.kp + (size_t)u * a.kp_unit_rows * a.ld * E::EB);
   compact_build_tab<DT>(tab, s_idx, a.T, a.ld, out.sh);
@@ -214,7 +213,6 @@ void k_prune_onepass(PruneFusedArgs a) {
   __shared__ double s_part[kD];
   __shared__ float s_sc[kD];
   __shared__ int16_t s_idx[kD];
-  __shared__ uint32_t s_scratch[2 * kD + 1];
   __shared__ int s_flag;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int64_t item = blockIdx.x;
@@ -289,7 +287,7 @@ void k_prune_onepass(PruneFusedArgs a) {
   if (tid < kD) s_part[tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
   __syncthreads();
 
-  if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
+  if (!unit_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag)) return;
 
   // ---- compaction: the LDS tiles first, then the register tiles through slot 0 ---------------
   const FlatOut<DT> dst((char *)a.kp + (size_t)u * a.kp_unit_rows * a.ld * E::EB);
@@ -342,7 +340,6 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
     // sums in the same order give the same list.
     __shared__ float s_sc[kD];
     __shared__ int16_t s_idx[kD];
-    __shared__ uint32_t s_scratch[2 * kD + 1];
     const int tid = threadIdx.x;
     const int n_grp = (a.NB + a.GS - 1) / a.GS;
     const double *gp = a.gpartial + (size_t)u * kMaxGroups * kD;
@@ -353,7 +350,7 @@ __global__ __launch_bounds__(256) void k_prune_repair(PruneFusedArgs a) {
         half[j / (kMaxGroups / 2)] += __longlong_as_double((long long)(pub_load_bits(gp + (size_t)j * kD + tid) & ~1ull));
       kss = half[0] + half[1];
     }
-    score_and_select(a, u, tid < kD ? a.qn[(size_t)u * kD + tid] : 0.0, kss, s_sc, s_idx, s_scratch, true);
+    score_and_select(a, u, tid < kD ? a.qn[(size_t)u * kD + tid] : 0.0, kss, s_sc, s_idx, true);
     compact_build_tab<DT>(tab, s_idx, a.T, a.ld, dst.sh);
   } else {
     compact_build_tab<DT>(tab, a.idx + (size_t)u * a.T, a.T, a.ld, dst.sh);

@@ -109,9 +109,9 @@ __device__ inline unsigned long long pub_load_bits(const double *p) {
 }
 
 // Scores of the unit from its column sums (kss, valid in threads < 128) and the index list;
-// `writer` also stores both for the caller.  scratch: 257 words of LDS.
+// `writer` also stores both for the caller.
 __device__ __forceinline__ void score_and_select(const PruneFusedArgs &a, int64_t u, double qn_c, double kss,
-                                                 float *s_sc, int16_t *s_idx, uint32_t *scratch, bool writer) {
+                                                 float *s_sc, int16_t *s_idx, bool writer) {
   const int tid = threadIdx.x;
   if (tid < kD) {
     const float scf = (float)(qn_c * sqrt(kss));
@@ -119,7 +119,7 @@ __device__ __forceinline__ void score_and_select(const PruneFusedArgs &a, int64_
     s_sc[tid] = scf;
   }
   __syncthreads();
-  select_block(s_sc, a.T, s_idx, scratch);
+  select_block(s_sc, a.T, s_idx);
   if (writer && tid < a.T) a.idx[(size_t)u * a.T + tid] = s_idx[tid];
 }
 

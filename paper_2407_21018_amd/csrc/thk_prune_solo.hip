@@ -169,7 +169,7 @@ __device__ __forceinline__ bool read_group_sums(const PruneFusedArgs &a, int64_t
 // A row block's way from its column sums (s_part) to the unit's index list (s_idx).
 // item: u * NB + the block's number among the unit's row blocks.
 __device__ __forceinline__ int solo_index_list(const PruneFusedArgs &a, int64_t u, int64_t item, double *s_part,
-                                               float *s_sc, int16_t *s_idx, int *s_flag, uint32_t *scratch) {
+                                               float *s_sc, int16_t *s_idx, int *s_flag) {
   const int tid = threadIdx.x;
   if (tid < kD) pub_store_f64(a.partial + (size_t)item * kD + tid, s_part[tid]);
   block_stores_done();
@@ -199,14 +199,14 @@ __device__ __forceinline__ int solo_index_list(const PruneFusedArgs &a, int64_t 
     }
     double kss;
     if (!read_group_sums(a, u, s_part, s_flag, finisher ? kSurePolls : a.spin_limit, kss)) return kGaveUp;
-    score_and_select(a, u, qn_c, kss, s_sc, s_idx, scratch, finisher);
+    score_and_select(a, u, qn_c, kss, s_sc, s_idx, finisher);
     return finisher ? kFinisher : kHaveList;
   }
 
   if (arrive_tagged(a.tctr + u, a.nonce, a.NB, s_flag)) {
     const double qn_c = tid < kD ? pub_load_f64(a.qn + (size_t)u * kD + tid) : 0.0;
     const double kss = merge_partials(src, a.NB, s_part);   // s_part: its sums are published already
-    score_and_select(a, u, qn_c, kss, s_sc, s_idx, scratch, true);
+    score_and_select(a, u, qn_c, kss, s_sc, s_idx, true);
     if (tid < kWave) {
       const uint32_t lo = 2 * tid < a.T ? (uint16_t)s_idx[2 * tid] : 0u;
       const uint32_t hi = 2 * tid + 1 < a.T ? (uint16_t)s_idx[2 * tid + 1] : 0u;
@@ -224,7 +224,7 @@ __device__ __forceinline__ int solo_index_list(const PruneFusedArgs &a, int64_t 
 // means that the finisher will not look again -- and that the list is in place: the block then
 // fetches it after all (true) and goes on as usual.
 __device__ __forceinline__ bool hand_over_rows(const PruneFusedArgs &a, int64_t u, int64_t item, double *s_part,
-                                               float *s_sc, int16_t *s_idx, int *s_flag, uint32_t *scratch) {
+                                               float *s_sc, int16_t *s_idx, int *s_flag) {
   const int tid = threadIdx.x;
   if (tid == 0)
     __hip_atomic_store(a.undone + item, (unsigned char)1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -238,7 +238,7 @@ __device__ __forceinline__ bool hand_over_rows(const PruneFusedArgs &a, int64_t 
     const double qn_c = tid < kD ? pub_load_f64(a.qn + (size_t)u * kD + tid) : 0.0;
     double kss;
     read_group_sums(a, u, s_part, s_flag, kSurePolls, kss);
-    score_and_select(a, u, qn_c, kss, s_sc, s_idx, scratch, false);
+    score_and_select(a, u, qn_c, kss, s_sc, s_idx, false);
   } else {
     read_list_words(a, u, s_idx, s_flag, kSurePolls);
   }
@@ -291,7 +291,6 @@ void k_prune_solo(PruneFusedArgs a) {
   __shared__ double s_part[kD];
   __shared__ float s_sc[kD];
   __shared__ int16_t s_idx[kD];
-  __shared__ uint32_t s_scratch[2 * kD + 1];
   __shared__ int s_flag;
   const int tid = threadIdx.x, lane = tid % kWave;
   const int wave = tid / kWave;
@@ -368,9 +367,9 @@ void k_prune_solo(PruneFusedArgs a) {
   if (tid < kD) s_part[tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
   __syncthreads();
 
-  int st = solo_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch);
+  int st = solo_index_list(a, u, item, s_part, s_sc, s_idx, &s_flag);
   if (st == kGaveUp) {
-    if (!hand_over_rows(a, u, item, s_part, s_sc, s_idx, &s_flag, s_scratch)) return;
+    if (!hand_over_rows(a, u, item, s_part, s_sc, s_idx, &s_flag)) return;
     st = kHaveList;
   }
   const int n_gaveup = st == kFinisher ? close_unit(a, u, &s_flag) : 0;
