@@ -47,6 +47,8 @@ def parse():
                     help="skip the value-cache extension leg (value score, value prune, decode over both caches)")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the replay of the step from a HIP graph (graph_ms_per_step)")
+    ap.add_argument("--no-plain-streams", action="store_true",
+                    help="skip the plain read / copy kernels of the workload's own sizes (plain_streams: the ceilings)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference dispatches of known size "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -153,6 +155,47 @@ def value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k, v, kp, idx, dec, 
             "decode_kv_us_per_step": dec_us, "decode_kv_GBps": dec_bytes / dec_us / 1e3,
             "decode_kv_frac_of_hbm_peak": dec_bytes / dec_us / 1e3 / HBM_PEAK_GBS,
             "decode_kv_bytes_vs_k_only": (T + T_v) / (T + D)}
+
+
+def plain_streams(thk, torch, k_launch_bytes, T, D, decode_bytes, reps=6):
+    """What the chip gives kernels that only move the bytes of one prune launch and of one decode
+    launch (thk_bench_stream: plain read; copy with the rows held in registers and w / 32 = T / D
+    of them written, no exchange between blocks), on cold buffers, by events attached to the
+    launches like the library's own kernels: the ceilings at the workload's own size."""
+    dev = "cuda:0"
+    blk = 128 << 10
+    nb_copy = max(1, k_launch_bytes // blk)
+    w = max(1, min(32, round(32 * T / D)))
+    nb_read = max(1, -(-int(decode_bytes) // blk))
+    # windows of a buffer of at least 1.5 GiB, so that a window is cold when its turn comes again
+    nwin_r = max(1, min(16, -(-(3 << 29) // (nb_read * blk))))
+    nwin_c = max(1, min(16, -(-(3 << 29) // (nb_copy * blk))))
+    src = torch.empty(max(nb_read * nwin_r, nb_copy * nwin_c) * blk, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty(nb_copy * w * 4096 * nwin_c, dtype=torch.uint8, device=dev)
+
+    def run(mode, nb, nwin, wbytes):
+        us = []
+        for i in range(reps + 2):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); b.record()
+            k = i % nwin
+            thk.thk_profile_next(a, b)
+            thk.thk_bench_stream(mode, src[k * nb * blk:(k + 1) * nb * blk],
+                                 dst[k * wbytes:(k + 1) * wbytes] if mode == thk.THK_STREAM_COPY else None, nb, w)
+            torch.cuda.synchronize()
+            if i >= 2:
+                us.append(a.elapsed_time(b) * 1e3)
+        return us
+    r_us = run(thk.THK_STREAM_READ, nb_read, nwin_r, 0)
+    c_us = run(thk.THK_STREAM_COPY, nb_copy, nwin_c, nb_copy * w * 4096)
+    r_bytes, c_bytes = nb_read * blk, nb_copy * (blk + w * 4096)
+    del src, dst
+    torch.cuda.empty_cache()
+    mean = lambda x: sum(x) / len(x)
+    return {"kernel": "thk_bench_stream (plain kernels: no exchange, no arithmetic)", "launches_timed": reps,
+            "read": {"bytes": r_bytes, "us": mean(r_us), "best_us": min(r_us), "GBps": r_bytes / mean(r_us) / 1e3},
+            "copy": {"bytes": c_bytes, "written_fraction": w / 32, "us": mean(c_us), "best_us": min(c_us),
+                     "GBps": c_bytes / mean(c_us) / 1e3}}
 
 
 def measured_traffic(cfg_id, kernel):
@@ -386,6 +429,12 @@ def run_config(cfg_id, args, torch, thk, synth, full):
     del q_obs, k0, v0, ks, vs, kps, dec, score, idx, out, kt, vt, ws, pairs, used_pairs, kp_l, v_l, idx_l, kt_l, vt_l, out_l
     gc.collect()
     torch.cuda.empty_cache()
+    if not args.no_plain_streams:
+        ps = plain_streams(thk, torch, L * U * S * D * eb, T, D, decode_bytes)
+        ps["decode_kernel_vs_read"] = kernels[decode_kernel]["GBps"] / ps["read"]["GBps"]
+        if form == 2:
+            ps["prune_kernel_vs_copy"] = kernels[prune_kernel]["GBps"] / ps["copy"]["GBps"]
+        res["plain_streams"] = ps
     if full and not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg_id, cfg, T, dev)
     return res

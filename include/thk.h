@@ -387,6 +387,28 @@ thk_status thk_tail_flush(const thk_shape *shape, const int16_t *idx, void *k_pr
  */
 void thk_profile_next(void *ev_start, void *ev_stop);
 
+/*
+ * Benchmark aid, not part of the method: a kernel that does nothing but stream
+ * memory, so that a prune or decode call can be set against what the chip gives
+ * a plain read, copy or write of the SAME number of bytes (a launch of a few
+ * hundred MB pays its start and its end: the rate of a long stream is not its
+ * ceiling).  Each of the n_blocks blocks owns 128 KiB of `src` and w * 4 KiB of
+ * `dst` (16 bytes per thread and access, non-temporal like the library's own
+ * streams, all of a block's loads in flight at once):
+ *   THK_STREAM_READ   reads src (n_blocks * 128 KiB); dst may be NULL, w is ignored
+ *   THK_STREAM_COPY   reads src, keeps the block's bytes in registers, then writes
+ *                     the first w / 32 of them to dst -- the traffic of a prune
+ *                     block with w / 32 = T / D, without the exchange between blocks
+ *   THK_STREAM_WRITE  writes dst (n_blocks * w * 4 KiB); src may be NULL
+ * src, dst: device pointers, 16-byte aligned, owned by the caller, at least
+ * the sizes above; 1 <= n_blocks <= 2^31 - 1, 0 <= w <= 32 (1 <= w for COPY and
+ * WRITE).  THK_ERR_NULL / THK_ERR_ALIGN / THK_ERR_SHAPE on misuse (nothing is
+ * enqueued then), THK_ERR_HIP if the launch fails.  Enqueues one kernel on `stream`;
+ * thk_profile_next applies to it.
+ */
+enum { THK_STREAM_READ = 0, THK_STREAM_COPY = 1, THK_STREAM_WRITE = 2 };
+thk_status thk_bench_stream(int32_t mode, const void *src, void *dst, int64_t n_blocks, int32_t w, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

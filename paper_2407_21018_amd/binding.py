@@ -98,6 +98,8 @@ def load():
     L.thk_cache_append.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp]
     L.thk_tail_flush.restype = ctypes.c_int
     L.thk_tail_flush.argtypes = [sp, vp, vp, vp, vp, vp, i32, i32, i32, vp]
+    L.thk_bench_stream.restype = ctypes.c_int
+    L.thk_bench_stream.argtypes = [i32, vp, vp, ctypes.c_int64, i32, vp]
     L.thk_profile_next.restype = None
     L.thk_profile_next.argtypes = [vp, vp]
     L.thk_tail_append.restype = ctypes.c_int
@@ -382,6 +384,19 @@ def thk_tail_flush(shape, idx, k_pruned, k_tail, v, v_tail, s_tail, s_tail_cap, 
     _need(v_tail, U * s_tail_cap * shape.D, "v_tail", "thk_tail_flush")
     _check(load().thk_tail_flush(ctypes.byref(shape), _ptr(idx), _ptr(k_pruned), _ptr(k_tail), _ptr(v),
                                  _ptr(v_tail), s_tail, s_tail_cap, n_flush, _stream(stream)), "thk_tail_flush")
+
+
+THK_STREAM_READ, THK_STREAM_COPY, THK_STREAM_WRITE = 0, 1, 2
+
+
+def thk_bench_stream(mode, src, dst, n_blocks, w, stream=None):
+    """Plain read / copy / write stream for benchmarks: n_blocks blocks of 128 KiB of src and
+    w * 4 KiB of dst each (src or dst may be None where the mode does not use it)."""
+    if src is not None:
+        _need(src, n_blocks * 131072 // src.element_size(), "src", "thk_bench_stream")
+    if dst is not None and mode != THK_STREAM_READ:
+        _need(dst, n_blocks * w * 4096 // dst.element_size(), "dst", "thk_bench_stream")
+    _check(load().thk_bench_stream(mode, _ptr(src), _ptr(dst), n_blocks, w, _stream(stream)), "thk_bench_stream")
 
 
 def thk_profile_next(ev_start, ev_stop):

@@ -329,6 +329,17 @@ void thk_profile_next(void *ev_start, void *ev_stop) {
   g_prof_stop = (ev_start != nullptr && ev_stop != nullptr) ? (hipEvent_t)ev_stop : nullptr;
 }
 
+thk_status thk_bench_stream(int32_t mode, const void *src, void *dst, int64_t n_blocks, int32_t w, void *stream) {
+  if (mode < THK_STREAM_READ || mode > THK_STREAM_WRITE) return THK_ERR_SHAPE;
+  if (n_blocks < 1 || n_blocks > 2147483647LL || w < 0 || w > 32) return THK_ERR_SHAPE;
+  if (mode != THK_STREAM_READ && w < 1) return THK_ERR_SHAPE;
+  if (mode != THK_STREAM_WRITE && src == nullptr) return THK_ERR_NULL;
+  if (mode != THK_STREAM_READ && dst == nullptr) return THK_ERR_NULL;
+  if (!aligned16(src) || !aligned16(dst)) return THK_ERR_ALIGN;
+  clear_stale_hip_error();
+  return failed(launch_bench_stream(mode, src, dst, n_blocks, w, (hipStream_t)stream)) ? THK_ERR_HIP : THK_OK;
+}
+
 const char *thk_last_hip_error(void) { return hipGetErrorString(g_last_hip); }
 
 const char *thk_status_string(thk_status st) {

@@ -231,6 +231,9 @@ hipError_t launch_tail_append(int dtype, const void *k_new, const void *v_new, v
                               int64_t U, int64_t k_unit_rows, int64_t k_row, int64_t v_unit_rows,
                               int64_t v_row, hipStream_t st);
 
+// ---- plain read / copy / write streams for benchmarks (thk_bench_stream.hip) ----
+hipError_t launch_bench_stream(int mode, const void *src, void *dst, int64_t n_blocks, int w, hipStream_t st);
+
 // ---- value-channel score (Appendix "Value Cache Pruning") ----
 struct ValueAttnArgs {
   const void *q_obs, *k, *v;

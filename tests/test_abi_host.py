@@ -357,3 +357,16 @@ def test_environment_switches_are_read_once_and_on_reload(monkeypatch):
     assert thk.thk_prune_is_fused(cfg2) == 0
     thk.thk_reload_env()
     assert thk.thk_prune_is_fused(cfg2) == 2 and thk.thk_decode_on_matrix_cores(gqa) == 1
+
+
+def test_bench_stream_rejects_misuse():
+    """The benchmark stream kernel checks its arguments on the host: nothing is launched on a bad
+    mode, block count, width, missing buffer or misaligned pointer."""
+    L = thk.load()
+    st = lambda mode, src, dst, n, w: L.thk_bench_stream(mode, src, dst, n, w, None)
+    assert st(3, A, A, 1, 1) == 2 and st(-1, A, A, 1, 1) == 2                    # mode
+    assert st(thk.THK_STREAM_COPY, A, A, 0, 1) == 2 and st(thk.THK_STREAM_COPY, A, A, 1 << 31, 1) == 2
+    assert st(thk.THK_STREAM_COPY, A, A, 1, 0) == 2 and st(thk.THK_STREAM_WRITE, None, A, 1, 33) == 2
+    assert st(thk.THK_STREAM_READ, None, None, 1, 0) == 1                          # src missing
+    assert st(thk.THK_STREAM_COPY, A, None, 1, 4) == 1 and st(thk.THK_STREAM_WRITE, None, None, 1, 4) == 1
+    assert st(thk.THK_STREAM_READ, A + 8, None, 1, 0) == 4 and st(thk.THK_STREAM_COPY, A, A + 4, 1, 4) == 4
