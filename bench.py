@@ -18,6 +18,11 @@ Bytes.  `value` and every fraction are computed from the bytes the path has to m
                     `*_metric_def`, as a rate only -- the one-pass kernel moves fewer bytes than
                     that, so a fraction of the HBM peak computed from it could exceed 1;
   decode per step   U * e * [S * (T + D) + s_tail * 2 D].
+
+Ceilings.  `plain_streams` (every workload) times the library's plain read and copy kernels
+(thk_bench_stream) on cold buffers of the workload's own sizes -- a read of the bytes of one decode
+launch, a copy with the traffic of one prune launch -- and gives the library's kernels' rates as
+fractions of those: what the chip grants a launch of that size, beside the 8 TB/s peak.
 """
 import argparse
 import gc
@@ -477,7 +482,7 @@ def main():
         "per_config": per_config,
         "device": device_facts(torch),
     }
-    for key in ("value_cache", "cpu_baseline"):
+    for key in ("plain_streams", "value_cache", "cpu_baseline"):
         if key in head:
             res[key] = head[key]
     print(json.dumps(res))
