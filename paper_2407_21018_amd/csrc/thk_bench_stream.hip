@@ -6,7 +6,7 @@
 // A block of 256 threads owns 128 KiB of the source (32 chunks of 16 bytes per thread, all
 // loads in flight at once, non-temporal like the library's own streams) and w x 4 KiB of the
 // destination (w chunks per thread, non-temporal stores):
-//   read   the chunks are folded into one word that is stored only if it has an impossible value
+//   read   the chunks are folded into one value that the compiler must produce; nothing is stored
 //   copy   the block keeps its 32 chunks in registers and then stores the first w of them -- the
 //          traffic of a prune block (w / 32 = T / 128) without any exchange between blocks
 //   write  w chunks per thread of a constant
@@ -16,6 +16,11 @@ namespace thk {
 namespace {
 
 constexpr int kProbeChunks = 32;   // 16-byte chunks per thread = 128 KiB per block
+
+// The value has to exist in registers here: the loads it was folded from cannot be dropped.
+__device__ __forceinline__ void keep_alive(const u32x4 &x) {
+  asm volatile("" ::"v"(x.x), "v"(x.y), "v"(x.z), "v"(x.w));
+}
 
 template <int MODE>   // 0 read, 1 copy, 2 write
 __global__ __launch_bounds__(256) void k_bench_stream(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int w) {
@@ -30,18 +35,16 @@ __global__ __launch_bounds__(256) void k_bench_stream(const u32x4 *__restrict__ 
     u32x4 x = r[0];
 #pragma unroll
     for (int j = 1; j < kProbeChunks; ++j) x ^= r[j];
-    // keeps the loads alive; the bytes of a probe buffer never fold to this value in practice,
-    // and a stray store of one word into the caller's own buffer would be harmless
-    if ((x.x ^ x.y ^ x.z ^ x.w) == 0x9e3779b9u && dst != nullptr) ((uint32_t *)dst)[b] = x.x;
+    keep_alive(x);
   } else {
     u32x4 *q = dst + b * ((size_t)w * 256) + threadIdx.x;
     if constexpr (MODE == 1) {
       // every chunk is really read, also those that are not written (a prune block reads whole
-      // rows): they are folded into a word that is stored only if it has an impossible value
+      // rows): they are folded into a value the compiler must produce
       u32x4 x = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (int j = 0; j < kProbeChunks; ++j) x ^= r[j];
-      if ((x.x ^ x.y ^ x.z ^ x.w) == 0x9e3779b9u) ((uint32_t *)dst)[b] = x.x;
+      keep_alive(x);
     }
 #pragma unroll
     for (int j = 0; j < kProbeChunks; ++j) {
