@@ -29,7 +29,10 @@
  *   - Built for one card: gfx950 code only, and the launch heuristics (default splits,
  *     block sizes of the prune, its graded start) assume an MI355X in SPX mode -- 256
  *     compute units at about 2.4 GHz behind one device, 8 TB/s of HBM.  On another
- *     partitioning the results are the same and the launch shapes are merely not tuned.
+ *     partitioning the results are the same and the launch shapes are merely not tuned;
+ *     the one rule that safety rests on -- thk_prune keeps a unit's rows on chip only if all
+ *     of the unit's row blocks can be resident at once, because they wait for each other --
+ *     uses the compute-unit count the current device reports (every wait is bounded besides).
  *   - The THK_* environment switches named below are for experiments and tests.  They
  *     are read once per process, on the first call that needs them; thk_reload_env()
  *     reads them again.

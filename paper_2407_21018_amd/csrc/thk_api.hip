@@ -79,6 +79,30 @@ inline bool failed(hipError_t e) {
 }
 
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// Compute units of the current device, looked up once per device: 256 on the MI355X the launch
+// heuristics are fitted to, fewer on a partitioned one; 256 where no device answers (the planning
+// functions are also called by hosts without a GPU).  Only the rule that decides whether a unit's
+// row blocks can all be resident at once -- a matter of safety of the one-pass prune, whose
+// blocks wait for each other -- uses it; the tuning constants stay those of the 256-unit chip.
+int device_cus() {
+  constexpr int kMaxDev = 64;
+  static std::atomic<int> cache[kMaxDev];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) {
+    (void)hipGetLastError();
+    return kCUs;
+  }
+  int n = cache[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+      (void)hipGetLastError();
+      n = kCUs;
+    }
+    cache[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
 inline int elem_bytes(int dtype) { return dtype == THK_BF16 ? 2 : 4; }
 inline int64_t units_of(const thk_shape *s) { return (int64_t)s->L * s->B * s->N_kv; }
 inline int ld_of(const thk_shape *s) { return s->ld_keep ? s->ld_keep : s->T; }
@@ -258,7 +282,7 @@ FusedPlan fused_plan(const thk_shape *s) {
   // the rows are read twice (the second read wants the unit's rows still in the memory-side cache)
   // (LDS decides: 2 KB + four tiles + 7 KB per block, i.e. three bf16 blocks or two fp32 blocks
   // per compute unit)
-  const long fit = p.hold == 0 ? 256L : (s->dtype == THK_BF16 ? 3L : 2L) * kCUs;
+  const long fit = p.hold == 0 ? 256L : (s->dtype == THK_BF16 ? 3L : 2L) * std::min(device_cus(), kCUs);
   const bool forced = path == 'f' || path == 'r';   // regardless of the env limit
   if (nb > (forced || env.max_blocks < 0 ? fit : std::min(fit, env.max_blocks))) return p;
   p.RB = rb;
