@@ -157,7 +157,7 @@ def value_cache_leg(thk, torch, cfg, T, tdt, dt, eb, q_obs, k, v, kp, idx, dec, 
             "score_TFLOPs": score_flops / score_us / 1e6,
             "prune_value_ms_per_layer": prune_ms_layer, "prune_value_GBps": prune_v_bytes / L / prune_ms_layer / 1e6,
             "prune_value_frac_of_hbm_peak": prune_v_bytes / L / prune_ms_layer / 1e6 / HBM_PEAK_GBS,
-            "decode_kv_us_per_step": dec_us, "decode_kv_GBps": dec_bytes / dec_us / 1e3,
+            "decode_kv_us_per_step": dec_us, "decode_kv_bytes": dec_bytes, "decode_kv_GBps": dec_bytes / dec_us / 1e3,
             "decode_kv_frac_of_hbm_peak": dec_bytes / dec_us / 1e3 / HBM_PEAK_GBS,
             "decode_kv_bytes_vs_k_only": (T + T_v) / (T + D)}
 
@@ -201,6 +201,28 @@ def plain_streams(thk, torch, k_launch_bytes, T, D, decode_bytes, reps=6):
             "read": {"bytes": r_bytes, "us": mean(r_us), "best_us": min(r_us), "GBps": r_bytes / mean(r_us) / 1e3},
             "copy": {"bytes": c_bytes, "written_fraction": w / 32, "us": mean(c_us), "best_us": min(c_us),
                      "GBps": c_bytes / mean(c_us) / 1e3}}
+
+
+def plain_read_us(thk, torch, nbytes, reps=6):
+    """Mean and best duration (us) of a plain read (thk_bench_stream) of nbytes, on cold windows
+    of a buffer of at least 1.5 GiB, by events attached to the launches."""
+    blk = 128 << 10
+    nb = max(1, -(-int(nbytes) // blk))
+    nwin = max(1, min(16, -(-(3 << 29) // (nb * blk))))
+    src = torch.empty(nb * nwin * blk, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    us = []
+    for i in range(reps + 2):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); b.record()
+        k = i % nwin
+        thk.thk_profile_next(a, b)
+        thk.thk_bench_stream(thk.THK_STREAM_READ, src[k * nb * blk:(k + 1) * nb * blk], None, nb, 1)
+        torch.cuda.synchronize()
+        if i >= 2:
+            us.append(a.elapsed_time(b) * 1e3)
+    del src
+    torch.cuda.empty_cache()
+    return sum(us) / len(us), min(us)
 
 
 def measured_traffic(cfg_id, kernel):
@@ -440,6 +462,12 @@ def run_config(cfg_id, args, torch, thk, synth, full):
         if form == 2:
             ps["prune_kernel_vs_copy"] = kernels[prune_kernel]["GBps"] / ps["copy"]["GBps"]
         res["plain_streams"] = ps
+        if "value_cache" in res:
+            # the decode step over both pruned caches moves fewer bytes per launch: its own ceiling
+            vc = res["value_cache"]
+            r_us, r_best = plain_read_us(thk, torch, vc["decode_kv_bytes"])
+            vc["decode_kv_plain_read_us"] = r_us
+            vc["decode_kv_call_vs_read"] = r_us / vc["decode_kv_us_per_step"]
     if full and not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg_id, cfg, T, dev)
     return res

@@ -149,12 +149,19 @@ struct TileState {
 // A lane's view of a tile of channel-pruned value rows staged in its wave's LDS slab: rows are
 // ld elements apart, groups of 4 kept channels go to lanes (col), and rpw rows are handled per
 // step (rsub = this lane's row within a step).
+constexpr int kPsPad = 32;   // zero rows behind a wave's probabilities (channel-pruned values only)
+
 struct VPruned {
   char *vbuf;
   int shift;        // bytes from the slab start to the tile's first row
   int ld;
   int rpw, rsub, col;
   bool active;
+  // the wave's next tile of value rows: its loads are issued as soon as the current tile's bytes
+  // have left the registers for LDS (nx_rows = 0: there is none)
+  const char *vsrc;
+  size_t nx_beg;
+  int nx_rows, nx_shift, T_v;
 };
 
 // Issue the global loads of a tile of `nrows` rows, W elements wide with row
@@ -234,7 +241,7 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
                                              const u32x4 *__restrict__ vg,
                                              u32x4 (&vr)[NV], const char *kbuf,
                                              float *ps, TileState<DT, GT> &st, double scale_d, int lane,
-                                             const u32x4 (*vrp)[KBV] = nullptr, const VPruned *vp = nullptr) {
+                                             u32x4 (*vrp)[KBV] = nullptr, VPruned *vp = nullptr) {
   using E = Elem<DT>;
   using ZT = typename LogitType<DT>::type;   // accumulator of a logit: float (bf16 inputs), double (fp32 inputs)
   const ZT scale = (ZT)scale_d;
@@ -339,19 +346,23 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
   if constexpr (PV == 1) {
     // ---- accp += p . V_pruned: value bytes to LDS, then 4 kept channels per lane ----------
     k_commit<KBV>(*vrp, vp->vbuf, lane);
+    if (vp->nx_rows > 0)
+      vp->nx_shift = k_issue<DT, KBV>(*vrp, vp->vsrc, vp->nx_beg, vp->nx_rows, vp->T_v, vp->ld, lane);
     wave_sync_lds();
-    // Rows r0 + rsub, r0 = 0, rpw, 2 rpw, ...; four steps are read before they are used.  A row
-    // past the tile's end is read as the tile's last row with weight 0, so nothing branches.
-    const char *vbase = vp->vbuf + vp->shift + (size_t)vp->col * 4 * EB;
+    // Rows r0 + rsub, r0 = 0, rpw, 2 rpw, ...; four steps are read before they are used.  Nothing
+    // branches: a row past the tile's end takes the bytes of the tile's last row and a weight of 0
+    // -- rows nrows .. TR - 1 of ps were written as 0 above, and rows TR .. TR + kPsPad - 1 are
+    // zero for the whole kernel (four steps of at most 8 rows may start at row nrows - 1).
     const int rowb = vp->ld * EB;
+    const int vstep = vp->rpw * rowb, pstep = vp->rpw * GT;
+    int voff = vp->shift + vp->col * 4 * EB + vp->rsub * rowb;
+    const int vlast = vp->shift + vp->col * 4 * EB + (nrows - 1) * rowb;
+    const float *pp = ps + vp->rsub * GT;
     for (int r0 = 0; r0 < nrows; r0 += 4 * vp->rpw) {
       float f[4][4], pg[4][GT];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int row = r0 + i * vp->rpw + vp->rsub;
-        const bool live = row < nrows;
-        const int rr = live ? row : nrows - 1;
-        const char *vrow = vbase + rr * rowb;
+        const char *vrow = vp->vbuf + min(voff, vlast);
         if constexpr (DT == THK_BF16) {
           const uint2 w = *(const uint2 *)vrow;
           f[i][0] = __uint_as_float(w.x << 16); f[i][1] = __uint_as_float(w.x & 0xffff0000u);
@@ -360,8 +371,18 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
           const float4 w = *(const float4 *)vrow;
           f[i][0] = w.x; f[i][1] = w.y; f[i][2] = w.z; f[i][3] = w.w;
         }
+        if constexpr (GT == 4) {
+          const float4 t4 = *(const float4 *)pp;
+          pg[i][0] = t4.x; pg[i][1] = t4.y; pg[i][2] = t4.z; pg[i][3] = t4.w;
+        } else if constexpr (GT == 2) {
+          const float2 t2 = *(const float2 *)pp;
+          pg[i][0] = t2.x; pg[i][1] = t2.y;
+        } else {
 #pragma unroll
-        for (int g = 0; g < GT; ++g) pg[i][g] = live ? ps[rr * GT + g] : 0.f;
+          for (int g = 0; g < GT; ++g) pg[i][g] = pp[g];
+        }
+        voff += vstep;
+        pp += pstep;
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -536,19 +557,24 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   char *wbase = (char *)(mrg + 4 * GT * (kD + 2));
   __shared__ int s_last;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-  const int wstride = kbuf_bytes + GT * TR * 4;
+  const int wstride = kbuf_bytes + GT * (TR + (VP ? kPsPad : 0)) * 4;
   char *kbuf = wbase + (size_t)wave * wstride;
   float *ps = (float *)(kbuf + kbuf_bytes);
   VPruned vpd;
   vpd.vbuf = kbuf;   // the key bytes of a tile are consumed before its value bytes are staged
   vpd.shift = 0;
   vpd.ld = a.ld_v;
+  vpd.vsrc = (const char *)a.v;
+  vpd.T_v = a.T_v;
+  vpd.nx_beg = 0;
+  vpd.nx_rows = 0;
+  vpd.nx_shift = 0;
   {
     const int lprv = VP ? (a.T_v + 3) / 4 : 1;          // lanes per value row, <= 32
     vpd.rpw = min(kWave / lprv, 8);
-    vpd.rsub = lane / lprv;
     vpd.col = lane % lprv;
-    vpd.active = vpd.rsub < vpd.rpw;
+    vpd.active = lane / lprv < vpd.rpw;
+    vpd.rsub = vpd.active ? lane / lprv : 0;   // idle lanes repeat row group 0; their sums are dropped
   }
 
   const int sp = (int)(blockIdx.x % a.n_split);
@@ -560,6 +586,18 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   // the unit's last block may have fewer than GT heads left: the other slots carry a zero query
   // (their logits are 0, their output is never stored)
   const int hb = min(GT, G - gi * GT);
+
+  // channel-pruned values: the channel numbers of this lane's four sums are fetched now and used
+  // after the last tile (a fetch there would add its round trips to the end of every block)
+  int cv[4] = {0, 0, 0, 0};
+  if constexpr (VP) {
+    const int16_t *uidv = a.idx_v + (size_t)u * a.T_v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int t = vpd.col * 4 + e;
+      cv[e] = t < a.T_v ? uidv[t] : -1;
+    }
+  }
 
   const int64_t s0 = min(a.S, (int64_t)sp * a.rows_per_split);
   const int64_t s1 = min(a.S, s0 + a.rows_per_split);
@@ -607,6 +645,9 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
       qkp[o] = k0 | (k1 << 16);
     }
   }
+  if constexpr (VP) {
+    for (int o = lane; o < GT * kPsPad; o += kWave) ps[GT * TR + o] = 0.f;
+  }
   __syncthreads();
 
   TileState<DT, GT> st;
@@ -626,22 +667,22 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     const u32x4 *vg = vbase + (size_t)ti * TR * LPR;
     const int shift = shift_next;
     k_commit<KB>(kr, kbuf, lane);
-    if (ti != wave) {
-      if constexpr (VP)
-        vpd.shift = k_issue<DT, KB>(vrp, (const char *)a.v, (krow0 + (size_t)ti * TR) * a.ld_v * EB, nrows,
-                                    a.T_v, a.ld_v, lane);
-      else
-        v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
+    if constexpr (!VP) {
+      if (ti != wave) v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
     }
+    vpd.nx_rows = 0;
     if (ti + 4 < nt_p) {
       const int nr = (int)min((int64_t)TR, s1 - s0 - (int64_t)(ti + 4) * TR);
       shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)(ti + 4) * TR) * a.ldk * EB, nr, a.T, a.ldk, lane);
+      vpd.nx_rows = nr;
+      vpd.nx_beg = (krow0 + (size_t)(ti + 4) * TR) * a.ld_v * EB;
     }
     wave_sync_lds();
-    if constexpr (VP)
+    if constexpr (VP) {
       tile_compute<DT, GT, RA, TR, NV, 1, KB>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st,
                                               a.scale_log2_d, lane, &vrp, &vpd);
-    else
+      vpd.shift = vpd.nx_shift;
+    } else
       tile_compute<DT, GT, RA, TR, NV>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st, a.scale_log2_d, lane);
   }
 
@@ -678,17 +719,14 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   }
   if constexpr (VP) {
     // the sums over the pruned rows go to their channels, one row-within-step group at a time
-    const int16_t *uidv = a.idx_v + (size_t)u * a.T_v;
     for (int rs = 0; rs < vpd.rpw; ++rs) {
       wave_sync_lds();
       if (vpd.active && vpd.rsub == rs) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int t = vpd.col * 4 + e;
-          if (t < a.T_v) {
-            const int c = uidv[t];
+          if (cv[e] >= 0) {
 #pragma unroll
-            for (int g = 0; g < GT; ++g) mrg[(size_t)(wave * GT + g) * (kD + 2) + 2 + c] += st.accp[g][e];
+            for (int g = 0; g < GT; ++g) mrg[(size_t)(wave * GT + g) * (kD + 2) + 2 + cv[e]] += st.accp[g][e];
           }
         }
       }
@@ -724,7 +762,7 @@ inline hipError_t decode_launch_one(const DecodeArgs &a, int groups, hipStream_t
   int kbuf = KB * kWave * 16;                      // every staged chunk has an LDS slot
   const int tailbuf = kTailRows * kD * eb;
   if (kbuf < tailbuf) kbuf = tailbuf;
-  const size_t lds = (size_t)(3 * GT * kQS + 4 * GT * (kD + 2)) * 4 + 4 * ((size_t)kbuf + GT * TR * 4);
+  const size_t lds = (size_t)(3 * GT * kQS + 4 * GT * (kD + 2)) * 4 + 4 * ((size_t)kbuf + GT * (TR + (VP ? kPsPad : 0)) * 4);
   const dim3 grid((unsigned)(a.units * groups * a.n_split)), block(256);
   {
     static DynLds set;   // one per instantiation
