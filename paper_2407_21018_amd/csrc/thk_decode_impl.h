@@ -263,20 +263,34 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
 #pragma unroll
   for (int g = 0; g < GT; ++g) z[g] = (ZT)0;
   if constexpr (DT == THK_BF16 && RA >= 4) {
-    // bf16 pairs straight from LDS into v_dot2c_f32_bf16: products are exact, sums in fp32
+    // bf16 pairs straight from LDS into v_dot2c_f32_bf16: products are exact, sums in fp32.
+    // Keys and packed query share their byte offsets (two bytes per channel), so one offset
+    // walks both; the steps that every lane has run without a test, and where share 0 has one
+    // granule more, the lanes of share 1 take granule 0 against the zero slot of q in that step.
     constexpr int DW = RA / 4;   // words per granule
+    const int common = LPK == 1 ? gran0 : n_gran - gran0;
+    const char *kw_p = rowp + my_first * RA;
+    const char *qw_p = (const char *)qp + my_first * RA;
 #pragma unroll 2
-    for (int i = 0; i < gran0; ++i) {
-      // a lane whose share is exhausted re-reads granule 0 against the zero slot of q
-      const bool valid = (LPK == 1) || i < my_cnt;
-      const int tk = valid ? (my_first + i) * EPR : 0;
-      const int tq = valid ? tk : kD;
+    for (int i = 0; i < common; ++i) {
       uint32_t kw[DW];
-      lds_words<DW>(rowp + (size_t)tk * EB, kw);
+      lds_words<DW>(kw_p + i * RA, kw);
 #pragma unroll
       for (int g = 0; g < GT; ++g) {
         uint32_t qw[DW];
-        lds_words<DW>((const char *)(qp + g * (kQS / 2) + tq / 2), qw);
+        lds_words<DW>(qw_p + g * (kQS * 2) + i * RA, qw);
+#pragma unroll
+        for (int d = 0; d < DW; ++d) z[g] = dot2_bf16(kw[d], qw[d], z[g]);
+      }
+    }
+    if (LPK == 2 && common < gran0) {
+      uint32_t kw[DW];
+      lds_words<DW>(rowp + (h == 0 ? common * RA : 0), kw);
+      const char *qz = (const char *)qp + (h == 0 ? common * RA : kD * 2);
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        uint32_t qw[DW];
+        lds_words<DW>(qz + g * (kQS * 2), qw);
 #pragma unroll
         for (int d = 0; d < DW; ++d) z[g] = dot2_bf16(kw[d], qw[d], z[g]);
       }
