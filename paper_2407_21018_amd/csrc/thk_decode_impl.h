@@ -157,11 +157,6 @@ struct VPruned {
   int ld;
   int rpw, rsub, col;
   bool active;
-  // the wave's next tile of value rows: its loads are issued as soon as the current tile's bytes
-  // have left the registers for LDS (nx_rows = 0: there is none)
-  const char *vsrc;
-  size_t nx_beg;
-  int nx_rows, nx_shift, T_v;
 };
 
 // Issue the global loads of a tile of `nrows` rows, W elements wide with row
@@ -241,7 +236,7 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
                                              const u32x4 *__restrict__ vg,
                                              u32x4 (&vr)[NV], const char *kbuf,
                                              float *ps, TileState<DT, GT> &st, double scale_d, int lane,
-                                             u32x4 (*vrp)[KBV] = nullptr, VPruned *vp = nullptr) {
+                                             const u32x4 (*vrp)[KBV] = nullptr, const VPruned *vp = nullptr) {
   using E = Elem<DT>;
   using ZT = typename LogitType<DT>::type;   // accumulator of a logit: float (bf16 inputs), double (fp32 inputs)
   const ZT scale = (ZT)scale_d;
@@ -360,22 +355,21 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
   if constexpr (PV == 1) {
     // ---- accp += p . V_pruned: value bytes to LDS, then 4 kept channels per lane ----------
     k_commit<KBV>(*vrp, vp->vbuf, lane);
-    if (vp->nx_rows > 0)
-      vp->nx_shift = k_issue<DT, KBV>(*vrp, vp->vsrc, vp->nx_beg, vp->nx_rows, vp->T_v, vp->ld, lane);
     wave_sync_lds();
-    // Rows r0 + rsub, r0 = 0, rpw, 2 rpw, ...; four steps are read before they are used.  Nothing
+    // Rows r0 + rsub, r0 = 0, rpw, 2 rpw, ...; NS steps are read before they are used.  Nothing
     // branches: a row past the tile's end takes the bytes of the tile's last row and a weight of 0
     // -- rows nrows .. TR - 1 of ps were written as 0 above, and rows TR .. TR + kPsPad - 1 are
     // zero for the whole kernel (four steps of at most 8 rows may start at row nrows - 1).
+    constexpr int NS = GT == 1 ? 4 : 2;   // steps read before they are used (registers)
     const int rowb = vp->ld * EB;
     const int vstep = vp->rpw * rowb, pstep = vp->rpw * GT;
     int voff = vp->shift + vp->col * 4 * EB + vp->rsub * rowb;
     const int vlast = vp->shift + vp->col * 4 * EB + (nrows - 1) * rowb;
     const float *pp = ps + vp->rsub * GT;
-    for (int r0 = 0; r0 < nrows; r0 += 4 * vp->rpw) {
-      float f[4][4], pg[4][GT];
+    for (int r0 = 0; r0 < nrows; r0 += NS * vp->rpw) {
+      float f[NS][4], pg[NS][GT];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NS; ++i) {
         const char *vrow = vp->vbuf + min(voff, vlast);
         if constexpr (DT == THK_BF16) {
           const uint2 w = *(const uint2 *)vrow;
@@ -399,7 +393,7 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
         pp += pstep;
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < NS; ++i)
 #pragma unroll
         for (int g = 0; g < GT; ++g)
 #pragma unroll
@@ -578,11 +572,6 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   vpd.vbuf = kbuf;   // the key bytes of a tile are consumed before its value bytes are staged
   vpd.shift = 0;
   vpd.ld = a.ld_v;
-  vpd.vsrc = (const char *)a.v;
-  vpd.T_v = a.T_v;
-  vpd.nx_beg = 0;
-  vpd.nx_rows = 0;
-  vpd.nx_shift = 0;
   {
     const int lprv = VP ? (a.T_v + 3) / 4 : 1;          // lanes per value row, <= 32
     vpd.rpw = min(kWave / lprv, 8);
@@ -600,18 +589,6 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   // the unit's last block may have fewer than GT heads left: the other slots carry a zero query
   // (their logits are 0, their output is never stored)
   const int hb = min(GT, G - gi * GT);
-
-  // channel-pruned values: the channel numbers of this lane's four sums are fetched now and used
-  // after the last tile (a fetch there would add its round trips to the end of every block)
-  int cv[4] = {0, 0, 0, 0};
-  if constexpr (VP) {
-    const int16_t *uidv = a.idx_v + (size_t)u * a.T_v;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int t = vpd.col * 4 + e;
-      cv[e] = t < a.T_v ? uidv[t] : -1;
-    }
-  }
 
   const int64_t s0 = min(a.S, (int64_t)sp * a.rows_per_split);
   const int64_t s1 = min(a.S, s0 + a.rows_per_split);
@@ -681,22 +658,22 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
     const u32x4 *vg = vbase + (size_t)ti * TR * LPR;
     const int shift = shift_next;
     k_commit<KB>(kr, kbuf, lane);
-    if constexpr (!VP) {
-      if (ti != wave) v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
+    if (ti != wave) {
+      if constexpr (VP)
+        vpd.shift = k_issue<DT, KB>(vrp, (const char *)a.v, (krow0 + (size_t)ti * TR) * a.ld_v * EB, nrows,
+                                    a.T_v, a.ld_v, lane);
+      else
+        v_issue<DT, TR, NV>(vr, vg, nrows, 0, lane);
     }
-    vpd.nx_rows = 0;
     if (ti + 4 < nt_p) {
       const int nr = (int)min((int64_t)TR, s1 - s0 - (int64_t)(ti + 4) * TR);
       shift_next = k_issue<DT, KB>(kr, kpg, (krow0 + (size_t)(ti + 4) * TR) * a.ldk * EB, nr, a.T, a.ldk, lane);
-      vpd.nx_rows = nr;
-      vpd.nx_beg = (krow0 + (size_t)(ti + 4) * TR) * a.ld_v * EB;
     }
     wave_sync_lds();
-    if constexpr (VP) {
+    if constexpr (VP)
       tile_compute<DT, GT, RA, TR, NV, 1, KB>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st,
                                               a.scale_log2_d, lane, &vrp, &vpd);
-      vpd.shift = vpd.nx_shift;
-    } else
+    else
       tile_compute<DT, GT, RA, TR, NV>(shift, nrows, a.T, a.ldk, qk, qkp, vg, vr, kbuf, ps, st, a.scale_log2_d, lane);
   }
 
@@ -733,6 +710,13 @@ __global__ __launch_bounds__(256, WPE) void k_decode(DecodeArgs a, int groups, i
   }
   if constexpr (VP) {
     // the sums over the pruned rows go to their channels, one row-within-step group at a time
+    const int16_t *uidv = a.idx_v + (size_t)u * a.T_v;
+    int cv[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int t = vpd.col * 4 + e;
+      cv[e] = t < a.T_v ? uidv[t] : -1;
+    }
     for (int rs = 0; rs < vpd.rpw; ++rs) {
       wave_sync_lds();
       if (vpd.active && vpd.rsub == rs) {
