@@ -266,7 +266,8 @@ __device__ __forceinline__ void tile_compute(int shift, int nrows, int W, int ld
     const int common = LPK == 1 ? gran0 : n_gran - gran0;
     const char *kw_p = rowp + my_first * RA;
     const char *qw_p = (const char *)qp + my_first * RA;
-#pragma unroll 2
+    constexpr int UNR = (GT == 4 && DW == 2) ? 1 : 2;   // the one shape that ran out of registers at 2
+#pragma unroll UNR
     for (int i = 0; i < common; ++i) {
       uint32_t kw[DW];
       lds_words<DW>(kw_p + i * RA, kw);
