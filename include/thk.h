@@ -193,7 +193,12 @@ thk_status thk_score_value(const thk_shape *shape, const void *q_obs, const void
  * thk_score_value + thk_select_topk + thk_compact_keys applied to V in one call.
  * The shape's T, ld_keep, S_recent and S_cap describe the pruned VALUE cache here
  * (T = channels kept, the paper's T for I_i = Top_T(Score_v, T)).  `score_v` may
- * be NULL (then it lives in ws).
+ * be NULL (then it lives in ws).  Calls of at least 16 rounds of resident blocks
+ * (12288 blocks of 512 bf16 rows) compact V with the kernels of thk_prune, the index
+ * list given: their hand-off makes the blocks of a unit store together, which the
+ * memory takes better than stores scattered between other units' loads; shorter
+ * calls use the kernel of thk_compact_keys.  Same bytes either way.
+ * Environment (experiments and tests): THK_VALUE_COMPACT = flat | burst.
  *   in : q_obs, k, v (device)   out: score_v (float), idx_v (int16), v_pruned
  *   ws : THK_OP_PRUNE_VALUE bytes.
  */

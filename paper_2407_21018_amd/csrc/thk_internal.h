@@ -131,6 +131,8 @@ struct EnvSwitches {
   long prologue_delay_us; // THK_PRUNE_PROLOGUE_DELAY_US (test hook of the single-launch prune), <= 0 = none
   char decode_merge;      // first letter of THK_DECODE_MERGE ('k'ernel: a second launch merges the split
                           // records, 'f'used: the last block of a head group merges), 0 = unset
+  char value_compact;     // first letter of THK_VALUE_COMPACT ('f'lat: the plain compaction kernel,
+                          // 'b'urst: the one-pass prune kernels with the list given), 0 = unset
 };
 const EnvSwitches &env_switches();
 
@@ -187,10 +189,13 @@ size_t prune_fused_ws_bytes(int64_t U, int NB);
 // S rows per unit are scored; rows [0, S_keep) are compacted into K_pruned, whose units are
 // kp_unit_rows rows apart.  hold = 0: blocks of RB rows re-read their rows for the compaction;
 // hold = 1, 2, 4 (fp32: 1, 2): RB = 128 * hold and the rows stay on chip in between.
+// given = 1: idx is an INPUT (the list is known; pass G = 1, S_obs = 0, q_obs = k, score = nullptr):
+// the call compacts with the same kernels, whose hand-off then only makes a unit's blocks store
+// their rows together.
 hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float *score, int16_t *idx,
                               void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
                               int64_t kp_unit_rows, int G, int S_obs, int T, int ld, int NB, int64_t RB,
-                              int hold, int spin_limit, hipStream_t st);
+                              int hold, int spin_limit, int given, hipStream_t st);
 
 // The same work in ONE launch (rows held on chip only: hold = 1, 2, 4; fp32: 1, 2): the state is
 // initialised and the query norms are computed by a prologue block per unit, and blocks whose

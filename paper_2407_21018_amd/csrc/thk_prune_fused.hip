@@ -385,9 +385,10 @@ size_t prune_fused_ws_bytes(int64_t U, int NB) {
 hipError_t launch_prune_fused(int dtype, const void *q_obs, const void *k, float *score, int16_t *idx,
                               void *kp, void *ws, int64_t U, int64_t S, int64_t S_keep,
                               int64_t kp_unit_rows, int G, int S_obs, int T, int ld, int NB, int64_t RB,
-                              int hold, int spin_limit, hipStream_t st) {
+                              int hold, int spin_limit, int given, hipStream_t st) {
   clear_stale_hip_error();
   PruneFusedArgs a;
+  a.given = given;
   const int eb = dtype == THK_BF16 ? 2 : 4;
   a.k = k; a.q_obs = q_obs; a.kp = kp; a.score = score; a.idx = idx;
   char *w = (char *)ws;

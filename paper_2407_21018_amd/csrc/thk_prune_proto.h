@@ -44,6 +44,10 @@ struct PruneFusedArgs {
   int64_t S_keep;         // rows [0, S_keep) of every unit are compacted
   int64_t kp_unit_rows;   // rows between units of K_pruned
   int32_t T, ld, G, S_obs, NB, spin_limit;   // ld: elements from row to row of K_pruned
+  // 1: the index list in `idx` is the caller's INPUT (compaction of a cache whose list is known,
+  // e.g. the value cache).  The blocks of a unit still exchange their column sums, but only as
+  // the barrier that makes a unit's rows leave the chip in one burst; no score is written.
+  int32_t given;
 };
 
 __device__ inline void pub_store_f64(double *p, double v) {
@@ -113,6 +117,11 @@ __device__ inline unsigned long long pub_load_bits(const double *p) {
 __device__ __forceinline__ void score_and_select(const PruneFusedArgs &a, int64_t u, double qn_c, double kss,
                                                  float *s_sc, int16_t *s_idx, bool writer) {
   const int tid = threadIdx.x;
+  if (a.given) {
+    if (tid < a.T) s_idx[tid] = a.idx[(size_t)u * a.T + tid];
+    __syncthreads();
+    return;
+  }
   if (tid < kD) {
     const float scf = (float)(qn_c * sqrt(kss));
     if (writer) a.score[(size_t)u * kD + tid] = scf;

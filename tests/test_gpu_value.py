@@ -269,6 +269,50 @@ def test_decode_attn_kv_argument_errors():
     assert st(s, big, big, big, big, big, 64, 64, big, None, 2, 4, big, big) == 1     # tail without v_tail
 
 
+# ------------------------------- thk_prune_value: the two forms of the compaction step ----
+@pytest.mark.parametrize("spin", [None, "0"], ids=["wait", "give-up"])
+@pytest.mark.parametrize("dtype,G,S,T_v,ld_v,S_recent", [
+    ("bf16", 1, 1500, 76, 76, 0),
+    ("bf16", 2, 4100, 51, 52, 32),      # padded rows, the last 32 rows stay with the caller
+    ("f32", 1, 700, 64, 64, 0),
+    ("bf16", 1, 1037, 1, 4, 0),         # one kept channel, odd length
+    ("bf16", 1, 40000, 100, 104, 0),    # 79 row blocks per unit: the sums travel in two levels
+])
+def test_value_prune_compaction_in_bursts(dtype, G, S, T_v, ld_v, S_recent, spin, thk_env):
+    """Long thk_prune_value calls compact V through the one-pass prune kernels with the index
+    list given (their hand-off only groups a unit's stores).  Forced here on small calls, with
+    the blocks waiting for each other and with every wait given up at once (the repair launch
+    then compacts from the given list): scores, list and compacted values must equal those of
+    the plain compaction kernel bit for bit, and the oracle's compaction."""
+    L, B, N_kv, S_obs = 1, 2, 2, 32
+    U = L * B * N_kv
+    q_obs = _randn((L, B, N_kv * G, S_obs, D), dtype, 401, 0.5)
+    k = _randn((L, B, N_kv, S, D), dtype, 402, 0.5)
+    v = _randn((L, B, N_kv, S, D), dtype, 403, 0.7)
+    shape = thk.make_shape(L, B, N_kv * G, N_kv, D, S, S_obs, T_v, ld_v, DT[dtype], 0, S_recent)
+    got = {}
+    if spin is not None:
+        thk_env.setenv("THK_PRUNE_SPIN_LIMIT", spin)
+    for form in ("flat", "burst"):
+        thk_env.setenv("THK_VALUE_COMPACT", form)
+        score_v = torch.empty(U, D, dtype=torch.float32, device="cuda")
+        idx_v = torch.full((U, T_v), -1, dtype=torch.int16, device="cuda")
+        vp = torch.full((U, S - S_recent, ld_v), float("nan"), dtype=TDT[dtype], device="cuda")
+        ws = ws_tensor(thk.thk_workspace_bytes(shape, thk.THK_OP_PRUNE_VALUE))
+        print(f"prune_value {form} {dtype} G={G} S={S} T_v={T_v} ld_v={ld_v} S_recent={S_recent} spin={spin}",
+              flush=True)
+        thk.thk_prune_value(shape, q_obs, k, v, 1, score_v, idx_v, vp, ws)
+        torch.cuda.synchronize()
+        got[form] = (score_v.cpu(), idx_v.cpu(), vp.cpu())
+    assert torch.equal(got["flat"][0], got["burst"][0])
+    assert torch.equal(got["flat"][1], got["burst"][1])
+    assert torch.equal(got["flat"][2].view(torch.uint8), got["burst"][2].view(torch.uint8))
+    want_vp = O.compact_keys(as_numpy(v).reshape(U, S, D)[:, :S - S_recent], got["burst"][1].numpy(), dtype)
+    np.testing.assert_array_equal(as_numpy(got["burst"][2][:, :, :T_v].contiguous()), want_vp)
+    if ld_v > T_v:
+        assert (got["burst"][2][:, :, T_v:] == 0).all()   # the padding of the rows written is zero
+
+
 # -------------------------------------------- the whole path: prune K, prune V, decode ----
 @pytest.mark.parametrize("dtype,G,S,lam_k,lam_v,causal", [("bf16", 1, 1500, 0.4, 0.4, 1), ("bf16", 4, 2300, 0.5, 0.3, 1),
                                                          ("f32", 2, 700, 0.5, 0.5, 0)])
