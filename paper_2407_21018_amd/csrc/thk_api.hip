@@ -672,7 +672,8 @@ thk_status thk_score_value(const thk_shape *s, const void *q_obs, const void *k,
   if ((int64_t)G * s->S_obs > 32 * 1024) return THK_ERR_SHAPE;
   const Split sp = value_split(s);
   const int QT = value_attn_qt(G, s->S_obs);
-  const int64_t grid = units_of(s) * sp.n * ceil_div((G * s->S_obs + 31) / 32, QT);
+  // (the launch rounds the pieces up to a multiple of 8 where a unit has several query blocks)
+  const int64_t grid = (units_of(s) * sp.n + 7) * ceil_div((G * s->S_obs + 31) / 32, QT);
   if (grid > kMaxGrid) return THK_ERR_SHAPE;
   if (ws == nullptr || !aligned16(ws) || ws_bytes < thk_workspace_bytes(s, THK_OP_SCORE_VALUE))
     return THK_ERR_WORKSPACE;

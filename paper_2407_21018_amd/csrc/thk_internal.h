@@ -244,6 +244,7 @@ struct ValueAttnArgs {
   const void *q_obs, *k, *v;
   float *part;                 // partial records, value_part_bytes() bytes
   int64_t S, rows_per_split;   // rows_per_split is a multiple of 128
+  int64_t U;                   // units of the call
   int32_t G, S_obs, n_split, causal, n_qblk;
   float scale_log2;            // log2(e) / sqrt(D)
 };

@@ -62,6 +62,30 @@ __device__ __forceinline__ void softmax_step(f32x16 &s, int64_t kb, int h, int64
   for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -m_run));
 }
 
+constexpr int kXcds = 8;   // workgroup i of a launch runs on XCD i % 8, each XCD behind an L2 of its own
+
+// Which (query block, S piece, unit) a workgroup takes.  With one query block per unit the
+// order is plain.  With several (more than 128 query rows per KV head) the blocks that stream
+// the SAME keys and values are placed 8 workgroup numbers apart: same XCD, dispatched one after
+// the other, so the second finds the rows in that XCD's L2 instead of fetching them again.
+// False: a surplus workgroup of the rounded-up grid.
+__device__ __forceinline__ bool value_block_work(const ValueAttnArgs &a, int &qb, int &sp, int64_t &u) {
+  const int64_t bid = blockIdx.x;
+  int64_t piece;   // (unit, S piece)
+  if (a.n_qblk == 1) {
+    qb = 0;
+    piece = bid;
+  } else {
+    const int x = (int)(bid % kXcds);
+    const int64_t slot = bid / kXcds;
+    qb = (int)(slot % a.n_qblk);
+    piece = (slot / a.n_qblk) * kXcds + x;
+  }
+  sp = (int)(piece % a.n_split);
+  u = piece / a.n_split;
+  return u < a.U;
+}
+
 // Partial record of one (unit, split, query tile): O^T [128][32], then m [32] and l [32].
 __device__ __forceinline__ void write_record(float *rec, const f32x16 (&o)[4], float m_run, float l_tot, int n,
                                              int h) {
@@ -96,11 +120,9 @@ __global__ __launch_bounds__(256, 2) void k_value_attn_bf16(ValueAttnArgs a) {
   const int qt = w % QT, ksub = w / QT;
   const int n = lane & 31, h = lane >> 5;
 
-  int64_t bid = blockIdx.x;
-  const int qb = (int)(bid % a.n_qblk);
-  bid /= a.n_qblk;
-  const int sp = (int)(bid % a.n_split);
-  const int64_t u = bid / a.n_split;
+  int qb, sp;
+  int64_t u;
+  if (!value_block_work(a, qb, sp, u)) return;
 
   const int rows_q = a.G * a.S_obs;
   const int qtile = qb * QT + qt;
@@ -287,11 +309,9 @@ __global__ __launch_bounds__(64 * QT) void k_value_attn_f32(ValueAttnArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, qt = tid >> 6;
   const int n = lane & 31, h = lane >> 5;
 
-  int64_t bid = blockIdx.x;
-  const int qb = (int)(bid % a.n_qblk);
-  bid /= a.n_qblk;
-  const int sp = (int)(bid % a.n_split);
-  const int64_t u = bid / a.n_split;
+  int qb, sp;
+  int64_t u;
+  if (!value_block_work(a, qb, sp, u)) return;
 
   const int rows_q = a.G * a.S_obs;
   const int qtile = qb * QT + qt;
@@ -505,7 +525,11 @@ hipError_t launch_value_score(int dtype, const void *q_obs, const void *k, const
   a.G = G; a.S_obs = S_obs; a.n_split = n_split; a.causal = causal;
   a.n_qblk = (nqt_real + QT - 1) / QT;
   a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)kD));
-  const unsigned grid = (unsigned)(U * n_split * a.n_qblk);
+  a.U = U;
+  // several query blocks per (unit, piece): pieces rounded up to a multiple of the XCD count
+  // (value_block_work; the surplus workgroups return at once)
+  const int64_t pieces = a.n_qblk == 1 ? U * n_split : (U * n_split + kXcds - 1) / kXcds * kXcds;
+  const unsigned grid = (unsigned)(pieces * a.n_qblk);
   const void *fn;
   int threads = 256;
   if (dtype == THK_BF16) {

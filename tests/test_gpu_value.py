@@ -78,6 +78,8 @@ CASES = [
     (2, 5, 40, 0, 1, 0.0),
     (4, 32, 4100, 0, 0, 1.0),
     (1, 32, 4100, 8, 1, 1.0),
+    (16, 32, 500, 3, 1, 0.5),    # 16 query tiles: four blocks per (unit, piece), placed 8 workgroups apart
+    (5, 64, 900, 5, 0, 0.5),     # 10 tiles: three blocks, the last half empty; pieces not a multiple of 8
 ]
 
 
