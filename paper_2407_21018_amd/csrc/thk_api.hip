@@ -330,7 +330,7 @@ bool value_compact_in_bursts(const thk_shape *s, const FusedPlan &fp) {
 }
 
 // Split of the S axis for the value score: pieces are whole 128-row chunks of at least 512
-// rows, enough of them for one resident set of blocks (two per compute unit: 74 KB of LDS
+// rows (fp32: 128), enough of them for one resident set of blocks (two per compute unit: 74 KB of LDS
 // each; more pieces only add merge work -- one layer of config 2: 65 us with 8 pieces per
 // unit, 54-55 us with 2-4), and few enough that the merge kernel's weight table (at most 256
 // pieces) fits.
@@ -342,7 +342,10 @@ Split value_split(const thk_shape *s) {
   int n = s->n_split;
   if (n == 0) {
     n = (int)ceil_div((int64_t)kCUs * 2, blocks1);
-    const int64_t cap = ceil_div(s->S, 512);
+    // fp32: pieces down to one 128-row chunk (a block is one to four wavefronts bound by the
+    // fp32 matrix rate: 8 units x 2048 rows 110 -> 47 us, 64 x 1024 rows 112 -> 48 us); bf16
+    // blocks take four chunks side by side and lose 10-15 % with smaller pieces
+    const int64_t cap = ceil_div(s->S, s->dtype == THK_F32 ? 128 : 512);
     if (n > cap) n = (int)cap;
     if (n < 1) n = 1;
   }
